@@ -1,0 +1,230 @@
+/*
+ * kvswitch.h - C ABI of libkvswitch: chunk-wise KV-cache scoring, compression
+ * and swap-in for LLM context switching on one AMD MI355X (gfx950) GPU.
+ *
+ * The operations are those of "LLM as a System Service on Mobile Devices"
+ * (arXiv 2403.11805): the context memory of an LLM is a KV cache cut along the
+ * token axis into fixed-size chunks (Sec. 3.1, chunk memory model); a chunk is
+ * compressed at a bit-width chosen from its attention-derived information
+ * density (Sec. 3.2, Eq. 1 and Eq. 2), swapped out ahead of time (Sec. 3.4,
+ * AoT swapping), evicted in LCTRU order (Sec. 3.4) and brought back by the
+ * Load primitive (Sec. 3.1, primitives; Sec. 3.3).
+ *
+ * Conventions
+ *  - Every function returns 0 (KV_OK) or a negative kv_status; a text for the
+ *    last failure on the calling thread is available from kv_last_error().
+ *    No C++ exception crosses this boundary.
+ *  - The caller owns every buffer.  "dev" pointers are device (HBM) addresses,
+ *    "host" pointers ordinary host memory, "pinned" host memory obtained from
+ *    hipHostMalloc (or torch pin_memory).  The library keeps no pointer after a
+ *    call returns and allocates no device memory (kv_swapin_pinned and
+ *    kv_swapout_aot create and destroy one HIP event per call).
+ *  - Device entry points only enqueue work on the caller's hipStream_t (passed
+ *    as void*, NULL = the default stream) and never synchronise.  Host
+ *    arguments are validated before anything is enqueued: an error return
+ *    means nothing was launched and nothing written.  Device-side lists
+ *    (bits, offsets, gather lists) are trusted: the caller builds them with
+ *    the host helpers below, which validate them.
+ *  - fp16 inputs must be finite; NaN/Inf give unspecified codes.
+ *
+ * Layouts
+ *  fp16 KV cache (dev), contiguous: [n_layers][2 (K=0,V=1)][n_kv_heads][n_tokens][head_dim].
+ *  A "slab" is the chunk_tokens x head_dim block of one (layer, K|V, kv-head)
+ *  for one token chunk; a chunk is all n_layers*2*n_kv_heads slabs of the same
+ *  chunk_tokens tokens and has ONE bit-width (Sec. 3.1: same number of tokens
+ *  and same in-chunk ratio per chunk).
+ *
+ *  Packed record of a chunk with bit-width b in {8,4,2}, sections back to back:
+ *    codes : [n_layers][2][n_kv_heads][chunk_tokens][head_dim*b/8] bytes; in a
+ *            token row element d sits in byte d*b/8 at bit (d mod (8/b))*b,
+ *            lowest-index element in the least-significant bits (Sec. 4:
+ *            sub-byte codes are bit-shifted into 8-bit containers);
+ *    scale : [n_layers][2][n_kv_heads][chunk_tokens][head_dim/group] fp32;
+ *    mn    : same shape, fp32 (the group minimum).
+ *  b = 16 is pass-through: the record is the chunk's fp16 bytes in the order
+ *  [n_layers][2][n_kv_heads][chunk_tokens][head_dim], no metadata.
+ *  Record i starts at byte offset off[i] of the packed pool (kv_chunk_offsets).
+ *
+ *  Quantisation of one group of `group` consecutive head_dim elements of one
+ *  token (linear min/max quantisation, Sec. 3.2 "Compressing chunks"), all in
+ *  IEEE binary32, round-to-nearest, no contraction:
+ *    mn = min x + 0.0f, mx = max x + 0.0f, scale = (mx - mn) / (2^b - 1),
+ *    code = scale == 0 ? 0 : clamp(rint((x - mn) / scale), 0, 2^b - 1)
+ *  with rint rounding halves to even.  Dequantisation: fp16_rne(fp32(code) *
+ *  scale + mn), product and sum rounded separately.
+ */
+#ifndef KVSWITCH_H
+#define KVSWITCH_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    KV_OK      = 0,
+    KV_EINVAL  = -1,  /* NULL pointer or argument out of range            */
+    KV_ESHAPE  = -2,  /* kv_shape_t violates the requirements below        */
+    KV_EBITS   = -3,  /* a bit-width outside {16,8,4,2}                    */
+    KV_EINDEX  = -4,  /* chunk index out of range, unsorted or repeated    */
+    KV_ENOMEM  = -5,  /* capacity too small / not enough evictable bytes   */
+    KV_EHIP    = -6   /* a HIP runtime call failed (text has the HIP error) */
+} kv_status;
+
+/* Geometry of one context's KV cache.
+ * Requirements (else KV_ESHAPE): all fields > 0; n_tokens % chunk_tokens == 0
+ * (chunks hold the same number of tokens, Sec. 3.1); head_dim % group == 0;
+ * group % 64 == 0; n_q_heads % n_kv_heads == 0; head_dim <= 1024;
+ * chunk_tokens <= 1024. */
+typedef struct {
+    int32_t n_layers;
+    int32_t n_kv_heads;
+    int32_t n_q_heads;     /* used by kv_score_chunks only */
+    int32_t head_dim;
+    int32_t n_tokens;
+    int32_t chunk_tokens;
+    int32_t group;         /* quantisation group along head_dim */
+} kv_shape_t;
+
+enum { KV_NORM_VISIBLE = 0, KV_NORM_NONE = 1 };
+
+/* Text of the last error on this thread (never NULL; "" if none). */
+const char* kv_last_error(void);
+
+/* ---------------------------------------------------------------- host, pure */
+
+/* Bytes of one chunk's packed record at bit-width `bits`; 0 if shape or bits
+ * are invalid.  b<16: slabs*T*(D*b/8 + 8*D/G); b=16: slabs*T*D*2. */
+uint64_t kv_record_bytes(const kv_shape_t* shape, int32_t bits);
+
+/* Exclusive prefix sum of record sizes: off[0]=0, off[i+1]=off[i]+record_bytes(bits[i]).
+ * bits: host [n_chunks]; off: host [n_chunks+1].  Chunks are compressed and
+ * swapped independently (Sec. 1 / Sec. 3.1), so records are self-contained. */
+int32_t kv_chunk_offsets(const kv_shape_t* shape, const uint8_t* bits, uint64_t* off);
+
+/* Rank chunks by density and bucket them (Sec. 3.2, Eq. 2, with fixed
+ * thresholds): order by (density descending, index ascending); the first
+ * k8 = n*num8/den chunks get 8 bits, the next k4 = n*(num8+num4)/den - k8 get
+ * 4 bits, the rest 2 bits (integer division).  density: host [n]; bits: host [n].
+ * Requires den > 0, num8 >= 0, num4 >= 0, num8 + num4 <= den. */
+int32_t kv_bits_from_scores(const float* density, int32_t n, int32_t num8,
+                            int32_t num4, int32_t den, uint8_t* bits);
+
+/* Load primitive, list building (Sec. 3.1, primitive 3): for n_sel strictly
+ * ascending chunk indices produce src_off[j] = off[idx_j], dst_tok[j] =
+ * idx_j*chunk_tokens, sel_bits[j] = bits[idx_j].  All pointers host. */
+int32_t kv_build_gather(const kv_shape_t* shape, const uint64_t* off, const uint8_t* bits,
+                        const int32_t* chunk_idx, int32_t n_sel,
+                        uint64_t* src_off, int32_t* dst_tok, uint8_t* sel_bits);
+
+/* ------------------------------------------------------------ device, async */
+
+/* Bytes of device workspace kv_score_chunks needs for this shape and number
+ * of query rows; 0 on invalid arguments. */
+uint64_t kv_score_workspace_bytes(const kv_shape_t* shape, int32_t n_queries);
+
+/* Information density of every chunk (Sec. 3.2, Eq. 1).
+ *   q    dev fp16 [n_layers][n_q_heads][n_queries][head_dim]: the query rows of
+ *        the last n_queries tokens (row r sits at position n_tokens-n_queries+r);
+ *        1 <= n_queries <= min(n_tokens, 256).
+ *   kv   dev fp16 cache; only the K planes are read.  Query head h attends to
+ *        kv head h / (n_q_heads / n_kv_heads).
+ *   A = softmax(causal_mask(Q K^T / sqrt(head_dim))) per (layer, head), fp32.
+ *   norm_mode KV_NORM_VISIBLE: each column is averaged over the rows that can
+ *        see it (the reading fixed by the paper's worked example of Eq. 1);
+ *        KV_NORM_NONE: plain column sums (their total per head is n_queries).
+ *   chunk_mass dev fp32 [n_layers][n_q_heads][n_chunks]: sum over the chunk's
+ *        columns of the normalised column mass.
+ *   density    dev fp32 [n_chunks]: mean of chunk_mass over layers and heads,
+ *        divided by chunk_tokens (= D_i of Eq. 1).
+ *   workspace  dev, >= kv_score_workspace_bytes(), 256-byte aligned; contents
+ *        are scratch. */
+int32_t kv_score_chunks(const kv_shape_t* shape, const void* q, int32_t n_queries,
+                        const void* kv, int32_t norm_mode,
+                        void* workspace, uint64_t workspace_bytes,
+                        float* chunk_mass, float* density, void* stream);
+
+/* Quantise and bit-pack every chunk at its bit-width (Sec. 3.2 "Compressing
+ * chunks"; Sec. 4 bit-shift packing).
+ *   kv dev fp16 cache (read only); bits_dev dev u8 [n_chunks];
+ *   off_dev dev u64 [n_chunks+1] from kv_chunk_offsets;
+ *   packed_out dev, >= off[n_chunks] bytes, 16-byte aligned. */
+int32_t kv_compress_chunks(const kv_shape_t* shape, const void* kv,
+                           const uint8_t* bits_dev, const uint64_t* off_dev,
+                           void* packed_out, void* stream);
+
+/* Load primitive, data movement (Sec. 3.1 primitive 3; Sec. 3.3): unpack and
+ * dequantise the n_sel listed records into tokens [dst_tok[j], dst_tok[j] +
+ * chunk_tokens) of every slab of kv_out; other tokens are untouched.
+ *   packed dev pool; src_off_dev dev u64 [n_sel] (byte offsets into packed);
+ *   dst_tok_dev dev i32 [n_sel]; sel_bits_dev dev u8 [n_sel]; kv_out dev fp16
+ *   cache.  n_sel == 0 is a no-op.  The Fault primitive is this call with
+ *   n_sel == 1. */
+int32_t kv_swapin_chunks(const kv_shape_t* shape, const void* packed,
+                         const uint64_t* src_off_dev, const int32_t* dst_tok_dev,
+                         const uint8_t* sel_bits_dev, int32_t n_sel,
+                         void* kv_out, void* stream);
+
+/* Streaming Load from pinned host memory: the IO half of the swapping-
+ * recompute pipeline (Sec. 3.3), with the dequantise kernel in the place of
+ * the recompute stage.  The listed records are copied host->device in batches
+ * on copy_stream into n_buffers staging slots while earlier batches are
+ * dequantised on compute_stream.
+ *   packed_pinned pinned host pool; src_off/dst_tok/sel_bits HOST lists [n_sel]
+ *   as produced by kv_build_gather (ascending chunks, hence ascending offsets);
+ *   staging_dev dev scratch of staging_bytes, 256-byte aligned, split into
+ *   n_buffers (2..8) equal slots, each of which must hold the largest listed
+ *   record plus 16 bytes per record of list (else KV_ENOMEM);
+ *   kv_out dev fp16 cache.  copy_stream and compute_stream must differ and
+ *   must not be the NULL stream.  Returns after enqueuing everything;
+ *   completion = both streams idle (the last kernel is on compute_stream). */
+int32_t kv_swapin_pinned(const kv_shape_t* shape, const void* packed_pinned,
+                         const uint64_t* src_off, const int32_t* dst_tok,
+                         const uint8_t* sel_bits, int32_t n_sel,
+                         void* staging_dev, uint64_t staging_bytes, int32_t n_buffers,
+                         void* kv_out, void* copy_stream, void* compute_stream);
+
+/* Ahead-of-time swap-out (Sec. 3.4 i): enqueue on copy_stream, after the work
+ * currently enqueued on producer_stream, a device->pinned-host copy of
+ * packed_dev[begin, end) to the same offsets of packed_pinned, so that a later
+ * Reclaim of these chunks moves no data. */
+int32_t kv_swapout_aot(const void* packed_dev, void* packed_pinned,
+                       uint64_t begin, uint64_t end,
+                       void* producer_stream, void* copy_stream);
+
+/* -------------------------------------------- host lifecycle (Sec. 3.4 ii) */
+
+/* LCTRU queue: concatenated sub-queues, one per bit-width, least compressed
+ * first; inside a sub-queue the least recently used context first; ties by
+ * (ctx, chunk) ascending.  Only memory-resident chunks are queued.  Contexts
+ * locked as a working set are skipped by eviction (Sec. 3.4, working set). */
+typedef struct kv_lctru kv_lctru_t;
+
+kv_lctru_t* kv_lctru_create(void);
+void        kv_lctru_destroy(kv_lctru_t* q);
+
+/* Claim: a chunk becomes resident.  KV_EINVAL if (ctx,chunk) is already queued. */
+int32_t kv_lctru_insert(kv_lctru_t* q, int32_t ctx, int32_t chunk, int32_t bits,
+                        uint64_t bytes, uint64_t now);
+/* On every call into a context: all its resident chunks get last_access = now. */
+int32_t kv_lctru_touch_ctx(kv_lctru_t* q, int32_t ctx, uint64_t now);
+int32_t kv_lctru_lock(kv_lctru_t* q, int32_t ctx);
+int32_t kv_lctru_unlock(kv_lctru_t* q, int32_t ctx);
+/* Reclaim: pop from the front until the popped bytes reach bytes_needed.
+ * KV_ENOMEM (nothing popped) if the unlocked resident bytes are fewer than
+ * bytes_needed or more than cap entries would be needed. */
+int32_t kv_lctru_evict(kv_lctru_t* q, uint64_t bytes_needed, int32_t* out_ctx,
+                       int32_t* out_chunk, int32_t cap, int32_t* n_out);
+/* Current eviction order of all unlocked entries, front first (no change). */
+int32_t kv_lctru_order(const kv_lctru_t* q, int32_t* out_ctx, int32_t* out_chunk,
+                       int32_t cap, int32_t* n_out);
+/* Context deleted: drop all its entries (and its lock). */
+int32_t kv_lctru_remove_ctx(kv_lctru_t* q, int32_t ctx);
+/* Number of queued (resident) entries and their total bytes. */
+int32_t kv_lctru_size(const kv_lctru_t* q, int32_t* n_entries, uint64_t* bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVSWITCH_H */

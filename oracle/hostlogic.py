@@ -1,0 +1,115 @@
+"""Oracle for the host-side bookkeeping of the context-switch path: record
+sizes and offsets, rank-to-bit-width bucketing (Sec. 3.2, Eq. 2 with fixed
+thresholds), the gather list of the Load primitive (Sec. 3.1) and the LCTRU
+eviction queue with its working-set lock (Sec. 3.4).
+
+TEST INFRASTRUCTURE ONLY.  Plain Python on small integer inputs; written as the
+definitions read, not for speed.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+VALID_BITS = (16, 8, 4, 2)
+
+
+def record_bytes(shape, bits: int) -> int:
+    """Bytes of one chunk's packed record.  b < 16: every token row of every
+    slab holds D*b/8 code bytes plus one fp32 scale and one fp32 minimum per
+    group of G elements; b = 16: the raw fp16 bytes."""
+    assert bits in VALID_BITS
+    slabs = shape.L * 2 * shape.Hkv
+    if bits == 16:
+        return slabs * shape.T * shape.D * 2
+    return slabs * shape.T * (shape.D * bits // 8 + 8 * (shape.D // shape.G))
+
+
+def chunk_offsets(shape, bits) -> np.ndarray:
+    """off[0] = 0, off[i+1] = off[i] + record_bytes(bits[i])."""
+    off = [0]
+    for b in bits:
+        off.append(off[-1] + record_bytes(shape, int(b)))
+    return np.array(off, dtype=np.uint64)
+
+
+def bits_from_scores(density, num8: int, num4: int, den: int) -> np.ndarray:
+    """Rank chunks by density (highest first, ties by lower index first); the
+    densest n*num8//den chunks keep 8 bits, the following ones up to
+    n*(num8+num4)//den in total get 4 bits, the rest 2 bits."""
+    density = [float(np.float32(d)) for d in density]
+    n = len(density)
+    order = sorted(range(n), key=lambda i: (-density[i], i))
+    k8 = n * num8 // den
+    k84 = n * (num8 + num4) // den
+    bits = np.zeros(n, dtype=np.uint8)
+    for rank, i in enumerate(order):
+        bits[i] = 8 if rank < k8 else (4 if rank < k84 else 2)
+    return bits
+
+
+def build_gather(shape, off, bits, chunk_idx):
+    """Gather list for loading the chunks `chunk_idx` (strictly ascending):
+    where each record starts, which token it lands on, and its bit-width."""
+    idx = [int(i) for i in chunk_idx]
+    assert all(0 <= i < shape.N // shape.T for i in idx)
+    assert all(a < b for a, b in zip(idx, idx[1:]))
+    src_off = np.array([int(off[i]) for i in idx], dtype=np.uint64)
+    dst_tok = np.array([i * shape.T for i in idx], dtype=np.int32)
+    sel_bits = np.array([int(bits[i]) for i in idx], dtype=np.uint8)
+    return src_off, dst_tok, sel_bits
+
+
+class LctruModel:
+    """LCTRU queue (Sec. 3.4): one sub-queue per bit-width, concatenated with
+    the least compressed (most bits) first; inside a sub-queue the entry whose
+    context was used longest ago comes first.  Ties: lower context id, then
+    lower chunk index.  Chunks of a locked context (the working set of a call in
+    progress) are never handed out."""
+
+    def __init__(self):
+        self.entries = {}   # (ctx, chunk) -> dict(bits, bytes, last)
+        self.locked = set()
+
+    def insert(self, ctx, chunk, bits, nbytes, now):
+        assert (ctx, chunk) not in self.entries and bits in VALID_BITS
+        self.entries[(ctx, chunk)] = dict(bits=bits, bytes=nbytes, last=now)
+
+    def touch_ctx(self, ctx, now):
+        for (c, _), e in self.entries.items():
+            if c == ctx:
+                e["last"] = now
+
+    def lock(self, ctx):
+        self.locked.add(ctx)
+
+    def unlock(self, ctx):
+        self.locked.discard(ctx)
+
+    def remove_ctx(self, ctx):
+        self.entries = {k: v for k, v in self.entries.items() if k[0] != ctx}
+        self.locked.discard(ctx)
+
+    def order(self):
+        keys = [k for k in self.entries if k[0] not in self.locked]
+        keys.sort(key=lambda k: (-self.entries[k]["bits"], self.entries[k]["last"], k[0], k[1]))
+        return keys
+
+    def evict(self, bytes_needed, cap=None):
+        """Pop from the front until the freed bytes reach bytes_needed; None
+        (and no change) if the unlocked entries cannot supply that much or more
+        than `cap` entries would be needed."""
+        order = self.order()
+        got, out = 0, []
+        for k in order:
+            if got >= bytes_needed:
+                break
+            out.append(k)
+            got += self.entries[k]["bytes"]
+        if got < bytes_needed or (cap is not None and len(out) > cap):
+            return None
+        for k in out:
+            del self.entries[k]
+        return out
+
+    def size(self):
+        return len(self.entries), sum(e["bytes"] for e in self.entries.values())

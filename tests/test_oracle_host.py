@@ -1,0 +1,96 @@
+"""Pins for the oracle's host bookkeeping: record sizes, offsets, rank-based
+bit-widths (Sec. 3.2, Eq. 2), gather lists (Load, Sec. 3.1) and the LCTRU
+queue with working-set lock (Sec. 3.4).  Expected values are worked out by
+hand from the definitions."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2403_11805_amd import synth
+
+
+def oshape(i):
+    return oracle.Shape(*synth.WORKLOADS[i].geom)
+
+
+def test_record_sizes_by_hand():
+    # tiny: 16 slabs x 16 tokens; a token row is 64 elements, one group
+    s = oshape(0)
+    assert oracle.record_bytes(s, 16) == 16 * 16 * 64 * 2 == 32768
+    assert oracle.record_bytes(s, 8) == 16 * 16 * (64 + 8) == 18432
+    assert oracle.record_bytes(s, 4) == 16 * 16 * (32 + 8) == 10240
+    assert oracle.record_bytes(s, 2) == 16 * 16 * (16 + 8) == 6144
+    # Llama-2-7B shape: 2048 slabs x 16 tokens; rows of 128 elements, two groups
+    s = oshape(2)
+    assert oracle.record_bytes(s, 16) == 8388608
+    assert oracle.record_bytes(s, 8) == 2048 * 16 * (128 + 16) == 4718592
+    assert oracle.record_bytes(s, 4) == 2621440 and oracle.record_bytes(s, 2) == 1572864
+    # 32k GQA shape: 512 slabs x 32 tokens, group 128
+    s = oshape(4)
+    assert [oracle.record_bytes(s, b) for b in (16, 8, 4, 2)] == [4194304, 2228224, 1179648, 655360]
+    # the whole 4k Llama-2-7B context is 2 GiB in fp16 (Sec. 2.3: "over 2GB")
+    assert oracle.record_bytes(oshape(2), 16) * oshape(2).n_chunks == 2 ** 31
+
+
+def test_offsets_are_a_prefix_sum():
+    s = oshape(1)
+    bits = np.array([8] * 64 + [4] * 128 + [2] * 64, dtype=np.uint8)
+    off = oracle.chunk_offsets(s, bits)
+    assert off[0] == 0 and len(off) == 257
+    assert int(off[-1]) == 64 * 165888 + 128 * 92160 + 64 * 55296 == 25952256
+    assert np.all(np.diff(off.astype(np.int64)) == [oracle.record_bytes(s, int(b)) for b in bits])
+    s = oshape(2)
+    bits = np.array([8] * 85 + [4] * 85 + [2] * 86, dtype=np.uint8)
+    assert int(oracle.chunk_offsets(s, bits)[-1]) == 759169024
+
+
+def test_bits_from_scores_counts_and_ties():
+    d = synth.draw_scores(256, 1).numpy()
+    bits = oracle.bits_from_scores(d, 1, 2, 4)
+    assert [(bits == b).sum() for b in (8, 4, 2)] == [64, 128, 64]
+    assert d[bits == 8].min() >= d[bits == 4].max() and d[bits == 4].min() >= d[bits == 2].max()
+    bits = oracle.bits_from_scores(d, 1, 1, 3)
+    assert [(bits == b).sum() for b in (8, 4, 2)] == [85, 85, 86]
+    bits = oracle.bits_from_scores(np.arange(1024, dtype=np.float32), 1, 1, 3)
+    assert [(bits == b).sum() for b in (8, 4, 2)] == [341, 341, 342]
+    # equal scores: the lower index ranks first
+    bits = oracle.bits_from_scores(np.array([1, 1, 1, 1, 1, 1], dtype=np.float32), 1, 1, 3)
+    assert bits.tolist() == [8, 8, 4, 4, 2, 2]
+    bits = oracle.bits_from_scores(np.array([0.1, 0.9, 0.5, 0.9], dtype=np.float32), 1, 2, 4)
+    assert bits.tolist() == [2, 8, 4, 4]
+
+
+def test_gather_list():
+    s = oshape(0)
+    bits = np.array([8, 4, 2, 16] * 8, dtype=np.uint8)
+    off = oracle.chunk_offsets(s, bits)
+    src, dst, sb = oracle.build_gather(s, off, bits, [1, 2, 7, 31])
+    assert src.tolist() == [18432, 18432 + 10240, int(off[7]), int(off[31])]
+    assert dst.tolist() == [16, 32, 112, 496] and sb.tolist() == [4, 2, 16, 16]
+    with pytest.raises(AssertionError):
+        oracle.build_gather(s, off, bits, [2, 1])
+    with pytest.raises(AssertionError):
+        oracle.build_gather(s, off, bits, [32])
+
+
+def test_lctru_heavy_first_then_least_recent_and_lock():
+    q = oracle.LctruModel()
+    # ctx 0 used at t=1, ctx 1 at t=2, ctx 2 at t=3
+    for ctx, now in ((0, 1), (1, 2), (2, 3)):
+        q.insert(ctx, 0, 8, 100, now)
+        q.insert(ctx, 1, 4, 60, now)
+        q.insert(ctx, 2, 2, 30, now)
+    # heavy (8-bit) sub-queue first, oldest context first inside each sub-queue
+    assert q.order() == [(0, 0), (1, 0), (2, 0), (0, 1), (1, 1), (2, 1), (0, 2), (1, 2), (2, 2)]
+    q.touch_ctx(0, 10)         # ctx 0 becomes the most recent
+    assert q.order()[:3] == [(1, 0), (2, 0), (0, 0)]
+    q.lock(1)                  # working set of a call in progress
+    assert all(k[0] != 1 for k in q.order())
+    assert q.evict(10 ** 6) is None and q.size() == (9, 570)    # cannot supply: nothing popped
+    got = q.evict(150)         # 100 (ctx 2) + 100 (ctx 0) >= 150
+    assert got == [(2, 0), (0, 0)]
+    q.unlock(1)
+    assert q.order()[0] == (1, 0)
+    q.remove_ctx(1)
+    assert q.size() == (4, 180)
+    assert q.evict(0) == []

@@ -1,0 +1,193 @@
+"""Pins for the scoring oracle (Sec. 3.2, Eq. 1).  CPU only.
+
+Each test ties the oracle to something other than itself: the paper's worked
+example, closed forms, library softmax, an explicit extended-precision brute
+force, and invariants (rows sum to one, lower-triangular mask).
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def load_worked_example():
+    rows = []
+    with open(os.path.join(GOLDEN, "eq1_worked_example.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if line and not line.startswith("#"):
+                rows.append([float(x) for x in line.split()])
+    return np.array(rows, dtype=np.float64)
+
+
+def f16(x):
+    return np.asarray(x, dtype=np.float16)
+
+
+def test_worked_example_density_of_token_a():
+    """Column 'a' = (0.3, 0.5, 0.1) over its three visible rows -> 0.3 (Eq. 1 example)."""
+    A = load_worked_example()
+    assert A.shape == (5, 5)
+    np.testing.assert_allclose(A.sum(axis=1), 1.0, atol=1e-15)
+    assert A[2, 1] == 0.5                       # 'a' pays 50 % to 'are'
+    assert list(A[2:, 2]) == [0.3, 0.5, 0.1]
+    d = oracle.column_density(A, T=1, norm_mode=oracle.NORM_VISIBLE)
+    assert d[2] == pytest.approx(0.3, abs=1e-15)
+    np.testing.assert_allclose(d, [0.44, 0.325, 0.3, 0.25, 0.1], atol=1e-15)
+    # a divisor of R (=5) instead of the visible rows would give 0.18: must not match
+    assert abs(d[2] - 0.9 / 5) > 0.1
+    # un-normalised mode returns the plain column sums
+    raw = oracle.column_density(A, T=1, norm_mode=oracle.NORM_NONE)
+    np.testing.assert_allclose(raw, A.sum(axis=0), atol=1e-15)
+
+
+def test_worked_example_chunks_accumulate_tokens():
+    """With T=5 the one chunk's mass is the sum of the token densities (Eq. 1 sums tokens p..q)."""
+    A = load_worked_example()
+    d = oracle.column_density(A, T=5, norm_mode=oracle.NORM_VISIBLE)
+    assert d.shape == (1,)
+    assert d[0] == pytest.approx(0.44 + 0.325 + 0.3 + 0.25 + 0.1, abs=1e-14)
+
+
+def test_worked_example_through_q_and_k():
+    """Build Q, K whose softmax is the worked-example matrix: K = sqrt(D)*identity rows,
+    Q[r][c] = log A[r][c]; the end-to-end score of token 'a' must again be 0.3."""
+    A = load_worked_example()
+    N, D = 5, 16
+    k = np.zeros((N, D))
+    for c in range(N):
+        k[c, c] = math.sqrt(D)        # 4.0, exact in fp16
+    q = np.zeros((N, D))
+    for r in range(N):
+        for c in range(r + 1):
+            q[r, c] = math.log(A[r, c])
+    att = oracle.attention(f16(q), f16(k))
+    np.testing.assert_allclose(att, A, atol=2e-3)    # fp16 rounding of the logs
+    shape = oracle.Shape(L=1, Hkv=1, Hq=1, D=D, N=N, T=1, G=16)
+    kv = np.zeros((1, 2, 1, N, D), dtype=np.float16)
+    kv[0, 0, 0] = f16(k)
+    kv[0, 1, 0] = 7.0                 # V plane must be ignored
+    cm, dens = oracle.score_chunks(shape, f16(q)[None, None], kv)
+    assert dens[2] == pytest.approx(0.3, abs=2e-3)
+    np.testing.assert_allclose(cm[0, 0], dens, rtol=1e-6)
+
+
+def test_rows_sum_to_one_and_mask_is_lower_triangular():
+    rng = np.random.default_rng(1)
+    R, N, D = 7, 24, 16
+    q = f16(rng.normal(size=(R, D)))
+    k = f16(rng.normal(size=(N, D)))
+    A = oracle.attention(q, k)
+    np.testing.assert_allclose(A.sum(axis=1), 1.0, atol=1e-13)
+    for r in range(R):
+        last = N - R + r
+        assert np.all(A[r, : last + 1] > 0)
+        assert np.all(A[r, last + 1:] == 0)
+
+
+def test_uniform_attention_closed_form():
+    """Q = 0: row r spreads 1/(P_r+1) over its visible columns, so the column
+    mass is a difference of harmonic numbers."""
+    R, N, D, T = 6, 32, 16, 4
+    q = np.zeros((R, D), dtype=np.float16)
+    k = f16(np.random.default_rng(2).normal(size=(N, D)))
+    A = oracle.attention(q, k)
+    mass = np.zeros(N)
+    for c in range(N):
+        for r in range(R):
+            p = N - R + r
+            if c <= p:
+                mass[c] += 1.0 / (p + 1)
+    visible = np.array([N - max(c, N - R) for c in range(N)], dtype=np.float64)
+    none = oracle.column_density(A, T, oracle.NORM_NONE)
+    vis = oracle.column_density(A, T, oracle.NORM_VISIBLE)
+    np.testing.assert_allclose(none, mass.reshape(-1, T).sum(1), rtol=1e-13)
+    np.testing.assert_allclose(vis, (mass / visible).reshape(-1, T).sum(1), rtol=1e-13)
+    # columns before the first query row are seen by all R rows
+    assert visible[0] == R and visible[N - 1] == 1
+
+
+def test_matches_library_softmax_when_every_token_is_a_query():
+    """R = N: the textbook causal attention; compare with torch's softmax."""
+    rng = np.random.default_rng(3)
+    N, D, T = 48, 32, 8
+    q = f16(rng.normal(size=(N, D)))
+    k = f16(rng.normal(size=(N, D)))
+    s = torch.from_numpy(q.astype(np.float64)) @ torch.from_numpy(k.astype(np.float64)).T
+    s = s / math.sqrt(D)
+    s = s.masked_fill(torch.triu(torch.ones(N, N, dtype=torch.bool), diagonal=1), float("-inf"))
+    ref = torch.softmax(s, dim=1).numpy()
+    A = oracle.attention(q, k)
+    np.testing.assert_allclose(A, ref, rtol=1e-12, atol=1e-15)
+    col = ref.sum(0) / np.arange(N, 0, -1)
+    np.testing.assert_allclose(oracle.column_density(A, T, oracle.NORM_VISIBLE),
+                               col.reshape(-1, T).sum(1), rtol=1e-12)
+
+
+def test_brute_force_extended_precision_with_offset_rows():
+    """Independent element-by-element evaluation in long double with R < N."""
+    rng = np.random.default_rng(4)
+    R, N, D, T = 5, 20, 8, 4
+    q = f16(rng.normal(size=(R, D)) * 2)
+    k = f16(rng.normal(size=(N, D)) * 2)
+    ld = np.longdouble
+    A = np.zeros((R, N), dtype=ld)
+    for r in range(R):
+        pos = N - R + r
+        logits = [sum(ld(float(q[r, d])) * ld(float(k[c, d])) for d in range(D)) / np.sqrt(ld(D))
+                  for c in range(pos + 1)]
+        m = max(logits)
+        e = [np.exp(x - m) for x in logits]
+        z = sum(e)
+        for c in range(pos + 1):
+            A[r, c] = e[c] / z
+    got = oracle.attention(q, k)
+    np.testing.assert_allclose(got, A.astype(np.float64), rtol=1e-12, atol=1e-16)
+    want = np.zeros(N // T, dtype=ld)
+    for c in range(N):
+        rows = [r for r in range(R) if c <= N - R + r]
+        want[c // T] += sum(A[r, c] for r in rows) / len(rows)
+    np.testing.assert_allclose(oracle.column_density(got, T, oracle.NORM_VISIBLE),
+                               want.astype(np.float64), rtol=1e-12)
+
+
+def test_total_mass_equals_number_of_query_rows_and_gqa_mapping():
+    """NORM_NONE: every head's chunk masses sum to R (rows sum to one), hence
+    sum_i T*D_i = R.  Query head h must read kv head h // (Hq/Hkv)."""
+    rng = np.random.default_rng(5)
+    shape = oracle.Shape(L=2, Hkv=2, Hq=4, D=16, N=32, T=8, G=16)
+    R = 6
+    q = f16(rng.normal(size=(shape.L, shape.Hq, R, shape.D)))
+    kv = f16(rng.normal(size=(shape.L, 2, shape.Hkv, shape.N, shape.D)))
+    cm, dens = oracle.score_chunks(shape, q, kv, oracle.NORM_NONE)
+    np.testing.assert_allclose(cm.sum(axis=2), R, rtol=1e-6)
+    assert float(dens.sum()) * shape.T == pytest.approx(R, rel=1e-6)
+    for l in range(shape.L):
+        for h in range(shape.Hq):
+            A = oracle.attention(q[l, h], kv[l, 0, h // 2])
+            np.testing.assert_allclose(cm[l, h], oracle.column_density(A, shape.T, oracle.NORM_NONE),
+                                       rtol=1e-6)
+            np.testing.assert_allclose(oracle.score_head(shape, q, kv, l, h, oracle.NORM_NONE),
+                                       oracle.column_density(A, shape.T, oracle.NORM_NONE),
+                                       rtol=1e-14)
+    # density is the mean over layers and heads, per token
+    np.testing.assert_allclose(dens, cm.astype(np.float64).mean(axis=(0, 1)) / shape.T, rtol=1e-6)
+
+
+def test_large_logits_do_not_overflow():
+    """Softmax must subtract the row maximum: logits of several hundred stay finite."""
+    N, D = 8, 16
+    q = np.full((N, D), 30.0, dtype=np.float16)
+    k = np.zeros((N, D), dtype=np.float16)
+    k[3] = 30.0
+    A = oracle.attention(q, k)
+    assert np.all(np.isfinite(A))
+    # rows that see column 3 put all their weight there
+    for r in range(3, N):
+        assert A[r, 3] == pytest.approx(1.0, abs=1e-12)
