@@ -18,7 +18,7 @@
  *    "host" pointers ordinary host memory, "pinned" host memory obtained from
  *    hipHostMalloc (or torch pin_memory).  The library keeps no pointer after a
  *    call returns and allocates no device memory (kv_swapin_pinned and
- *    kv_swapout_aot create and destroy one HIP event per call).
+ *    kv_swapout_aot create and destroy a few HIP events per call).
  *  - Device entry points only enqueue work on the caller's hipStream_t (passed
  *    as void*, NULL = the default stream) and never synchronise.  Host
  *    arguments are validated before anything is enqueued: an error return
@@ -75,8 +75,10 @@ typedef enum {
 /* Geometry of one context's KV cache.
  * Requirements (else KV_ESHAPE): all fields > 0; n_tokens % chunk_tokens == 0
  * (chunks hold the same number of tokens, Sec. 3.1); head_dim % group == 0;
- * group % 64 == 0; n_q_heads % n_kv_heads == 0; head_dim <= 1024;
- * chunk_tokens <= 1024. */
+ * group in {64, 128, 256, 512}; n_q_heads % n_kv_heads == 0; head_dim <= 1024;
+ * chunk_tokens <= 1024; chunk_tokens * head_dim % 512 == 0;
+ * (chunk_tokens * head_dim / group) % 4 == 0 (keeps every record section
+ * 16-byte aligned). */
 typedef struct {
     int32_t n_layers;
     int32_t n_kv_heads;
@@ -127,7 +129,9 @@ uint64_t kv_score_workspace_bytes(const kv_shape_t* shape, int32_t n_queries);
 /* Information density of every chunk (Sec. 3.2, Eq. 1).
  *   q    dev fp16 [n_layers][n_q_heads][n_queries][head_dim]: the query rows of
  *        the last n_queries tokens (row r sits at position n_tokens-n_queries+r);
- *        1 <= n_queries <= min(n_tokens, 256).
+ *        1 <= n_queries <= min(n_tokens, 256).  Scoring additionally needs
+ *        head_dim in {64,128,256}, chunk_tokens a power of two >= 8 and
+ *        n_tokens % 32 == 0 (else KV_ESHAPE).
  *   kv   dev fp16 cache; only the K planes are read.  Query head h attends to
  *        kv head h / (n_q_heads / n_kv_heads).
  *   A = softmax(causal_mask(Q K^T / sqrt(head_dim))) per (layer, head), fp32.
@@ -174,8 +178,8 @@ int32_t kv_swapin_chunks(const kv_shape_t* shape, const void* packed,
  *   packed_pinned pinned host pool; src_off/dst_tok/sel_bits HOST lists [n_sel]
  *   as produced by kv_build_gather (ascending chunks, hence ascending offsets);
  *   staging_dev dev scratch of staging_bytes, 256-byte aligned, split into
- *   n_buffers (2..8) equal slots, each of which must hold the largest listed
- *   record plus 16 bytes per record of list (else KV_ENOMEM);
+ *   n_buffers (2..8) equal slots (rounded down to 256 bytes), each of which
+ *   must hold the largest listed record (else KV_ENOMEM);
  *   kv_out dev fp16 cache.  copy_stream and compute_stream must differ and
  *   must not be the NULL stream.  Returns after enqueuing everything;
  *   completion = both streams idle (the last kernel is on compute_stream). */

@@ -1,0 +1,329 @@
+"""ctypes binding of libkvswitch: same names as the C ABI, argument marshalling only.
+
+Every computation runs in the library's HIP kernels (device entry points) or its
+C++ host code.  There is no Python or CPU fallback: if the shared library has
+not been built, importing a function from here raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import NamedTuple
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libkvswitch.so")
+
+KV_OK, KV_EINVAL, KV_ESHAPE, KV_EBITS, KV_EINDEX, KV_ENOMEM, KV_EHIP = 0, -1, -2, -3, -4, -5, -6
+KV_NORM_VISIBLE, KV_NORM_NONE = 0, 1
+
+
+class KvError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"libkvswitch error {code}: {text}")
+        self.code = code
+
+
+class kv_shape_t(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("n_layers", "n_kv_heads", "n_q_heads", "head_dim", "n_tokens", "chunk_tokens", "group")]
+
+
+class Shape(NamedTuple):
+    n_layers: int
+    n_kv_heads: int
+    n_q_heads: int
+    head_dim: int
+    n_tokens: int
+    chunk_tokens: int
+    group: int
+
+    @property
+    def n_chunks(self) -> int:
+        return self.n_tokens // self.chunk_tokens
+
+    @property
+    def slabs(self) -> int:
+        return self.n_layers * 2 * self.n_kv_heads
+
+    @property
+    def kv_dims(self):
+        return (self.n_layers, 2, self.n_kv_heads, self.n_tokens, self.head_dim)
+
+    def c(self) -> kv_shape_t:
+        return kv_shape_t(*self)
+
+
+_lib = None
+_vp, _i32, _u64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_uint64
+
+_SIGNATURES = {
+    "kv_last_error": (ctypes.c_char_p, []),
+    "kv_record_bytes": (_u64, [_vp, _i32]),
+    "kv_chunk_offsets": (_i32, [_vp, _vp, _vp]),
+    "kv_bits_from_scores": (_i32, [_vp, _i32, _i32, _i32, _i32, _vp]),
+    "kv_build_gather": (_i32, [_vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp]),
+    "kv_score_workspace_bytes": (_u64, [_vp, _i32]),
+    "kv_score_chunks": (_i32, [_vp, _vp, _i32, _vp, _i32, _vp, _u64, _vp, _vp, _vp]),
+    "kv_compress_chunks": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp]),
+    "kv_swapin_chunks": (_i32, [_vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp]),
+    "kv_swapin_pinned": (_i32, [_vp, _vp, _vp, _vp, _vp, _i32, _vp, _u64, _i32, _vp, _vp, _vp]),
+    "kv_swapout_aot": (_i32, [_vp, _vp, _u64, _u64, _vp, _vp]),
+    "kv_lctru_create": (_vp, []),
+    "kv_lctru_destroy": (None, [_vp]),
+    "kv_lctru_insert": (_i32, [_vp, _i32, _i32, _i32, _u64, _u64]),
+    "kv_lctru_touch_ctx": (_i32, [_vp, _i32, _u64]),
+    "kv_lctru_lock": (_i32, [_vp, _i32]),
+    "kv_lctru_unlock": (_i32, [_vp, _i32]),
+    "kv_lctru_evict": (_i32, [_vp, _u64, _vp, _vp, _i32, _vp]),
+    "kv_lctru_order": (_i32, [_vp, _vp, _vp, _i32, _vp]),
+    "kv_lctru_remove_ctx": (_i32, [_vp, _i32]),
+    "kv_lctru_size": (_i32, [_vp, _vp, _vp]),
+}
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded shared library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: build it first (python -m paper_2403_11805_amd.build); "
+                "there is no fallback path")
+        handle = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGNATURES.items():
+            fn = getattr(handle, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = handle
+    return _lib
+
+
+def kv_last_error() -> str:
+    return lib().kv_last_error().decode()
+
+
+def _check(rc: int) -> None:
+    if rc != KV_OK:
+        raise KvError(rc, kv_last_error())
+
+
+def _np(a, dtype) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=dtype)
+
+
+def _hp(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _dev(t: torch.Tensor, dtype=None) -> int:
+    if not t.is_cuda:
+        raise TypeError("expected a device tensor")
+    if not t.is_contiguous():
+        raise TypeError("expected a contiguous tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"expected dtype {dtype}, got {t.dtype}")
+    return t.data_ptr()
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, torch.cuda.Stream):
+        return stream.cuda_stream
+    return int(stream)
+
+
+# ------------------------------------------------------------------ host, pure
+
+def kv_record_bytes(shape: Shape, bits: int) -> int:
+    s = shape.c()
+    n = int(lib().kv_record_bytes(ctypes.byref(s), bits))
+    if n == 0:
+        raise KvError(KV_EINVAL, kv_last_error())
+    return n
+
+
+def kv_chunk_offsets(shape: Shape, bits) -> np.ndarray:
+    s = shape.c()
+    bits = _np(bits, np.uint8)
+    if bits.shape != (shape.n_chunks,):
+        raise ValueError("bits must have n_chunks entries")
+    off = np.empty(shape.n_chunks + 1, dtype=np.uint64)
+    _check(lib().kv_chunk_offsets(ctypes.byref(s), _hp(bits), _hp(off)))
+    return off
+
+
+def kv_bits_from_scores(density, num8: int, num4: int, den: int) -> np.ndarray:
+    density = _np(density, np.float32)
+    bits = np.empty(len(density), dtype=np.uint8)
+    _check(lib().kv_bits_from_scores(_hp(density), len(density), num8, num4, den, _hp(bits)))
+    return bits
+
+
+def kv_build_gather(shape: Shape, off, bits, chunk_idx):
+    s = shape.c()
+    off, bits, idx = _np(off, np.uint64), _np(bits, np.uint8), _np(chunk_idx, np.int32)
+    if off.shape != (shape.n_chunks + 1,) or bits.shape != (shape.n_chunks,):
+        raise ValueError("off/bits have the wrong length")
+    n = len(idx)
+    src_off = np.empty(n, dtype=np.uint64)
+    dst_tok = np.empty(n, dtype=np.int32)
+    sel_bits = np.empty(n, dtype=np.uint8)
+    _check(lib().kv_build_gather(ctypes.byref(s), _hp(off), _hp(bits), _hp(idx), n,
+                                 _hp(src_off), _hp(dst_tok), _hp(sel_bits)))
+    return src_off, dst_tok, sel_bits
+
+
+# ------------------------------------------------------------------ device, async
+
+def kv_score_workspace_bytes(shape: Shape, n_queries: int) -> int:
+    s = shape.c()
+    n = int(lib().kv_score_workspace_bytes(ctypes.byref(s), n_queries))
+    if n == 0:
+        raise KvError(KV_ESHAPE, kv_last_error())
+    return n
+
+
+def kv_score_chunks(shape: Shape, q: torch.Tensor, kv: torch.Tensor, norm_mode: int,
+                    workspace: torch.Tensor, chunk_mass: torch.Tensor, density: torch.Tensor,
+                    stream=None) -> None:
+    s = shape.c()
+    n_queries = q.shape[2]
+    if tuple(q.shape) != (shape.n_layers, shape.n_q_heads, n_queries, shape.head_dim):
+        raise ValueError("q must be [L][Hq][R][D]")
+    if tuple(kv.shape) != shape.kv_dims:
+        raise ValueError("kv must be [L][2][Hkv][N][D]")
+    if chunk_mass.numel() != shape.n_layers * shape.n_q_heads * shape.n_chunks or \
+            density.numel() != shape.n_chunks:
+        raise ValueError("chunk_mass/density have the wrong size")
+    _check(lib().kv_score_chunks(ctypes.byref(s), _dev(q, torch.float16), n_queries,
+                                 _dev(kv, torch.float16), norm_mode, _dev(workspace),
+                                 workspace.numel() * workspace.element_size(),
+                                 _dev(chunk_mass, torch.float32), _dev(density, torch.float32),
+                                 _stream(stream)))
+
+
+def kv_compress_chunks(shape: Shape, kv: torch.Tensor, bits_dev: torch.Tensor,
+                       off_dev: torch.Tensor, packed_out: torch.Tensor, stream=None) -> None:
+    s = shape.c()
+    if tuple(kv.shape) != shape.kv_dims:
+        raise ValueError("kv must be [L][2][Hkv][N][D]")
+    if bits_dev.numel() != shape.n_chunks or off_dev.numel() != shape.n_chunks + 1:
+        raise ValueError("bits_dev/off_dev have the wrong length")
+    _check(lib().kv_compress_chunks(ctypes.byref(s), _dev(kv, torch.float16),
+                                    _dev(bits_dev, torch.uint8), _dev(off_dev, torch.int64),
+                                    _dev(packed_out, torch.uint8), _stream(stream)))
+
+
+def kv_swapin_chunks(shape: Shape, packed: torch.Tensor, src_off_dev: torch.Tensor,
+                     dst_tok_dev: torch.Tensor, sel_bits_dev: torch.Tensor, kv_out: torch.Tensor,
+                     stream=None) -> None:
+    s = shape.c()
+    n_sel = src_off_dev.numel()
+    if dst_tok_dev.numel() != n_sel or sel_bits_dev.numel() != n_sel:
+        raise ValueError("gather lists differ in length")
+    if tuple(kv_out.shape) != shape.kv_dims:
+        raise ValueError("kv_out must be [L][2][Hkv][N][D]")
+    if n_sel == 0:
+        return
+    _check(lib().kv_swapin_chunks(ctypes.byref(s), _dev(packed, torch.uint8),
+                                  _dev(src_off_dev, torch.int64), _dev(dst_tok_dev, torch.int32),
+                                  _dev(sel_bits_dev, torch.uint8), n_sel,
+                                  _dev(kv_out, torch.float16), _stream(stream)))
+
+
+def kv_swapin_pinned(shape: Shape, packed_pinned: torch.Tensor, src_off, dst_tok, sel_bits,
+                     staging_dev: torch.Tensor, n_buffers: int, kv_out: torch.Tensor,
+                     copy_stream, compute_stream) -> None:
+    s = shape.c()
+    if packed_pinned.is_cuda or not packed_pinned.is_pinned():
+        raise TypeError("packed_pinned must be a pinned host tensor")
+    src_off, dst_tok, sel_bits = _np(src_off, np.uint64), _np(dst_tok, np.int32), _np(sel_bits, np.uint8)
+    n_sel = len(src_off)
+    if len(dst_tok) != n_sel or len(sel_bits) != n_sel:
+        raise ValueError("gather lists differ in length")
+    if tuple(kv_out.shape) != shape.kv_dims:
+        raise ValueError("kv_out must be [L][2][Hkv][N][D]")
+    _check(lib().kv_swapin_pinned(ctypes.byref(s), packed_pinned.data_ptr(), _hp(src_off),
+                                  _hp(dst_tok), _hp(sel_bits), n_sel, _dev(staging_dev),
+                                  staging_dev.numel() * staging_dev.element_size(), n_buffers,
+                                  _dev(kv_out, torch.float16), _stream(copy_stream),
+                                  _stream(compute_stream)))
+
+
+def kv_swapout_aot(packed_dev: torch.Tensor, packed_pinned: torch.Tensor, begin: int, end: int,
+                   producer_stream, copy_stream) -> None:
+    if packed_pinned.is_cuda or not packed_pinned.is_pinned():
+        raise TypeError("packed_pinned must be a pinned host tensor")
+    nbytes = packed_dev.numel() * packed_dev.element_size()
+    if end > nbytes or end > packed_pinned.numel() * packed_pinned.element_size():
+        raise ValueError("range exceeds a buffer")
+    _check(lib().kv_swapout_aot(_dev(packed_dev), packed_pinned.data_ptr(), begin, end,
+                                _stream(producer_stream), _stream(copy_stream)))
+
+
+# ------------------------------------------------------------------ host lifecycle
+
+class Lctru:
+    """Thin owner of a kv_lctru_t handle; methods are the kv_lctru_* calls."""
+
+    def __init__(self):
+        self._h = lib().kv_lctru_create()
+        if not self._h:
+            raise MemoryError("kv_lctru_create failed")
+
+    def close(self):
+        if self._h:
+            lib().kv_lctru_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def insert(self, ctx, chunk, bits, nbytes, now):
+        _check(lib().kv_lctru_insert(self._h, ctx, chunk, bits, nbytes, now))
+
+    def touch_ctx(self, ctx, now):
+        _check(lib().kv_lctru_touch_ctx(self._h, ctx, now))
+
+    def lock(self, ctx):
+        _check(lib().kv_lctru_lock(self._h, ctx))
+
+    def unlock(self, ctx):
+        _check(lib().kv_lctru_unlock(self._h, ctx))
+
+    def remove_ctx(self, ctx):
+        _check(lib().kv_lctru_remove_ctx(self._h, ctx))
+
+    def size(self):
+        n = ctypes.c_int32()
+        b = ctypes.c_uint64()
+        _check(lib().kv_lctru_size(self._h, ctypes.byref(n), ctypes.byref(b)))
+        return n.value, b.value
+
+    def _lists(self, fn, *head):
+        cap = self.size()[0]
+        ctx = np.empty(max(cap, 1), dtype=np.int32)
+        chunk = np.empty(max(cap, 1), dtype=np.int32)
+        n = ctypes.c_int32()
+        rc = fn(self._h, *head, _hp(ctx), _hp(chunk), cap, ctypes.byref(n))
+        return rc, [(int(ctx[i]), int(chunk[i])) for i in range(n.value)]
+
+    def order(self):
+        rc, out = self._lists(lib().kv_lctru_order)
+        _check(rc)
+        return out
+
+    def evict(self, bytes_needed):
+        """Popped (ctx, chunk) pairs, or None if the unlocked chunks cannot free that much."""
+        rc, out = self._lists(lib().kv_lctru_evict, bytes_needed)
+        if rc == KV_ENOMEM:
+            return None
+        _check(rc)
+        return out

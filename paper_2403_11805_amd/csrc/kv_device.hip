@@ -1,0 +1,317 @@
+// Device entry points of libkvswitch: argument checks on the host, then kernel
+// launches on the caller's stream.  Nothing here synchronises or allocates
+// device memory.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <vector>
+
+#include "kv_internal.h"
+#include "kv_quant_kernels.hpp"
+#include "kv_score_kernels.hpp"
+
+using namespace kvs;
+
+namespace {
+
+int hip_fail(hipError_t e, const char* what) {
+    return fail(KV_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+#define KV_HIP(call)                                         \
+    do {                                                     \
+        hipError_t e_ = (call);                              \
+        if (e_ != hipSuccess) return hip_fail(e_, #call);    \
+    } while (0)
+
+int ilog2(int v) {
+    int l = 0;
+    while ((1 << l) < v) ++l;
+    return l;
+}
+
+QuantGeom quant_geom(const kv_shape_t& s) {
+    QuantGeom g;
+    g.n_tokens = s.n_tokens;
+    g.chunk_tokens = s.chunk_tokens;
+    g.slabs = static_cast<int32_t>(slabs_of(s));
+    g.pieces = s.chunk_tokens * s.head_dim / 8;
+    g.row_pieces = s.head_dim / 8;
+    g.lpg_log2 = ilog2(s.group / 8);
+    return g;
+}
+
+int launch_status(const char* what) {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e, what);
+    return KV_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t kv_compress_chunks(const kv_shape_t* shape, const void* kv, const uint8_t* bits_dev,
+                           const uint64_t* off_dev, void* packed_out, void* stream) {
+    if (int rc = check_shape(shape)) return rc;
+    if (!kv || !bits_dev || !off_dev || !packed_out) return fail(KV_EINVAL, "NULL device pointer");
+    if (!aligned(kv, 16) || !aligned(packed_out, 16) || !aligned(off_dev, 8))
+        return fail(KV_EINVAL, "kv/packed_out must be 16-byte aligned, off_dev 8-byte aligned");
+    const QuantGeom g = quant_geom(*shape);
+    const int32_t n_chunks = shape->n_tokens / shape->chunk_tokens;
+    const int64_t units = static_cast<int64_t>(n_chunks) * g.slabs;
+    const int64_t blocks = (units + 3) / 4;
+    if (blocks > 0x7fffffff) return fail(KV_ESHAPE, "too many work units");
+    hipLaunchKernelGGL(compress_kernel, dim3(static_cast<uint32_t>(blocks)), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), static_cast<const uint4*>(kv), bits_dev,
+                       off_dev, static_cast<uint8_t*>(packed_out), g, n_chunks);
+    return launch_status("compress_kernel launch");
+}
+
+int32_t kv_swapin_chunks(const kv_shape_t* shape, const void* packed, const uint64_t* src_off_dev,
+                         const int32_t* dst_tok_dev, const uint8_t* sel_bits_dev, int32_t n_sel,
+                         void* kv_out, void* stream) {
+    if (int rc = check_shape(shape)) return rc;
+    const int32_t n_chunks = shape->n_tokens / shape->chunk_tokens;
+    if (n_sel < 0 || n_sel > n_chunks) return fail(KV_EINVAL, "n_sel %d outside [0,%d]", n_sel, n_chunks);
+    if (n_sel == 0) return KV_OK;
+    if (!packed || !src_off_dev || !dst_tok_dev || !sel_bits_dev || !kv_out)
+        return fail(KV_EINVAL, "NULL device pointer");
+    if (!aligned(kv_out, 16) || !aligned(packed, 16) || !aligned(src_off_dev, 8) ||
+        !aligned(dst_tok_dev, 4))
+        return fail(KV_EINVAL, "kv_out/packed must be 16-byte aligned, lists naturally aligned");
+    const QuantGeom g = quant_geom(*shape);
+    const int64_t units = static_cast<int64_t>(n_sel) * g.slabs;
+    const int64_t blocks = (units + 3) / 4;
+    hipLaunchKernelGGL(swapin_kernel, dim3(static_cast<uint32_t>(blocks)), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), static_cast<const uint8_t*>(packed),
+                       src_off_dev, dst_tok_dev, sel_bits_dev, static_cast<uint4*>(kv_out), g, n_sel);
+    return launch_status("swapin_kernel launch");
+}
+
+// --------------------------------------------------------------------- scoring
+
+static int score_geom(const kv_shape_t* shape, int32_t n_queries, int32_t norm_mode, ScoreGeom* out,
+                      int* nrbw) {
+    if (int rc = check_shape(shape)) return rc;
+    const kv_shape_t& s = *shape;
+    if (n_queries < 1 || n_queries > s.n_tokens || n_queries > 256)
+        return fail(KV_EINVAL, "n_queries %d outside [1, min(n_tokens, 256)]", n_queries);
+    if (norm_mode != KV_NORM_VISIBLE && norm_mode != KV_NORM_NONE)
+        return fail(KV_EINVAL, "norm_mode %d unknown", norm_mode);
+    if (s.head_dim != 64 && s.head_dim != 128 && s.head_dim != 256)
+        return fail(KV_ESHAPE, "scoring needs head_dim in {64,128,256}, got %d", s.head_dim);
+    if (s.chunk_tokens < 8 || (s.chunk_tokens & (s.chunk_tokens - 1)))
+        return fail(KV_ESHAPE, "scoring needs chunk_tokens a power of two >= 8, got %d", s.chunk_tokens);
+    if (s.n_tokens % 32) return fail(KV_ESHAPE, "scoring needs n_tokens %% 32 == 0, got %d", s.n_tokens);
+    ScoreGeom g;
+    g.L = s.n_layers; g.Hkv = s.n_kv_heads; g.Hq = s.n_q_heads; g.N = s.n_tokens; g.R = n_queries;
+    g.T = s.chunk_tokens;
+    g.sb_tokens = std::min(s.chunk_tokens, 32);
+    g.n_tiles = s.n_tokens / 32;
+    g.RB = (n_queries + 31) / 32;
+    g.rows_p = g.RB * 32;
+    g.n_rb = (s.n_q_heads / s.n_kv_heads) * g.RB;
+    *nrbw = g.n_rb == 1 ? 1 : 2;
+    g.n_rg = (g.n_rb + *nrbw - 1) / *nrbw;
+    g.rg_per_wg = std::min(g.n_rg, 4);
+    g.tile_par = 4 / g.rg_per_wg;
+    g.tiles_per_wg = 4 * g.tile_par;
+    g.norm_mode = norm_mode;
+    g.scale_log2e = static_cast<float>(1.4426950408889634 / std::sqrt(static_cast<double>(s.head_dim)));
+    *out = g;
+    return KV_OK;
+}
+
+static uint64_t ws_floats_tile(const ScoreGeom& g) {
+    return static_cast<uint64_t>(g.L) * g.Hq * g.n_tiles * g.rows_p;
+}
+static uint64_t ws_floats_sub(const ScoreGeom& g) {
+    return static_cast<uint64_t>(g.L) * g.Hq * (g.N / g.sb_tokens) * g.rows_p;
+}
+
+uint64_t kv_score_workspace_bytes(const kv_shape_t* shape, int32_t n_queries) {
+    ScoreGeom g;
+    int nrbw;
+    if (score_geom(shape, n_queries, KV_NORM_VISIBLE, &g, &nrbw) != KV_OK) return 0;
+    const uint64_t bytes = (2 * ws_floats_tile(g) + ws_floats_sub(g)) * sizeof(float);
+    return (bytes + 255) & ~static_cast<uint64_t>(255);
+}
+
+int32_t kv_score_chunks(const kv_shape_t* shape, const void* q, int32_t n_queries, const void* kv,
+                        int32_t norm_mode, void* workspace, uint64_t workspace_bytes,
+                        float* chunk_mass, float* density, void* stream) {
+    ScoreGeom g;
+    int nrbw;
+    if (int rc = score_geom(shape, n_queries, norm_mode, &g, &nrbw)) return rc;
+    if (!q || !kv || !workspace || !chunk_mass || !density) return fail(KV_EINVAL, "NULL device pointer");
+    if (!aligned(q, 16) || !aligned(kv, 16) || !aligned(workspace, 256))
+        return fail(KV_EINVAL, "q/kv must be 16-byte aligned, workspace 256-byte aligned");
+    const uint64_t need = kv_score_workspace_bytes(shape, n_queries);
+    if (workspace_bytes < need)
+        return fail(KV_ENOMEM, "workspace %llu bytes, %llu needed",
+                    static_cast<unsigned long long>(workspace_bytes), static_cast<unsigned long long>(need));
+    ScoreWs ws;
+    ws.m_tile = static_cast<float*>(workspace);
+    ws.l_tile = ws.m_tile + ws_floats_tile(g);
+    ws.e_sub = ws.l_tile + ws_floats_tile(g);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const dim3 grid((g.n_tiles + g.tiles_per_wg - 1) / g.tiles_per_wg,
+                    (g.n_rg + g.rg_per_wg - 1) / g.rg_per_wg, g.L * g.Hkv);
+    const _Float16* qp = static_cast<const _Float16*>(q);
+    const _Float16* kp = static_cast<const _Float16*>(kv);
+#define KV_SCORE_LAUNCH(DD, NR) \
+    hipLaunchKernelGGL((score_tiles_kernel<DD, NR>), grid, dim3(256), 0, st, qp, kp, g, ws)
+    const int D = shape->head_dim;
+    if (D == 64 && nrbw == 1) KV_SCORE_LAUNCH(64, 1);
+    else if (D == 64) KV_SCORE_LAUNCH(64, 2);
+    else if (D == 128 && nrbw == 1) KV_SCORE_LAUNCH(128, 1);
+    else if (D == 128) KV_SCORE_LAUNCH(128, 2);
+    else if (nrbw == 1) KV_SCORE_LAUNCH(256, 1);
+    else KV_SCORE_LAUNCH(256, 2);
+#undef KV_SCORE_LAUNCH
+    if (int rc = launch_status("score_tiles_kernel launch")) return rc;
+    hipLaunchKernelGGL(score_combine_kernel, dim3(g.L * g.Hq), dim3(256), 0, st, g, ws, chunk_mass);
+    if (int rc = launch_status("score_combine_kernel launch")) return rc;
+    const int n_chunks = g.N / g.T;
+    const float inv_norm = static_cast<float>(1.0 / (static_cast<double>(g.T) * g.L * g.Hq));
+    hipLaunchKernelGGL(score_density_kernel, dim3((n_chunks + 255) / 256), dim3(256), 0, st,
+                       chunk_mass, density, g.L * g.Hq, n_chunks, inv_norm);
+    return launch_status("score_density_kernel launch");
+}
+
+// --------------------------------------------------------------------- streaming Load / AoT swap-out
+
+int32_t kv_swapin_pinned(const kv_shape_t* shape, const void* packed_pinned, const uint64_t* src_off,
+                         const int32_t* dst_tok, const uint8_t* sel_bits, int32_t n_sel,
+                         void* staging_dev, uint64_t staging_bytes, int32_t n_buffers, void* kv_out,
+                         void* copy_stream, void* compute_stream) {
+    if (int rc = check_shape(shape)) return rc;
+    const int32_t n_chunks = shape->n_tokens / shape->chunk_tokens;
+    if (n_sel < 0 || n_sel > n_chunks) return fail(KV_EINVAL, "n_sel %d outside [0,%d]", n_sel, n_chunks);
+    if (n_sel == 0) return KV_OK;
+    if (!packed_pinned || !src_off || !dst_tok || !sel_bits || !staging_dev || !kv_out)
+        return fail(KV_EINVAL, "NULL pointer");
+    if (n_buffers < 2 || n_buffers > 8) return fail(KV_EINVAL, "n_buffers %d outside [2,8]", n_buffers);
+    if (!copy_stream || !compute_stream || copy_stream == compute_stream)
+        return fail(KV_EINVAL, "copy_stream and compute_stream must be two distinct non-NULL streams");
+    if (!aligned(staging_dev, 256) || !aligned(kv_out, 16) || !aligned(packed_pinned, 16))
+        return fail(KV_EINVAL, "staging_dev must be 256-byte aligned, kv_out/packed_pinned 16-byte");
+    const uint64_t slot = (staging_bytes / static_cast<uint64_t>(n_buffers)) & ~static_cast<uint64_t>(255);
+    uint64_t largest = 0;
+    for (int32_t j = 0; j < n_sel; ++j) {
+        if (!valid_bits(sel_bits[j])) return fail(KV_EBITS, "sel_bits[%d] = %d", j, sel_bits[j]);
+        if (dst_tok[j] < 0 || dst_tok[j] % shape->chunk_tokens ||
+            dst_tok[j] + shape->chunk_tokens > shape->n_tokens)
+            return fail(KV_EINDEX, "dst_tok[%d] = %d is not a chunk start inside the cache", j, dst_tok[j]);
+        if (j && src_off[j] < src_off[j - 1] + record_bytes(*shape, sel_bits[j - 1]))
+            return fail(KV_EINDEX, "src_off not ascending / records overlap at position %d", j);
+        if (src_off[j] % 16) return fail(KV_EINVAL, "src_off[%d] not 16-byte aligned", j);
+        largest = std::max(largest, record_bytes(*shape, sel_bits[j]));
+    }
+    if (slot < largest)
+        return fail(KV_ENOMEM, "staging slot %llu bytes, largest record %llu",
+                    static_cast<unsigned long long>(slot), static_cast<unsigned long long>(largest));
+
+    const QuantGeom g = quant_geom(*shape);
+    hipStream_t cs = static_cast<hipStream_t>(copy_stream);
+    hipStream_t ks = static_cast<hipStream_t>(compute_stream);
+    hipEvent_t copied[8], consumed[8];
+    int n_ev = 0;
+    auto destroy_events = [&]() {
+        for (int i = 0; i < n_ev; ++i) {
+            (void)hipEventDestroy(copied[i]);
+            (void)hipEventDestroy(consumed[i]);
+        }
+    };
+    for (; n_ev < n_buffers; ++n_ev) {
+        hipError_t e = hipEventCreateWithFlags(&copied[n_ev], hipEventDisableTiming);
+        if (e == hipSuccess) {
+            e = hipEventCreateWithFlags(&consumed[n_ev], hipEventDisableTiming);
+            if (e != hipSuccess) (void)hipEventDestroy(copied[n_ev]);
+        }
+        if (e != hipSuccess) {
+            destroy_events();
+            return hip_fail(e, "hipEventCreateWithFlags");
+        }
+    }
+
+    const uint8_t* host = static_cast<const uint8_t*>(packed_pinned);
+    uint8_t* staging = static_cast<uint8_t*>(staging_dev);
+    int rc = KV_OK;
+    int32_t j = 0;
+    for (int batch = 0; j < n_sel && rc == KV_OK; ++batch) {
+        const int b = batch % n_buffers;
+        uint8_t* slot_dev = staging + static_cast<uint64_t>(b) * slot;
+        // records of one batch: as many consecutive list entries as fit the slot
+        SwapinBatch list;
+        list.n = 0;
+        uint64_t used = 0;
+        if (batch >= n_buffers) {   // slot is free once the kernel that read it has finished
+            hipError_t e = hipStreamWaitEvent(cs, consumed[b], 0);
+            if (e != hipSuccess) { rc = hip_fail(e, "hipStreamWaitEvent"); break; }
+        }
+        while (j < n_sel && list.n < kBatchMax) {
+            const uint64_t bytes = record_bytes(*shape, sel_bits[j]);
+            if (used + bytes > slot) break;
+            // extend the copy over records that are adjacent in the host pool
+            int32_t j2 = j;
+            uint64_t run = 0;
+            while (j2 < n_sel && list.n + (j2 - j) < kBatchMax) {
+                const uint64_t bj = record_bytes(*shape, sel_bits[j2]);
+                if (src_off[j2] != src_off[j] + run || used + run + bj > slot) break;
+                run += bj;
+                ++j2;
+            }
+            hipError_t e = hipMemcpyAsync(slot_dev + used, host + src_off[j], run,
+                                          hipMemcpyHostToDevice, cs);
+            if (e != hipSuccess) { rc = hip_fail(e, "hipMemcpyAsync H2D"); break; }
+            uint64_t o = used;
+            for (int32_t k = j; k < j2; ++k) {
+                list.src_off[list.n] = o;
+                list.dst_tok[list.n] = dst_tok[k];
+                list.bits[list.n] = sel_bits[k];
+                ++list.n;
+                o += record_bytes(*shape, sel_bits[k]);
+            }
+            used += run;
+            j = j2;
+        }
+        if (rc != KV_OK) break;
+        hipError_t e = hipEventRecord(copied[b], cs);
+        if (e == hipSuccess) e = hipStreamWaitEvent(ks, copied[b], 0);
+        if (e != hipSuccess) { rc = hip_fail(e, "event record/wait"); break; }
+        const int64_t units = static_cast<int64_t>(list.n) * g.slabs;
+        hipLaunchKernelGGL(swapin_batch_kernel, dim3(static_cast<uint32_t>((units + 3) / 4)), dim3(256),
+                           0, ks, slot_dev, list, static_cast<uint4*>(kv_out), g);
+        rc = launch_status("swapin_batch_kernel launch");
+        if (rc != KV_OK) break;
+        e = hipEventRecord(consumed[b], ks);
+        if (e != hipSuccess) { rc = hip_fail(e, "hipEventRecord"); break; }
+    }
+    destroy_events();
+    return rc;
+}
+
+int32_t kv_swapout_aot(const void* packed_dev, void* packed_pinned, uint64_t begin, uint64_t end,
+                       void* producer_stream, void* copy_stream) {
+    if (!packed_dev || !packed_pinned) return fail(KV_EINVAL, "NULL pointer");
+    if (end < begin) return fail(KV_EINVAL, "end < begin");
+    if (!copy_stream || copy_stream == producer_stream)
+        return fail(KV_EINVAL, "copy_stream must be non-NULL and differ from producer_stream");
+    if (end == begin) return KV_OK;
+    hipEvent_t produced;
+    KV_HIP(hipEventCreateWithFlags(&produced, hipEventDisableTiming));
+    hipError_t e = hipEventRecord(produced, static_cast<hipStream_t>(producer_stream));
+    if (e == hipSuccess) e = hipStreamWaitEvent(static_cast<hipStream_t>(copy_stream), produced, 0);
+    if (e == hipSuccess)
+        e = hipMemcpyAsync(static_cast<uint8_t*>(packed_pinned) + begin,
+                           static_cast<const uint8_t*>(packed_dev) + begin, end - begin,
+                           hipMemcpyDeviceToHost, static_cast<hipStream_t>(copy_stream));
+    (void)hipEventDestroy(produced);
+    if (e != hipSuccess) return hip_fail(e, "AoT swap-out enqueue");
+    return KV_OK;
+}
+
+}  // extern "C"

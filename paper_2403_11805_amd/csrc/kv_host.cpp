@@ -1,0 +1,126 @@
+// Host-side, GPU-free part of libkvswitch: error text, shape validation,
+// record sizes and offsets, rank-based bit-width assignment (Sec. 3.2, Eq. 2)
+// and the gather list of the Load primitive (Sec. 3.1).
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <numeric>
+#include <vector>
+
+#include "kv_internal.h"
+
+namespace kvs {
+
+static thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+void clear_error() { g_err[0] = '\0'; }
+
+int check_shape(const kv_shape_t* s) {
+    if (!s) return fail(KV_EINVAL, "shape is NULL");
+    if (s->n_layers <= 0 || s->n_kv_heads <= 0 || s->n_q_heads <= 0 || s->head_dim <= 0 ||
+        s->n_tokens <= 0 || s->chunk_tokens <= 0 || s->group <= 0)
+        return fail(KV_ESHAPE, "every shape field must be positive");
+    if (s->n_tokens % s->chunk_tokens)
+        return fail(KV_ESHAPE, "n_tokens %d is not a multiple of chunk_tokens %d", s->n_tokens,
+                    s->chunk_tokens);
+    if (s->group != 64 && s->group != 128 && s->group != 256 && s->group != 512)
+        return fail(KV_ESHAPE, "group %d not in {64,128,256,512}", s->group);
+    if (s->head_dim % s->group)
+        return fail(KV_ESHAPE, "head_dim %d is not a multiple of group %d", s->head_dim, s->group);
+    if (s->n_q_heads % s->n_kv_heads)
+        return fail(KV_ESHAPE, "n_q_heads %d is not a multiple of n_kv_heads %d", s->n_q_heads,
+                    s->n_kv_heads);
+    if (s->head_dim > 1024 || s->chunk_tokens > 1024)
+        return fail(KV_ESHAPE, "head_dim and chunk_tokens must be <= 1024");
+    if ((static_cast<int64_t>(s->chunk_tokens) * s->head_dim) % 512)
+        return fail(KV_ESHAPE, "chunk_tokens*head_dim must be a multiple of 512");
+    if ((s->chunk_tokens * s->head_dim / s->group) % 4)
+        return fail(KV_ESHAPE, "chunk_tokens*head_dim/group must be a multiple of 4");
+    const uint64_t slab_rows = slabs_of(*s) * static_cast<uint64_t>(s->n_tokens);
+    if (slab_rows > (1ull << 31))
+        return fail(KV_ESHAPE, "layers*2*kv_heads*tokens exceeds 2^31");
+    return KV_OK;
+}
+
+}  // namespace kvs
+
+using namespace kvs;
+
+extern "C" {
+
+const char* kv_last_error(void) { return g_err; }
+
+uint64_t kv_record_bytes(const kv_shape_t* shape, int32_t bits) {
+    if (check_shape(shape) != KV_OK) return 0;
+    if (!valid_bits(bits)) {
+        fail(KV_EBITS, "bits %d not in {16,8,4,2}", bits);
+        return 0;
+    }
+    return record_bytes(*shape, bits);
+}
+
+int32_t kv_chunk_offsets(const kv_shape_t* shape, const uint8_t* bits, uint64_t* off) {
+    if (int rc = check_shape(shape)) return rc;
+    if (!bits || !off) return fail(KV_EINVAL, "bits/off is NULL");
+    const int32_t n = shape->n_tokens / shape->chunk_tokens;
+    for (int32_t i = 0; i < n; ++i)
+        if (!valid_bits(bits[i])) return fail(KV_EBITS, "bits[%d] = %d not in {16,8,4,2}", i, bits[i]);
+    uint64_t acc = 0;
+    for (int32_t i = 0; i < n; ++i) {
+        off[i] = acc;
+        acc += record_bytes(*shape, bits[i]);
+    }
+    off[n] = acc;
+    return KV_OK;
+}
+
+int32_t kv_bits_from_scores(const float* density, int32_t n, int32_t num8, int32_t num4,
+                            int32_t den, uint8_t* bits) {
+    if (!density || !bits) return fail(KV_EINVAL, "density/bits is NULL");
+    if (n < 0 || den <= 0 || num8 < 0 || num4 < 0 || num8 + num4 > den)
+        return fail(KV_EINVAL, "need n >= 0, den > 0, 0 <= num8, 0 <= num4, num8+num4 <= den");
+    std::vector<int32_t> order(static_cast<size_t>(n));
+    std::iota(order.begin(), order.end(), 0);
+    // densest first; equal densities keep index order
+    std::stable_sort(order.begin(), order.end(),
+                     [&](int32_t a, int32_t b) { return density[a] > density[b]; });
+    const int64_t k8 = static_cast<int64_t>(n) * num8 / den;
+    const int64_t k84 = static_cast<int64_t>(n) * (num8 + num4) / den;
+    for (int64_t r = 0; r < n; ++r) bits[order[static_cast<size_t>(r)]] = r < k8 ? 8 : (r < k84 ? 4 : 2);
+    return KV_OK;
+}
+
+int32_t kv_build_gather(const kv_shape_t* shape, const uint64_t* off, const uint8_t* bits,
+                        const int32_t* chunk_idx, int32_t n_sel, uint64_t* src_off,
+                        int32_t* dst_tok, uint8_t* sel_bits) {
+    if (int rc = check_shape(shape)) return rc;
+    if (n_sel < 0) return fail(KV_EINVAL, "n_sel %d < 0", n_sel);
+    if (n_sel == 0) return KV_OK;
+    if (!off || !bits || !chunk_idx || !src_off || !dst_tok || !sel_bits)
+        return fail(KV_EINVAL, "NULL list pointer");
+    const int32_t n = shape->n_tokens / shape->chunk_tokens;
+    for (int32_t j = 0; j < n_sel; ++j) {
+        const int32_t i = chunk_idx[j];
+        if (i < 0 || i >= n) return fail(KV_EINDEX, "chunk_idx[%d] = %d outside [0,%d)", j, i, n);
+        if (j && i <= chunk_idx[j - 1])
+            return fail(KV_EINDEX, "chunk_idx not strictly ascending at position %d", j);
+        if (!valid_bits(bits[i])) return fail(KV_EBITS, "bits[%d] = %d not in {16,8,4,2}", i, bits[i]);
+    }
+    for (int32_t j = 0; j < n_sel; ++j) {
+        const int32_t i = chunk_idx[j];
+        src_off[j] = off[i];
+        dst_tok[j] = i * shape->chunk_tokens;
+        sel_bits[j] = bits[i];
+    }
+    return KV_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,35 @@
+// Internal helpers shared by the translation units of libkvswitch.
+#pragma once
+
+#include <cstdint>
+
+#include "kvswitch.h"
+
+namespace kvs {
+
+// Records code + formatted text as the calling thread's last error; returns code.
+int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+void clear_error();
+
+// KV_OK, or KV_EINVAL / KV_ESHAPE with the error text set.
+int check_shape(const kv_shape_t* s);
+
+inline bool valid_bits(int b) { return b == 16 || b == 8 || b == 4 || b == 2; }
+
+inline uint64_t slabs_of(const kv_shape_t& s) {
+    return static_cast<uint64_t>(s.n_layers) * 2u * static_cast<uint64_t>(s.n_kv_heads);
+}
+
+// Bytes of one chunk's record; shape and bits already validated.
+inline uint64_t record_bytes(const kv_shape_t& s, int bits) {
+    const uint64_t rows = slabs_of(s) * static_cast<uint64_t>(s.chunk_tokens);
+    if (bits == 16) return rows * static_cast<uint64_t>(s.head_dim) * 2u;
+    return rows * (static_cast<uint64_t>(s.head_dim) * bits / 8u +
+                   8u * static_cast<uint64_t>(s.head_dim / s.group));
+}
+
+inline bool aligned(const void* p, uintptr_t a) {
+    return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0;
+}
+
+}  // namespace kvs

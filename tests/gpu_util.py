@@ -1,0 +1,64 @@
+"""Helpers shared by the GPU parity tests: run the library through its C ABI
+binding on device tensors and bring results back for comparison with the oracle."""
+import numpy as np
+import torch
+
+import oracle
+import paper_2403_11805_amd as kvs
+from paper_2403_11805_amd import synth
+
+DEV = "cuda:0"
+
+
+def both_shapes(geom):
+    g = synth.Geometry(*geom)
+    return kvs.Shape(g.L, g.Hkv, g.Hq, g.D, g.N, g.T, g.G), oracle.Shape(*g)
+
+
+def dev_lists(off, bits):
+    return (torch.from_numpy(np.asarray(bits, dtype=np.uint8)).to(DEV),
+            torch.from_numpy(np.asarray(off, dtype=np.uint64).view(np.int64)).to(DEV))
+
+
+def gpu_compress(ks, kv_dev, bits):
+    """-> (packed device uint8 tensor, off numpy uint64)."""
+    off = kvs.kv_chunk_offsets(ks, bits)
+    bits_dev, off_dev = dev_lists(off, bits)
+    packed = torch.empty(int(off[-1]) + 64, dtype=torch.uint8, device=DEV)
+    packed.fill_(0xA5)
+    kvs.kv_compress_chunks(ks, kv_dev, bits_dev, off_dev, packed)
+    torch.cuda.synchronize()
+    assert bool((packed[int(off[-1]):] == 0xA5).all()), "compress wrote past the pool"
+    return packed, off
+
+
+def gpu_swapin(ks, packed_dev, off, bits, chunk_idx, kv_out):
+    src, dst, sb = kvs.kv_build_gather(ks, off, bits, chunk_idx)
+    kvs.kv_swapin_chunks(ks, packed_dev,
+                         torch.from_numpy(src.view(np.int64)).to(DEV),
+                         torch.from_numpy(dst).to(DEV), torch.from_numpy(sb).to(DEV), kv_out)
+    torch.cuda.synchronize()
+    return kv_out
+
+
+def gpu_score(ks, q_dev, kv_dev, norm_mode):
+    R = q_dev.shape[2]
+    ws = torch.empty(kvs.kv_score_workspace_bytes(ks, R), dtype=torch.uint8, device=DEV)
+    cm = torch.full((ks.n_layers, ks.n_q_heads, ks.n_chunks), float("nan"), dtype=torch.float32, device=DEV)
+    dens = torch.full((ks.n_chunks,), float("nan"), dtype=torch.float32, device=DEV)
+    kvs.kv_score_chunks(ks, q_dev, kv_dev, norm_mode, ws, cm, dens)
+    torch.cuda.synchronize()
+    return cm.cpu().numpy(), dens.cpu().numpy()
+
+
+def half_ulp_distance(a_u16, b_u16):
+    """Distance in fp16 units-in-the-last-place between two arrays of finite fp16 bit patterns."""
+    def key(u):
+        u = u.astype(np.int32)
+        return np.where(u & 0x8000, -(u & 0x7fff), u & 0x7fff)
+    return np.abs(key(a_u16) - key(b_u16))
+
+
+def chunk_view(kv_dev, T, i):
+    """Tokens of chunk i of every slab as a contiguous host array [L][2][Hkv][T][D]."""
+    return kv_dev[:, :, :, i * T:(i + 1) * T, :].contiguous().cpu().numpy()

@@ -1,0 +1,131 @@
+"""GPU parity: kv_score_chunks (Eq. 1) against the fp64 CPU oracle.
+
+Bar: chunk masses and densities within 1e-4 relative of the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2403_11805_amd as kvs
+from paper_2403_11805_amd import synth
+
+from gpu_util import DEV, both_shapes, gpu_score
+
+pytestmark = pytest.mark.gpu
+RTOL = 1e-4
+
+
+def assert_close(got, want, what):
+    got = np.asarray(got, dtype=np.float64)
+    want = np.asarray(want, dtype=np.float64)
+    assert np.all(np.isfinite(got)), f"{what}: non-finite values"
+    rel = np.abs(got - want) / np.maximum(np.abs(want), 1e-30)
+    assert rel.max() <= RTOL, f"{what}: max relative error {rel.max():.3e} at {np.argmax(rel)}"
+
+
+@pytest.mark.parametrize("geom,R", [
+    ((2, 2, 2, 64, 128, 16, 64), 32),     # MHA, one row block
+    ((1, 2, 4, 128, 256, 16, 64), 7),     # GQA x2, fewer rows than a block
+    ((2, 1, 4, 128, 192, 32, 128), 64),   # four heads share a kv head, two row blocks each
+    ((1, 1, 8, 64, 96, 8, 64), 33),       # eight heads per kv head, padded second block
+    ((1, 2, 2, 256, 160, 16, 64), 100),   # head_dim 256, R not a multiple of 32
+    ((1, 1, 3, 128, 512, 64, 64), 1),     # one query row, chunk larger than a tile
+    ((1, 1, 2, 128, 256, 128, 64), 256),  # the largest R, every token a query
+    ((1, 3, 3, 64, 32, 32, 64), 32),      # a single tile
+])
+@pytest.mark.parametrize("norm", [oracle.NORM_VISIBLE, oracle.NORM_NONE])
+def test_small_shapes_full(geom, R, norm):
+    g = synth.Geometry(*geom)
+    ks, os_ = both_shapes(g)
+    kv = synth.make_kv(g, 21, "cpu", 1, 4.0)
+    q = (synth.make_q(g, 21, R).float() * 6).to(torch.float16)   # logits with a real spread
+    cm_want, d_want = oracle.score_chunks(os_, q.numpy(), kv.numpy(), norm)
+    cm, d = gpu_score(ks, q.to(DEV), kv.to(DEV), norm)
+    assert_close(cm, cm_want, "chunk_mass")
+    assert_close(d, d_want, "density")
+    if norm == oracle.NORM_NONE:
+        np.testing.assert_allclose(cm.sum(axis=2), R, rtol=1e-5)
+
+
+def test_peaked_and_huge_logits():
+    """One key dominates every row; logits of a few hundred must not overflow."""
+    g = synth.Geometry(1, 1, 1, 128, 128, 16, 64)
+    ks, os_ = both_shapes(g)
+    kv = torch.zeros((1, 2, 1, 128, 128), dtype=torch.float16)
+    kv[0, 0, 0, 37] = 20.0
+    kv[0, 0, 0, 100] = -20.0
+    q = torch.full((1, 1, 32, 128), 2.0, dtype=torch.float16)
+    cm_want, d_want = oracle.score_chunks(os_, q.numpy(), kv.numpy(), oracle.NORM_NONE)
+    cm, d = gpu_score(ks, q.to(DEV), kv.to(DEV), oracle.NORM_NONE)
+    assert cm[0, 0, 37 // 16] == pytest.approx(32.0, rel=1e-5)
+    np.testing.assert_allclose(cm, cm_want, rtol=RTOL, atol=1e-30)
+    np.testing.assert_allclose(d, d_want, rtol=RTOL, atol=1e-30)
+
+
+def test_zero_queries_closed_form():
+    """Q = 0 gives uniform attention: harmonic-number column masses (checked against
+    the closed form directly, no oracle involved)."""
+    g = synth.Geometry(1, 1, 1, 64, 64, 8, 64)
+    ks, _ = both_shapes(g)
+    R, N, T = 16, g.N, g.T
+    kv = synth.make_kv(g, 3, DEV)
+    q = torch.zeros((1, 1, R, 64), dtype=torch.float16, device=DEV)
+    mass = np.zeros(N)
+    for c in range(N):
+        for r in range(R):
+            if c <= N - R + r:
+                mass[c] += 1.0 / (N - R + r + 1)
+    vis = np.array([N - max(c, N - R) for c in range(N)], dtype=np.float64)
+    cm, _ = gpu_score(ks, q, kv, oracle.NORM_VISIBLE)
+    assert_close(cm[0, 0], (mass / vis).reshape(-1, T).sum(1), "chunk_mass")
+    cm, _ = gpu_score(ks, q, kv, oracle.NORM_NONE)
+    assert_close(cm[0, 0], mass.reshape(-1, T).sum(1), "chunk_mass")
+
+
+def sampled_heads(wl_index, heads):
+    wl = synth.WORKLOADS[wl_index]
+    g = wl.geom
+    ks, os_ = both_shapes(g)
+    kv_dev = synth.make_kv(g, wl.seed, DEV, wl.outlier_channels, wl.outlier_scale)
+    q_dev = synth.make_q(g, wl.seed, wl.n_queries, DEV)
+    cm, d = gpu_score(ks, q_dev, kv_dev, oracle.NORM_VISIBLE)
+    q_host = q_dev.cpu().numpy()
+    for (l, h) in heads:
+        # the oracle reads only this layer's K plane: hand it a one-layer cache
+        kvh = h // (g.Hq // g.Hkv)
+        one = oracle.Shape(1, 1, 1, g.D, g.N, g.T, g.G)
+        k_host = kv_dev[l:l + 1, :, kvh:kvh + 1].contiguous().cpu().numpy()
+        want = oracle.score_head(one, q_host[l:l + 1, h:h + 1], k_host, 0, 0, oracle.NORM_VISIBLE)
+        assert_close(cm[l, h], want, f"chunk_mass[{l}][{h}]")
+    # density = mean over layers and heads per token, at full size
+    assert_close(d, cm.astype(np.float64).mean(axis=(0, 1)) / g.T, "density")
+    # un-normalised masses of every head sum to the number of query rows
+    cm_raw, d_raw = gpu_score(ks, q_dev, kv_dev, oracle.NORM_NONE)
+    np.testing.assert_allclose(cm_raw.astype(np.float64).sum(axis=2), wl.n_queries, rtol=2e-5)
+    assert float(d_raw.astype(np.float64).sum()) * g.T == pytest.approx(wl.n_queries, rel=2e-5)
+    return d
+
+
+def test_llama7b_4k_workload_sampled_heads():
+    """Configuration 3: R = 32, MHA, 4096 tokens; tercile widths from the GPU scores."""
+    d = sampled_heads(2, [(0, 0), (0, 31), (13, 7), (31, 31), (17, 16), (31, 0)])
+    bits = kvs.kv_bits_from_scores(d, 1, 1, 3)
+    assert [(bits == b).sum() for b in (8, 4, 2)] == [85, 85, 86]
+    assert np.array_equal(bits, oracle.bits_from_scores(d, 1, 1, 3))
+
+
+def test_llama3_32k_workload_sampled_heads():
+    """Configuration 5: R = 64, 32 query heads over 8 kv heads, 32768 tokens."""
+    d = sampled_heads(4, [(0, 0), (31, 31), (9, 14)])
+    bits = kvs.kv_bits_from_scores(d, 1, 1, 3)
+    assert [(bits == b).sum() for b in (8, 4, 2)] == [341, 341, 342]
+
+
+def test_determinism():
+    g = synth.Geometry(2, 2, 4, 128, 512, 16, 64)
+    ks, _ = both_shapes(g)
+    kv = synth.make_kv(g, 4, DEV)
+    q = synth.make_q(g, 4, 48, DEV)
+    a = gpu_score(ks, q, kv, oracle.NORM_VISIBLE)
+    b = gpu_score(ks, q, kv, oracle.NORM_VISIBLE)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])

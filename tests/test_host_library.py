@@ -1,0 +1,180 @@
+"""CPU tests of libkvswitch's host side: it loads, exports every declared
+symbol, rejects bad arguments without touching a GPU, and its bookkeeping
+(offsets, bit-widths, gather lists, LCTRU) is identical to the oracle's."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2403_11805_amd as kvs
+from paper_2403_11805_amd import binding, synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def shapes(i):
+    g = synth.WORKLOADS[i].geom
+    return kvs.Shape(g.L, g.Hkv, g.Hq, g.D, g.N, g.T, g.G), oracle.Shape(*g)
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "kvswitch.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(kv_[a-z0-9_]+)\s*\(", header))
+    assert {"kv_score_chunks", "kv_compress_chunks", "kv_swapin_chunks", "kv_swapin_pinned",
+            "kv_swapout_aot", "kv_lctru_evict", "kv_build_gather"} <= declared
+    handle = ctypes.CDLL(binding.LIB_PATH)
+    for name in sorted(declared):
+        assert hasattr(handle, name), f"{name} declared in kvswitch.h but not exported"
+    assert declared == set(binding._SIGNATURES), "binding and header disagree on the entry points"
+
+
+@pytest.mark.parametrize("cfg", range(5))
+def test_record_bytes_and_offsets_match_oracle(cfg):
+    ks, os_ = shapes(cfg)
+    for b in (16, 8, 4, 2):
+        assert kvs.kv_record_bytes(ks, b) == oracle.record_bytes(os_, b)
+    bits = synth.draw_bits_uniform(ks.n_chunks, cfg, widths=(16, 8, 4, 2)).numpy()
+    assert np.array_equal(kvs.kv_chunk_offsets(ks, bits), oracle.chunk_offsets(os_, bits))
+
+
+def test_bits_from_scores_matches_oracle_including_ties():
+    rng = np.random.default_rng(0)
+    for n in (1, 2, 3, 7, 256, 1024):
+        for (a, b, c) in ((1, 1, 3), (1, 2, 4), (0, 1, 2), (1, 0, 1), (0, 0, 5)):
+            d = rng.random(n).astype(np.float32)
+            d[rng.integers(0, n, size=n // 3)] = 0.5        # plenty of ties
+            assert np.array_equal(kvs.kv_bits_from_scores(d, a, b, c),
+                                  oracle.bits_from_scores(d, a, b, c))
+
+
+def test_gather_matches_oracle_and_rejects_bad_lists():
+    ks, os_ = shapes(3)
+    bits = synth.draw_bits_uniform(ks.n_chunks, 3).numpy()
+    off = kvs.kv_chunk_offsets(ks, bits)
+    for draw in range(4):
+        idx = synth.draw_subset(ks.n_chunks, 51, 3, draw).numpy()
+        got = kvs.kv_build_gather(ks, off, bits, idx)
+        want = oracle.build_gather(os_, off, bits, idx)
+        for g, w in zip(got, want):
+            assert g.dtype == w.dtype and np.array_equal(g, w)
+    for bad in ([3, 3], [5, 2], [-1], [ks.n_chunks]):
+        with pytest.raises(kvs.KvError) as e:
+            kvs.kv_build_gather(ks, off, bits, bad)
+        assert e.value.code == binding.KV_EINDEX
+    assert all(len(a) == 0 for a in kvs.kv_build_gather(ks, off, bits, []))
+
+
+def test_shape_and_bits_validation():
+    good = kvs.Shape(2, 4, 4, 64, 512, 16, 64)
+    bad_shapes = [good._replace(n_tokens=500), good._replace(group=32), good._replace(group=96),
+                  good._replace(head_dim=96), good._replace(n_q_heads=6), good._replace(n_layers=0),
+                  good._replace(chunk_tokens=4, n_tokens=512)]
+    for s in bad_shapes:
+        with pytest.raises(kvs.KvError) as e:
+            kvs.kv_chunk_offsets(s, np.full(max(s.n_chunks, 1), 8, dtype=np.uint8))
+        assert e.value.code == binding.KV_ESHAPE and kvs.kv_last_error()
+    with pytest.raises(kvs.KvError) as e:
+        kvs.kv_chunk_offsets(good, np.full(good.n_chunks, 3, dtype=np.uint8))
+    assert e.value.code == binding.KV_EBITS
+    with pytest.raises(kvs.KvError):
+        kvs.kv_record_bytes(good, 5)
+    with pytest.raises(kvs.KvError):
+        kvs.kv_bits_from_scores(np.zeros(4, dtype=np.float32), 2, 2, 3)
+    # scoring has extra requirements, checked on the host
+    with pytest.raises(kvs.KvError):
+        kvs.kv_score_workspace_bytes(good._replace(n_tokens=48), 8)
+    with pytest.raises(kvs.KvError):
+        kvs.kv_score_workspace_bytes(good, 0)
+    assert kvs.kv_score_workspace_bytes(good, 8) % 256 == 0
+
+
+def test_device_entry_points_validate_before_touching_the_gpu():
+    """NULL pointers and bad sizes are refused on the host (nothing is launched)."""
+    L = binding.lib()
+    s = kvs.Shape(2, 4, 4, 64, 512, 16, 64).c()
+    assert L.kv_compress_chunks(ctypes.byref(s), None, None, None, None, None) == binding.KV_EINVAL
+    assert L.kv_swapin_chunks(ctypes.byref(s), None, None, None, None, 3, None, None) == binding.KV_EINVAL
+    assert L.kv_swapin_chunks(ctypes.byref(s), None, None, None, None, 0, None, None) == binding.KV_OK
+    assert L.kv_swapin_chunks(ctypes.byref(s), None, None, None, None, 33, None, None) == binding.KV_EINVAL
+    assert L.kv_score_chunks(ctypes.byref(s), None, 8, None, 0, None, 0, None, None, None) == binding.KV_EINVAL
+    assert L.kv_swapout_aot(None, None, 0, 0, None, None) == binding.KV_EINVAL
+    bad = kvs.Shape(2, 4, 4, 64, 500, 16, 64).c()
+    assert L.kv_compress_chunks(ctypes.byref(bad), None, None, None, None, None) == binding.KV_ESHAPE
+
+
+def replay(ops):
+    """Apply the same operation sequence to the library queue and to the oracle model."""
+    q, m = kvs.Lctru(), oracle.LctruModel()
+    for op in ops:
+        kind = op[0]
+        if kind == "insert":
+            q.insert(*op[1:]); m.insert(*op[1:])
+        elif kind == "touch":
+            q.touch_ctx(*op[1:]); m.touch_ctx(*op[1:])
+        elif kind == "lock":
+            q.lock(op[1]); m.lock(op[1])
+        elif kind == "unlock":
+            q.unlock(op[1]); m.unlock(op[1])
+        elif kind == "remove":
+            q.remove_ctx(op[1]); m.remove_ctx(op[1])
+        elif kind == "evict":
+            assert q.evict(op[1]) == m.evict(op[1])
+        assert q.order() == m.order()
+        assert q.size() == m.size()
+    q.close()
+
+
+def test_lctru_matches_oracle_on_random_sequences():
+    rng = np.random.default_rng(7)
+    for trial in range(20):
+        ops, now, live = [], 0, set()
+        for _ in range(300):
+            now += int(rng.integers(0, 3))          # repeated timestamps exercise the tie rule
+            k = rng.random()
+            ctx = int(rng.integers(0, 6))
+            if k < 0.45:
+                chunk = int(rng.integers(0, 40))
+                if (ctx, chunk) not in live:
+                    live.add((ctx, chunk))
+                    b = int(rng.choice([16, 8, 4, 2]))
+                    ops.append(("insert", ctx, chunk, b, 100 * b + int(rng.integers(0, 5)), now))
+            elif k < 0.6:
+                ops.append(("touch", ctx, now))
+            elif k < 0.7:
+                ops.append(("lock", ctx))
+            elif k < 0.8:
+                ops.append(("unlock", ctx))
+            elif k < 0.85:
+                ops.append(("remove", ctx))
+                live = {x for x in live if x[0] != ctx}
+            else:
+                ops.append(("evict", int(rng.integers(0, 6000))))
+                live = None
+                break
+        replay(ops)
+
+
+def test_lctru_pool_workload_order():
+    """64 contexts x 128 chunks (the multi-app pool): order equals the oracle's sort."""
+    ks, _ = shapes(3)
+    q, m = kvs.Lctru(), oracle.LctruModel()
+    rng = np.random.default_rng(3)
+    for ctx in range(64):
+        bits = synth.draw_bits_uniform(ks.n_chunks, 3, context=ctx).numpy()
+        for chunk in range(ks.n_chunks):
+            args = (ctx, chunk, int(bits[chunk]), kvs.kv_record_bytes(ks, int(bits[chunk])), ctx)
+            q.insert(*args); m.insert(*args)
+    for step, ctx in enumerate(rng.integers(0, 64, size=50)):
+        q.touch_ctx(int(ctx), 100 + step); m.touch_ctx(int(ctx), 100 + step)
+    q.lock(5); m.lock(5)
+    assert q.order() == m.order()
+    need = 3 * 2 ** 30
+    assert q.evict(need) == m.evict(need)
+    assert q.size() == m.size()
+    with pytest.raises(kvs.KvError):
+        q.insert(0, 0, 8, 1, 1) if (0, 0) in m.entries else q.insert(1, 1, 3, 1, 1)
+    q.close()
