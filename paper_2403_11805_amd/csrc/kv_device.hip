@@ -39,7 +39,25 @@ QuantGeom quant_geom(const kv_shape_t& s) {
     g.pieces = s.chunk_tokens * s.head_dim / 8;
     g.row_pieces = s.head_dim / 8;
     g.lpg_log2 = ilog2(s.group / 8);
+    g.tpu = 0;
+    g.tpu_shift = -1;
     return g;
+}
+
+// Pieces per lane of a wavefront task (4, 2 or 1: the most that divides the
+// unit) and the resulting tasks per unit.
+int plan_tasks(QuantGeom* g) {
+    const int wpu = g->pieces / 64;
+    const int ppl = (wpu % 4 == 0) ? 4 : ((wpu % 2 == 0) ? 2 : 1);
+    g->tpu = wpu / ppl;
+    g->tpu_shift = ((g->tpu & (g->tpu - 1)) == 0) ? ilog2(g->tpu) : -1;
+    return ppl;
+}
+
+dim3 task_grid(const QuantGeom& g, int n_units) {
+    const int64_t tasks = static_cast<int64_t>(n_units) * g.tpu;
+    return dim3(static_cast<uint32_t>((tasks + kWavesPerBlock - 1) / kWavesPerBlock),
+                static_cast<uint32_t>(g.slabs));
 }
 
 int launch_status(const char* what) {
@@ -58,14 +76,17 @@ int32_t kv_compress_chunks(const kv_shape_t* shape, const void* kv, const uint8_
     if (!kv || !bits_dev || !off_dev || !packed_out) return fail(KV_EINVAL, "NULL device pointer");
     if (!aligned(kv, 16) || !aligned(packed_out, 16) || !aligned(off_dev, 8))
         return fail(KV_EINVAL, "kv/packed_out must be 16-byte aligned, off_dev 8-byte aligned");
-    const QuantGeom g = quant_geom(*shape);
+    QuantGeom g = quant_geom(*shape);
+    const int ppl = plan_tasks(&g);
     const int32_t n_chunks = shape->n_tokens / shape->chunk_tokens;
-    const int64_t units = static_cast<int64_t>(n_chunks) * g.slabs;
-    const int64_t blocks = (units + 3) / 4;
-    if (blocks > 0x7fffffff) return fail(KV_ESHAPE, "too many work units");
-    hipLaunchKernelGGL(compress_kernel, dim3(static_cast<uint32_t>(blocks)), dim3(256), 0,
-                       static_cast<hipStream_t>(stream), static_cast<const uint4*>(kv), bits_dev,
-                       off_dev, static_cast<uint8_t*>(packed_out), g, n_chunks);
+    if (g.slabs > 65535) return fail(KV_ESHAPE, "more than 65535 slabs exceed the launch grid");
+    const dim3 grid = task_grid(g, n_chunks);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const u4_t* src = static_cast<const u4_t*>(kv);
+    uint8_t* dst = static_cast<uint8_t*>(packed_out);
+    if (ppl == 4) hipLaunchKernelGGL(compress_kernel<4>, grid, dim3(256), 0, st, src, bits_dev, off_dev, dst, g, n_chunks);
+    else if (ppl == 2) hipLaunchKernelGGL(compress_kernel<2>, grid, dim3(256), 0, st, src, bits_dev, off_dev, dst, g, n_chunks);
+    else hipLaunchKernelGGL(compress_kernel<1>, grid, dim3(256), 0, st, src, bits_dev, off_dev, dst, g, n_chunks);
     return launch_status("compress_kernel launch");
 }
 
@@ -81,12 +102,16 @@ int32_t kv_swapin_chunks(const kv_shape_t* shape, const void* packed, const uint
     if (!aligned(kv_out, 16) || !aligned(packed, 16) || !aligned(src_off_dev, 8) ||
         !aligned(dst_tok_dev, 4))
         return fail(KV_EINVAL, "kv_out/packed must be 16-byte aligned, lists naturally aligned");
-    const QuantGeom g = quant_geom(*shape);
-    const int64_t units = static_cast<int64_t>(n_sel) * g.slabs;
-    const int64_t blocks = (units + 3) / 4;
-    hipLaunchKernelGGL(swapin_kernel, dim3(static_cast<uint32_t>(blocks)), dim3(256), 0,
-                       static_cast<hipStream_t>(stream), static_cast<const uint8_t*>(packed),
-                       src_off_dev, dst_tok_dev, sel_bits_dev, static_cast<uint4*>(kv_out), g, n_sel);
+    QuantGeom g = quant_geom(*shape);
+    const int ppl = plan_tasks(&g);
+    if (g.slabs > 65535) return fail(KV_ESHAPE, "more than 65535 slabs exceed the launch grid");
+    const dim3 grid = task_grid(g, n_sel);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const uint8_t* src = static_cast<const uint8_t*>(packed);
+    u4_t* dst = static_cast<u4_t*>(kv_out);
+    if (ppl == 4) hipLaunchKernelGGL(swapin_kernel<4>, grid, dim3(256), 0, st, src, src_off_dev, dst_tok_dev, sel_bits_dev, dst, g, n_sel);
+    else if (ppl == 2) hipLaunchKernelGGL(swapin_kernel<2>, grid, dim3(256), 0, st, src, src_off_dev, dst_tok_dev, sel_bits_dev, dst, g, n_sel);
+    else hipLaunchKernelGGL(swapin_kernel<1>, grid, dim3(256), 0, st, src, src_off_dev, dst_tok_dev, sel_bits_dev, dst, g, n_sel);
     return launch_status("swapin_kernel launch");
 }
 
@@ -176,7 +201,7 @@ int32_t kv_score_chunks(const kv_shape_t* shape, const void* q, int32_t n_querie
     if (int rc = launch_status("score_combine_kernel launch")) return rc;
     const int n_chunks = g.N / g.T;
     const float inv_norm = static_cast<float>(1.0 / (static_cast<double>(g.T) * g.L * g.Hq));
-    hipLaunchKernelGGL(score_density_kernel, dim3((n_chunks + 255) / 256), dim3(256), 0, st,
+    hipLaunchKernelGGL(score_density_kernel, dim3((n_chunks + 63) / 64), dim3(1024), 0, st,
                        chunk_mass, density, g.L * g.Hq, n_chunks, inv_norm);
     return launch_status("score_density_kernel launch");
 }
@@ -214,7 +239,9 @@ int32_t kv_swapin_pinned(const kv_shape_t* shape, const void* packed_pinned, con
         return fail(KV_ENOMEM, "staging slot %llu bytes, largest record %llu",
                     static_cast<unsigned long long>(slot), static_cast<unsigned long long>(largest));
 
-    const QuantGeom g = quant_geom(*shape);
+    QuantGeom g = quant_geom(*shape);
+    const int ppl = plan_tasks(&g);
+    if (g.slabs > 65535) return fail(KV_ESHAPE, "more than 65535 slabs exceed the launch grid");
     hipStream_t cs = static_cast<hipStream_t>(copy_stream);
     hipStream_t ks = static_cast<hipStream_t>(compute_stream);
     hipEvent_t copied[8], consumed[8];
@@ -282,9 +309,11 @@ int32_t kv_swapin_pinned(const kv_shape_t* shape, const void* packed_pinned, con
         hipError_t e = hipEventRecord(copied[b], cs);
         if (e == hipSuccess) e = hipStreamWaitEvent(ks, copied[b], 0);
         if (e != hipSuccess) { rc = hip_fail(e, "event record/wait"); break; }
-        const int64_t units = static_cast<int64_t>(list.n) * g.slabs;
-        hipLaunchKernelGGL(swapin_batch_kernel, dim3(static_cast<uint32_t>((units + 3) / 4)), dim3(256),
-                           0, ks, slot_dev, list, static_cast<uint4*>(kv_out), g);
+        const dim3 grid = task_grid(g, list.n);
+        u4_t* dst = static_cast<u4_t*>(kv_out);
+        if (ppl == 4) hipLaunchKernelGGL(swapin_batch_kernel<4>, grid, dim3(256), 0, ks, slot_dev, list, dst, g);
+        else if (ppl == 2) hipLaunchKernelGGL(swapin_batch_kernel<2>, grid, dim3(256), 0, ks, slot_dev, list, dst, g);
+        else hipLaunchKernelGGL(swapin_batch_kernel<1>, grid, dim3(256), 0, ks, slot_dev, list, dst, g);
         rc = launch_status("swapin_batch_kernel launch");
         if (rc != KV_OK) break;
         e = hipEventRecord(consumed[b], ks);

@@ -4,11 +4,14 @@
 //
 // Work unit: one (chunk, slab) pair = chunk_tokens x head_dim contiguous fp16
 // on the cache side and one contiguous run of code bytes on the record side.
-// One 64-lane wavefront handles one unit; a lane owns "pieces" of 8
-// consecutive elements (one 16-byte cache access), so a quantisation group of
-// G elements is spread over G/8 neighbouring lanes and its min/max is a short
-// DPP butterfly.  Both sides stream: the kernels are HBM-bound, the arithmetic
-// is kept to a few VALU operations per element.
+// A lane owns one "piece" of 8 consecutive elements (one 16-byte cache access)
+// and a wavefront owns 64 consecutive pieces (1 KiB of cache): the shape that
+// streams fastest from HBM on this part is the plainest one, a single 16-byte
+// access per lane with as many independent wavefronts in flight as possible.
+// A quantisation group of G elements is spread over G/8 neighbouring lanes, so
+// its min/max is a short DPP butterfly.  A wavefront task is PPL * 64 pieces of
+// one unit; its chunk index is wave-uniform, so the bit-width and the record
+// offset are scalar loads and the branch on the width is uniform.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -16,8 +19,9 @@
 
 namespace kvs {
 
-typedef _Float16 h2_t __attribute__((ext_vector_type(2)));
 typedef _Float16 h8_t __attribute__((ext_vector_type(8)));
+typedef unsigned int u4_t __attribute__((ext_vector_type(4)));
+typedef unsigned int u2_t __attribute__((ext_vector_type(2)));
 
 struct QuantGeom {
     int32_t n_tokens;      // N
@@ -26,80 +30,139 @@ struct QuantGeom {
     int32_t pieces;        // T * D / 8: 16-byte pieces per unit (multiple of 64)
     int32_t row_pieces;    // D / 8
     int32_t lpg_log2;      // log2(G / 8): lanes per quantisation group (3..6)
+    int32_t tpu;           // wavefront tasks per unit = pieces / (64 * pieces-per-lane)
+    int32_t tpu_shift;     // log2(tpu) if tpu is a power of two, else -1
 };
+
+constexpr int kWavesPerBlock = 4;
+
+// Entry i of a byte list at a wave-uniform index, read through the aligned
+// 32-bit word that contains it so that it can be a scalar load.
+__device__ __forceinline__ int uniform_byte(const uint8_t* list, int i) {
+    const uintptr_t a = reinterpret_cast<uintptr_t>(list) + static_cast<uintptr_t>(i);
+    const uint32_t w = *reinterpret_cast<const uint32_t*>(a & ~static_cast<uintptr_t>(3));
+    return static_cast<int>((w >> ((a & 3) * 8)) & 0xffu);
+}
+
+// Wavefront task -> (unit index along y, first piece).  Task ids are uniform
+// per wavefront; readfirstlane keeps everything derived from them in SGPRs, so
+// the per-chunk list entries become scalar loads and the width branch is uniform.
+__device__ __forceinline__ bool wave_task(const QuantGeom& g, int n_units, int ppl, int& unit,
+                                          int& piece0) {
+    const int wave = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6));
+    const int t = blockIdx.x * kWavesPerBlock + wave;
+    int sub;
+    if (g.tpu_shift >= 0) {
+        unit = t >> g.tpu_shift;
+        sub = t & (g.tpu - 1);
+    } else {
+        unit = t / g.tpu;
+        sub = t - unit * g.tpu;
+    }
+    piece0 = sub * 64 * ppl;
+    return unit < n_units;
+}
+
+// Streaming accesses: every byte is touched once.  Whether marking them
+// non-temporal pays differs per access (measured), hence the switches.
+#ifndef KVS_NT_CACHE_LOAD
+#define KVS_NT_CACHE_LOAD 1     // compress: 16-byte loads of the fp16 cache
+#endif
+#ifndef KVS_NT_CODE_STORE
+#define KVS_NT_CODE_STORE 1     // compress: code stores into the record
+#endif
+#ifndef KVS_NT_CODE_LOAD
+#define KVS_NT_CODE_LOAD 1      // swap-in: code loads from the record
+#endif
+#ifndef KVS_NT_CACHE_STORE
+#define KVS_NT_CACHE_STORE 1    // swap-in: 16-byte stores into the fp16 cache
+#endif
+template <bool NT, typename T>
+__device__ __forceinline__ T stream_load(const T* p) {
+    if constexpr (NT) return __builtin_nontemporal_load(p);
+    else return *p;
+}
+template <bool NT, typename T>
+__device__ __forceinline__ void stream_store(T v, T* p) {
+    if constexpr (NT) __builtin_nontemporal_store(v, p);
+    else *p = v;
+}
+
+// Packed fp16 min/max on raw registers.  Written as instructions so that no
+// NaN-quieting copies are inserted in front of them (inputs are finite).
+__device__ __forceinline__ uint32_t pk_min_f16(uint32_t a, uint32_t b) {
+    uint32_t r;
+    asm("v_pk_min_f16 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+__device__ __forceinline__ uint32_t pk_max_f16(uint32_t a, uint32_t b) {
+    uint32_t r;
+    asm("v_pk_max_f16 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
 
 // DPP lane exchange inside a row of 16 lanes.  CTRL: 0xB1 = swap neighbours,
 // 0x4E = swap lane pairs, 0x141 = mirror inside 8 lanes, 0x140 = mirror inside 16.
 template <int CTRL>
 __device__ __forceinline__ uint32_t dpp_u32(uint32_t v) {
     return static_cast<uint32_t>(
-        __builtin_amdgcn_update_dpp(0, static_cast<int>(v), CTRL, 0xF, 0xF, false));
+        __builtin_amdgcn_update_dpp(static_cast<int>(v), static_cast<int>(v), CTRL, 0xF, 0xF, false));
 }
 
-__device__ __forceinline__ h2_t h2_from_u32(uint32_t u) { return __builtin_bit_cast(h2_t, u); }
-__device__ __forceinline__ uint32_t u32_from_h2(h2_t h) { return __builtin_bit_cast(uint32_t, h); }
-
-template <int CTRL>
-__device__ __forceinline__ h2_t pkmin_dpp(h2_t m) {
-    return __builtin_elementwise_min(m, h2_from_u32(dpp_u32<CTRL>(u32_from_h2(m))));
+// x + 0.0f of the format definition (-0 becomes +0, everything else is kept),
+// as an instruction so that no floating-point simplification can drop it.
+__device__ __forceinline__ float plus_zero(float x) {
+    float r;
+    asm("v_add_f32 %0, 0, %1" : "=v"(r) : "v"(x));
+    return r;
 }
 
-// (min, -max) of the 8 halfs of a piece, reduced over the 2^lpg_log2 lanes of
-// the quantisation group; every lane of the group ends with the same pair.
-__device__ __forceinline__ h2_t group_min_negmax(const h8_t& x, int lpg_log2) {
-    h2_t a = {x[0], x[1]}, b = {x[2], x[3]}, c = {x[4], x[5]}, d = {x[6], x[7]};
-    h2_t lo = __builtin_elementwise_min(__builtin_elementwise_min(a, b),
-                                        __builtin_elementwise_min(c, d));
-    h2_t hi = __builtin_elementwise_max(__builtin_elementwise_max(a, b),
-                                        __builtin_elementwise_max(c, d));
-    _Float16 mn = lo[0] < lo[1] ? lo[0] : lo[1];
-    _Float16 mx = hi[0] > hi[1] ? hi[0] : hi[1];
-    h2_t m = {mn, static_cast<_Float16>(-mx)};
-    m = pkmin_dpp<0xB1>(m);
-    m = pkmin_dpp<0x4E>(m);
-    m = pkmin_dpp<0x141>(m);
-    if (lpg_log2 >= 4) m = pkmin_dpp<0x140>(m);
-    if (lpg_log2 >= 5) {
-        uint32_t o = static_cast<uint32_t>(__shfl_xor(static_cast<int>(u32_from_h2(m)), 16));
-        m = __builtin_elementwise_min(m, h2_from_u32(o));
-    }
-    if (lpg_log2 >= 6) {
-        uint32_t o = static_cast<uint32_t>(__shfl_xor(static_cast<int>(u32_from_h2(m)), 32));
-        m = __builtin_elementwise_min(m, h2_from_u32(o));
-    }
-    return m;
+// min and max of the quantisation group this lane's piece belongs to
+// (2^lpg_log2 neighbouring lanes), as binary32 with -0 canonicalised to +0.
+__device__ __forceinline__ void group_min_max(const u4_t& raw, int lpg_log2, float& mn, float& mx) {
+    uint32_t lo = pk_min_f16(pk_min_f16(raw.x, raw.y), pk_min_f16(raw.z, raw.w));
+    uint32_t hi = pk_max_f16(pk_max_f16(raw.x, raw.y), pk_max_f16(raw.z, raw.w));
+    lo = pk_min_f16(lo, lo >> 16);     // low half: min of the 8 elements
+    hi = pk_max_f16(hi, hi >> 16);     // low half: max of the 8 elements
+    // one register holding (min, -max): a packed min reduces both at once
+    uint32_t m = (lo & 0xffffu) | ((hi ^ 0x8000u) << 16);
+    m = pk_min_f16(m, dpp_u32<0xB1>(m));
+    m = pk_min_f16(m, dpp_u32<0x4E>(m));
+    m = pk_min_f16(m, dpp_u32<0x141>(m));
+    if (lpg_log2 >= 4) m = pk_min_f16(m, dpp_u32<0x140>(m));
+    if (lpg_log2 >= 5) m = pk_min_f16(m, static_cast<uint32_t>(__shfl_xor(static_cast<int>(m), 16)));
+    if (lpg_log2 >= 6) m = pk_min_f16(m, static_cast<uint32_t>(__shfl_xor(static_cast<int>(m), 32)));
+    const _Float16 hmin = __builtin_bit_cast(_Float16, static_cast<uint16_t>(m & 0xffffu));
+    const _Float16 hneg = __builtin_bit_cast(_Float16, static_cast<uint16_t>(m >> 16));
+    mn = plus_zero(static_cast<float>(hmin));
+    mx = plus_zero(-static_cast<float>(hneg));
 }
 
-// x + 0.0f of the format definition: -0 becomes +0, everything else is kept.
-// Done on the bit pattern so that no floating-point simplification can drop it.
-__device__ __forceinline__ float positive_zero(float x) {
-    const uint32_t u = __builtin_bit_cast(uint32_t, x);
-    return __builtin_bit_cast(float, (u << 1) ? u : 0u);
-}
-
-// Quantise the 8 elements of one piece to BITS-bit codes (as exact small
-// floats in r[]).  The contract is code = rint((x - mn) / scale) with a true
-// binary32 division.  The fast path multiplies by an approximate reciprocal;
-// its result q' differs from the true rounded quotient by less than
-// 8 * 2^-24 * q, so rint(q') can only differ when q' lies within that distance
-// of a half-integer.  Lanes that see such a value redo the piece with the
-// exact division, which keeps every code bit-identical to the definition.
+// Quantise the 8 elements of one piece to BITS-bit codes (exact small floats
+// in r[]).  The contract is code = rint((x - mn) / scale) with a true binary32
+// division.  The fast path multiplies by an approximate reciprocal (1 ulp); its
+// result q' differs from the correctly rounded quotient by less than
+// 4.1 * 2^-24 * q, so rint(q') can only differ from the defined code when q'
+// lies within that distance of a half-integer.  A lane that sees |q' - rint(q')|
+// >= 0.5 - 2^BITS * 2^-20 redoes its piece with the exact division, which keeps
+// every code bit-identical to the definition.
 template <int BITS>
 __device__ __forceinline__ void quantise_piece(const h8_t& x, float mn, float scale, float r[8]) {
     constexpr float kLevels = static_cast<float>((1 << BITS) - 1);
-    // 0.5 - 2^BITS * 2^-20: a half-integer closer than 16 * 2^-24 * q_max is "dangerous"
     constexpr float kSafe = 0.5f - static_cast<float>(1 << BITS) * 9.5367431640625e-07f;
     const float inv = (scale != 0.0f) ? __builtin_amdgcn_rcpf(scale) : 0.0f;
-    bool danger = false;
+    float e[8];
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
         const float d = static_cast<float>(x[k]) - mn;
         const float q = d * inv;
-        const float c = __builtin_rintf(q);
-        danger |= (__builtin_fabsf(q - c) >= kSafe);
-        r[k] = c;
+        r[k] = __builtin_rintf(q);
+        e[k] = __builtin_fabsf(q - r[k]);
     }
-    if (danger) {
+    const float e01 = __builtin_fmaxf(__builtin_fmaxf(e[0], e[1]), e[2]);
+    const float e02 = __builtin_fmaxf(__builtin_fmaxf(e[3], e[4]), e[5]);
+    const float emax = __builtin_fmaxf(__builtin_fmaxf(e01, e02), __builtin_fmaxf(e[6], e[7]));
+    if (emax >= kSafe) {
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
             const float d = static_cast<float>(x[k]) - mn;
@@ -110,156 +173,160 @@ __device__ __forceinline__ void quantise_piece(const h8_t& x, float mn, float sc
     }
 }
 
-// One (chunk, slab) unit -> codes, scale and mn of its record.
+// One piece -> its codes (and, from the first lane of each group, scale and mn).
 template <int BITS>
-__device__ __forceinline__ void compress_unit(const uint4* __restrict__ src,
-                                              uint8_t* __restrict__ codes,
-                                              float* __restrict__ scale_out,
-                                              float* __restrict__ mn_out, const QuantGeom& g,
-                                              int lane) {
+__device__ __forceinline__ void compress_piece(const u4_t& raw, uint8_t* __restrict__ codes,
+                                               float* __restrict__ scale_out,
+                                               float* __restrict__ mn_out, int p, int lpg_log2,
+                                               int lane) {
     constexpr float kLevels = static_cast<float>((1 << BITS) - 1);
-    const int lpg_mask = (1 << g.lpg_log2) - 1;
-    for (int p0 = 0; p0 < g.pieces; p0 += 256) {
-        uint4 raw[4];
+    float mn, mx;
+    group_min_max(raw, lpg_log2, mn, mx);
+    const float scale = (mx - mn) / kLevels;
+    const h8_t x = __builtin_bit_cast(h8_t, raw);
+    float r[8];
+    quantise_piece<BITS>(x, mn, scale, r);
+    if constexpr (BITS == 8) {
+        uint32_t w0 = 0, w1 = 0;
+        w0 = __builtin_amdgcn_cvt_pk_u8_f32(r[0], 0, w0);
+        w0 = __builtin_amdgcn_cvt_pk_u8_f32(r[1], 1, w0);
+        w0 = __builtin_amdgcn_cvt_pk_u8_f32(r[2], 2, w0);
+        w0 = __builtin_amdgcn_cvt_pk_u8_f32(r[3], 3, w0);
+        w1 = __builtin_amdgcn_cvt_pk_u8_f32(r[4], 0, w1);
+        w1 = __builtin_amdgcn_cvt_pk_u8_f32(r[5], 1, w1);
+        w1 = __builtin_amdgcn_cvt_pk_u8_f32(r[6], 2, w1);
+        w1 = __builtin_amdgcn_cvt_pk_u8_f32(r[7], 3, w1);
+        u2_t w = {w0, w1};
+        stream_store<KVS_NT_CODE_STORE>(w, reinterpret_cast<u2_t*>(codes) + p);
+    } else if constexpr (BITS == 4) {
+        // four 4-bit codes = 16 bits: exact as a float sum
+        const float lo = __builtin_fmaf(r[3], 4096.0f,
+                         __builtin_fmaf(r[2], 256.0f, __builtin_fmaf(r[1], 16.0f, r[0])));
+        const float hi = __builtin_fmaf(r[7], 4096.0f,
+                         __builtin_fmaf(r[6], 256.0f, __builtin_fmaf(r[5], 16.0f, r[4])));
+        stream_store<KVS_NT_CODE_STORE>(static_cast<uint32_t>(lo) | (static_cast<uint32_t>(hi) << 16),
+                     reinterpret_cast<uint32_t*>(codes) + p);
+    } else {
+        // eight 2-bit codes = 16 bits
+        float acc = r[7];
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
-            if (p0 + u * 64 < g.pieces) raw[u] = src[p0 + u * 64 + lane];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            if (p0 + u * 64 >= g.pieces) break;
-            const int p = p0 + u * 64 + lane;
-            const h8_t x = __builtin_bit_cast(h8_t, raw[u]);
-            const h2_t m = group_min_negmax(x, g.lpg_log2);
-            const float mn = positive_zero(static_cast<float>(m[0]));
-            const float mx = positive_zero(static_cast<float>(static_cast<_Float16>(-m[1])));
-            const float scale = (mx - mn) / kLevels;
-            float r[8];
-            quantise_piece<BITS>(x, mn, scale, r);
-            if constexpr (BITS == 8) {
-                uint32_t w0 = 0, w1 = 0;
-                w0 = __builtin_amdgcn_cvt_pk_u8_f32(r[0], 0, w0);
-                w0 = __builtin_amdgcn_cvt_pk_u8_f32(r[1], 1, w0);
-                w0 = __builtin_amdgcn_cvt_pk_u8_f32(r[2], 2, w0);
-                w0 = __builtin_amdgcn_cvt_pk_u8_f32(r[3], 3, w0);
-                w1 = __builtin_amdgcn_cvt_pk_u8_f32(r[4], 0, w1);
-                w1 = __builtin_amdgcn_cvt_pk_u8_f32(r[5], 1, w1);
-                w1 = __builtin_amdgcn_cvt_pk_u8_f32(r[6], 2, w1);
-                w1 = __builtin_amdgcn_cvt_pk_u8_f32(r[7], 3, w1);
-                reinterpret_cast<uint2*>(codes)[p] = make_uint2(w0, w1);
-            } else if constexpr (BITS == 4) {
-                // four 4-bit codes = 16 bits: exact as a float sum
-                const float lo = __builtin_fmaf(r[3], 4096.0f,
-                                 __builtin_fmaf(r[2], 256.0f, __builtin_fmaf(r[1], 16.0f, r[0])));
-                const float hi = __builtin_fmaf(r[7], 4096.0f,
-                                 __builtin_fmaf(r[6], 256.0f, __builtin_fmaf(r[5], 16.0f, r[4])));
-                reinterpret_cast<uint32_t*>(codes)[p] =
-                    static_cast<uint32_t>(lo) | (static_cast<uint32_t>(hi) << 16);
-            } else {
-                // eight 2-bit codes = 16 bits
-                float acc = r[7];
-#pragma unroll
-                for (int k = 6; k >= 0; --k) acc = __builtin_fmaf(acc, 4.0f, r[k]);
-                reinterpret_cast<uint16_t*>(codes)[p] =
-                    static_cast<uint16_t>(static_cast<uint32_t>(acc));
-            }
-            if ((lane & lpg_mask) == 0) {
-                scale_out[p >> g.lpg_log2] = scale;
-                mn_out[p >> g.lpg_log2] = mn;
-            }
-        }
+        for (int k = 6; k >= 0; --k) acc = __builtin_fmaf(acc, 4.0f, r[k]);
+        stream_store<KVS_NT_CODE_STORE>(static_cast<uint16_t>(static_cast<uint32_t>(acc)),
+                     reinterpret_cast<uint16_t*>(codes) + p);
+    }
+    if ((lane & ((1 << lpg_log2) - 1)) == 0) {
+        scale_out[p >> lpg_log2] = scale;
+        mn_out[p >> lpg_log2] = mn;
     }
 }
 
-__device__ __forceinline__ void copy_unit(const uint4* __restrict__ src, uint4* __restrict__ dst,
-                                          int pieces, int lane) {
-    for (int p0 = 0; p0 < pieces; p0 += 256) {
-        uint4 raw[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-            if (p0 + u * 64 < pieces) raw[u] = src[p0 + u * 64 + lane];
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-            if (p0 + u * 64 < pieces) dst[p0 + u * 64 + lane] = raw[u];
-    }
-}
-
-// Grid: ceil(n_chunks * slabs / 4) blocks of 256 threads.  Units are numbered
-// slab-major (consecutive units walk the token axis of one slab) so that the
-// cache side is read as one forward stream.
-__global__ __launch_bounds__(256) void compress_kernel(const uint4* __restrict__ kv,
+// Grid (ceil(n_chunks * tpu / 4), slabs), block 256 threads = 4 wavefront
+// tasks of PPL * 64 pieces each.  Tasks run along the token axis of one slab, so
+// the cache side is read as one forward stream.
+template <int PPL>
+__global__ __launch_bounds__(256) void compress_kernel(const u4_t* __restrict__ kv,
                                                        const uint8_t* __restrict__ bits,
                                                        const uint64_t* __restrict__ off,
-                                                       uint8_t* __restrict__ packed,
-                                                       QuantGeom g, int32_t n_chunks) {
+                                                       uint8_t* __restrict__ packed, QuantGeom g,
+                                                       int32_t n_chunks) {
     const int lane = threadIdx.x & 63;
-    const int64_t unit = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
-    if (unit >= static_cast<int64_t>(n_chunks) * g.slabs) return;
-    const int slab = static_cast<int>(unit / n_chunks);
-    const int chunk = static_cast<int>(unit - static_cast<int64_t>(slab) * n_chunks);
-    const int b = __builtin_amdgcn_readfirstlane(static_cast<int>(bits[chunk]));
-    const uint64_t rec = off[chunk];
-    const uint4* src = kv + (static_cast<uint64_t>(slab) * g.n_tokens +
-                             static_cast<uint64_t>(chunk) * g.chunk_tokens) * g.row_pieces;
-    uint8_t* base = packed + rec;
+    const int slab = blockIdx.y;
+    int chunk, p0;
+    if (!wave_task(g, n_chunks, PPL, chunk, p0)) return;
+    const u4_t* src = kv + (static_cast<uint64_t>(slab) * g.n_tokens +
+                            static_cast<uint64_t>(chunk) * g.chunk_tokens) * g.row_pieces;
+    u4_t raw[PPL];
+#pragma unroll
+    for (int u = 0; u < PPL; ++u) raw[u] = stream_load<KVS_NT_CACHE_LOAD>(src + p0 + u * 64 + lane);
+    const int b = uniform_byte(bits, chunk);
+    uint8_t* base = packed + off[chunk];
     if (b == 16) {
-        copy_unit(src, reinterpret_cast<uint4*>(base) + static_cast<uint64_t>(slab) * g.pieces,
-                  g.pieces, lane);
+#pragma unroll
+        for (int u = 0; u < PPL; ++u)
+            stream_store<KVS_NT_CODE_STORE>(raw[u], reinterpret_cast<u4_t*>(base) +
+                                            static_cast<uint64_t>(slab) * g.pieces + p0 + u * 64 + lane);
         return;
     }
-    const uint64_t code_bytes = static_cast<uint64_t>(g.pieces) * b;      // per unit
+    const uint64_t code_bytes = static_cast<uint64_t>(g.pieces) * b;        // per unit
     const uint32_t groups = static_cast<uint32_t>(g.pieces) >> g.lpg_log2;  // per unit
     uint8_t* codes = base + slab * code_bytes;
     float* scale = reinterpret_cast<float*>(base + g.slabs * code_bytes) +
                    static_cast<uint64_t>(slab) * groups;
     float* mn = scale + static_cast<uint64_t>(g.slabs) * groups;
-    if (b == 8) compress_unit<8>(src, codes, scale, mn, g, lane);
-    else if (b == 4) compress_unit<4>(src, codes, scale, mn, g, lane);
-    else compress_unit<2>(src, codes, scale, mn, g, lane);
+    if (b == 8) {
+#pragma unroll
+        for (int u = 0; u < PPL; ++u)
+            compress_piece<8>(raw[u], codes, scale, mn, p0 + u * 64 + lane, g.lpg_log2, lane);
+    } else if (b == 4) {
+#pragma unroll
+        for (int u = 0; u < PPL; ++u)
+            compress_piece<4>(raw[u], codes, scale, mn, p0 + u * 64 + lane, g.lpg_log2, lane);
+    } else {
+#pragma unroll
+        for (int u = 0; u < PPL; ++u)
+            compress_piece<2>(raw[u], codes, scale, mn, p0 + u * 64 + lane, g.lpg_log2, lane);
+    }
 }
 
 // ------------------------------------------------------------------ swap-in
 
+// Codes of one piece as loaded from the record (8, 4 or 2 bytes).
 template <int BITS>
-__device__ __forceinline__ void swapin_unit(const uint8_t* __restrict__ codes,
-                                            const float* __restrict__ scale_in,
-                                            const float* __restrict__ mn_in,
-                                            uint4* __restrict__ dst, const QuantGeom& g,
-                                            int lane) {
-    constexpr uint32_t kMask = (1u << BITS) - 1u;
-    for (int p0 = 0; p0 < g.pieces; p0 += 64) {
-        const int p = p0 + lane;
-        uint32_t w0, w1 = 0;
-        if constexpr (BITS == 8) {
-            const uint2 w = reinterpret_cast<const uint2*>(codes)[p];
-            w0 = w.x;
-            w1 = w.y;
-        } else if constexpr (BITS == 4) {
-            w0 = reinterpret_cast<const uint32_t*>(codes)[p];
-        } else {
-            w0 = reinterpret_cast<const uint16_t*>(codes)[p];
-        }
-        const float sc = scale_in[p >> g.lpg_log2];
-        const float mn = mn_in[p >> g.lpg_log2];
-        h8_t out;
-#pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            uint32_t c;
-            if constexpr (BITS == 8) c = ((k < 4 ? w0 : w1) >> ((k & 3) * 8)) & kMask;
-            else c = (w0 >> (k * BITS)) & kMask;
-            const float prod = static_cast<float>(c) * sc;   // rounded product, then rounded sum
-            out[k] = static_cast<_Float16>(prod + mn);
-        }
-        dst[p] = __builtin_bit_cast(uint4, out);
-    }
+__device__ __forceinline__ u2_t load_codes(const uint8_t* __restrict__ codes, int p) {
+    u2_t w = {0u, 0u};
+    if constexpr (BITS == 8) w = stream_load<KVS_NT_CODE_LOAD>(reinterpret_cast<const u2_t*>(codes) + p);
+    else if constexpr (BITS == 4) w.x = stream_load<KVS_NT_CODE_LOAD>(reinterpret_cast<const uint32_t*>(codes) + p);
+    else w.x = stream_load<KVS_NT_CODE_LOAD>(reinterpret_cast<const uint16_t*>(codes) + p);
+    return w;
 }
 
-// One (selected record, slab) unit of the Load primitive.
-__device__ __forceinline__ void swapin_dispatch(const uint8_t* __restrict__ base, int b, int slab,
-                                                uint4* __restrict__ dst, const QuantGeom& g,
-                                                int lane) {
+template <int BITS>
+__device__ __forceinline__ u4_t dequantise_piece(u2_t w, float sc, float mn) {
+    constexpr uint32_t kMask = (1u << BITS) - 1u;
+    h8_t out;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        uint32_t c;
+        if constexpr (BITS == 8) c = ((k < 4 ? w.x : w.y) >> ((k & 3) * 8)) & kMask;
+        else c = (w.x >> (k * BITS)) & kMask;
+        const float prod = static_cast<float>(c) * sc;   // rounded product, then rounded sum
+        out[k] = static_cast<_Float16>(prod + mn);
+    }
+    return __builtin_bit_cast(u4_t, out);
+}
+
+template <int BITS, int PPL>
+__device__ __forceinline__ void swapin_pieces(const uint8_t* __restrict__ codes,
+                                              const float* __restrict__ scale,
+                                              const float* __restrict__ mn, u4_t* __restrict__ dst,
+                                              int p0, int lane, int lpg_log2) {
+    u2_t w[PPL];
+    float sc[PPL], m[PPL];
+#pragma unroll
+    for (int u = 0; u < PPL; ++u) {
+        const int p = p0 + u * 64 + lane;
+        w[u] = load_codes<BITS>(codes, p);
+        sc[u] = scale[p >> lpg_log2];
+        m[u] = mn[p >> lpg_log2];
+    }
+#pragma unroll
+    for (int u = 0; u < PPL; ++u)
+        stream_store<KVS_NT_CACHE_STORE>(dequantise_piece<BITS>(w[u], sc[u], m[u]),
+                                         dst + p0 + u * 64 + lane);
+}
+
+// PPL * 64 pieces of one (selected record, slab) unit of the Load primitive.
+template <int PPL>
+__device__ __forceinline__ void swapin_task(const uint8_t* __restrict__ base, int b, int slab,
+                                            u4_t* __restrict__ dst, const QuantGeom& g, int p0,
+                                            int lane) {
     if (b == 16) {
-        copy_unit(reinterpret_cast<const uint4*>(base) + static_cast<uint64_t>(slab) * g.pieces,
-                  dst, g.pieces, lane);
+        const u4_t* src = reinterpret_cast<const u4_t*>(base) + static_cast<uint64_t>(slab) * g.pieces;
+        u4_t raw[PPL];
+#pragma unroll
+        for (int u = 0; u < PPL; ++u) raw[u] = stream_load<KVS_NT_CODE_LOAD>(src + p0 + u * 64 + lane);
+#pragma unroll
+        for (int u = 0; u < PPL; ++u) stream_store<KVS_NT_CACHE_STORE>(raw[u], dst + p0 + u * 64 + lane);
         return;
     }
     const uint64_t code_bytes = static_cast<uint64_t>(g.pieces) * b;
@@ -268,28 +335,28 @@ __device__ __forceinline__ void swapin_dispatch(const uint8_t* __restrict__ base
     const float* scale = reinterpret_cast<const float*>(base + g.slabs * code_bytes) +
                          static_cast<uint64_t>(slab) * groups;
     const float* mn = scale + static_cast<uint64_t>(g.slabs) * groups;
-    if (b == 8) swapin_unit<8>(codes, scale, mn, dst, g, lane);
-    else if (b == 4) swapin_unit<4>(codes, scale, mn, dst, g, lane);
-    else swapin_unit<2>(codes, scale, mn, dst, g, lane);
+    if (b == 8) swapin_pieces<8, PPL>(codes, scale, mn, dst, p0, lane, g.lpg_log2);
+    else if (b == 4) swapin_pieces<4, PPL>(codes, scale, mn, dst, p0, lane, g.lpg_log2);
+    else swapin_pieces<2, PPL>(codes, scale, mn, dst, p0, lane, g.lpg_log2);
 }
 
-// Grid: ceil(n_sel * slabs / 4) blocks of 256 threads; units slab-major so the
-// cache side is written as forward streams.  Gather lists in device memory.
+// Grid (ceil(n_sel * tpu / 4), slabs), block 256 threads; gather lists in
+// device memory.  With ascending selections the cache side is written as
+// forward streams.
+template <int PPL>
 __global__ __launch_bounds__(256) void swapin_kernel(const uint8_t* __restrict__ packed,
                                                      const uint64_t* __restrict__ src_off,
                                                      const int32_t* __restrict__ dst_tok,
                                                      const uint8_t* __restrict__ sel_bits,
-                                                     uint4* __restrict__ kv_out, QuantGeom g,
+                                                     u4_t* __restrict__ kv_out, QuantGeom g,
                                                      int32_t n_sel) {
     const int lane = threadIdx.x & 63;
-    const int64_t unit = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
-    if (unit >= static_cast<int64_t>(n_sel) * g.slabs) return;
-    const int slab = static_cast<int>(unit / n_sel);
-    const int j = static_cast<int>(unit - static_cast<int64_t>(slab) * n_sel);
-    const int b = __builtin_amdgcn_readfirstlane(static_cast<int>(sel_bits[j]));
-    uint4* dst = kv_out + (static_cast<uint64_t>(slab) * g.n_tokens +
-                           static_cast<uint64_t>(dst_tok[j])) * g.row_pieces;
-    swapin_dispatch(packed + src_off[j], b, slab, dst, g, lane);
+    const int slab = blockIdx.y;
+    int j, p0;
+    if (!wave_task(g, n_sel, PPL, j, p0)) return;
+    u4_t* dst = kv_out + (static_cast<uint64_t>(slab) * g.n_tokens +
+                          static_cast<uint64_t>(dst_tok[j])) * g.row_pieces;
+    swapin_task<PPL>(packed + src_off[j], uniform_byte(sel_bits, j), slab, dst, g, p0, lane);
 }
 
 // Same work for one staged batch of the streaming Load: the (short) gather
@@ -302,19 +369,17 @@ struct SwapinBatch {
     int32_t n;
 };
 
+template <int PPL>
 __global__ __launch_bounds__(256) void swapin_batch_kernel(const uint8_t* __restrict__ staged,
                                                            SwapinBatch list,
-                                                           uint4* __restrict__ kv_out,
-                                                           QuantGeom g) {
+                                                           u4_t* __restrict__ kv_out, QuantGeom g) {
     const int lane = threadIdx.x & 63;
-    const int64_t unit = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
-    if (unit >= static_cast<int64_t>(list.n) * g.slabs) return;
-    const int slab = static_cast<int>(unit / list.n);
-    const int j = static_cast<int>(unit - static_cast<int64_t>(slab) * list.n);
-    const int b = list.bits[j];
-    uint4* dst = kv_out + (static_cast<uint64_t>(slab) * g.n_tokens +
-                           static_cast<uint64_t>(list.dst_tok[j])) * g.row_pieces;
-    swapin_dispatch(staged + list.src_off[j], b, slab, dst, g, lane);
+    const int slab = blockIdx.y;
+    int j, p0;
+    if (!wave_task(g, list.n, PPL, j, p0)) return;
+    u4_t* dst = kv_out + (static_cast<uint64_t>(slab) * g.n_tokens +
+                          static_cast<uint64_t>(list.dst_tok[j])) * g.row_pieces;
+    swapin_task<PPL>(staged + list.src_off[j], list.bits[j], slab, dst, g, p0, lane);
 }
 
 }  // namespace kvs

@@ -223,15 +223,33 @@ __global__ __launch_bounds__(256) void score_combine_kernel(ScoreGeom g, ScoreWs
 }
 
 // density[i] = mean over (layer, head) of chunk_mass[.][i], per token of the chunk.
-__global__ __launch_bounds__(256) void score_density_kernel(const float* __restrict__ chunk_mass,
-                                                            float* __restrict__ density,
-                                                            int32_t n_lh, int32_t n_chunks,
-                                                            float inv_norm) {
-    const int i = blockIdx.x * 256 + threadIdx.x;
-    if (i >= n_chunks) return;
-    float acc = 0.0f;
-    for (int k = 0; k < n_lh; ++k) acc += chunk_mass[static_cast<int64_t>(k) * n_chunks + i];
-    density[i] = acc * inv_norm;
+// Block = 64 chunks x 16 partial sums over the (layer, head) axis; the 16
+// partials are added in a fixed order.
+__global__ __launch_bounds__(1024) void score_density_kernel(const float* __restrict__ chunk_mass,
+                                                             float* __restrict__ density,
+                                                             int32_t n_lh, int32_t n_chunks,
+                                                             float inv_norm) {
+    __shared__ float part[16][64];
+    const int ci = threadIdx.x & 63, p = threadIdx.x >> 6;
+    const int i = blockIdx.x * 64 + ci;
+    float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (i < n_chunks) {
+        int k = p;
+        for (; k + 48 < n_lh; k += 64) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                acc[u] += chunk_mass[static_cast<int64_t>(k + 16 * u) * n_chunks + i];
+        }
+        for (; k < n_lh; k += 16) acc[0] += chunk_mass[static_cast<int64_t>(k) * n_chunks + i];
+    }
+    part[p][ci] = (acc[0] + acc[1]) + (acc[2] + acc[3]);
+    __syncthreads();
+    if (p == 0 && i < n_chunks) {
+        float t = 0.0f;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) t += part[k][ci];
+        density[i] = t * inv_norm;
+    }
 }
 
 }  // namespace kvs
