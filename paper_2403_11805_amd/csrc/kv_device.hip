@@ -142,7 +142,8 @@ static int score_geom(const kv_shape_t* shape, int32_t n_queries, int32_t norm_m
     g.n_rg = (g.n_rb + *nrbw - 1) / *nrbw;
     g.rg_per_wg = std::min(g.n_rg, 4);
     g.tile_par = 4 / g.rg_per_wg;
-    g.tiles_per_wg = 4 * g.tile_par;
+    g.run_len = std::min(g.n_tiles, g.tile_par == 1 ? 16 : 8);
+    g.n_runs = (g.n_tiles + g.run_len - 1) / g.run_len;
     g.norm_mode = norm_mode;
     g.scale_log2e = static_cast<float>(1.4426950408889634 / std::sqrt(static_cast<double>(s.head_dim)));
     *out = g;
@@ -155,12 +156,15 @@ static uint64_t ws_floats_tile(const ScoreGeom& g) {
 static uint64_t ws_floats_sub(const ScoreGeom& g) {
     return static_cast<uint64_t>(g.L) * g.Hq * (g.N / g.sb_tokens) * g.rows_p;
 }
+static uint64_t ws_floats_run(const ScoreGeom& g) {
+    return static_cast<uint64_t>(g.L) * g.Hq * g.n_runs * g.rows_p;
+}
 
 uint64_t kv_score_workspace_bytes(const kv_shape_t* shape, int32_t n_queries) {
     ScoreGeom g;
     int nrbw;
     if (score_geom(shape, n_queries, KV_NORM_VISIBLE, &g, &nrbw) != KV_OK) return 0;
-    const uint64_t bytes = (2 * ws_floats_tile(g) + ws_floats_sub(g)) * sizeof(float);
+    const uint64_t bytes = (ws_floats_tile(g) + ws_floats_sub(g) + 2 * ws_floats_run(g)) * sizeof(float);
     return (bytes + 255) & ~static_cast<uint64_t>(255);
 }
 
@@ -179,10 +183,11 @@ int32_t kv_score_chunks(const kv_shape_t* shape, const void* q, int32_t n_querie
                     static_cast<unsigned long long>(workspace_bytes), static_cast<unsigned long long>(need));
     ScoreWs ws;
     ws.m_tile = static_cast<float*>(workspace);
-    ws.l_tile = ws.m_tile + ws_floats_tile(g);
-    ws.e_sub = ws.l_tile + ws_floats_tile(g);
+    ws.e_sub = ws.m_tile + ws_floats_tile(g);
+    ws.m_run = ws.e_sub + ws_floats_sub(g);
+    ws.l_run = ws.m_run + ws_floats_run(g);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const dim3 grid((g.n_tiles + g.tiles_per_wg - 1) / g.tiles_per_wg,
+    const dim3 grid((g.n_runs + g.tile_par - 1) / g.tile_par,
                     (g.n_rg + g.rg_per_wg - 1) / g.rg_per_wg, g.L * g.Hkv);
     const _Float16* qp = static_cast<const _Float16*>(q);
     const _Float16* kp = static_cast<const _Float16*>(kv);

@@ -3,15 +3,17 @@
 // mean over layers and heads.
 //
 // K is read once.  Kernel 1 sweeps K in tiles of 32 tokens; one wavefront holds
-// one or two blocks of 32 query rows in registers and produces, per tile, the
-// 32x32 logit block with MFMA (K tile as the A operand, so a lane owns one query
-// row and 16 of the tile's tokens, which makes the row reductions mostly
-// in-lane).  Because the softmax denominator of a row is only known after the
-// whole sweep, each tile is exponentiated against its own row maximum and the
-// partial results are written out: per (row, tile) the local maximum and sum,
-// per (row, sub-block of min(T,32) tokens) the weighted sum.  Kernel 2 combines
-// them per (layer, head) into chunk masses; kernel 3 averages over layers and
-// heads.  All reductions run in a fixed order: results are deterministic.
+// one or two blocks of 32 query rows in registers, walks a contiguous run of
+// tiles and produces, per tile, the 32x32 logit block with MFMA (K tile as the A
+// operand, so a lane owns one query row and 16 of the tile's tokens, which makes
+// the row reductions mostly in-lane).  Because the softmax denominator of a row
+// is only known after the whole sweep, each tile is exponentiated against its
+// own row maximum and partial results are written out: per (row, tile) the
+// local maximum, per (row, sub-block of min(T,32) tokens) the weighted sum, and
+// per (row, run) the running maximum and denominator of the run (kept in
+// registers, flash-attention style).  Kernel 2 combines them per (layer, head)
+// into chunk masses; kernel 3 averages over layers and heads.  All reductions
+// run in a fixed order: results are deterministic.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -32,17 +34,22 @@ struct ScoreGeom {
     int32_t n_rb;         // (Hq / Hkv) * RB: row blocks per kv head
     int32_t n_rg;         // row groups (each NRBW row blocks) per kv head
     int32_t rg_per_wg;    // row groups handled by one workgroup (1..4)
-    int32_t tile_par;     // tiles processed in parallel by one workgroup (4 / rg_per_wg)
-    int32_t tiles_per_wg; // consecutive tiles per workgroup
+    int32_t tile_par;     // runs of tiles processed side by side by one workgroup (4 / rg_per_wg)
+    int32_t run_len;      // consecutive tiles per wavefront run
+    int32_t n_runs;       // ceil(n_tiles / run_len): runs per (layer, head)
     int32_t norm_mode;    // 0: divide each column by its number of visible rows; 1: plain sums
     float   scale_log2e;  // log2(e) / sqrt(D)
 };
 
-// Workspace planes (floats): m_tile [L*Hq][n_tiles][rows_p], l_tile same, e_sub [L*Hq][n_sb][rows_p].
+// Workspace planes (floats), row index fastest:
+//   m_tile [L*Hq][n_tiles][rows_p]   tile-local row maximum (log2 units)
+//   e_sub  [L*Hq][n_sb][rows_p]      weighted sum of 2^(s - m_tile) over the sub-block
+//   m_run, l_run [L*Hq][n_runs][rows_p]  maximum and denominator of a run of tiles
 struct ScoreWs {
     float* m_tile;
-    float* l_tile;
     float* e_sub;
+    float* m_run;
+    float* l_run;
 };
 
 __device__ __forceinline__ float xhalf_f(float v) { return __shfl_xor(v, 32); }
@@ -58,15 +65,20 @@ __global__ __launch_bounds__(256) void score_tiles_kernel(const _Float16* __rest
     if (tpar >= g.tile_par) return;
     const int rg = blockIdx.y * g.rg_per_wg + rg_local;
     if (rg >= g.n_rg) return;
+    const int run = blockIdx.x * g.tile_par + tpar;
+    const int tile_begin = run * g.run_len;
+    if (tile_begin >= g.n_tiles) return;
+    const int tile_end = min(tile_begin + g.run_len, g.n_tiles);
     const int l = blockIdx.z / g.Hkv, kvh = blockIdx.z % g.Hkv;
     const int qh_per_kv = g.Hq / g.Hkv;
     const int n_sb = g.N / g.sb_tokens;
     const int sb_per_tile = 32 / g.sb_tokens;
 
-    // query rows of this wave, resident for the whole sweep
+    // query rows of this wave, resident for the whole run
     v8h_t qreg[NRBW][KS];
     int row[NRBW];       // row inside its head, or -1 if padding
     int lh[NRBW];        // layer * Hq + head
+    float m_run[NRBW], l_run[NRBW];
 #pragma unroll
     for (int u = 0; u < NRBW; ++u) {
         const int rb = rg * NRBW + u;
@@ -75,6 +87,8 @@ __global__ __launch_bounds__(256) void score_tiles_kernel(const _Float16* __rest
         const bool ok = rb < g.n_rb && r < g.R;
         row[u] = ok ? r : -1;
         lh[u] = l * g.Hq + (rb < g.n_rb ? head : 0);
+        m_run[u] = -INFINITY;
+        l_run[u] = 0.0f;
         const _Float16* qp = q + (static_cast<int64_t>(lh[u]) * g.R + (ok ? r : 0)) * D + half * 8;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
@@ -86,13 +100,25 @@ __global__ __launch_bounds__(256) void score_tiles_kernel(const _Float16* __rest
 
     const _Float16* kbase = kv + (static_cast<int64_t>(l) * 2 * g.Hkv + kvh) * g.N * D;
     const int first_q_pos = g.N - g.R;
-    const int tile_end = min((blockIdx.x + 1) * g.tiles_per_wg, g.n_tiles);
-    for (int tile = blockIdx.x * g.tiles_per_wg + tpar; tile < tile_end; tile += g.tile_par) {
+    const float w_const = (g.norm_mode == 0) ? 1.0f / static_cast<float>(g.R) : 1.0f;
+    // K tiles are double-buffered in registers: the loads of the next tile are
+    // in flight while the current one goes through MFMA and the softmax.
+    v8h_t knext[KS];
+    {
+        const _Float16* kp = kbase + static_cast<int64_t>(tile_begin * 32 + lrow) * D + half * 8;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) knext[ks] = *reinterpret_cast<const v8h_t*>(kp + ks * 16);
+    }
+    for (int tile = tile_begin; tile < tile_end; ++tile) {
         const int t0 = tile * 32;
         v8h_t kreg[KS];
-        const _Float16* kp = kbase + static_cast<int64_t>(t0 + lrow) * D + half * 8;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) kreg[ks] = *reinterpret_cast<const v8h_t*>(kp + ks * 16);
+        for (int ks = 0; ks < KS; ++ks) kreg[ks] = knext[ks];
+        if (tile + 1 < tile_end) {
+            const _Float16* kp = kbase + static_cast<int64_t>(t0 + 32 + lrow) * D + half * 8;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) knext[ks] = *reinterpret_cast<const v8h_t*>(kp + ks * 16);
+        }
         const bool tail = (t0 + 31 > first_q_pos);   // wave-uniform: some entry may be masked
 #pragma unroll
         for (int u = 0; u < NRBW; ++u) {
@@ -101,50 +127,68 @@ __global__ __launch_bounds__(256) void score_tiles_kernel(const _Float16* __rest
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks)
                 acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(kreg[ks], qreg[u][ks], acc, 0, 0, 0);
-            // acc[v] = logit of (token t0 + 8*(v/4) + 4*half + v%4, query row lrow)
-            float s[16];
-            float mloc = -INFINITY;
-            const int last_visible = (row[u] >= 0) ? first_q_pos + row[u] : -1;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int tk = t0 + 8 * (v / 4) + 4 * half + (v % 4);
-                float x = acc[v] * g.scale_log2e;
-                if (tail || row[u] < 0) x = (tk <= last_visible) ? x : -INFINITY;
-                s[v] = x;
-                mloc = fmaxf(mloc, x);
-            }
-            const float m_t = fmaxf(mloc, xhalf_f(mloc));
-            const float m_use = (m_t == -INFINITY) ? 0.0f : m_t;
-            float lsum = 0.0f;
+            // acc[v] = raw logit of (token t0 + 8*(v/4) + 4*half + v%4, query row lrow)
+            float m_t, lsum;
             float esub[4] = {0.0f, 0.0f, 0.0f, 0.0f};   // up to 4 sub-blocks of 8 tokens
+            if (!tail) {
+                // every entry is visible and every column has the same weight
+                float mloc = acc[0];
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int tk = t0 + 8 * (v / 4) + 4 * half + (v % 4);
-                const float e = __builtin_amdgcn_exp2f(s[v] - m_use);
-                lsum += e;
-                float w = 1.0f;
-                if (g.norm_mode == 0) {
-                    const int vis = g.N - max(tk, first_q_pos);
-                    w = tail ? 1.0f / static_cast<float>(vis) : 1.0f;   // constant 1/R applied below
+                for (int v = 1; v < 16; ++v) mloc = fmaxf(mloc, acc[v]);
+                mloc = fmaxf(mloc, xhalf_f(mloc));
+                m_t = mloc * g.scale_log2e;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(acc[v], g.scale_log2e, -m_t));
+                    if (g.sb_tokens == 8) esub[v / 4] += e;
+                    else if (g.sb_tokens == 16) esub[v / 8] += e;
+                    else esub[0] += e;
                 }
-                const float ew = e * w;
-                // sub-block index inside the tile: token offset / sb_tokens
-                if (g.sb_tokens == 8) esub[v / 4] += ew;
-                else if (g.sb_tokens == 16) esub[v / 8] += ew;
-                else esub[0] += ew;
-            }
-            if (g.norm_mode == 0 && !tail) {
-                const float w = 1.0f / static_cast<float>(g.R);
 #pragma unroll
-                for (int k = 0; k < 4; ++k) esub[k] *= w;
-            }
-            lsum += xhalf_f(lsum);
+                for (int k = 0; k < 4; ++k) esub[k] += xhalf_f(esub[k]);
+                lsum = (esub[0] + esub[1]) + (esub[2] + esub[3]);
 #pragma unroll
-            for (int k = 0; k < 4; ++k) esub[k] += xhalf_f(esub[k]);
+                for (int k = 0; k < 4; ++k) esub[k] *= w_const;
+            } else {
+                float s[16];
+                float mloc = -INFINITY;
+                const int last_visible = (row[u] >= 0) ? first_q_pos + row[u] : -1;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int tk = t0 + 8 * (v / 4) + 4 * half + (v % 4);
+                    const float x = (tk <= last_visible) ? acc[v] * g.scale_log2e : -INFINITY;
+                    s[v] = x;
+                    mloc = fmaxf(mloc, x);
+                }
+                m_t = fmaxf(mloc, xhalf_f(mloc));
+                const float m_use = (m_t == -INFINITY) ? 0.0f : m_t;
+                lsum = 0.0f;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int tk = t0 + 8 * (v / 4) + 4 * half + (v % 4);
+                    const float e = __builtin_amdgcn_exp2f(s[v] - m_use);
+                    lsum += e;
+                    float w = 1.0f;
+                    if (g.norm_mode == 0) w = 1.0f / static_cast<float>(g.N - max(tk, first_q_pos));
+                    const float ew = e * w;
+                    if (g.sb_tokens == 8) esub[v / 4] += ew;
+                    else if (g.sb_tokens == 16) esub[v / 8] += ew;
+                    else esub[0] += ew;
+                }
+                lsum += xhalf_f(lsum);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) esub[k] += xhalf_f(esub[k]);
+            }
+            // running maximum / denominator of this run
+            {
+                const float m_new = fmaxf(m_run[u], m_t);
+                const float m_safe = (m_new == -INFINITY) ? 0.0f : m_new;
+                l_run[u] = l_run[u] * __builtin_amdgcn_exp2f(m_run[u] - m_safe) +
+                           lsum * __builtin_amdgcn_exp2f(m_t - m_safe);
+                m_run[u] = m_new;
+            }
             if (half == 0 && row[u] >= 0) {
-                const int64_t ti = (static_cast<int64_t>(lh[u]) * g.n_tiles + tile) * g.rows_p + row[u];
-                ws.m_tile[ti] = m_t;
-                ws.l_tile[ti] = lsum;
+                ws.m_tile[(static_cast<int64_t>(lh[u]) * g.n_tiles + tile) * g.rows_p + row[u]] = m_t;
                 for (int k = 0; k < sb_per_tile; ++k) {
                     const int64_t ei = (static_cast<int64_t>(lh[u]) * n_sb + tile * sb_per_tile + k) *
                                        g.rows_p + row[u];
@@ -153,10 +197,18 @@ __global__ __launch_bounds__(256) void score_tiles_kernel(const _Float16* __rest
             }
         }
     }
+#pragma unroll
+    for (int u = 0; u < NRBW; ++u) {
+        if (half == 0 && row[u] >= 0) {
+            const int64_t ri = (static_cast<int64_t>(lh[u]) * g.n_runs + run) * g.rows_p + row[u];
+            ws.m_run[ri] = m_run[u];
+            ws.l_run[ri] = l_run[u];
+        }
+    }
 }
 
 // One workgroup per (layer, head): global row maximum and denominator from
-// the per-tile partials, then the chunk masses.
+// the per-run partials, then the chunk masses from the per-tile partials.
 __global__ __launch_bounds__(256) void score_combine_kernel(ScoreGeom g, ScoreWs ws,
                                                             float* __restrict__ chunk_mass) {
     __shared__ float sh_m[256];
@@ -167,13 +219,13 @@ __global__ __launch_bounds__(256) void score_combine_kernel(ScoreGeom g, ScoreWs
     const int tid = threadIdx.x;
     const int parts = 256 / g.rows_p;            // rows_p in {32,...,256}
     const int r = tid % g.rows_p, part = tid / g.rows_p;
-    const float* mt = ws.m_tile + static_cast<int64_t>(lh) * g.n_tiles * g.rows_p;
-    const float* lt = ws.l_tile + static_cast<int64_t>(lh) * g.n_tiles * g.rows_p;
+    const float* mr = ws.m_run + static_cast<int64_t>(lh) * g.n_runs * g.rows_p;
+    const float* lr = ws.l_run + static_cast<int64_t>(lh) * g.n_runs * g.rows_p;
     float m = -INFINITY, lsum = 0.0f;
     if (part < parts && r < g.R) {
-        for (int t = part; t < g.n_tiles; t += parts) {
-            const float mi = mt[static_cast<int64_t>(t) * g.rows_p + r];
-            const float li = lt[static_cast<int64_t>(t) * g.rows_p + r];
+        for (int t = part; t < g.n_runs; t += parts) {
+            const float mi = mr[static_cast<int64_t>(t) * g.rows_p + r];
+            const float li = lr[static_cast<int64_t>(t) * g.rows_p + r];
             if (mi > m) {
                 lsum = lsum * __builtin_amdgcn_exp2f(m - mi) + li;   // m == -inf: lsum is 0
                 m = mi;
@@ -199,6 +251,7 @@ __global__ __launch_bounds__(256) void score_combine_kernel(ScoreGeom g, ScoreWs
     __syncthreads();
 
     // chunk masses: 32 lanes per chunk, lane <-> row (coalesced), fixed-order sums
+    const float* mt = ws.m_tile + static_cast<int64_t>(lh) * g.n_tiles * g.rows_p;
     const int n_chunks = g.N / g.T;
     const int sb_per_chunk = g.T / g.sb_tokens;
     const int sb_per_tile = 32 / g.sb_tokens;
