@@ -4,14 +4,16 @@
 //
 // Work unit: one (chunk, slab) pair = chunk_tokens x head_dim contiguous fp16
 // on the cache side and one contiguous run of code bytes on the record side.
-// A lane owns one "piece" of 8 consecutive elements (one 16-byte cache access)
-// and a wavefront owns 64 consecutive pieces (1 KiB of cache): the shape that
-// streams fastest from HBM on this part is the plainest one, a single 16-byte
-// access per lane with as many independent wavefronts in flight as possible.
-// A quantisation group of G elements is spread over G/8 neighbouring lanes, so
-// its min/max is a short DPP butterfly.  A wavefront task is PPL * 64 pieces of
-// one unit; its chunk index is wave-uniform, so the bit-width and the record
-// offset are scalar loads and the branch on the width is uniform.
+// A lane owns "pieces" of 8 consecutive elements (one 16-byte cache access); a
+// wavefront instruction touches 64 consecutive pieces (1 KiB of cache), fully
+// coalesced.  A quantisation group of G elements is spread over G/8
+// neighbouring lanes, so its min/max is a short DPP butterfly.  A wavefront
+// task is PPL * 64 pieces of one unit, all loads issued before any arithmetic:
+// measured on MI355X, one piece per lane streams best for a plain copy, but
+// the quantising paths need 4 to amortise the dependent scalar loads of the
+// per-chunk lists and to hide their arithmetic.  The chunk index of a task is
+// wave-uniform, so the bit-width and the record offset are scalar loads and
+// the branch on the width is uniform.
 #pragma once
 
 #include <hip/hip_runtime.h>

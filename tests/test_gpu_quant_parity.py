@@ -57,6 +57,10 @@ def test_tiny_workload_full():
     (2, 1, 1, 64, 64, 8, 64),
     (1, 1, 1, 1024, 6, 2, 128),
     (1, 5, 5, 128, 2048, 1024, 64),  # the largest chunk
+    (1, 2, 2, 64, 72, 24, 64),       # 3 wavefront tasks per unit (not a power of two), 1 piece per lane
+    (2, 1, 1, 64, 144, 48, 64),      # 6 -> 2 pieces per lane, 3 tasks per unit
+    (1, 1, 2, 128, 96, 48, 128),     # 12 -> 4 pieces per lane, 3 tasks per unit
+    (1, 1, 1, 64, 40, 8, 64),        # one task per unit, 5 chunks: last workgroup partly idle
 ])
 def test_shapes_and_mixed_widths(geom):
     g = synth.Geometry(*geom)
