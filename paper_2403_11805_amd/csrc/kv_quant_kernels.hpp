@@ -34,6 +34,8 @@ struct QuantGeom {
     int32_t lpg_log2;      // log2(G / 8): lanes per quantisation group (3..6)
     int32_t tpu;           // wavefront tasks per unit = pieces / (64 * pieces-per-lane)
     int32_t tpu_shift;     // log2(tpu) if tpu is a power of two, else -1
+    int32_t record_major;  // task order: 0 = walk the chunks of one slab (cache side is one
+                           // stream), 1 = walk the slabs of one chunk (record side is one stream)
 };
 
 constexpr int kWavesPerBlock = 4;
@@ -49,11 +51,11 @@ __device__ __forceinline__ int uniform_byte(const uint8_t* list, int i) {
 // Wavefront task -> (unit index along y, first piece).  Task ids are uniform
 // per wavefront; readfirstlane keeps everything derived from them in SGPRs, so
 // the per-chunk list entries become scalar loads and the width branch is uniform.
-__device__ __forceinline__ bool wave_task(const QuantGeom& g, int n_units, int ppl, int& unit,
-                                          int& piece0) {
+__device__ __forceinline__ bool wave_task(const QuantGeom& g, int n_chunks, int ppl, int& chunk,
+                                          int& slab, int& piece0) {
     const int wave = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6));
     const int t = blockIdx.x * kWavesPerBlock + wave;
-    int sub;
+    int unit, sub;
     if (g.tpu_shift >= 0) {
         unit = t >> g.tpu_shift;
         sub = t & (g.tpu - 1);
@@ -62,7 +64,14 @@ __device__ __forceinline__ bool wave_task(const QuantGeom& g, int n_units, int p
         sub = t - unit * g.tpu;
     }
     piece0 = sub * 64 * ppl;
-    return unit < n_units;
+    if (g.record_major) {
+        slab = unit;
+        chunk = blockIdx.y;
+        return unit < g.slabs;
+    }
+    chunk = unit;
+    slab = blockIdx.y;
+    return unit < n_chunks;
 }
 
 // Streaming accesses: every byte is touched once.  Whether marking them
@@ -222,9 +231,8 @@ __device__ __forceinline__ void compress_piece(const u4_t& raw, uint8_t* __restr
     }
 }
 
-// Grid (ceil(n_chunks * tpu / 4), slabs), block 256 threads = 4 wavefront
-// tasks of PPL * 64 pieces each.  Tasks run along the token axis of one slab, so
-// the cache side is read as one forward stream.
+// Grid (ceil(n_chunks * tpu / 4), slabs) or, record-major, (ceil(slabs * tpu / 4),
+// n_chunks); block 256 threads = 4 wavefront tasks of PPL * 64 pieces each.
 template <int PPL>
 __global__ __launch_bounds__(256) void compress_kernel(const u4_t* __restrict__ kv,
                                                        const uint8_t* __restrict__ bits,
@@ -232,9 +240,8 @@ __global__ __launch_bounds__(256) void compress_kernel(const u4_t* __restrict__ 
                                                        uint8_t* __restrict__ packed, QuantGeom g,
                                                        int32_t n_chunks) {
     const int lane = threadIdx.x & 63;
-    const int slab = blockIdx.y;
-    int chunk, p0;
-    if (!wave_task(g, n_chunks, PPL, chunk, p0)) return;
+    int chunk, slab, p0;
+    if (!wave_task(g, n_chunks, PPL, chunk, slab, p0)) return;
     const u4_t* src = kv + (static_cast<uint64_t>(slab) * g.n_tokens +
                             static_cast<uint64_t>(chunk) * g.chunk_tokens) * g.row_pieces;
     u4_t raw[PPL];
@@ -342,9 +349,8 @@ __device__ __forceinline__ void swapin_task(const uint8_t* __restrict__ base, in
     else swapin_pieces<2, PPL>(codes, scale, mn, dst, p0, lane, g.lpg_log2);
 }
 
-// Grid (ceil(n_sel * tpu / 4), slabs), block 256 threads; gather lists in
-// device memory.  With ascending selections the cache side is written as
-// forward streams.
+// Grid as for compress_kernel with the n_sel listed records in the place of
+// the chunks; gather lists in device memory.
 template <int PPL>
 __global__ __launch_bounds__(256) void swapin_kernel(const uint8_t* __restrict__ packed,
                                                      const uint64_t* __restrict__ src_off,
@@ -353,9 +359,8 @@ __global__ __launch_bounds__(256) void swapin_kernel(const uint8_t* __restrict__
                                                      u4_t* __restrict__ kv_out, QuantGeom g,
                                                      int32_t n_sel) {
     const int lane = threadIdx.x & 63;
-    const int slab = blockIdx.y;
-    int j, p0;
-    if (!wave_task(g, n_sel, PPL, j, p0)) return;
+    int j, slab, p0;
+    if (!wave_task(g, n_sel, PPL, j, slab, p0)) return;
     u4_t* dst = kv_out + (static_cast<uint64_t>(slab) * g.n_tokens +
                           static_cast<uint64_t>(dst_tok[j])) * g.row_pieces;
     swapin_task<PPL>(packed + src_off[j], uniform_byte(sel_bits, j), slab, dst, g, p0, lane);
@@ -376,9 +381,8 @@ __global__ __launch_bounds__(256) void swapin_batch_kernel(const uint8_t* __rest
                                                            SwapinBatch list,
                                                            u4_t* __restrict__ kv_out, QuantGeom g) {
     const int lane = threadIdx.x & 63;
-    const int slab = blockIdx.y;
-    int j, p0;
-    if (!wave_task(g, list.n, PPL, j, p0)) return;
+    int j, slab, p0;
+    if (!wave_task(g, list.n, PPL, j, slab, p0)) return;
     u4_t* dst = kv_out + (static_cast<uint64_t>(slab) * g.n_tokens +
                           static_cast<uint64_t>(list.dst_tok[j])) * g.row_pieces;
     swapin_task<PPL>(staged + list.src_off[j], list.bits[j], slab, dst, g, p0, lane);
