@@ -48,7 +48,7 @@ __device__ __forceinline__ int uniform_byte(const uint8_t* list, int i) {
     return static_cast<int>((w >> ((a & 3) * 8)) & 0xffu);
 }
 
-// Wavefront task -> (unit index along y, first piece).  Task ids are uniform
+// Wavefront task -> (chunk or list index, slab, first piece).  Task ids are uniform
 // per wavefront; readfirstlane keeps everything derived from them in SGPRs, so
 // the per-chunk list entries become scalar loads and the width branch is uniform.
 __device__ __forceinline__ bool wave_task(const QuantGeom& g, int n_chunks, int ppl, int& chunk,
@@ -234,7 +234,7 @@ __device__ __forceinline__ void compress_piece(const u4_t& raw, uint8_t* __restr
 // Grid (ceil(n_chunks * tpu / 4), slabs) or, record-major, (ceil(slabs * tpu / 4),
 // n_chunks); block 256 threads = 4 wavefront tasks of PPL * 64 pieces each.
 template <int PPL>
-__global__ __launch_bounds__(256) void compress_kernel(const u4_t* __restrict__ kv,
+__global__ __launch_bounds__(64 * kWavesPerBlock) void compress_kernel(const u4_t* __restrict__ kv,
                                                        const uint8_t* __restrict__ bits,
                                                        const uint64_t* __restrict__ off,
                                                        uint8_t* __restrict__ packed, QuantGeom g,
@@ -352,7 +352,7 @@ __device__ __forceinline__ void swapin_task(const uint8_t* __restrict__ base, in
 // Grid as for compress_kernel with the n_sel listed records in the place of
 // the chunks; gather lists in device memory.
 template <int PPL>
-__global__ __launch_bounds__(256) void swapin_kernel(const uint8_t* __restrict__ packed,
+__global__ __launch_bounds__(64 * kWavesPerBlock) void swapin_kernel(const uint8_t* __restrict__ packed,
                                                      const uint64_t* __restrict__ src_off,
                                                      const int32_t* __restrict__ dst_tok,
                                                      const uint8_t* __restrict__ sel_bits,
@@ -377,7 +377,7 @@ struct SwapinBatch {
 };
 
 template <int PPL>
-__global__ __launch_bounds__(256) void swapin_batch_kernel(const uint8_t* __restrict__ staged,
+__global__ __launch_bounds__(64 * kWavesPerBlock) void swapin_batch_kernel(const uint8_t* __restrict__ staged,
                                                            SwapinBatch list,
                                                            u4_t* __restrict__ kv_out, QuantGeom g) {
     const int lane = threadIdx.x & 63;
