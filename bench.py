@@ -163,7 +163,7 @@ def read_traffic(workload, kernel):
     path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
     try:
         for line in open(path):
-            parts = line.split()
+            parts = line.replace("traffic_bytes=", " traffic_bytes=").split()
             if len(parts) >= 2 and parts[0] == kernel and parts[1].startswith("traffic_bytes="):
                 return int(float(parts[1].split("=", 1)[1]))
     except OSError:
