@@ -113,6 +113,26 @@ int32_t kv_chunk_offsets(const kv_shape_t* shape, const uint8_t* bits, uint64_t*
 int32_t kv_bits_from_scores(const float* density, int32_t n, int32_t num8,
                             int32_t num4, int32_t den, uint8_t* bits);
 
+/* Thresholds from a global ratio (Sec. 3.2, Eq. 2 and Eq. 3) for the paper's
+ * three levels {8/8, 4/8, 2/8}: chunks are ranked as in kv_bits_from_scores and
+ * the k8 densest get 8 bits, the next k4 get 4 bits, the remaining k2 get 2 bits,
+ * where (k8, k4, k2) maximises
+ *     ctxInfo = w8 * S8 + w4 * S4 + w2 * S2      (S = sum of densities in the bucket)
+ * subject to the average ratio (k8 + k4/2 + k2/4) / n being the largest value
+ * not above ratio_num / ratio_den.  That leaves one free variable, k8:
+ * 3*k8 + k4 = M = floor(n * (4*ratio_num - ratio_den) / ratio_den), k2 = n - k8 - k4,
+ * and every feasible k8 is tried.  objective selects the weights:
+ *   KV_OBJ_BITS_TO_DENSE  (w8, w4, w2) = (1, 1/2, 1/4) = ratio_w: the reading that
+ *                          gives denser chunks more bits (the stated intent);
+ *   KV_OBJ_AS_PRINTED     (1, 2, 4) = 1 / ratio_w: Eq. 3 exactly as printed.
+ * Sums are accumulated in double in rank order; of equal maxima the smallest k8
+ * wins.  density, bits: host [n]; counts (may be NULL): host [3] = k8, k4, k2.
+ * Requires n >= 0, ratio_den > 0, 1/4 <= ratio_num/ratio_den <= 1. */
+enum { KV_OBJ_BITS_TO_DENSE = 0, KV_OBJ_AS_PRINTED = 1 };
+int32_t kv_bits_optimise(const float* density, int32_t n, int32_t ratio_num,
+                         int32_t ratio_den, int32_t objective, uint8_t* bits,
+                         int32_t* counts);
+
 /* Load primitive, list building (Sec. 3.1, primitive 3): for n_sel strictly
  * ascending chunk indices produce src_off[j] = off[idx_j], dst_tok[j] =
  * idx_j*chunk_tokens, sel_bits[j] = bits[idx_j].  All pointers host. */

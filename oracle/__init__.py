@@ -18,6 +18,7 @@ import numpy as np
 from .hostlogic import (  # noqa: F401  (re-exported)
     LctruModel,
     bits_from_scores,
+    bits_optimise,
     build_gather,
     chunk_offsets,
     record_bytes,

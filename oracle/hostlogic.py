@@ -47,6 +47,44 @@ def bits_from_scores(density, num8: int, num4: int, den: int) -> np.ndarray:
     return bits
 
 
+def bits_optimise(density, ratio_num: int, ratio_den: int, as_printed: bool = False):
+    """Thresholds of Eq. 2 chosen by Eq. 3 for the levels {8/8, 4/8, 2/8}.
+
+    Chunks are ranked densest first (ties: lower index).  With k8 chunks at 8
+    bits, k4 at 4 and k2 at 2, the average ratio (k8 + k4/2 + k2/4)/n has to be
+    the largest value that does not exceed ratio_num/ratio_den; that fixes
+    3*k8 + k4 = M = floor(n*(4*ratio - 1)) and leaves k8 free.  Every feasible k8
+    is evaluated: ctxInfo = sum_w weight_w * (sum of densities in bucket w), with
+    weight_w = ratio_w (denser chunks should get more bits) or, as_printed,
+    1/ratio_w (the formula as printed).  The first maximum (smallest k8) wins.
+    Returns (bits, (k8, k4, k2))."""
+    d = [float(np.float32(x)) for x in density]
+    n = len(d)
+    order = sorted(range(n), key=lambda i: (-d[i], i))
+    prefix = [0.0]
+    for i in order:
+        prefix.append(prefix[-1] + d[i])
+    w8, w4, w2 = (1.0, 2.0, 4.0) if as_printed else (1.0, 0.5, 0.25)
+    M = n * (4 * ratio_num - ratio_den) // ratio_den
+    best = None
+    for k8 in range(0, n + 1):
+        k4 = M - 3 * k8
+        k2 = n - k8 - k4
+        if k4 < 0 or k2 < 0:
+            continue
+        s8 = prefix[k8]
+        s4 = prefix[k8 + k4] - prefix[k8]
+        s2 = prefix[n] - prefix[k8 + k4]
+        info = w8 * s8 + w4 * s4 + w2 * s2
+        if best is None or info > best[0]:
+            best = (info, k8, k4, k2)
+    _, k8, k4, k2 = best
+    bits = np.zeros(n, dtype=np.uint8)
+    for rank, i in enumerate(order):
+        bits[i] = 8 if rank < k8 else (4 if rank < k8 + k4 else 2)
+    return bits, (k8, k4, k2)
+
+
 def build_gather(shape, off, bits, chunk_idx):
     """Gather list for loading the chunks `chunk_idx` (strictly ascending):
     where each record starts, which token it lands on, and its bit-width."""

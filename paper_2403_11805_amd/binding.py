@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libkvswitch.so")
 
 KV_OK, KV_EINVAL, KV_ESHAPE, KV_EBITS, KV_EINDEX, KV_ENOMEM, KV_EHIP = 0, -1, -2, -3, -4, -5, -6
 KV_NORM_VISIBLE, KV_NORM_NONE = 0, 1
+KV_OBJ_BITS_TO_DENSE, KV_OBJ_AS_PRINTED = 0, 1
 
 
 class KvError(RuntimeError):
@@ -64,6 +65,7 @@ _SIGNATURES = {
     "kv_record_bytes": (_u64, [_vp, _i32]),
     "kv_chunk_offsets": (_i32, [_vp, _vp, _vp]),
     "kv_bits_from_scores": (_i32, [_vp, _i32, _i32, _i32, _i32, _vp]),
+    "kv_bits_optimise": (_i32, [_vp, _i32, _i32, _i32, _i32, _vp, _vp]),
     "kv_build_gather": (_i32, [_vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp]),
     "kv_score_workspace_bytes": (_u64, [_vp, _i32]),
     "kv_score_chunks": (_i32, [_vp, _vp, _i32, _vp, _i32, _vp, _u64, _vp, _vp, _vp]),
@@ -161,6 +163,16 @@ def kv_bits_from_scores(density, num8: int, num4: int, den: int) -> np.ndarray:
     bits = np.empty(len(density), dtype=np.uint8)
     _check(lib().kv_bits_from_scores(_hp(density), len(density), num8, num4, den, _hp(bits)))
     return bits
+
+
+def kv_bits_optimise(density, ratio_num: int, ratio_den: int, objective: int = KV_OBJ_BITS_TO_DENSE):
+    """-> (bits uint8 [n], (k8, k4, k2))."""
+    density = _np(density, np.float32)
+    bits = np.empty(len(density), dtype=np.uint8)
+    counts = np.zeros(3, dtype=np.int32)
+    _check(lib().kv_bits_optimise(_hp(density), len(density), ratio_num, ratio_den, objective,
+                                  _hp(bits), _hp(counts)))
+    return bits, tuple(int(c) for c in counts)
 
 
 def kv_build_gather(shape: Shape, off, bits, chunk_idx):

@@ -98,6 +98,53 @@ int32_t kv_bits_from_scores(const float* density, int32_t n, int32_t num8, int32
     return KV_OK;
 }
 
+int32_t kv_bits_optimise(const float* density, int32_t n, int32_t ratio_num, int32_t ratio_den,
+                         int32_t objective, uint8_t* bits, int32_t* counts) {
+    if (n < 0 || ratio_den <= 0 || ratio_num <= 0) return fail(KV_EINVAL, "need n >= 0 and a positive ratio");
+    if (static_cast<int64_t>(ratio_num) * 4 < ratio_den || ratio_num > ratio_den)
+        return fail(KV_EINVAL, "ratio %d/%d outside [1/4, 1]", ratio_num, ratio_den);
+    if (objective != KV_OBJ_BITS_TO_DENSE && objective != KV_OBJ_AS_PRINTED)
+        return fail(KV_EINVAL, "objective %d unknown", objective);
+    if (n > 0 && (!density || !bits)) return fail(KV_EINVAL, "density/bits is NULL");
+    std::vector<int32_t> order(static_cast<size_t>(n));
+    std::iota(order.begin(), order.end(), 0);
+    std::stable_sort(order.begin(), order.end(),
+                     [&](int32_t a, int32_t b) { return density[a] > density[b]; });
+    // prefix[k] = sum of the k densest, accumulated in rank order
+    std::vector<double> prefix(static_cast<size_t>(n) + 1, 0.0);
+    for (int32_t k = 0; k < n; ++k)
+        prefix[static_cast<size_t>(k) + 1] = prefix[static_cast<size_t>(k)] +
+                                             static_cast<double>(density[order[static_cast<size_t>(k)]]);
+    const double w8 = 1.0;
+    const double w4 = objective == KV_OBJ_BITS_TO_DENSE ? 0.5 : 2.0;
+    const double w2 = objective == KV_OBJ_BITS_TO_DENSE ? 0.25 : 4.0;
+    const int64_t M = static_cast<int64_t>(n) * (4LL * ratio_num - ratio_den) / ratio_den;
+    const int64_t k8_lo = std::max<int64_t>(0, (M - n + 1) / 2);   // k2 = n - M + 2*k8 >= 0
+    const int64_t k8_hi = M / 3;                                   // k4 = M - 3*k8 >= 0
+    int64_t best_k8 = k8_lo;
+    double best = 0.0;
+    for (int64_t k8 = k8_lo; k8 <= k8_hi; ++k8) {
+        const int64_t k4 = M - 3 * k8;
+        const double s8 = prefix[static_cast<size_t>(k8)];
+        const double s4 = prefix[static_cast<size_t>(k8 + k4)] - prefix[static_cast<size_t>(k8)];
+        const double s2 = prefix[static_cast<size_t>(n)] - prefix[static_cast<size_t>(k8 + k4)];
+        const double info = w8 * s8 + w4 * s4 + w2 * s2;
+        if (k8 == k8_lo || info > best) {
+            best = info;
+            best_k8 = k8;
+        }
+    }
+    const int64_t k4 = M - 3 * best_k8;
+    for (int64_t r = 0; r < n; ++r)
+        bits[order[static_cast<size_t>(r)]] = r < best_k8 ? 8 : (r < best_k8 + k4 ? 4 : 2);
+    if (counts) {
+        counts[0] = static_cast<int32_t>(best_k8);
+        counts[1] = static_cast<int32_t>(k4);
+        counts[2] = static_cast<int32_t>(n - best_k8 - k4);
+    }
+    return KV_OK;
+}
+
 int32_t kv_build_gather(const kv_shape_t* shape, const uint64_t* off, const uint8_t* bits,
                         const int32_t* chunk_idx, int32_t n_sel, uint64_t* src_off,
                         int32_t* dst_tok, uint8_t* sel_bits) {

@@ -178,3 +178,22 @@ def test_lctru_pool_workload_order():
     with pytest.raises(kvs.KvError):
         q.insert(0, 0, 8, 1, 1) if (0, 0) in m.entries else q.insert(1, 1, 3, 1, 1)
     q.close()
+
+
+def test_bits_optimise_matches_oracle():
+    rng = np.random.default_rng(11)
+    for n in (0, 1, 2, 3, 7, 12, 100, 256, 1024):
+        for (num, den) in ((1, 2), (1, 4), (1, 1), (3, 8), (5, 8), (2, 3)):
+            for printed in (0, 1):
+                d = (rng.random(n) ** 3).astype(np.float32)
+                if n > 4:
+                    d[rng.integers(0, n, size=n // 4)] = 0.25
+                got_bits, got_counts = kvs.kv_bits_optimise(d, num, den, printed)
+                want_bits, want_counts = oracle.bits_optimise(d, num, den, bool(printed))
+                assert got_counts == want_counts, (n, num, den, printed)
+                assert np.array_equal(got_bits, want_bits)
+    for bad in ((1, 5), (3, 2), (0, 1), (1, 0)):
+        with pytest.raises(kvs.KvError):
+            kvs.kv_bits_optimise(np.ones(4, dtype=np.float32), bad[0], bad[1], 0)
+    with pytest.raises(kvs.KvError):
+        kvs.kv_bits_optimise(np.ones(4, dtype=np.float32), 1, 2, 7)

@@ -94,3 +94,83 @@ def test_lctru_heavy_first_then_least_recent_and_lock():
     q.remove_ctx(1)
     assert q.size() == (4, 180)
     assert q.evict(0) == []
+
+
+# ------------------------------------------------------------------ thresholds from a global ratio (Eq. 2 / Eq. 3)
+
+def ctx_info(density, bits, weights):
+    return sum(weights[int(b)] * float(np.float32(d)) for d, b in zip(density, bits))
+
+
+def test_optimised_thresholds_meet_the_global_ratio():
+    """Levels {8/8, 4/8, 2/8} at a global ratio of 50 % (the paper's setting, Sec. 3.2
+    micro experiments and Sec. 4): the mean of the per-chunk ratios must be 1/2."""
+    rng = np.random.default_rng(0)
+    for n in (12, 48, 256):
+        d = rng.random(n).astype(np.float32)
+        for printed in (False, True):
+            bits, (k8, k4, k2) = oracle.bits_optimise(d, 1, 2, printed)
+            assert k8 + k4 + k2 == n and [(bits == b).sum() for b in (8, 4, 2)] == [k8, k4, k2]
+            assert k8 * 1.0 + k4 * 0.5 + k2 * 0.25 == n * 0.5
+            # Eq. 2: buckets follow the ranking, densest chunks in the least compressed bucket
+            if k8 and k4:
+                assert d[bits == 8].min() >= d[bits == 4].max()
+            if k2 and (k4 or k8):
+                assert d[bits != 2].min() >= d[bits == 2].max()
+    # other ratios: the largest average that does not exceed the target
+    d = rng.random(10).astype(np.float32)
+    for num, den in ((1, 4), (1, 1), (3, 8), (5, 8), (2, 3)):
+        bits, (k8, k4, k2) = oracle.bits_optimise(d, num, den)
+        avg = (k8 + k4 / 2 + k2 / 4) / 10
+        assert avg <= num / den + 1e-12 and avg + 0.025 > num / den
+    assert oracle.bits_optimise(d, 1, 4)[1] == (0, 0, 10) and oracle.bits_optimise(d, 1, 1)[1] == (10, 0, 0)
+
+
+def test_optimised_thresholds_against_brute_force():
+    """Weights = ratio_w: no assignment of widths with the same bit budget (not only the
+    rank-ordered ones) has a larger ctxInfo."""
+    import itertools
+    rng = np.random.default_rng(1)
+    w = {8: 1.0, 4: 0.5, 2: 0.25}
+    for trial in range(6):
+        n = int(rng.integers(3, 9))
+        d = rng.random(n).astype(np.float32)
+        if trial % 2:
+            d[rng.integers(0, n, size=2)] = 0.5          # ties
+        for num, den in ((1, 2), (5, 8)):
+            bits, (k8, k4, k2) = oracle.bits_optimise(d, num, den)
+            budget = 4 * k8 + 2 * k4 + k2
+            best = max(ctx_info(d, a, w) for a in itertools.product((8, 4, 2), repeat=n)
+                       if sum(x // 2 for x in a) == budget)
+            assert ctx_info(d, bits, w) == pytest.approx(best, rel=1e-12)
+
+
+def test_optimised_thresholds_closed_forms():
+    """One free variable: k4 = n - 3*k8, k2 = 2*k8 at a 50 % ratio.
+    Weights ratio_w: ctxInfo rises with k8 whenever densities differ -> k8 = n // 3.
+    Weights 1/ratio_w (as printed): d ctxInfo / d k8 = 4*D(rank n-2*k8) - D(rank k8);
+    with a fraction `a` of chunks at density H and the rest at 1 the optimum is
+    k8 = n/3 if a*(H-1) < 1 and k8 = 0 if a*(H-1) > 1; equal densities -> k8 = n/3."""
+    n = 12
+    distinct = np.linspace(1.0, 2.0, n).astype(np.float32)
+    assert oracle.bits_optimise(distinct, 1, 2)[1] == (4, 0, 8)
+    assert oracle.bits_optimise(np.ones(n, dtype=np.float32), 1, 2)[1] == (0, 12, 0)   # all equal: first maximum
+    assert oracle.bits_optimise(np.ones(n, dtype=np.float32), 1, 2, True)[1] == (4, 0, 8)
+    two = np.ones(n, dtype=np.float32)
+    two[[3, 7]] = 4.0             # a = 1/6, H = 4: a*(H-1) = 0.5 < 1
+    bits, counts = oracle.bits_optimise(two, 1, 2, True)
+    assert counts == (4, 0, 8) and bits[3] == 8 and bits[7] == 8
+    two[[3, 7]] = 10.0            # a*(H-1) = 1.5 > 1: every chunk stays at 4 bits
+    assert oracle.bits_optimise(two, 1, 2, True)[1] == (0, 12, 0)
+    # the printed objective at its optimum is not below its neighbours
+    rng = np.random.default_rng(5)
+    d = (rng.random(60) ** 4).astype(np.float32)
+    w = {8: 1.0, 4: 2.0, 2: 4.0}
+    bits, (k8, k4, k2) = oracle.bits_optimise(d, 1, 2, True)
+    order = sorted(range(60), key=lambda i: (-float(d[i]), i))
+    for k in (k8 - 1, k8 + 1):
+        if 0 <= k <= 20:
+            alt = np.zeros(60, dtype=np.uint8)
+            for rank, i in enumerate(order):
+                alt[i] = 8 if rank < k else (4 if rank < k + 60 - 3 * k else 2)
+            assert ctx_info(d, bits, w) >= ctx_info(d, alt, w)
