@@ -153,7 +153,9 @@ static int score_geom(const kv_shape_t* shape, int32_t n_queries, int32_t norm_m
     *nrbw = g.n_rb == 1 ? 1 : 2;
     g.n_rg = (g.n_rb + *nrbw - 1) / *nrbw;
     g.rg_per_wg = std::min(g.n_rg, 4);
-    g.tile_par = 4 / g.rg_per_wg;
+    // several row groups per kv head: the workgroup shares each K tile through LDS and all
+    // its wavefronts walk the same run; a single row group: four independent runs per workgroup
+    g.tile_par = g.rg_per_wg > 1 ? 1 : 4;
     g.run_len = std::min(g.n_tiles, g.tile_par == 1 ? 16 : 8);
     g.n_runs = (g.n_tiles + g.run_len - 1) / g.run_len;
     g.norm_mode = norm_mode;
@@ -203,8 +205,13 @@ int32_t kv_score_chunks(const kv_shape_t* shape, const void* q, int32_t n_querie
                     (g.n_rg + g.rg_per_wg - 1) / g.rg_per_wg, g.L * g.Hkv);
     const _Float16* qp = static_cast<const _Float16*>(q);
     const _Float16* kp = static_cast<const _Float16*>(kv);
-#define KV_SCORE_LAUNCH(DD, NR) \
-    hipLaunchKernelGGL((score_tiles_kernel<DD, NR>), grid, dim3(256), 0, st, qp, kp, g, ws)
+#define KV_SCORE_LAUNCH(DD, NR)                                                                       \
+    do {                                                                                             \
+        if (g.rg_per_wg > 1)                                                                         \
+            hipLaunchKernelGGL((score_tiles_shared_kernel<DD, NR>), grid, dim3(256), 0, st, qp, kp, g, ws); \
+        else                                                                                         \
+            hipLaunchKernelGGL((score_tiles_kernel<DD, NR>), grid, dim3(256), 0, st, qp, kp, g, ws);  \
+    } while (0)
     const int D = shape->head_dim;
     if (D == 64 && nrbw == 1) KV_SCORE_LAUNCH(64, 1);
     else if (D == 64) KV_SCORE_LAUNCH(64, 2);

@@ -52,7 +52,119 @@ struct ScoreWs {
     float* l_run;
 };
 
-__device__ __forceinline__ float xhalf_f(float v) { return __shfl_xor(v, 32); }
+// Lanes 0-31 and 32-63 of a wavefront hold the two halves of a row's tokens.
+// v_permlane32_swap returns (low half in both halves, high half in both halves),
+// so one VALU-speed instruction plus the combining op gives every lane the
+// reduction over both halves, with no trip through the LDS crossbar.
+typedef unsigned int xh_u2_t __attribute__((ext_vector_type(2)));
+// (The vector elements are copied to scalars before the bit casts: a bit cast
+// applied directly to a vector element reads element 0.)
+__device__ __forceinline__ void xhalf_both(float v, float& lo, float& hi) {
+    const unsigned int u = __builtin_bit_cast(unsigned int, v);
+    const xh_u2_t r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    const unsigned int rx = r.x, ry = r.y;
+    lo = __builtin_bit_cast(float, rx);
+    hi = __builtin_bit_cast(float, ry);
+}
+__device__ __forceinline__ float xhalf_max(float v) {
+    float lo, hi;
+    xhalf_both(v, lo, hi);
+    return fmaxf(lo, hi);
+}
+__device__ __forceinline__ float xhalf_sum(float v) {
+    float lo, hi;
+    xhalf_both(v, lo, hi);
+    return lo + hi;
+}
+
+// Softmax partials of one 32-token tile for one block of 32 query rows.
+// acc[v] = raw logit of (token tile*32 + 8*(v/4) + 4*half + v%4, query row of this lane);
+// row < 0 marks a padding row.  Writes the tile maximum and the weighted
+// sub-block sums, and folds the tile into the run's maximum / denominator.
+__device__ __forceinline__ void tile_epilogue(const v16f_t& acc, const ScoreGeom& g, const ScoreWs& ws,
+                                              int tile, int row, int lh, int half, float& m_run,
+                                              float& l_run) {
+    const int t0 = tile * 32;
+    const int first_q_pos = g.N - g.R;
+    const bool tail = (t0 + 31 > first_q_pos);   // wave-uniform: some entry may be masked
+    float m_t;
+    // q4[k]: (weighted) sum over the lane's tokens 8k..8k+7 of the tile; l4[k]: unweighted
+    float q4[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    float l4[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (!tail) {
+        // every entry is visible and every column has the same weight
+        float mloc = acc[0];
+#pragma unroll
+        for (int v = 1; v < 16; ++v) mloc = fmaxf(mloc, acc[v]);
+        mloc = xhalf_max(mloc);
+        m_t = mloc * g.scale_log2e;
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+            l4[v / 4] += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[v], g.scale_log2e, -m_t));
+        const float w_const = (g.norm_mode == 0) ? 1.0f / static_cast<float>(g.R) : 1.0f;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) q4[k] = l4[k] * w_const;
+    } else {
+        float s[16];
+        float mloc = -INFINITY;
+        const int last_visible = (row >= 0) ? first_q_pos + row : -1;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int tk = t0 + 8 * (v / 4) + 4 * half + (v % 4);
+            const float x = (tk <= last_visible) ? acc[v] * g.scale_log2e : -INFINITY;
+            s[v] = x;
+            mloc = fmaxf(mloc, x);
+        }
+        m_t = xhalf_max(mloc);
+        const float m_use = (m_t == -INFINITY) ? 0.0f : m_t;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int tk = t0 + 8 * (v / 4) + 4 * half + (v % 4);
+            const float e = __builtin_amdgcn_exp2f(s[v] - m_use);
+            l4[v / 4] += e;
+            float w = 1.0f;
+            if (g.norm_mode == 0) w = 1.0f / static_cast<float>(g.N - max(tk, first_q_pos));
+            q4[v / 4] += e * w;
+        }
+    }
+    // the lane's partial denominator, then both halves of the wavefront together
+    float lsum = (l4[0] + l4[1]) + (l4[2] + l4[3]);
+    lsum = xhalf_sum(lsum);
+    // sub-block sums: 8, 16 or 32 tokens each (uniform branch), both halves together
+    float esub[4];
+    int n_sub;
+    if (g.sb_tokens == 8) {
+        n_sub = 4;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) esub[k] = xhalf_sum(q4[k]);
+    } else if (g.sb_tokens == 16) {
+        n_sub = 2;
+        const float a = q4[0] + q4[1], b2 = q4[2] + q4[3];
+        esub[0] = xhalf_sum(a);
+        esub[1] = xhalf_sum(b2);
+        esub[2] = esub[3] = 0.0f;
+    } else {
+        n_sub = 1;
+        const float a = (q4[0] + q4[1]) + (q4[2] + q4[3]);
+        esub[0] = xhalf_sum(a);
+        esub[1] = esub[2] = esub[3] = 0.0f;
+    }
+    // running maximum / denominator of this run
+    {
+        const float m_new = fmaxf(m_run, m_t);
+        const float m_safe = (m_new == -INFINITY) ? 0.0f : m_new;
+        l_run = l_run * __builtin_amdgcn_exp2f(m_run - m_safe) + lsum * __builtin_amdgcn_exp2f(m_t - m_safe);
+        m_run = m_new;
+    }
+    if (half == 0 && row >= 0) {
+        const int n_sb = g.N / g.sb_tokens;
+        ws.m_tile[(static_cast<int64_t>(lh) * g.n_tiles + tile) * g.rows_p + row] = m_t;
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (k < n_sub)
+                ws.e_sub[(static_cast<int64_t>(lh) * n_sb + tile * n_sub + k) * g.rows_p + row] = esub[k];
+    }
+}
 
 template <int D, int NRBW>
 __global__ __launch_bounds__(256) void score_tiles_kernel(const _Float16* __restrict__ q,
@@ -71,8 +183,6 @@ __global__ __launch_bounds__(256) void score_tiles_kernel(const _Float16* __rest
     const int tile_end = min(tile_begin + g.run_len, g.n_tiles);
     const int l = blockIdx.z / g.Hkv, kvh = blockIdx.z % g.Hkv;
     const int qh_per_kv = g.Hq / g.Hkv;
-    const int n_sb = g.N / g.sb_tokens;
-    const int sb_per_tile = 32 / g.sb_tokens;
 
     // query rows of this wave, resident for the whole run
     v8h_t qreg[NRBW][KS];
@@ -99,8 +209,6 @@ __global__ __launch_bounds__(256) void score_tiles_kernel(const _Float16* __rest
     }
 
     const _Float16* kbase = kv + (static_cast<int64_t>(l) * 2 * g.Hkv + kvh) * g.N * D;
-    const int first_q_pos = g.N - g.R;
-    const float w_const = (g.norm_mode == 0) ? 1.0f / static_cast<float>(g.R) : 1.0f;
     // K tiles are double-buffered in registers: the loads of the next tile are
     // in flight while the current one goes through MFMA and the softmax.
     v8h_t knext[KS];
@@ -119,82 +227,20 @@ __global__ __launch_bounds__(256) void score_tiles_kernel(const _Float16* __rest
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) knext[ks] = *reinterpret_cast<const v8h_t*>(kp + ks * 16);
         }
-        const bool tail = (t0 + 31 > first_q_pos);   // wave-uniform: some entry may be masked
+        // independent accumulators of the row blocks are interleaved so that
+        // consecutive MFMAs do not depend on each other
+        v16f_t acc[NRBW];
+#pragma unroll
+        for (int u = 0; u < NRBW; ++u) acc[u] = v16f_t{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+            for (int u = 0; u < NRBW; ++u)
+                acc[u] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kreg[ks], qreg[u][ks], acc[u], 0, 0, 0);
 #pragma unroll
         for (int u = 0; u < NRBW; ++u) {
             if (rg * NRBW + u >= g.n_rb) break;
-            v16f_t acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(kreg[ks], qreg[u][ks], acc, 0, 0, 0);
-            // acc[v] = raw logit of (token t0 + 8*(v/4) + 4*half + v%4, query row lrow)
-            float m_t, lsum;
-            float esub[4] = {0.0f, 0.0f, 0.0f, 0.0f};   // up to 4 sub-blocks of 8 tokens
-            if (!tail) {
-                // every entry is visible and every column has the same weight
-                float mloc = acc[0];
-#pragma unroll
-                for (int v = 1; v < 16; ++v) mloc = fmaxf(mloc, acc[v]);
-                mloc = fmaxf(mloc, xhalf_f(mloc));
-                m_t = mloc * g.scale_log2e;
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(acc[v], g.scale_log2e, -m_t));
-                    if (g.sb_tokens == 8) esub[v / 4] += e;
-                    else if (g.sb_tokens == 16) esub[v / 8] += e;
-                    else esub[0] += e;
-                }
-#pragma unroll
-                for (int k = 0; k < 4; ++k) esub[k] += xhalf_f(esub[k]);
-                lsum = (esub[0] + esub[1]) + (esub[2] + esub[3]);
-#pragma unroll
-                for (int k = 0; k < 4; ++k) esub[k] *= w_const;
-            } else {
-                float s[16];
-                float mloc = -INFINITY;
-                const int last_visible = (row[u] >= 0) ? first_q_pos + row[u] : -1;
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int tk = t0 + 8 * (v / 4) + 4 * half + (v % 4);
-                    const float x = (tk <= last_visible) ? acc[v] * g.scale_log2e : -INFINITY;
-                    s[v] = x;
-                    mloc = fmaxf(mloc, x);
-                }
-                m_t = fmaxf(mloc, xhalf_f(mloc));
-                const float m_use = (m_t == -INFINITY) ? 0.0f : m_t;
-                lsum = 0.0f;
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int tk = t0 + 8 * (v / 4) + 4 * half + (v % 4);
-                    const float e = __builtin_amdgcn_exp2f(s[v] - m_use);
-                    lsum += e;
-                    float w = 1.0f;
-                    if (g.norm_mode == 0) w = 1.0f / static_cast<float>(g.N - max(tk, first_q_pos));
-                    const float ew = e * w;
-                    if (g.sb_tokens == 8) esub[v / 4] += ew;
-                    else if (g.sb_tokens == 16) esub[v / 8] += ew;
-                    else esub[0] += ew;
-                }
-                lsum += xhalf_f(lsum);
-#pragma unroll
-                for (int k = 0; k < 4; ++k) esub[k] += xhalf_f(esub[k]);
-            }
-            // running maximum / denominator of this run
-            {
-                const float m_new = fmaxf(m_run[u], m_t);
-                const float m_safe = (m_new == -INFINITY) ? 0.0f : m_new;
-                l_run[u] = l_run[u] * __builtin_amdgcn_exp2f(m_run[u] - m_safe) +
-                           lsum * __builtin_amdgcn_exp2f(m_t - m_safe);
-                m_run[u] = m_new;
-            }
-            if (half == 0 && row[u] >= 0) {
-                ws.m_tile[(static_cast<int64_t>(lh[u]) * g.n_tiles + tile) * g.rows_p + row[u]] = m_t;
-                for (int k = 0; k < sb_per_tile; ++k) {
-                    const int64_t ei = (static_cast<int64_t>(lh[u]) * n_sb + tile * sb_per_tile + k) *
-                                       g.rows_p + row[u];
-                    ws.e_sub[ei] = esub[k];
-                }
-            }
+            tile_epilogue(acc[u], g, ws, tile, row[u], lh[u], half, m_run[u], l_run[u]);
         }
     }
 #pragma unroll
@@ -203,6 +249,117 @@ __global__ __launch_bounds__(256) void score_tiles_kernel(const _Float16* __rest
             const int64_t ri = (static_cast<int64_t>(lh[u]) * g.n_runs + run) * g.rows_p + row[u];
             ws.m_run[ri] = m_run[u];
             ws.l_run[ri] = l_run[u];
+        }
+    }
+}
+
+// Variant for grouped-query attention: the 2-4 wavefronts of a workgroup hold
+// the row blocks of different query heads that read the SAME kv head, so the K
+// tile is fetched once per workgroup (fully coalesced, 16 bytes per thread and
+// access), staged in LDS (double-buffered, rows padded by 16 bytes so that the
+// operand reads are bank-conflict free) and read from there by every wavefront.
+template <int D, int NRBW>
+__global__ __launch_bounds__(256) void score_tiles_shared_kernel(const _Float16* __restrict__ q,
+                                                                 const _Float16* __restrict__ kv,
+                                                                 ScoreGeom g, ScoreWs ws) {
+    constexpr int KS = D / 16;
+    constexpr int kRowPieces = D / 8;               // 16-byte pieces per token row
+    constexpr int kLdsRow = kRowPieces + 1;         // padded row, in pieces
+    constexpr int kTilePieces = 32 * kRowPieces;
+    constexpr int kPerThread = kTilePieces / 256;   // 1, 2 or 4
+    typedef unsigned int su4_t __attribute__((ext_vector_type(4)));
+    __shared__ su4_t ktile[2][32 * kLdsRow];
+
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63;
+    const int lrow = lane & 31, half = lane >> 5;
+    const int run = blockIdx.x;
+    const int tile_begin = run * g.run_len;
+    if (tile_begin >= g.n_tiles) return;             // whole workgroup
+    const int tile_end = min(tile_begin + g.run_len, g.n_tiles);
+    const int rg = blockIdx.y * g.rg_per_wg + wave;
+    const bool active = wave < g.rg_per_wg && rg < g.n_rg;
+    const int l = blockIdx.z / g.Hkv, kvh = blockIdx.z % g.Hkv;
+    const int qh_per_kv = g.Hq / g.Hkv;
+
+    v8h_t qreg[NRBW][KS];
+    int row[NRBW], lh[NRBW];
+    float m_run[NRBW], l_run[NRBW];
+#pragma unroll
+    for (int u = 0; u < NRBW; ++u) {
+        const int rb = rg * NRBW + u;
+        const int head = kvh * qh_per_kv + rb / g.RB;
+        const int r = (rb % g.RB) * 32 + lrow;
+        const bool ok = active && rb < g.n_rb && r < g.R;
+        row[u] = ok ? r : -1;
+        lh[u] = l * g.Hq + ((active && rb < g.n_rb) ? head : 0);
+        m_run[u] = -INFINITY;
+        l_run[u] = 0.0f;
+        const _Float16* qp = q + (static_cast<int64_t>(lh[u]) * g.R + (ok ? r : 0)) * D + half * 8;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            v8h_t v = {0, 0, 0, 0, 0, 0, 0, 0};
+            if (ok) v = *reinterpret_cast<const v8h_t*>(qp + ks * 16);
+            qreg[u][ks] = v;
+        }
+    }
+
+    const su4_t* kbase = reinterpret_cast<const su4_t*>(
+        kv + (static_cast<int64_t>(l) * 2 * g.Hkv + kvh) * g.N * D);
+    su4_t stage[kPerThread];
+#pragma unroll
+    for (int i = 0; i < kPerThread; ++i)
+        stage[i] = kbase[static_cast<int64_t>(tile_begin) * kTilePieces + i * 256 + tid];
+#pragma unroll
+    for (int i = 0; i < kPerThread; ++i) {
+        const int p = i * 256 + tid;
+        ktile[0][(p / kRowPieces) * kLdsRow + (p % kRowPieces)] = stage[i];
+    }
+    __syncthreads();
+    for (int tile = tile_begin; tile < tile_end; ++tile) {
+        const int buf = (tile - tile_begin) & 1;
+        const bool more = tile + 1 < tile_end;
+        if (more) {
+#pragma unroll
+            for (int i = 0; i < kPerThread; ++i)
+                stage[i] = kbase[static_cast<int64_t>(tile + 1) * kTilePieces + i * 256 + tid];
+        }
+        if (active) {
+            v8h_t kreg[KS];
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+                kreg[ks] = __builtin_bit_cast(v8h_t, ktile[buf][lrow * kLdsRow + 2 * ks + half]);
+            v16f_t acc[NRBW];
+#pragma unroll
+            for (int u = 0; u < NRBW; ++u) acc[u] = v16f_t{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+                for (int u = 0; u < NRBW; ++u)
+                    acc[u] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kreg[ks], qreg[u][ks], acc[u], 0, 0, 0);
+#pragma unroll
+            for (int u = 0; u < NRBW; ++u) {
+                if (rg * NRBW + u >= g.n_rb) break;
+                tile_epilogue(acc[u], g, ws, tile, row[u], lh[u], half, m_run[u], l_run[u]);
+            }
+        }
+        if (more) {
+#pragma unroll
+            for (int i = 0; i < kPerThread; ++i) {
+                const int p = i * 256 + tid;
+                ktile[buf ^ 1][(p / kRowPieces) * kLdsRow + (p % kRowPieces)] = stage[i];
+            }
+        }
+        __syncthreads();
+    }
+    if (active) {
+#pragma unroll
+        for (int u = 0; u < NRBW; ++u) {
+            if (half == 0 && row[u] >= 0) {
+                const int64_t ri = (static_cast<int64_t>(lh[u]) * g.n_runs + run) * g.rows_p + row[u];
+                ws.m_run[ri] = m_run[u];
+                ws.l_run[ri] = l_run[u];
+            }
         }
     }
 }
