@@ -415,20 +415,33 @@ __global__ __launch_bounds__(256) void score_combine_kernel(ScoreGeom g, ScoreWs
     const int n_sb = g.N / g.sb_tokens;
     const float* es = ws.e_sub + static_cast<int64_t>(lh) * n_sb * g.rows_p;
     const int grp = tid >> 5, gl = tid & 31;
-    for (int c = grp; c < n_chunks; c += 8) {
-        float acc = 0.0f;
+    // four chunks per group and pass, all their loads issued before the arithmetic
+    constexpr int kUnroll = 4;
+    for (int c0 = grp * kUnroll; c0 < n_chunks; c0 += 8 * kUnroll) {
+        float acc[kUnroll] = {0.0f, 0.0f, 0.0f, 0.0f};
         for (int k = 0; k < sb_per_chunk; ++k) {
-            const int sb = c * sb_per_chunk + k;
-            const int tile = sb / sb_per_tile;
             for (int rr = gl; rr < g.R; rr += 32) {
-                const float mi = mt[static_cast<int64_t>(tile) * g.rows_p + rr];
-                const float e = es[static_cast<int64_t>(sb) * g.rows_p + rr];
-                if (mi != -INFINITY) acc += e * __builtin_amdgcn_exp2f(mi - row_m[rr]) * row_f[rr];
+                float mi[kUnroll], e[kUnroll];
+#pragma unroll
+                for (int u = 0; u < kUnroll; ++u) {
+                    const int c = min(c0 + u, n_chunks - 1);
+                    const int sb = c * sb_per_chunk + k;
+                    mi[u] = mt[static_cast<int64_t>(sb / sb_per_tile) * g.rows_p + rr];
+                    e[u] = es[static_cast<int64_t>(sb) * g.rows_p + rr];
+                }
+                const float rm = row_m[rr], rf = row_f[rr];
+#pragma unroll
+                for (int u = 0; u < kUnroll; ++u)
+                    if (mi[u] != -INFINITY) acc[u] += e[u] * __builtin_amdgcn_exp2f(mi[u] - rm) * rf;
             }
         }
 #pragma unroll
-        for (int o = 16; o >= 1; o >>= 1) acc += __shfl_xor(acc, o);
-        if (gl == 0) chunk_mass[static_cast<int64_t>(lh) * n_chunks + c] = acc;
+        for (int u = 0; u < kUnroll; ++u) {
+            float a = acc[u];
+#pragma unroll
+            for (int o = 16; o >= 1; o >>= 1) a += __shfl_xor(a, o);
+            if (gl == 0 && c0 + u < n_chunks) chunk_mass[static_cast<int64_t>(lh) * n_chunks + c0 + u] = a;
+        }
     }
 }
 
