@@ -311,6 +311,24 @@ def run_stream(wl, args, dev):
     mean = {k: float(np.mean(v)) for k, v in res.items() if v}
     cache_bytes = g.elements * 2
     gbps = (cache_bytes + total) / mean["swapin_resident"] / 1e6
+    # one-shot profiling of the IO delay at discrete sizes (Sec. 3.3 i) and a plan (Eq. 4) for
+    # loading the whole context when recomputing a chunk would cost --re-us-per-chunk
+    sizes, times = [], []
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for mib in (1, 4, 16, 64, 256, 1024):
+        nbytes = min(mib << 20, total)
+        with torch.cuda.stream(copy_s):
+            for rep in range(3):
+                ev0.record()
+                path.packed[:nbytes].copy_(pinned[:nbytes], non_blocking=True)
+                ev1.record()
+                copy_s.synchronize()
+        sizes.append(float(nbytes)); times.append(ev0.elapsed_time(ev1) * 1e-3)
+    io_per_byte, io_fixed = kvs.kv_fit_line(sizes, times)
+    rec = [kvs.kv_record_bytes(shape, b) for b in (8, 4, 2)]
+    missing = [int((path.bits == b).sum()) for b in (8, 4, 2)]
+    model = (args.re_us_per_chunk * 1e-6, 0.0, max(io_per_byte, 0.0), max(io_fixed, 0.0))
+    recompute, delay = kvs.kv_plan_pipeline(model, missing, rec)
     return {
         "metric": "KV GB/s (fp16-equiv) compress + swap-in, % of HBM peak; ms per 4K-ctx switch",
         "value": round(cache_bytes / mean["stream"] / 1e6, 2), "unit": "GB/s",
@@ -326,6 +344,10 @@ def run_stream(wl, args, dev):
         "h2d_gbps": round(total / mean["h2d"] / 1e6, 2),
         "d2h_aot_gbps": round(total / mean["aot"] / 1e6, 2),
         "overlap_efficiency": round(max(mean["h2d"], mean["swapin_resident"]) / mean["stream"], 4),
+        "io_model": {"seconds_per_byte": io_per_byte, "fixed_seconds": io_fixed,
+                     "gbps": round(1e-9 / io_per_byte, 2), "points": len(sizes)},
+        "plan_example": {"assumed_recompute_us_per_chunk": args.re_us_per_chunk, "missing_8_4_2": missing,
+                         "recompute_8_4_2": list(recompute), "planned_delay_ms": round(delay * 1e3, 3)},
         "roofline": {"kernel": "swapin_kernel", "bound": "hbm", "achieved": round(gbps, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(gbps / HBM_PEAK_GBPS, 4),
                      "traffic": None},
@@ -342,6 +364,8 @@ def main():
     ap.add_argument("--contexts", type=int, default=0, help="pool workload: number of contexts (default: all)")
     ap.add_argument("--stream-buffers", type=int, default=4)
     ap.add_argument("--stream-slot-mib", type=int, default=64)
+    ap.add_argument("--re-us-per-chunk", type=float, default=50.0,
+                    help="streaming workload: assumed recompute cost per chunk for the Eq. 4 plan example")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="N",
                     help="instead of the benchmark, run N pass-through (16-bit) compress launches: "
                          "a plain copy of the whole cache, used to scale rocprofv3 byte counters")

@@ -133,6 +133,32 @@ int32_t kv_bits_optimise(const float* density, int32_t n, int32_t ratio_num,
                          int32_t ratio_den, int32_t objective, uint8_t* bits,
                          int32_t* counts);
 
+/* Swapping-recompute pipeline, profiling and planning (Sec. 3.3 i and ii, Eq. 4).
+ * Delays are modelled as lines fitted to a few measured points: recompute
+ * T_re(x) = re_per_chunk * x + re_fixed for x chunks, IO T_IO(m) = io_per_byte * m
+ * + io_fixed for m bytes; a stage with nothing to do takes no time
+ * (T_re(0) = T_IO(0) = 0). */
+typedef struct {
+    double re_per_chunk, re_fixed;   /* seconds */
+    double io_per_byte, io_fixed;    /* seconds */
+} kv_pipeline_model_t;
+
+/* Least-squares line t = slope * x + intercept through n >= 2 points with at
+ * least two different x (else KV_EINVAL).  All pointers host. */
+int32_t kv_fit_line(const double* x, const double* t, int32_t n, double* slope, double* intercept);
+
+/* Eq. 4: of the missing[w] chunks of width w = 8, 4, 2 bits (index 0, 1, 2; record
+ * sizes record_bytes[w], strictly decreasing) choose how many to recompute,
+ * recompute[w] <= missing[w], so that
+ *     max( T_re(sum_w recompute[w]),  T_IO(sum_w (missing[w] - recompute[w]) * record_bytes[w]) )
+ * is smallest.  For a given number of recomputed chunks the heaviest records are
+ * taken off the IO first (T_IO does not decrease with bytes), so every total
+ * 0..sum(missing) is tried with that choice; of equal delays the smallest total
+ * wins.  delay (may be NULL) receives the minimum.  Requires non-negative model
+ * slopes and intercepts. */
+int32_t kv_plan_pipeline(const kv_pipeline_model_t* model, const int32_t* missing,
+                         const uint64_t* record_bytes, int32_t* recompute, double* delay);
+
 /* Load primitive, list building (Sec. 3.1, primitive 3): for n_sel strictly
  * ascending chunk indices produce src_off[j] = off[idx_j], dst_tok[j] =
  * idx_j*chunk_tokens, sel_bits[j] = bits[idx_j].  All pointers host. */

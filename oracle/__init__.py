@@ -21,6 +21,9 @@ from .hostlogic import (  # noqa: F401  (re-exported)
     bits_optimise,
     build_gather,
     chunk_offsets,
+    fit_line,
+    pipeline_delay,
+    plan_pipeline,
     record_bytes,
 )
 

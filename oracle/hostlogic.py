@@ -85,6 +85,46 @@ def bits_optimise(density, ratio_num: int, ratio_den: int, as_printed: bool = Fa
     return bits, (k8, k4, k2)
 
 
+def fit_line(x, t):
+    """Least-squares line t = slope*x + intercept (Sec. 3.3 i: delays are approximated by
+    linear functions fitted to discrete test points)."""
+    n = len(x)
+    mx = sum(float(v) for v in x) / n
+    mt = sum(float(v) for v in t) / n
+    sxx = sum((float(a) - mx) * (float(a) - mx) for a in x)
+    sxt = sum((float(a) - mx) * (float(b) - mt) for a, b in zip(x, t))
+    slope = sxt / sxx
+    return slope, mt - slope * mx
+
+
+def pipeline_delay(model, missing, record_bytes, recompute):
+    """Eq. 4 for one choice: max(T_re(#recomputed), T_IO(bytes still loaded)); an idle stage costs 0."""
+    re_per_chunk, re_fixed, io_per_byte, io_fixed = model
+    x = sum(recompute)
+    all_bytes = (float(missing[0]) * float(record_bytes[0]) + float(missing[1]) * float(record_bytes[1]) +
+                 float(missing[2]) * float(record_bytes[2]))
+    removed = (float(recompute[0]) * float(record_bytes[0]) + float(recompute[1]) * float(record_bytes[1]) +
+               float(recompute[2]) * float(record_bytes[2]))
+    t_re = re_per_chunk * float(x) + re_fixed if x > 0 else 0.0
+    t_io = io_per_byte * (all_bytes - removed) + io_fixed if x < sum(missing) else 0.0
+    return max(t_re, t_io)
+
+
+def plan_pipeline(model, missing, record_bytes):
+    """Eq. 4: how many missing chunks of each width (8, 4, 2 bits) to recompute instead of
+    loading.  For every total, the heaviest records are recomputed first; the first total
+    with the smallest delay wins.  Returns ((r8, r4, r2), delay)."""
+    best = None
+    for x in range(sum(missing) + 1):
+        r8 = min(x, missing[0])
+        r4 = min(x - r8, missing[1])
+        r = (r8, r4, x - r8 - r4)
+        d = pipeline_delay(model, missing, record_bytes, r)
+        if best is None or d < best[1]:
+            best = (r, d)
+    return best
+
+
 def build_gather(shape, off, bits, chunk_idx):
     """Gather list for loading the chunks `chunk_idx` (strictly ascending):
     where each record starts, which token it lands on, and its bit-width."""

@@ -66,6 +66,8 @@ _SIGNATURES = {
     "kv_chunk_offsets": (_i32, [_vp, _vp, _vp]),
     "kv_bits_from_scores": (_i32, [_vp, _i32, _i32, _i32, _i32, _vp]),
     "kv_bits_optimise": (_i32, [_vp, _i32, _i32, _i32, _i32, _vp, _vp]),
+    "kv_fit_line": (_i32, [_vp, _vp, _i32, _vp, _vp]),
+    "kv_plan_pipeline": (_i32, [_vp, _vp, _vp, _vp, _vp]),
     "kv_build_gather": (_i32, [_vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp]),
     "kv_score_workspace_bytes": (_u64, [_vp, _i32]),
     "kv_score_chunks": (_i32, [_vp, _vp, _i32, _vp, _i32, _vp, _u64, _vp, _vp, _vp]),
@@ -173,6 +175,32 @@ def kv_bits_optimise(density, ratio_num: int, ratio_den: int, objective: int = K
     _check(lib().kv_bits_optimise(_hp(density), len(density), ratio_num, ratio_den, objective,
                                   _hp(bits), _hp(counts)))
     return bits, tuple(int(c) for c in counts)
+
+
+class kv_pipeline_model_t(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_double) for n in ("re_per_chunk", "re_fixed", "io_per_byte", "io_fixed")]
+
+
+def kv_fit_line(x, t):
+    """-> (slope, intercept) of the least-squares line through the points."""
+    x, t = _np(x, np.float64), _np(t, np.float64)
+    if len(x) != len(t):
+        raise ValueError("x and t differ in length")
+    a, b = ctypes.c_double(), ctypes.c_double()
+    _check(lib().kv_fit_line(_hp(x), _hp(t), len(x), ctypes.byref(a), ctypes.byref(b)))
+    return a.value, b.value
+
+
+def kv_plan_pipeline(model, missing, record_bytes):
+    """model = (re_per_chunk, re_fixed, io_per_byte, io_fixed) -> (recompute[3], delay)."""
+    m = kv_pipeline_model_t(*[float(v) for v in model])
+    missing, record_bytes = _np(missing, np.int32), _np(record_bytes, np.uint64)
+    if missing.shape != (3,) or record_bytes.shape != (3,):
+        raise ValueError("missing and record_bytes have three entries (8, 4, 2 bits)")
+    out = np.zeros(3, dtype=np.int32)
+    d = ctypes.c_double()
+    _check(lib().kv_plan_pipeline(ctypes.byref(m), _hp(missing), _hp(record_bytes), _hp(out), ctypes.byref(d)))
+    return tuple(int(v) for v in out), d.value
 
 
 def kv_build_gather(shape: Shape, off, bits, chunk_idx):

@@ -145,6 +145,67 @@ int32_t kv_bits_optimise(const float* density, int32_t n, int32_t ratio_num, int
     return KV_OK;
 }
 
+int32_t kv_fit_line(const double* x, const double* t, int32_t n, double* slope, double* intercept) {
+    if (!x || !t || !slope || !intercept) return fail(KV_EINVAL, "NULL pointer");
+    if (n < 2) return fail(KV_EINVAL, "need at least two points");
+    double sx = 0.0, st = 0.0;
+    for (int32_t i = 0; i < n; ++i) {
+        sx += x[i];
+        st += t[i];
+    }
+    const double mx = sx / n, mt = st / n;
+    double sxx = 0.0, sxt = 0.0;
+    for (int32_t i = 0; i < n; ++i) {
+        sxx += (x[i] - mx) * (x[i] - mx);
+        sxt += (x[i] - mx) * (t[i] - mt);
+    }
+    if (!(sxx > 0.0)) return fail(KV_EINVAL, "all x are equal");
+    *slope = sxt / sxx;
+    *intercept = mt - *slope * mx;
+    return KV_OK;
+}
+
+int32_t kv_plan_pipeline(const kv_pipeline_model_t* model, const int32_t* missing,
+                         const uint64_t* rec_bytes, int32_t* recompute, double* delay) {
+    if (!model || !missing || !rec_bytes || !recompute) return fail(KV_EINVAL, "NULL pointer");
+    if (!(model->re_per_chunk >= 0.0) || !(model->re_fixed >= 0.0) || !(model->io_per_byte >= 0.0) ||
+        !(model->io_fixed >= 0.0))
+        return fail(KV_EINVAL, "model coefficients must be non-negative");
+    if (missing[0] < 0 || missing[1] < 0 || missing[2] < 0) return fail(KV_EINVAL, "negative chunk count");
+    if (!(rec_bytes[0] > rec_bytes[1] && rec_bytes[1] > rec_bytes[2] && rec_bytes[2] > 0))
+        return fail(KV_EINVAL, "record sizes must be positive and strictly decreasing (8, 4, 2 bits)");
+    const int64_t total = static_cast<int64_t>(missing[0]) + missing[1] + missing[2];
+    const double all_bytes = static_cast<double>(missing[0]) * static_cast<double>(rec_bytes[0]) +
+                             static_cast<double>(missing[1]) * static_cast<double>(rec_bytes[1]) +
+                             static_cast<double>(missing[2]) * static_cast<double>(rec_bytes[2]);
+    double best = 0.0;
+    int64_t best_x = 0;
+    for (int64_t x = 0; x <= total; ++x) {
+        // heaviest records leave the IO first
+        const int64_t r8 = std::min<int64_t>(x, missing[0]);
+        const int64_t r4 = std::min<int64_t>(x - r8, missing[1]);
+        const int64_t r2 = x - r8 - r4;
+        const double removed = static_cast<double>(r8) * static_cast<double>(rec_bytes[0]) +
+                               static_cast<double>(r4) * static_cast<double>(rec_bytes[1]) +
+                               static_cast<double>(r2) * static_cast<double>(rec_bytes[2]);
+        const double io_b = all_bytes - removed;
+        const double t_re = x > 0 ? model->re_per_chunk * static_cast<double>(x) + model->re_fixed : 0.0;
+        const double t_io = (x < total) ? model->io_per_byte * io_b + model->io_fixed : 0.0;
+        const double d = std::max(t_re, t_io);
+        if (x == 0 || d < best) {
+            best = d;
+            best_x = x;
+        }
+    }
+    const int64_t r8 = std::min<int64_t>(best_x, missing[0]);
+    const int64_t r4 = std::min<int64_t>(best_x - r8, missing[1]);
+    recompute[0] = static_cast<int32_t>(r8);
+    recompute[1] = static_cast<int32_t>(r4);
+    recompute[2] = static_cast<int32_t>(best_x - r8 - r4);
+    if (delay) *delay = best;
+    return KV_OK;
+}
+
 int32_t kv_build_gather(const kv_shape_t* shape, const uint64_t* off, const uint8_t* bits,
                         const int32_t* chunk_idx, int32_t n_sel, uint64_t* src_off,
                         int32_t* dst_tok, uint8_t* sel_bits) {

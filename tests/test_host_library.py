@@ -197,3 +197,32 @@ def test_bits_optimise_matches_oracle():
             kvs.kv_bits_optimise(np.ones(4, dtype=np.float32), bad[0], bad[1], 0)
     with pytest.raises(kvs.KvError):
         kvs.kv_bits_optimise(np.ones(4, dtype=np.float32), 1, 2, 7)
+
+
+def test_fit_line_and_plan_pipeline_match_oracle():
+    rng = np.random.default_rng(21)
+    for _ in range(20):
+        n = int(rng.integers(2, 9))
+        x = np.cumsum(rng.random(n) + 0.1)
+        t = rng.random(n)
+        assert kvs.kv_fit_line(x, t) == pytest.approx(oracle.fit_line(x, t), rel=1e-12)
+    with pytest.raises(kvs.KvError):
+        kvs.kv_fit_line([1.0, 1.0], [2.0, 3.0])
+    with pytest.raises(kvs.KvError):
+        kvs.kv_fit_line([1.0], [2.0])
+    ks, _ = shapes(2)
+    rec = [kvs.kv_record_bytes(ks, b) for b in (8, 4, 2)]
+    for _ in range(200):
+        missing = [int(v) for v in rng.integers(0, 90, size=3)]
+        model = (float(rng.random() * 2e-3), float(rng.random() * 1e-3) * (rng.random() < 0.7),
+                 float(rng.random() / 2e10), float(rng.random() * 1e-3) * (rng.random() < 0.7))
+        got = kvs.kv_plan_pipeline(model, missing, rec)
+        want = oracle.plan_pipeline(model, missing, rec)
+        assert got[0] == want[0] and got[1] == want[1], (model, missing)
+    for bad_model in ((-1.0, 0, 0, 0), (0, 0, float("nan"), 0)):
+        with pytest.raises(kvs.KvError):
+            kvs.kv_plan_pipeline(bad_model, [1, 1, 1], rec)
+    with pytest.raises(kvs.KvError):
+        kvs.kv_plan_pipeline((1, 0, 1, 0), [1, 1, 1], rec[::-1])
+    with pytest.raises(kvs.KvError):
+        kvs.kv_plan_pipeline((1, 0, 1, 0), [1, -1, 1], rec)

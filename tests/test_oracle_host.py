@@ -174,3 +174,49 @@ def test_optimised_thresholds_closed_forms():
             for rank, i in enumerate(order):
                 alt[i] = 8 if rank < k else (4 if rank < k + 60 - 3 * k else 2)
             assert ctx_info(d, bits, w) >= ctx_info(d, alt, w)
+
+
+# ------------------------------------------------------------------ swapping-recompute planning (Sec. 3.3, Eq. 4)
+
+def test_fit_line_recovers_exact_lines_and_matches_polyfit():
+    x = [1.0, 2.0, 4.0, 8.0, 16.0]
+    slope, icpt = oracle.fit_line(x, [3.0 * v + 0.5 for v in x])
+    assert slope == pytest.approx(3.0, rel=1e-14) and icpt == pytest.approx(0.5, rel=1e-12)
+    rng = np.random.default_rng(2)
+    t = rng.random(5)
+    ref = np.polyfit(x, t, 1)                      # library least squares
+    slope, icpt = oracle.fit_line(x, t)
+    assert slope == pytest.approx(ref[0], rel=1e-10) and icpt == pytest.approx(ref[1], rel=1e-10)
+
+
+def test_plan_pipeline_against_brute_force_over_all_choices():
+    """No triple (r8, r4, r2) <= missing, heaviest-first or not, has a smaller delay."""
+    import itertools
+    rng = np.random.default_rng(3)
+    rec = [4718592, 2621440, 1572864]
+    for trial in range(30):
+        missing = [int(v) for v in rng.integers(0, 7, size=3)]
+        model = (float(rng.random() * 2e-3), float(rng.random() * 1e-3),
+                 float(rng.random() / 2e9), float(rng.random() * 1e-3))
+        r, d = oracle.plan_pipeline(model, missing, rec)
+        assert all(0 <= a <= b for a, b in zip(r, missing))
+        assert d == oracle.pipeline_delay(model, missing, rec, r)
+        best = min(oracle.pipeline_delay(model, missing, rec, c)
+                   for c in itertools.product(*[range(m + 1) for m in missing]))
+        assert d == pytest.approx(best, rel=1e-12, abs=1e-18)
+
+
+def test_plan_pipeline_closed_forms():
+    """One width, no fixed costs: T_re = a*x and T_IO = c*B*(n - x) cross at x* = n*c*B/(a + c*B);
+    the best integer is next to it.  Free recompute -> recompute everything; free IO -> load
+    everything; heaviest chunks leave the IO first."""
+    rec = [4000, 2000, 1000]
+    n, a, c = 100, 1.0, 0.5 / 4000          # c*B = 0.5 -> x* = 100 * 0.5 / 1.5 = 33.3
+    r, d = oracle.plan_pipeline((a, 0.0, c, 0.0), [n, 0, 0], rec)
+    assert r in ((33, 0, 0), (34, 0, 0)) and d == pytest.approx(min(max(33, 0.5 * 67), max(34, 0.5 * 66)))
+    assert oracle.plan_pipeline((0.0, 0.0, 1e-6, 0.0), [3, 4, 5], rec) == ((3, 4, 5), 0.0)
+    assert oracle.plan_pipeline((1.0, 0.0, 0.0, 0.0), [3, 4, 5], rec) == ((0, 0, 0), 0.0)
+    r, _ = oracle.plan_pipeline((1e-3, 0.0, 1e-6, 0.0), [2, 50, 50], rec)
+    assert r[0] == 2 and r[2] == 0 and 0 < r[1] < 50      # 8-bit chunks first, then 4-bit
+    # a fixed recompute cost larger than the whole IO: do not start recomputing
+    assert oracle.plan_pipeline((1e-6, 1.0, 1e-6, 0.0), [5, 5, 5], rec)[0] == (0, 0, 0)
