@@ -354,6 +354,43 @@ def run_stream(wl, args, dev):
     }
 
 
+def run_chunk_sweep(wl, args, dev):
+    """Compress and swap-in rates against the chunk size (the paper's chunk-size study, Sec. 5.4,
+    looks at IO efficiency against redundant swapping; here: how the kernels take smaller or
+    larger units).  Widths are seeded uniform draws; the cache is the workload's."""
+    g0 = wl.geom
+    kv = synth.make_kv(g0, wl.seed, dev, wl.outlier_channels, wl.outlier_scale)
+    out = torch.empty_like(kv)
+    rows = []
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    for T in (4, 8, 16, 32, 64, 128, 256):
+        if g0.N % T or (T * g0.D) % 512 or (T * g0.D // g0.G) % 4:
+            continue
+        shape = kvs.Shape(g0.L, g0.Hkv, g0.Hq, g0.D, g0.N, T, g0.G)
+        bits = synth.draw_bits_uniform(shape.n_chunks, wl.seed).numpy()
+        off = kvs.kv_chunk_offsets(shape, bits)
+        src, dst, sb = kvs.kv_build_gather(shape, off, bits, np.arange(shape.n_chunks, dtype=np.int32))
+        packed = torch.empty(int(off[-1]), dtype=torch.uint8, device=dev)
+        d = [torch.from_numpy(a).to(dev) for a in (bits, off.view(np.int64), src.view(np.int64), dst, sb)]
+        tc, ts = [], []
+        for it in range(args.warmup + args.steps):
+            ev[0].record()
+            kvs.kv_compress_chunks(shape, kv, d[0], d[1], packed)
+            ev[1].record()
+            kvs.kv_swapin_chunks(shape, packed, d[2], d[3], d[4], out)
+            ev[2].record()
+            torch.cuda.synchronize()
+            if it >= args.warmup:
+                tc.append(ev[0].elapsed_time(ev[1])); ts.append(ev[1].elapsed_time(ev[2]))
+        moved = g0.elements * 2 + int(off[-1])
+        rows.append({"chunk_tokens": T, "n_chunks": shape.n_chunks, "packed_bytes": int(off[-1]),
+                     "compress_ms": round(float(np.mean(tc)), 4), "swapin_ms": round(float(np.mean(ts)), 4),
+                     "compress_gbps": round(moved / float(np.mean(tc)) / 1e6, 1),
+                     "swapin_gbps": round(moved / float(np.mean(ts)) / 1e6, 1)})
+        del packed
+    return {"sweep": "chunk_tokens", "workload": wl.name, "unit": "GB/s of algorithmic bytes", "rows": rows}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -361,6 +398,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="llama2-7b-4k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep-chunk-tokens", action="store_true",
+                    help="instead of the benchmark: compress / swap-in rates for chunk sizes 4..256")
     ap.add_argument("--contexts", type=int, default=0, help="pool workload: number of contexts (default: all)")
     ap.add_argument("--stream-buffers", type=int, default=4)
     ap.add_argument("--stream-slot-mib", type=int, default=64)
@@ -378,6 +417,9 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     wl = find_workload(args.workload)
+    if args.sweep_chunk_tokens:
+        print(json.dumps(run_chunk_sweep(wl, args, dev)))
+        return
     if wl.n_contexts > 1:
         print(json.dumps(run_pool(wl, args, dev)))
         return
