@@ -31,12 +31,12 @@ int ilog2(int v) {
     return l;
 }
 
-// Measured on MI355X (llama2-7b-4k, mixed widths): both kernels stream best with
-// 4 pieces per lane and with the task order that makes their WRITE side one
-// forward stream: compress walks the slabs of one chunk (record-major), swap-in
-// walks the chunks of one slab.
+// Measured on MI355X (llama2-7b-4k, widths by score terciles): compress streams
+// best with 4 pieces per lane, swap-in with 2, each with the task order that
+// makes its WRITE side one forward stream: compress walks the slabs of one chunk
+// (record-major), swap-in walks the chunks of one slab.
 constexpr int kCompressPiecesPerLane = 4;
-constexpr int kSwapinPiecesPerLane = 4;
+constexpr int kSwapinPiecesPerLane = 2;
 
 QuantGeom quant_geom(const kv_shape_t& s) {
     QuantGeom g;
