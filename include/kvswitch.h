@@ -45,6 +45,18 @@
  *  [n_layers][2][n_kv_heads][chunk_tokens][head_dim], no metadata.
  *  Record i starts at byte offset off[i] of the packed pool (kv_chunk_offsets).
  *
+ *  The above is format KV_FMT_F16_GROUPS (shape.format = 0).  Format
+ *  KV_FMT_I8_CHANNELS (= 1) follows the paper's own setting more closely (Sec. 3.2
+ *  "Compressing chunks", Sec. 4): the cache is already stored as 8-bit integers
+ *  by the engine, [n_layers][2][n_kv_heads][n_tokens][head_dim] int8, and a chunk
+ *  is quantised further, channel-wise: one (scale, mn) pair per head_dim channel
+ *  of a slab, taken over the slab's chunk_tokens tokens.  Widths {8, 4, 2, 1};
+ *  8 is pass-through (the slab's int8 bytes).  Record for b < 8:
+ *    codes : [slab][chunk_tokens][head_dim*b/8] bytes, bit order as above;
+ *    scale : [slab][head_dim] fp32;   mn : [slab][head_dim] fp32.
+ *  Same arithmetic as below with x the int8 value as binary32; dequantisation
+ *  gives int8(clamp(rint(fp32(code) * scale + mn), -128, 127)).
+ *
  *  Quantisation of one group of `group` consecutive head_dim elements of one
  *  token (linear min/max quantisation, Sec. 3.2 "Compressing chunks"), all in
  *  IEEE binary32, round-to-nearest, no contraction:
@@ -78,7 +90,10 @@ typedef enum {
  * group in {64, 128, 256, 512}; n_q_heads % n_kv_heads == 0; head_dim <= 1024;
  * chunk_tokens <= 1024; chunk_tokens * head_dim % 512 == 0;
  * (chunk_tokens * head_dim / group) % 4 == 0 (keeps every record section
- * 16-byte aligned). */
+ * 16-byte aligned).
+ * Format 1 instead of the group rules: head_dim a power of two in [64, 1024];
+ * chunk_tokens * head_dim in {1024, 2048, 4096} (one wavefront holds a slab);
+ * group is ignored.  Scoring (kv_score_chunks) needs format 0. */
 typedef struct {
     int32_t n_layers;
     int32_t n_kv_heads;
@@ -86,8 +101,11 @@ typedef struct {
     int32_t head_dim;
     int32_t n_tokens;
     int32_t chunk_tokens;
-    int32_t group;         /* quantisation group along head_dim */
+    int32_t group;         /* quantisation group along head_dim (format 0) */
+    int32_t format;        /* KV_FMT_F16_GROUPS (0) or KV_FMT_I8_CHANNELS (1) */
 } kv_shape_t;
+
+enum { KV_FMT_F16_GROUPS = 0, KV_FMT_I8_CHANNELS = 1 };
 
 enum { KV_NORM_VISIBLE = 0, KV_NORM_NONE = 1 };
 
@@ -97,7 +115,8 @@ const char* kv_last_error(void);
 /* ---------------------------------------------------------------- host, pure */
 
 /* Bytes of one chunk's packed record at bit-width `bits`; 0 if shape or bits
- * are invalid.  b<16: slabs*T*(D*b/8 + 8*D/G); b=16: slabs*T*D*2. */
+ * are invalid.  Format 0: b<16: slabs*T*(D*b/8 + 8*D/G); b=16: slabs*T*D*2.
+ * Format 1: b<8: slabs*(T*D*b/8 + 8*D); b=8: slabs*T*D. */
 uint64_t kv_record_bytes(const kv_shape_t* shape, int32_t bits);
 
 /* Exclusive prefix sum of record sizes: off[0]=0, off[i+1]=off[i]+record_bytes(bits[i]).

@@ -36,7 +36,7 @@ NORM_NONE = 1
 
 
 class _CShape(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_int32) for n in ("L", "Hkv", "Hq", "D", "N", "T", "G")]
+    _fields_ = [(n, ctypes.c_int32) for n in ("L", "Hkv", "Hq", "D", "N", "T", "G", "fmt")]
 
 
 @dataclass(frozen=True)
@@ -50,6 +50,7 @@ class Shape:
     N: int
     T: int
     G: int
+    fmt: int = 0    # 0: fp16 cache, groups of G along head_dim; 1: int8 cache, channel-wise
 
     @property
     def n_chunks(self) -> int:
@@ -60,7 +61,7 @@ class Shape:
         return self.L * 2 * self.Hkv
 
     def c(self) -> _CShape:
-        return _CShape(self.L, self.Hkv, self.Hq, self.D, self.N, self.T, self.G)
+        return _CShape(self.L, self.Hkv, self.Hq, self.D, self.N, self.T, self.G, self.fmt)
 
 
 def build(force: bool = False) -> str:
@@ -195,5 +196,34 @@ def swapin_chunks(shape: Shape, packed: np.ndarray, src_off, dst_tok, sel_bits,
     cs = shape.c()
     rc = lib().orc_swapin_chunks(ctypes.byref(cs), _p(packed), _p(src_off), _p(dst_tok),
                                  _p(sel_bits), ctypes.c_int(n_sel), _p(kv_out))
+    assert rc == 0, rc
+    return kv_out
+
+
+def compress_chunks_i8(shape: Shape, kv, bits: np.ndarray, off: np.ndarray) -> np.ndarray:
+    """Channel-wise quantise + pack of an int8 cache (format 1) -> uint8 pool."""
+    kv = np.ascontiguousarray(kv, dtype=np.int8)
+    assert shape.fmt == 1 and kv.shape == (shape.L, 2, shape.Hkv, shape.N, shape.D)
+    bits = np.ascontiguousarray(bits, dtype=np.uint8)
+    off = np.ascontiguousarray(off, dtype=np.uint64)
+    assert bits.shape == (shape.n_chunks,) and off.shape == (shape.n_chunks + 1,)
+    packed = np.zeros(int(off[-1]), dtype=np.uint8)
+    cs = shape.c()
+    rc = lib().orc_compress_chunks_i8(ctypes.byref(cs), _p(kv), _p(bits), _p(off), _p(packed))
+    assert rc == 0, rc
+    return packed
+
+
+def swapin_chunks_i8(shape: Shape, packed, src_off, dst_tok, sel_bits, kv_out: np.ndarray) -> np.ndarray:
+    """Unpack + dequantise listed records into an int8 cache (format 1), in place."""
+    packed = np.ascontiguousarray(packed, dtype=np.uint8)
+    src_off = np.ascontiguousarray(src_off, dtype=np.uint64)
+    dst_tok = np.ascontiguousarray(dst_tok, dtype=np.int32)
+    sel_bits = np.ascontiguousarray(sel_bits, dtype=np.uint8)
+    assert shape.fmt == 1 and kv_out.flags["C_CONTIGUOUS"] and kv_out.dtype == np.int8
+    assert kv_out.shape == (shape.L, 2, shape.Hkv, shape.N, shape.D)
+    cs = shape.c()
+    rc = lib().orc_swapin_chunks_i8(ctypes.byref(cs), _p(packed), _p(src_off), _p(dst_tok),
+                                    _p(sel_bits), ctypes.c_int(len(src_off)), _p(kv_out))
     assert rc == 0, rc
     return kv_out

@@ -14,8 +14,9 @@
  * the paper's worked example, closed forms, invariants or library routines; no
  * function is "parity unpinned".
  *
- * Shapes: KV cache [L][2 (K=0,V=1)][Hkv][N][D] fp16; a chunk is T tokens of
- * every (layer, K|V, kv-head) slab and has one bit-width (Sec. 3.1).
+ * Shapes: KV cache [L][2 (K=0,V=1)][Hkv][N][D] fp16 (or int8 for the channel-wise
+ * variant); a chunk is T tokens of every (layer, K|V, kv-head) slab and has one
+ * bit-width (Sec. 3.1).
  */
 #include <math.h>
 #include <stdint.h>
@@ -27,6 +28,7 @@
 
 typedef struct {
     int32_t L, Hkv, Hq, D, N, T, G;
+    int32_t fmt;   /* 0: fp16 cache, groups of G along head_dim; 1: int8 cache, channel-wise */
 } orc_shape;
 
 int orc_threads(void)
@@ -197,6 +199,10 @@ int orc_score_chunks(const orc_shape* s, const uint16_t* q, int R, const uint16_
 uint64_t orc_record_bytes(const orc_shape* s, int bits)
 {
     const uint64_t slabs = (uint64_t)s->L * 2 * s->Hkv;
+    if (s->fmt == 1) {
+        if (bits == 8) return slabs * s->T * s->D;
+        return slabs * ((uint64_t)s->T * s->D * bits / 8 + 8ull * s->D);
+    }
     if (bits == 16) return slabs * s->T * s->D * 2;
     return slabs * s->T * ((uint64_t)s->D * bits / 8 + 8ull * (s->D / s->G));
 }
@@ -284,6 +290,115 @@ int orc_compress_chunks(const orc_shape* s, const uint16_t* kv, const uint8_t* b
                         const int per_byte = 8 / b;
                         row[d / per_byte] |= (uint8_t)(tmp[k] << ((d % per_byte) * b));
                     }
+                }
+            }
+        }
+    }
+    return 0;
+}
+
+/* ----------------------------------------------------------------- int8 cache, channel-wise (Sec. 3.2 / Sec. 4) */
+
+/*
+ * The paper's own setting: the cache is held as 8-bit integers and a chunk is
+ * quantised further, channel-wise.  For one slab (T tokens x D channels of one
+ * (layer, K|V, kv-head)) and every channel d, over the T tokens:
+ *   mn = min x + 0.0f, mx = max x + 0.0f, scale = (mx - mn) / (2^b - 1),
+ *   code = scale == 0 ? 0 : clamp(rintf((x - mn) / scale), 0, 2^b - 1)   (binary32)
+ * b in {4, 2, 1}; b = 8 copies the int8 bytes.  Record: codes [slab][T][D*b/8]
+ * (lowest-index element in the least-significant bits), scale [slab][D], mn [slab][D].
+ */
+int orc_compress_chunks_i8(const orc_shape* s, const int8_t* kv, const uint8_t* bits,
+                           const uint64_t* off, uint8_t* packed)
+{
+    const int n_chunks = s->N / s->T;
+    const int slabs = s->L * 2 * s->Hkv;
+    for (int i = 0; i < n_chunks; ++i) {
+        const int b = bits[i];
+        if (b != 8 && b != 4 && b != 2 && b != 1) return -3;
+    }
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int i = 0; i < n_chunks; ++i) {
+        for (int sl = 0; sl < slabs; ++sl) {
+            const int b = bits[i];
+            uint8_t* rec = packed + off[i];
+            const int8_t* src = kv + ((size_t)sl * s->N + (size_t)i * s->T) * s->D;
+            if (b == 8) {
+                memcpy(rec + (size_t)sl * s->T * s->D, src, (size_t)s->T * s->D);
+                continue;
+            }
+            const size_t row_bytes = (size_t)s->D * b / 8;
+            const int per_byte = 8 / b;
+            const float levels = (float)((1 << b) - 1);
+            uint8_t* codes = rec + (size_t)sl * s->T * row_bytes;
+            float* scale = (float*)(rec + (size_t)slabs * s->T * row_bytes) + (size_t)sl * s->D;
+            float* mn_out = scale + (size_t)slabs * s->D;
+            memset(codes, 0, (size_t)s->T * row_bytes);
+            for (int d = 0; d < s->D; ++d) {
+                float mn = (float)src[d], mx = mn;
+                for (int t = 1; t < s->T; ++t) {
+                    const float v = (float)src[(size_t)t * s->D + d];
+                    if (v < mn) mn = v;
+                    if (v > mx) mx = v;
+                }
+                mn = mn + 0.0f;
+                mx = mx + 0.0f;
+                const float range = mx - mn;
+                const float sc = range / levels;
+                scale[d] = sc;
+                mn_out[d] = mn;
+                for (int t = 0; t < s->T; ++t) {
+                    float c = 0.0f;
+                    if (sc != 0.0f) {
+                        const float dv = (float)src[(size_t)t * s->D + d] - mn;
+                        const float qv = dv / sc;
+                        c = rintf(qv);
+                        if (c < 0.0f) c = 0.0f;
+                        if (c > levels) c = levels;
+                    }
+                    codes[(size_t)t * row_bytes + d / per_byte] |= (uint8_t)((uint8_t)c << ((d % per_byte) * b));
+                }
+            }
+        }
+    }
+    return 0;
+}
+
+/* Load for the int8 format: x = int8(clamp(rintf((float)code * scale + mn), -128, 127)),
+ * product and sum rounded separately; b = 8 copies the bytes. */
+int orc_swapin_chunks_i8(const orc_shape* s, const uint8_t* packed, const uint64_t* src_off,
+                         const int32_t* dst_tok, const uint8_t* sel_bits, int n_sel, int8_t* kv_out)
+{
+    const int slabs = s->L * 2 * s->Hkv;
+    for (int j = 0; j < n_sel; ++j) {
+        const int b = sel_bits[j];
+        if (b != 8 && b != 4 && b != 2 && b != 1) return -3;
+        if (dst_tok[j] < 0 || dst_tok[j] + s->T > s->N) return -4;
+    }
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int j = 0; j < n_sel; ++j) {
+        for (int sl = 0; sl < slabs; ++sl) {
+            const int b = sel_bits[j];
+            const uint8_t* rec = packed + src_off[j];
+            int8_t* dst = kv_out + ((size_t)sl * s->N + (size_t)dst_tok[j]) * s->D;
+            if (b == 8) {
+                memcpy(dst, rec + (size_t)sl * s->T * s->D, (size_t)s->T * s->D);
+                continue;
+            }
+            const size_t row_bytes = (size_t)s->D * b / 8;
+            const int per_byte = 8 / b;
+            const unsigned mask = (1u << b) - 1u;
+            const uint8_t* codes = rec + (size_t)sl * s->T * row_bytes;
+            const float* scale = (const float*)(rec + (size_t)slabs * s->T * row_bytes) + (size_t)sl * s->D;
+            const float* mn = scale + (size_t)slabs * s->D;
+            for (int t = 0; t < s->T; ++t) {
+                for (int d = 0; d < s->D; ++d) {
+                    const unsigned code = (codes[(size_t)t * row_bytes + d / per_byte] >> ((d % per_byte) * b)) & mask;
+                    const float prod = (float)code * scale[d];
+                    float v = rintf(prod + mn[d]);
+                    if (v < -128.0f) v = -128.0f;
+                    if (v > 127.0f) v = 127.0f;
+                    dst[(size_t)t * s->D + d] = (int8_t)v;
                 }
             }
         }
