@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libkvswitch.so")
 
 KV_OK, KV_EINVAL, KV_ESHAPE, KV_EBITS, KV_EINDEX, KV_ENOMEM, KV_EHIP = 0, -1, -2, -3, -4, -5, -6
 KV_NORM_VISIBLE, KV_NORM_NONE = 0, 1
+KV_FMT_F16_GROUPS, KV_FMT_I8_CHANNELS = 0, 1
 KV_OBJ_BITS_TO_DENSE, KV_OBJ_AS_PRINTED = 0, 1
 
 
@@ -29,7 +30,8 @@ class KvError(RuntimeError):
 
 class kv_shape_t(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
-                ("n_layers", "n_kv_heads", "n_q_heads", "head_dim", "n_tokens", "chunk_tokens", "group")]
+                ("n_layers", "n_kv_heads", "n_q_heads", "head_dim", "n_tokens", "chunk_tokens", "group",
+                 "format")]
 
 
 class Shape(NamedTuple):
@@ -40,6 +42,11 @@ class Shape(NamedTuple):
     n_tokens: int
     chunk_tokens: int
     group: int
+    format: int = 0      # KV_FMT_F16_GROUPS or KV_FMT_I8_CHANNELS
+
+    @property
+    def cache_dtype(self):
+        return torch.int8 if self.format == KV_FMT_I8_CHANNELS else torch.float16
 
     @property
     def n_chunks(self) -> int:
@@ -253,7 +260,7 @@ def kv_compress_chunks(shape: Shape, kv: torch.Tensor, bits_dev: torch.Tensor,
         raise ValueError("kv must be [L][2][Hkv][N][D]")
     if bits_dev.numel() != shape.n_chunks or off_dev.numel() != shape.n_chunks + 1:
         raise ValueError("bits_dev/off_dev have the wrong length")
-    _check(lib().kv_compress_chunks(ctypes.byref(s), _dev(kv, torch.float16),
+    _check(lib().kv_compress_chunks(ctypes.byref(s), _dev(kv, shape.cache_dtype),
                                     _dev(bits_dev, torch.uint8), _dev(off_dev, torch.int64),
                                     _dev(packed_out, torch.uint8), _stream(stream)))
 
@@ -272,7 +279,7 @@ def kv_swapin_chunks(shape: Shape, packed: torch.Tensor, src_off_dev: torch.Tens
     _check(lib().kv_swapin_chunks(ctypes.byref(s), _dev(packed, torch.uint8),
                                   _dev(src_off_dev, torch.int64), _dev(dst_tok_dev, torch.int32),
                                   _dev(sel_bits_dev, torch.uint8), n_sel,
-                                  _dev(kv_out, torch.float16), _stream(stream)))
+                                  _dev(kv_out, shape.cache_dtype), _stream(stream)))
 
 
 def kv_swapin_pinned(shape: Shape, packed_pinned: torch.Tensor, src_off, dst_tok, sel_bits,
@@ -290,7 +297,7 @@ def kv_swapin_pinned(shape: Shape, packed_pinned: torch.Tensor, src_off, dst_tok
     _check(lib().kv_swapin_pinned(ctypes.byref(s), packed_pinned.data_ptr(), _hp(src_off),
                                   _hp(dst_tok), _hp(sel_bits), n_sel, _dev(staging_dev),
                                   staging_dev.numel() * staging_dev.element_size(), n_buffers,
-                                  _dev(kv_out, torch.float16), _stream(copy_stream),
+                                  _dev(kv_out, shape.cache_dtype), _stream(copy_stream),
                                   _stream(compute_stream)))
 
 

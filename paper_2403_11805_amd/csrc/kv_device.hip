@@ -9,6 +9,7 @@
 
 #include "kv_internal.h"
 #include "kv_quant_kernels.hpp"
+#include "kv_quant_i8_kernels.hpp"
 #include "kv_score_kernels.hpp"
 
 using namespace kvs;
@@ -52,6 +53,22 @@ QuantGeom quant_geom(const kv_shape_t& s) {
     return g;
 }
 
+// int8 channel-wise format: one wavefront task per (chunk, slab) unit of 16-byte pieces.
+QuantGeom quant_geom_i8(const kv_shape_t& s, int* ppl) {
+    QuantGeom g;
+    g.n_tokens = s.n_tokens;
+    g.chunk_tokens = s.chunk_tokens;
+    g.slabs = static_cast<int32_t>(slabs_of(s));
+    g.pieces = s.chunk_tokens * s.head_dim / 16;
+    g.row_pieces = s.head_dim / 16;
+    g.lpg_log2 = ilog2(g.row_pieces);
+    g.tpu = 1;
+    g.tpu_shift = 0;
+    g.record_major = 0;
+    *ppl = g.pieces / 64;      // 1, 2 or 4 (shape check)
+    return g;
+}
+
 // Pieces per lane of a wavefront task (the largest of 4, 2, 1 that is at most
 // max_ppl and divides the unit) and the resulting tasks per unit.
 int plan_tasks(QuantGeom* g, int max_ppl) {
@@ -86,8 +103,10 @@ int32_t kv_compress_chunks(const kv_shape_t* shape, const void* kv, const uint8_
     if (!kv || !bits_dev || !off_dev || !packed_out) return fail(KV_EINVAL, "NULL device pointer");
     if (!aligned(kv, 16) || !aligned(packed_out, 16) || !aligned(off_dev, 8))
         return fail(KV_EINVAL, "kv/packed_out must be 16-byte aligned, off_dev 8-byte aligned");
-    QuantGeom g = quant_geom(*shape);
-    const int ppl = plan_tasks(&g, kCompressPiecesPerLane);
+    const bool i8 = shape->format == KV_FMT_I8_CHANNELS;
+    int ppl = 0;
+    QuantGeom g = i8 ? quant_geom_i8(*shape, &ppl) : quant_geom(*shape);
+    if (!i8) ppl = plan_tasks(&g, kCompressPiecesPerLane);
     const int32_t n_chunks = shape->n_tokens / shape->chunk_tokens;
     g.record_major = n_chunks <= 65535 ? 1 : 0;
     if (!g.record_major && g.slabs > 65535)
@@ -96,6 +115,12 @@ int32_t kv_compress_chunks(const kv_shape_t* shape, const void* kv, const uint8_
     hipStream_t st = static_cast<hipStream_t>(stream);
     const u4_t* src = static_cast<const u4_t*>(kv);
     uint8_t* dst = static_cast<uint8_t*>(packed_out);
+    if (i8) {
+        if (ppl == 4) hipLaunchKernelGGL(compress_i8_kernel<4>, grid, dim3(256), 0, st, src, bits_dev, off_dev, dst, g, n_chunks);
+        else if (ppl == 2) hipLaunchKernelGGL(compress_i8_kernel<2>, grid, dim3(256), 0, st, src, bits_dev, off_dev, dst, g, n_chunks);
+        else hipLaunchKernelGGL(compress_i8_kernel<1>, grid, dim3(256), 0, st, src, bits_dev, off_dev, dst, g, n_chunks);
+        return launch_status("compress_i8_kernel launch");
+    }
     if (ppl == 4) hipLaunchKernelGGL(compress_kernel<4>, grid, dim3(256), 0, st, src, bits_dev, off_dev, dst, g, n_chunks);
     else if (ppl == 2) hipLaunchKernelGGL(compress_kernel<2>, grid, dim3(256), 0, st, src, bits_dev, off_dev, dst, g, n_chunks);
     else hipLaunchKernelGGL(compress_kernel<1>, grid, dim3(256), 0, st, src, bits_dev, off_dev, dst, g, n_chunks);
@@ -114,13 +139,21 @@ int32_t kv_swapin_chunks(const kv_shape_t* shape, const void* packed, const uint
     if (!aligned(kv_out, 16) || !aligned(packed, 16) || !aligned(src_off_dev, 8) ||
         !aligned(dst_tok_dev, 4))
         return fail(KV_EINVAL, "kv_out/packed must be 16-byte aligned, lists naturally aligned");
-    QuantGeom g = quant_geom(*shape);
-    const int ppl = plan_tasks(&g, kSwapinPiecesPerLane);
+    const bool i8 = shape->format == KV_FMT_I8_CHANNELS;
+    int ppl = 0;
+    QuantGeom g = i8 ? quant_geom_i8(*shape, &ppl) : quant_geom(*shape);
+    if (!i8) ppl = plan_tasks(&g, kSwapinPiecesPerLane);
     if (g.slabs > 65535) return fail(KV_ESHAPE, "more than 65535 slabs exceed the launch grid");
     const dim3 grid = task_grid(g, n_sel);
     hipStream_t st = static_cast<hipStream_t>(stream);
     const uint8_t* src = static_cast<const uint8_t*>(packed);
     u4_t* dst = static_cast<u4_t*>(kv_out);
+    if (i8) {
+        if (ppl == 4) hipLaunchKernelGGL(swapin_i8_kernel<4>, grid, dim3(256), 0, st, src, src_off_dev, dst_tok_dev, sel_bits_dev, dst, g, n_sel);
+        else if (ppl == 2) hipLaunchKernelGGL(swapin_i8_kernel<2>, grid, dim3(256), 0, st, src, src_off_dev, dst_tok_dev, sel_bits_dev, dst, g, n_sel);
+        else hipLaunchKernelGGL(swapin_i8_kernel<1>, grid, dim3(256), 0, st, src, src_off_dev, dst_tok_dev, sel_bits_dev, dst, g, n_sel);
+        return launch_status("swapin_i8_kernel launch");
+    }
     if (ppl == 4) hipLaunchKernelGGL(swapin_kernel<4>, grid, dim3(256), 0, st, src, src_off_dev, dst_tok_dev, sel_bits_dev, dst, g, n_sel);
     else if (ppl == 2) hipLaunchKernelGGL(swapin_kernel<2>, grid, dim3(256), 0, st, src, src_off_dev, dst_tok_dev, sel_bits_dev, dst, g, n_sel);
     else hipLaunchKernelGGL(swapin_kernel<1>, grid, dim3(256), 0, st, src, src_off_dev, dst_tok_dev, sel_bits_dev, dst, g, n_sel);
@@ -133,6 +166,7 @@ static int score_geom(const kv_shape_t* shape, int32_t n_queries, int32_t norm_m
                       int* nrbw) {
     if (int rc = check_shape(shape)) return rc;
     const kv_shape_t& s = *shape;
+    if (s.format != KV_FMT_F16_GROUPS) return fail(KV_ESHAPE, "scoring needs the fp16 format");
     if (n_queries < 1 || n_queries > s.n_tokens || n_queries > 256)
         return fail(KV_EINVAL, "n_queries %d outside [1, min(n_tokens, 256)]", n_queries);
     if (norm_mode != KV_NORM_VISIBLE && norm_mode != KV_NORM_NONE)
@@ -250,7 +284,7 @@ int32_t kv_swapin_pinned(const kv_shape_t* shape, const void* packed_pinned, con
     const uint64_t slot = (staging_bytes / static_cast<uint64_t>(n_buffers)) & ~static_cast<uint64_t>(255);
     uint64_t largest = 0;
     for (int32_t j = 0; j < n_sel; ++j) {
-        if (!valid_bits(sel_bits[j])) return fail(KV_EBITS, "sel_bits[%d] = %d", j, sel_bits[j]);
+        if (!valid_bits(*shape, sel_bits[j])) return fail(KV_EBITS, "sel_bits[%d] = %d", j, sel_bits[j]);
         if (dst_tok[j] < 0 || dst_tok[j] % shape->chunk_tokens ||
             dst_tok[j] + shape->chunk_tokens > shape->n_tokens)
             return fail(KV_EINDEX, "dst_tok[%d] = %d is not a chunk start inside the cache", j, dst_tok[j]);
@@ -263,8 +297,10 @@ int32_t kv_swapin_pinned(const kv_shape_t* shape, const void* packed_pinned, con
         return fail(KV_ENOMEM, "staging slot %llu bytes, largest record %llu",
                     static_cast<unsigned long long>(slot), static_cast<unsigned long long>(largest));
 
-    QuantGeom g = quant_geom(*shape);
-    const int ppl = plan_tasks(&g, kSwapinPiecesPerLane);
+    const bool i8 = shape->format == KV_FMT_I8_CHANNELS;
+    int ppl = 0;
+    QuantGeom g = i8 ? quant_geom_i8(*shape, &ppl) : quant_geom(*shape);
+    if (!i8) ppl = plan_tasks(&g, kSwapinPiecesPerLane);
     if (g.slabs > 65535) return fail(KV_ESHAPE, "more than 65535 slabs exceed the launch grid");
     hipStream_t cs = static_cast<hipStream_t>(copy_stream);
     hipStream_t ks = static_cast<hipStream_t>(compute_stream);
@@ -335,7 +371,10 @@ int32_t kv_swapin_pinned(const kv_shape_t* shape, const void* packed_pinned, con
         if (e != hipSuccess) { rc = hip_fail(e, "event record/wait"); break; }
         const dim3 grid = task_grid(g, list.n);
         u4_t* dst = static_cast<u4_t*>(kv_out);
-        if (ppl == 4) hipLaunchKernelGGL(swapin_batch_kernel<4>, grid, dim3(256), 0, ks, slot_dev, list, dst, g);
+        if (i8 && ppl == 4) hipLaunchKernelGGL(swapin_i8_batch_kernel<4>, grid, dim3(256), 0, ks, slot_dev, list, dst, g);
+        else if (i8 && ppl == 2) hipLaunchKernelGGL(swapin_i8_batch_kernel<2>, grid, dim3(256), 0, ks, slot_dev, list, dst, g);
+        else if (i8) hipLaunchKernelGGL(swapin_i8_batch_kernel<1>, grid, dim3(256), 0, ks, slot_dev, list, dst, g);
+        else if (ppl == 4) hipLaunchKernelGGL(swapin_batch_kernel<4>, grid, dim3(256), 0, ks, slot_dev, list, dst, g);
         else if (ppl == 2) hipLaunchKernelGGL(swapin_batch_kernel<2>, grid, dim3(256), 0, ks, slot_dev, list, dst, g);
         else hipLaunchKernelGGL(swapin_batch_kernel<1>, grid, dim3(256), 0, ks, slot_dev, list, dst, g);
         rc = launch_status("swapin_batch_kernel launch");

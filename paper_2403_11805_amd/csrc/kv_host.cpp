@@ -31,22 +31,32 @@ int check_shape(const kv_shape_t* s) {
     if (s->n_tokens % s->chunk_tokens)
         return fail(KV_ESHAPE, "n_tokens %d is not a multiple of chunk_tokens %d", s->n_tokens,
                     s->chunk_tokens);
-    if (s->group != 64 && s->group != 128 && s->group != 256 && s->group != 512)
-        return fail(KV_ESHAPE, "group %d not in {64,128,256,512}", s->group);
-    if (s->head_dim % s->group)
-        return fail(KV_ESHAPE, "head_dim %d is not a multiple of group %d", s->head_dim, s->group);
+    if (s->format != KV_FMT_F16_GROUPS && s->format != KV_FMT_I8_CHANNELS)
+        return fail(KV_ESHAPE, "format %d unknown", s->format);
     if (s->n_q_heads % s->n_kv_heads)
         return fail(KV_ESHAPE, "n_q_heads %d is not a multiple of n_kv_heads %d", s->n_q_heads,
                     s->n_kv_heads);
     if (s->head_dim > 1024 || s->chunk_tokens > 1024)
         return fail(KV_ESHAPE, "head_dim and chunk_tokens must be <= 1024");
+    if (slabs_of(*s) * static_cast<uint64_t>(s->n_tokens) > (1ull << 31))
+        return fail(KV_ESHAPE, "layers*2*kv_heads*tokens exceeds 2^31");
+    if (s->format == KV_FMT_I8_CHANNELS) {
+        if (s->head_dim < 64 || (s->head_dim & (s->head_dim - 1)))
+            return fail(KV_ESHAPE, "int8 format needs head_dim a power of two in [64,1024], got %d", s->head_dim);
+        const int64_t unit = static_cast<int64_t>(s->chunk_tokens) * s->head_dim;
+        if (unit != 1024 && unit != 2048 && unit != 4096)
+            return fail(KV_ESHAPE, "int8 format needs chunk_tokens*head_dim in {1024,2048,4096}, got %lld",
+                        static_cast<long long>(unit));
+        return KV_OK;
+    }
+    if (s->group != 64 && s->group != 128 && s->group != 256 && s->group != 512)
+        return fail(KV_ESHAPE, "group %d not in {64,128,256,512}", s->group);
+    if (s->head_dim % s->group)
+        return fail(KV_ESHAPE, "head_dim %d is not a multiple of group %d", s->head_dim, s->group);
     if ((static_cast<int64_t>(s->chunk_tokens) * s->head_dim) % 512)
         return fail(KV_ESHAPE, "chunk_tokens*head_dim must be a multiple of 512");
     if ((s->chunk_tokens * s->head_dim / s->group) % 4)
         return fail(KV_ESHAPE, "chunk_tokens*head_dim/group must be a multiple of 4");
-    const uint64_t slab_rows = slabs_of(*s) * static_cast<uint64_t>(s->n_tokens);
-    if (slab_rows > (1ull << 31))
-        return fail(KV_ESHAPE, "layers*2*kv_heads*tokens exceeds 2^31");
     return KV_OK;
 }
 
@@ -60,8 +70,8 @@ const char* kv_last_error(void) { return g_err; }
 
 uint64_t kv_record_bytes(const kv_shape_t* shape, int32_t bits) {
     if (check_shape(shape) != KV_OK) return 0;
-    if (!valid_bits(bits)) {
-        fail(KV_EBITS, "bits %d not in {16,8,4,2}", bits);
+    if (!valid_bits(*shape, bits)) {
+        fail(KV_EBITS, "bits %d not in %s", bits, bits_set(*shape));
         return 0;
     }
     return record_bytes(*shape, bits);
@@ -72,7 +82,8 @@ int32_t kv_chunk_offsets(const kv_shape_t* shape, const uint8_t* bits, uint64_t*
     if (!bits || !off) return fail(KV_EINVAL, "bits/off is NULL");
     const int32_t n = shape->n_tokens / shape->chunk_tokens;
     for (int32_t i = 0; i < n; ++i)
-        if (!valid_bits(bits[i])) return fail(KV_EBITS, "bits[%d] = %d not in {16,8,4,2}", i, bits[i]);
+        if (!valid_bits(*shape, bits[i]))
+            return fail(KV_EBITS, "bits[%d] = %d not in %s", i, bits[i], bits_set(*shape));
     uint64_t acc = 0;
     for (int32_t i = 0; i < n; ++i) {
         off[i] = acc;
@@ -220,7 +231,8 @@ int32_t kv_build_gather(const kv_shape_t* shape, const uint64_t* off, const uint
         if (i < 0 || i >= n) return fail(KV_EINDEX, "chunk_idx[%d] = %d outside [0,%d)", j, i, n);
         if (j && i <= chunk_idx[j - 1])
             return fail(KV_EINDEX, "chunk_idx not strictly ascending at position %d", j);
-        if (!valid_bits(bits[i])) return fail(KV_EBITS, "bits[%d] = %d not in {16,8,4,2}", i, bits[i]);
+        if (!valid_bits(*shape, bits[i]))
+            return fail(KV_EBITS, "bits[%d] = %d not in %s", i, bits[i], bits_set(*shape));
     }
     for (int32_t j = 0; j < n_sel; ++j) {
         const int32_t i = chunk_idx[j];

@@ -49,7 +49,8 @@ int32_t kv_lctru_insert(kv_lctru_t* q, int32_t ctx, int32_t chunk, int32_t bits,
                         uint64_t now) {
     if (!q) return fail(KV_EINVAL, "queue is NULL");
     if (ctx < 0 || chunk < 0) return fail(KV_EINVAL, "negative ctx/chunk id");
-    if (!valid_bits(bits)) return fail(KV_EBITS, "bits %d not in {16,8,4,2}", bits);
+    if (bits != 16 && bits != 8 && bits != 4 && bits != 2 && bits != 1)
+        return fail(KV_EBITS, "bits %d not in {16,8,4,2,1}", bits);
     try {
         const auto id = std::make_pair(ctx, chunk);
         if (q->entries.count(id)) return fail(KV_EINVAL, "(ctx %d, chunk %d) already resident", ctx, chunk);

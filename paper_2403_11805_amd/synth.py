@@ -63,7 +63,8 @@ WORKLOADS = (
              "score-terciles"),
 )
 
-_STREAM_KV, _STREAM_OUTLIER, _STREAM_Q, _STREAM_BITS, _STREAM_SUBSET, _STREAM_SCORES = range(6)
+(_STREAM_KV, _STREAM_OUTLIER, _STREAM_Q, _STREAM_BITS, _STREAM_SUBSET, _STREAM_SCORES,
+ _STREAM_KV_I8) = range(7)
 
 
 def _gen(seed: int, stream: int, device="cpu", context: int = 0) -> torch.Generator:
@@ -97,6 +98,20 @@ def make_kv(geom: Geometry, seed: int, device="cpu", outlier_channels: int = 0,
                         dtype=torch.float32)
         x.mul_(mult[l])
         kv[l].copy_(x)
+    return kv
+
+
+def make_kv_i8(geom: Geometry, seed: int, device="cpu", context: int = 0) -> torch.Tensor:
+    """int8 cache [L][2][Hkv][N][D] as an engine with static per-channel 8-bit scales holds it
+    (Sec. 4: the prototype keeps its KV cache in INT8): after such scaling every channel spans
+    a similar integer range, so values are round(N(0,1) * 32) clipped to [-128, 127]."""
+    dev = torch.device(device)
+    g = _gen(seed, _STREAM_KV_I8, dev, context)
+    kv = torch.empty((geom.L, 2, geom.Hkv, geom.N, geom.D), dtype=torch.int8, device=dev)
+    for l in range(geom.L):
+        x = torch.randn((2, geom.Hkv, geom.N, geom.D), generator=g, device=dev,
+                        dtype=torch.float32)
+        kv[l].copy_(x.mul_(32.0).round_().clamp_(-128, 127))
     return kv
 
 

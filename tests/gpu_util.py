@@ -10,9 +10,9 @@ from paper_2403_11805_amd import synth
 DEV = "cuda:0"
 
 
-def both_shapes(geom):
+def both_shapes(geom, fmt=0):
     g = synth.Geometry(*geom)
-    return kvs.Shape(g.L, g.Hkv, g.Hq, g.D, g.N, g.T, g.G), oracle.Shape(*g)
+    return kvs.Shape(g.L, g.Hkv, g.Hq, g.D, g.N, g.T, g.G, fmt), oracle.Shape(*g, fmt)
 
 
 def dev_lists(off, bits):
