@@ -116,9 +116,28 @@ int32_t kv_compress_chunks(const kv_shape_t* shape, const void* kv, const uint8_
     const u4_t* src = static_cast<const u4_t*>(kv);
     uint8_t* dst = static_cast<uint8_t*>(packed_out);
     if (i8) {
-        if (ppl == 4) hipLaunchKernelGGL(compress_i8_kernel<4>, grid, dim3(256), 0, st, src, bits_dev, off_dev, dst, g, n_chunks);
-        else if (ppl == 2) hipLaunchKernelGGL(compress_i8_kernel<2>, grid, dim3(256), 0, st, src, bits_dev, off_dev, dst, g, n_chunks);
-        else hipLaunchKernelGGL(compress_i8_kernel<1>, grid, dim3(256), 0, st, src, bits_dev, off_dev, dst, g, n_chunks);
+        I8View v;
+        v.head_dim = shape->head_dim;
+        v.group_lanes = shape->head_dim / 4 < 64 ? shape->head_dim / 4 : 64;
+        v.share_log2 = 6 - ilog2(v.group_lanes);
+        const int gpl = shape->head_dim > 256 ? shape->head_dim / 256 : 1;   // 1, 2 or 4
+#define KV_LAUNCH_I8(NDW, GPL)                                                                          \
+        hipLaunchKernelGGL((compress_i8_kernel<NDW, GPL>), grid, dim3(256), 0, st, src, bits_dev, off_dev, \
+                           dst, g, v, n_chunks)
+        const int key = ppl * 4 * 8 + gpl;          // dwords per lane, channel groups per lane
+        switch (key) {
+            case 4 * 8 + 1: KV_LAUNCH_I8(4, 1); break;
+            case 4 * 8 + 2: KV_LAUNCH_I8(4, 2); break;
+            case 4 * 8 + 4: KV_LAUNCH_I8(4, 4); break;
+            case 8 * 8 + 1: KV_LAUNCH_I8(8, 1); break;
+            case 8 * 8 + 2: KV_LAUNCH_I8(8, 2); break;
+            case 8 * 8 + 4: KV_LAUNCH_I8(8, 4); break;
+            case 16 * 8 + 1: KV_LAUNCH_I8(16, 1); break;
+            case 16 * 8 + 2: KV_LAUNCH_I8(16, 2); break;
+            case 16 * 8 + 4: KV_LAUNCH_I8(16, 4); break;
+            default: return fail(KV_ESHAPE, "int8 format: unit of %d pieces with head_dim %d", g.pieces, shape->head_dim);
+        }
+#undef KV_LAUNCH_I8
         return launch_status("compress_i8_kernel launch");
     }
     if (ppl == 4) hipLaunchKernelGGL(compress_kernel<4>, grid, dim3(256), 0, st, src, bits_dev, off_dev, dst, g, n_chunks);

@@ -13,6 +13,11 @@ namespace kvs {
 typedef unsigned int xh_u2_t __attribute__((ext_vector_type(2)));
 // (The vector elements are copied to scalars before the bit casts: a bit cast
 // applied directly to a vector element reads element 0.)
+__device__ __forceinline__ void xhalf_both_u32(unsigned int u, unsigned int& lo, unsigned int& hi) {
+    const xh_u2_t r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    lo = r.x;
+    hi = r.y;
+}
 __device__ __forceinline__ void xhalf_both(float v, float& lo, float& hi) {
     const unsigned int u = __builtin_bit_cast(unsigned int, v);
     const xh_u2_t r = __builtin_amdgcn_permlane32_swap(u, u, false, false);

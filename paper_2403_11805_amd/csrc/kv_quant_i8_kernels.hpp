@@ -4,14 +4,9 @@
 // (scale, minimum) pair per head_dim channel of a slab, taken over the slab's
 // chunk_tokens tokens.
 //
-// One wavefront holds one (chunk, slab) unit of chunk_tokens x head_dim bytes
-// (1, 2 or 4 KiB) in registers: a lane owns PPL pieces of 16 consecutive bytes,
-// piece u * 64 + lane, so all of a lane's pieces carry the same 16 channels
-// (64 is a multiple of the head_dim / 16 pieces of a token row).  The
-// per-channel min/max is an in-lane reduction over the lane's pieces followed
-// by an exchange between the lanes that hold the same channels.  Values are
-// handled as x + 128 (0..255), exact in binary32; the differences x - mn the
-// format defines are unchanged by the offset.
+// One wavefront handles one (chunk, slab) unit of chunk_tokens x head_dim bytes
+// (1, 2 or 4 KiB).  On the cache side a lane owns pieces of 16 consecutive
+// bytes, piece u * 64 + lane, so every access is a coalesced 16-byte one.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -22,147 +17,199 @@
 
 namespace kvs {
 
-// 16 bytes (as four words) -> 16 floats 0..255
-__device__ __forceinline__ void unpack16(const u4_t& w, float f[16]) {
-    const uint32_t d[4] = {w.x, w.y, w.z, w.w};
+// ------------------------------------------------------------------ compress
+//
+// The wavefront loads its unit with coalesced 16-byte accesses, parks it in LDS
+// and reads it back transposed: a lane then holds, for one group of 4 adjacent
+// channels (GPL groups where head_dim > 256), the dwords of RPL token rows, so
+// the per-channel min/max is an in-lane reduction on packed 16-bit pairs, with
+// one or two cross-lane steps where 2 or 4 lanes share a channel group
+// (head_dim 128 or 64).  Codes go back through LDS into record order and leave
+// as one coalesced store per lane.  No workgroup barrier: every LDS byte is
+// produced and consumed by the same wavefront.
+//
+// Arithmetic.  Values are handled as x + 128 (0..255), exact in binary32; the
+// differences x - mn of the format are unchanged by the offset.  With integer
+// data the quotient (x - mn) / scale is very often an exact half-integer, so
+// every element takes the correctly rounded division, spelled out: both
+// divisions of the format are the reciprocal-refinement sequence the compiler
+// emits for a binary32 '/', without its range scaling, which is the identity
+// for these operands (numerators 0..255, scales 0 or 1/15..255).
+
+__device__ __forceinline__ uint32_t pk_min_u16(uint32_t a, uint32_t b) {
+    uint32_t r;
+    asm("v_pk_min_u16 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+__device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b) {
+    uint32_t r;
+    asm("v_pk_max_u16 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+
+// (range / levels) correctly rounded, levels in {1, 3, 15}: with c the correctly
+// rounded reciprocal of the constant, one residual correction of the product
+// range * c gives the correctly rounded quotient (Markstein's theorem).
+template <int LEVELS>
+__device__ __forceinline__ float div_levels(float range) {
+    if constexpr (LEVELS == 1) return range;
+    constexpr float c = 1.0f / static_cast<float>(LEVELS);
+    const float q0 = range * c;
+    const float e = __builtin_fmaf(-static_cast<float>(LEVELS), q0, range);
+    return __builtin_fmaf(e, c, q0);
+}
+
+// Reciprocal of a scale, refined once (0 for a zero scale: every quotient is then 0).
+__device__ __forceinline__ float refined_rcp(float s) {
+    const float r0 = (s != 0.0f) ? __builtin_amdgcn_rcpf(s) : 0.0f;
+    const float e = __builtin_fmaf(-s, r0, 1.0f);
+    return (s != 0.0f) ? __builtin_fmaf(e, r0, r0) : 0.0f;
+}
+
+#ifndef KVS_I8_DIV_STEPS
+#define KVS_I8_DIV_STEPS 2
+#endif
+// d / s correctly rounded (rinv = refined_rcp(s)).
+__device__ __forceinline__ float div_exact(float d, float s, float rinv) {
+    float q = d * rinv;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        f[4 * j + 0] = static_cast<float>(d[j] & 0xffu);
-        f[4 * j + 1] = static_cast<float>((d[j] >> 8) & 0xffu);
-        f[4 * j + 2] = static_cast<float>((d[j] >> 16) & 0xffu);
-        f[4 * j + 3] = static_cast<float>(d[j] >> 24);
+    for (int i = 0; i < KVS_I8_DIV_STEPS; ++i) {
+        const float e = __builtin_fmaf(-s, q, d);
+        q = __builtin_fmaf(e, rinv, q);
     }
+    return q;
 }
 
-// rotate by N lanes inside each row of 16 lanes
-template <int N>
-__device__ __forceinline__ float row_ror(float v) {
-    const int u = __builtin_bit_cast(int, v);
-    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(u, u, 0x120 + N, 0xF, 0xF, false));
-}
-
-// min (or max) over all lanes that hold the same channels: lanes l + j * rp,
-// rp = 2^rp_log2 pieces per token row (4..64).
-template <bool IS_MIN>
-__device__ __forceinline__ float same_channel_reduce(float v, int rp_log2) {
-    auto op = [](float a, float b) { return IS_MIN ? fminf(a, b) : fmaxf(a, b); };
-    if (rp_log2 <= 2) v = op(v, row_ror<4>(v));
-    if (rp_log2 <= 3) v = op(v, row_ror<8>(v));
-    if (rp_log2 <= 4) v = op(v, __shfl_xor(v, 16));
-    if (rp_log2 <= 5) v = IS_MIN ? xhalf_min(v) : xhalf_max(v);
-    return v;
-}
-
-// Codes of 16 elements (exact small floats) -> BITS*2 bytes in up to two words.
-template <int BITS>
-__device__ __forceinline__ u2_t pack16(const float r[16]) {
-    u2_t w = {0u, 0u};
-    if constexpr (BITS == 4) {
-        // four 4-bit codes = 16 bits: exact as a float sum
-        float h[4];
+template <int BYTES>
+__device__ __forceinline__ void copy_out(const uint8_t* __restrict__ img, uint8_t* __restrict__ dst, int lane) {
+    if constexpr (BYTES >= 16) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            h[j] = __builtin_fmaf(r[4 * j + 3], 4096.0f,
-                   __builtin_fmaf(r[4 * j + 2], 256.0f, __builtin_fmaf(r[4 * j + 1], 16.0f, r[4 * j])));
-        w.x = static_cast<uint32_t>(h[0]) | (static_cast<uint32_t>(h[1]) << 16);
-        w.y = static_cast<uint32_t>(h[2]) | (static_cast<uint32_t>(h[3]) << 16);
-    } else if constexpr (BITS == 2) {
-        float lo = r[7], hi = r[15];
-#pragma unroll
-        for (int k = 6; k >= 0; --k) {
-            lo = __builtin_fmaf(lo, 4.0f, r[k]);
-            hi = __builtin_fmaf(hi, 4.0f, r[8 + k]);
-        }
-        w.x = static_cast<uint32_t>(lo) | (static_cast<uint32_t>(hi) << 16);
+        for (int u = 0; u < BYTES / 16; ++u)
+            stream_store<KVS_NT_CODE_STORE>(reinterpret_cast<const u4_t*>(img)[u * 64 + lane],
+                                            reinterpret_cast<u4_t*>(dst) + u * 64 + lane);
+    } else if constexpr (BYTES == 8) {
+        stream_store<KVS_NT_CODE_STORE>(reinterpret_cast<const u2_t*>(img)[lane], reinterpret_cast<u2_t*>(dst) + lane);
+    } else if constexpr (BYTES == 4) {
+        stream_store<KVS_NT_CODE_STORE>(reinterpret_cast<const uint32_t*>(img)[lane],
+                                        reinterpret_cast<uint32_t*>(dst) + lane);
     } else {
-        float a = r[15];
-#pragma unroll
-        for (int k = 14; k >= 0; --k) a = __builtin_fmaf(a, 2.0f, r[k]);
-        w.x = static_cast<uint32_t>(a);
+        stream_store<KVS_NT_CODE_STORE>(reinterpret_cast<const uint16_t*>(img)[lane],
+                                        reinterpret_cast<uint16_t*>(dst) + lane);
     }
-    return w;
 }
 
-template <int BITS, int PPL>
-__device__ __forceinline__ void compress_i8_unit(const u4_t raw[PPL], uint8_t* __restrict__ codes,
-                                                 float* __restrict__ scale_out,
-                                                 float* __restrict__ mn_out, int rp_log2, int lane) {
-    constexpr float kLevels = static_cast<float>((1 << BITS) - 1);
-    constexpr float kSafe = 0.5f - static_cast<float>(1 << BITS) * 9.5367431640625e-07f;
-    float f[PPL][16];
+// Geometry of the transposed view, uniform per launch.
+struct I8View {
+    int32_t head_dim;     // D
+    int32_t group_lanes;  // lanes along the channel groups: min(D / 4, 64)
+    int32_t share_log2;   // log2 of the lanes that share a channel group: 0, 1 (D = 128) or 2 (D = 64)
+};
+
+// NDW = dwords per lane (unit bytes / 256: 4, 8, 16); GPL = channel groups per lane (D / 256, at least 1).
+template <int BITS, int NDW, int GPL>
+__device__ __forceinline__ void compress_i8_unit(const uint8_t* __restrict__ raw_img, uint8_t* __restrict__ code_img,
+                                                 uint8_t* __restrict__ codes, float* __restrict__ scale_out,
+                                                 float* __restrict__ mn_out, const I8View& v, int lane) {
+    constexpr int LEVELS = (1 << BITS) - 1;
+    constexpr int RPL = NDW / GPL;                         // token rows per lane and group
+    const int c = lane & (v.group_lanes - 1);              // channel group (+ 64 * j)
+    const int rpart = lane >> (6 - v.share_log2);          // which block of RPL rows (0 unless lanes share)
+    const int row0 = rpart * RPL;
+    uint32_t w[GPL][RPL];
 #pragma unroll
-    for (int u = 0; u < PPL; ++u) {
-        const u4_t biased = raw[u] ^ 0x80808080u;      // int8 -> x + 128, order preserved
-        unpack16(biased, f[u]);
-    }
-    float scale[16], inv[16], mn[16];
+    for (int j = 0; j < GPL; ++j)
 #pragma unroll
-    for (int k = 0; k < 16; ++k) {
-        float lo = f[0][k], hi = f[0][k];
+        for (int k = 0; k < RPL; ++k)
+            w[j][k] = *reinterpret_cast<const uint32_t*>(raw_img + (row0 + k) * v.head_dim + 4 * (c + 64 * j));
 #pragma unroll
-        for (int u = 1; u < PPL; ++u) {
-            lo = fminf(lo, f[u][k]);
-            hi = fmaxf(hi, f[u][k]);
+    for (int j = 0; j < GPL; ++j) {
+        // bytes 0 and 2 of a dword as one 16-bit pair, bytes 1 and 3 as another
+        uint32_t mnE = w[j][0] & 0x00ff00ffu, mnO = (w[j][0] >> 8) & 0x00ff00ffu;
+        uint32_t mxE = mnE, mxO = mnO;
+#pragma unroll
+        for (int k = 1; k < RPL; ++k) {
+            const uint32_t e = w[j][k] & 0x00ff00ffu, o = (w[j][k] >> 8) & 0x00ff00ffu;
+            mnE = pk_min_u16(mnE, e); mxE = pk_max_u16(mxE, e);
+            mnO = pk_min_u16(mnO, o); mxO = pk_max_u16(mxO, o);
         }
-        lo = same_channel_reduce<true>(lo, rp_log2);
-        hi = same_channel_reduce<false>(hi, rp_log2);
-        mn[k] = lo;
-        scale[k] = (hi - lo) / kLevels;
-        inv[k] = (scale[k] != 0.0f) ? __builtin_amdgcn_rcpf(scale[k]) : 0.0f;
-    }
-#pragma unroll
-    for (int u = 0; u < PPL; ++u) {
-        float r[16];
-        float emax = 0.0f;
-#pragma unroll
-        for (int k = 0; k < 16; ++k) {
-            const float q = (f[u][k] - mn[k]) * inv[k];
-            r[k] = __builtin_rintf(q);
-            emax = fmaxf(emax, __builtin_fabsf(q - r[k]));
+        if (v.share_log2 >= 1) {       // lanes l and l ^ 32
+            uint32_t lo, hi;
+            xhalf_both_u32(mnE, lo, hi); mnE = pk_min_u16(lo, hi);
+            xhalf_both_u32(mnO, lo, hi); mnO = pk_min_u16(lo, hi);
+            xhalf_both_u32(mxE, lo, hi); mxE = pk_max_u16(lo, hi);
+            xhalf_both_u32(mxO, lo, hi); mxO = pk_max_u16(lo, hi);
         }
-        // integer data meet exact ties often: those lanes redo the piece with the true division
-        if (emax >= kSafe) {
+        if (v.share_log2 >= 2) {       // and l ^ 16
+            mnE = pk_min_u16(mnE, static_cast<uint32_t>(__shfl_xor(static_cast<int>(mnE), 16)));
+            mnO = pk_min_u16(mnO, static_cast<uint32_t>(__shfl_xor(static_cast<int>(mnO), 16)));
+            mxE = pk_max_u16(mxE, static_cast<uint32_t>(__shfl_xor(static_cast<int>(mxE), 16)));
+            mxO = pk_max_u16(mxO, static_cast<uint32_t>(__shfl_xor(static_cast<int>(mxO), 16)));
+        }
+        // channel 4g + i: i = 0, 2 in the even pair, 1, 3 in the odd pair
+        float mn[4], scale[4], rinv[4];
+        const uint32_t mnw[4] = {mnE & 0xffffu, mnO & 0xffffu, mnE >> 16, mnO >> 16};
+        const uint32_t mxw[4] = {mxE & 0xffffu, mxO & 0xffffu, mxE >> 16, mxO >> 16};
 #pragma unroll
-            for (int k = 0; k < 16; ++k) {
-                float c = 0.0f;
-                if (scale[k] != 0.0f) {
-                    c = __builtin_rintf((f[u][k] - mn[k]) / scale[k]);
-                    c = __builtin_fminf(__builtin_fmaxf(c, 0.0f), kLevels);
-                }
-                r[k] = c;
+        for (int i = 0; i < 4; ++i) {
+            mn[i] = static_cast<float>(mnw[i]);
+            scale[i] = div_levels<LEVELS>(static_cast<float>(mxw[i] - mnw[i]));
+            rinv[i] = refined_rcp(scale[i]);
+        }
+        const int g4 = c + 64 * j;                            // channel group index in the row
+#pragma unroll
+        for (int k = 0; k < RPL; ++k) {
+            const uint32_t x = w[j][k];
+            const float xf[4] = {static_cast<float>(x & 0xffu), static_cast<float>((x >> 8) & 0xffu),
+                                 static_cast<float>((x >> 16) & 0xffu), static_cast<float>(x >> 24)};
+            uint32_t acc = 0;
+#pragma unroll
+            for (int i = 3; i >= 0; --i) {
+                const float q = div_exact(xf[i] - mn[i], scale[i], rinv[i]);
+                // q + 1.5 * 2^23 rounds q to an integer, halves to even; the code is in the low mantissa bits
+                const uint32_t u = __builtin_bit_cast(uint32_t, q + 12582912.0f);
+                acc = (acc << BITS) + u;
+            }
+            const int row = row0 + k;
+            if constexpr (BITS == 4) {
+                *reinterpret_cast<uint16_t*>(code_img + row * (v.head_dim >> 1) + 2 * g4) = static_cast<uint16_t>(acc);
+            } else if constexpr (BITS == 2) {
+                code_img[row * (v.head_dim >> 2) + g4] = static_cast<uint8_t>(acc);
+            } else {
+                // two neighbouring lanes (adjacent channel groups) share a byte
+                const uint32_t nb = dpp_u32<0xB1>(acc);
+                if ((lane & 1) == 0)
+                    code_img[row * (v.head_dim >> 3) + (g4 >> 1)] = static_cast<uint8_t>((acc & 0xfu) | ((nb & 0xfu) << 4));
             }
         }
-        const u2_t w = pack16<BITS>(r);
-        const int p = u * 64 + lane;
-        if constexpr (BITS == 4) stream_store<KVS_NT_CODE_STORE>(w, reinterpret_cast<u2_t*>(codes) + p);
-        else if constexpr (BITS == 2) stream_store<KVS_NT_CODE_STORE>(w.x, reinterpret_cast<uint32_t*>(codes) + p);
-        else stream_store<KVS_NT_CODE_STORE>(static_cast<uint16_t>(w.x), reinterpret_cast<uint16_t*>(codes) + p);
-    }
-    // the first token row's lanes write their 16 channels' parameters
-    if (lane < (1 << rp_log2)) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const u4_t sv = {__builtin_bit_cast(uint32_t, scale[4 * j]), __builtin_bit_cast(uint32_t, scale[4 * j + 1]),
-                             __builtin_bit_cast(uint32_t, scale[4 * j + 2]), __builtin_bit_cast(uint32_t, scale[4 * j + 3])};
-            const float m0 = mn[4 * j] - 128.0f, m1 = mn[4 * j + 1] - 128.0f, m2 = mn[4 * j + 2] - 128.0f,
-                        m3 = mn[4 * j + 3] - 128.0f;
+        if (rpart == 0) {
+            const u4_t sv = {__builtin_bit_cast(uint32_t, scale[0]), __builtin_bit_cast(uint32_t, scale[1]),
+                             __builtin_bit_cast(uint32_t, scale[2]), __builtin_bit_cast(uint32_t, scale[3])};
+            const float m0 = mn[0] - 128.0f, m1 = mn[1] - 128.0f, m2 = mn[2] - 128.0f, m3 = mn[3] - 128.0f;
             const u4_t mv = {__builtin_bit_cast(uint32_t, m0), __builtin_bit_cast(uint32_t, m1),
                              __builtin_bit_cast(uint32_t, m2), __builtin_bit_cast(uint32_t, m3)};
-            reinterpret_cast<u4_t*>(scale_out)[lane * 4 + j] = sv;
-            reinterpret_cast<u4_t*>(mn_out)[lane * 4 + j] = mv;
+            reinterpret_cast<u4_t*>(scale_out)[g4] = sv;
+            reinterpret_cast<u4_t*>(mn_out)[g4] = mv;
         }
     }
+    // LDS writes of this wavefront are ordered before its reads below
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    copy_out<NDW * BITS / 2>(code_img, codes, lane);
 }
 
 // Grid as compress_kernel with one task per unit (g.tpu = 1); g.pieces = T * D / 16,
-// g.row_pieces = D / 16, g.lpg_log2 = log2(row_pieces).
-template <int PPL>
+// g.row_pieces = D / 16.  LDS: per wavefront the unit (NDW * 256 bytes) and its codes (at most half of that).
+template <int NDW, int GPL>
 __global__ __launch_bounds__(256) void compress_i8_kernel(const u4_t* __restrict__ kv,
                                                           const uint8_t* __restrict__ bits,
                                                           const uint64_t* __restrict__ off,
                                                           uint8_t* __restrict__ packed, QuantGeom g,
-                                                          int32_t n_chunks) {
+                                                          I8View v, int32_t n_chunks) {
+    constexpr int PPL = NDW / 4;
+    __shared__ __align__(16) uint8_t lds[kWavesPerBlock][NDW * 256 + NDW * 128];
     const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6));
     int chunk, slab, p0;
     if (!wave_task(g, n_chunks, PPL, chunk, slab, p0)) return;
     const u4_t* src = kv + (static_cast<uint64_t>(slab) * g.n_tokens +
@@ -179,15 +226,23 @@ __global__ __launch_bounds__(256) void compress_i8_kernel(const u4_t* __restrict
                                             static_cast<uint64_t>(slab) * g.pieces + u * 64 + lane);
         return;
     }
+    uint8_t* raw_img = lds[wave];
+    uint8_t* code_img = raw_img + NDW * 256;
+#pragma unroll
+    for (int u = 0; u < PPL; ++u)       // int8 -> x + 128, order preserved
+        reinterpret_cast<u4_t*>(raw_img)[u * 64 + lane] = raw[u] ^ 0x80808080u;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     const uint64_t code_bytes = static_cast<uint64_t>(g.pieces) * 2 * b;   // T * D * b / 8 per unit
-    const uint32_t channels = static_cast<uint32_t>(g.row_pieces) * 16;
+    const uint32_t channels = static_cast<uint32_t>(v.head_dim);
     uint8_t* codes = base + slab * code_bytes;
     float* scale = reinterpret_cast<float*>(base + g.slabs * code_bytes) +
                    static_cast<uint64_t>(slab) * channels;
     float* mn = scale + static_cast<uint64_t>(g.slabs) * channels;
-    if (b == 4) compress_i8_unit<4, PPL>(raw, codes, scale, mn, g.lpg_log2, lane);
-    else if (b == 2) compress_i8_unit<2, PPL>(raw, codes, scale, mn, g.lpg_log2, lane);
-    else compress_i8_unit<1, PPL>(raw, codes, scale, mn, g.lpg_log2, lane);
+    if (b == 4) compress_i8_unit<4, NDW, GPL>(raw_img, code_img, codes, scale, mn, v, lane);
+    else if (b == 2) compress_i8_unit<2, NDW, GPL>(raw_img, code_img, codes, scale, mn, v, lane);
+    else compress_i8_unit<1, NDW, GPL>(raw_img, code_img, codes, scale, mn, v, lane);
 }
 
 // ------------------------------------------------------------------ swap-in

@@ -86,6 +86,32 @@ def test_adversarial_values(b):
     check_full(g, x.astype(np.int8), np.full(g.n_chunks, b, dtype=np.uint8))
 
 
+@pytest.mark.parametrize("b", [4, 2, 1])
+def test_every_range_and_offset(b):
+    """The codes of a channel depend only on its range r = max - min and on x - min.  Every
+    pair 0 <= x - min <= r <= 255 occurs here (with varying minima), so this comparison
+    covers the whole domain of the format's two divisions."""
+    T, D = 16, 128
+    rng = np.random.default_rng(100 + b)
+    cols = []
+    for r in range(256):
+        inner = list(range(1, r))                      # offsets besides 0 and r
+        for i in range(0, max(len(inner), 1), T - 2):
+            part = inner[i:i + T - 2]
+            col = [0, r] + part + [0] * (T - 2 - len(part))
+            rng.shuffle(col)
+            lo = int(rng.integers(-128, 128 - r))
+            cols.append(np.array(col) + lo)
+    n_units = -(-len(cols) // D)
+    n_chunks = -(-n_units // 2)
+    cols += [np.zeros(T, dtype=np.int64)] * (n_chunks * 2 * D - len(cols))
+    x = np.stack(cols, axis=1).reshape(T, n_chunks, 2, D)              # [t][chunk][slab][d]
+    kv = np.ascontiguousarray(x.transpose(2, 1, 0, 3)).reshape(1, 2, 1, n_chunks * T, D)
+    assert kv.min() >= -128 and kv.max() <= 127
+    g = synth.Geometry(1, 1, 1, D, n_chunks * T, T, 64)
+    check_full(g, kv.astype(np.int8), np.full(n_chunks, b, dtype=np.uint8))
+
+
 def test_random_cache_many_channels():
     g = synth.Geometry(4, 4, 4, 128, 512, 16, 64)
     kv = synth.make_kv_i8(g, 5, "cpu").numpy()
