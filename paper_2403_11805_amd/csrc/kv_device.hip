@@ -209,10 +209,11 @@ static int score_geom(const kv_shape_t* shape, int32_t n_queries, int32_t norm_m
     // several row groups per kv head: the workgroup shares each K tile through LDS and all
     // its wavefronts walk the same run; a single row group: four independent runs per workgroup
     g.tile_par = g.rg_per_wg > 1 ? 1 : 4;
-    g.run_len = std::min(g.n_tiles, g.tile_par == 1 ? 16 : 8);
+    g.run_len = std::min(g.n_tiles, g.tile_par == 1 ? 64 : 8);
     g.n_runs = (g.n_tiles + g.run_len - 1) / g.run_len;
     g.norm_mode = norm_mode;
     g.scale_log2e = static_cast<float>(1.4426950408889634 / std::sqrt(static_cast<double>(s.head_dim)));
+    g.inv_R = 1.0f / static_cast<float>(n_queries);
     *out = g;
     return KV_OK;
 }
@@ -258,21 +259,30 @@ int32_t kv_score_chunks(const kv_shape_t* shape, const void* q, int32_t n_querie
                     (g.n_rg + g.rg_per_wg - 1) / g.rg_per_wg, g.L * g.Hkv);
     const _Float16* qp = static_cast<const _Float16*>(q);
     const _Float16* kp = static_cast<const _Float16*>(kv);
-#define KV_SCORE_LAUNCH(DD, NR)                                                                       \
+#define KV_SCORE_SHARED(DD)                                                                           \
     do {                                                                                             \
-        if (g.rg_per_wg > 1)                                                                         \
-            hipLaunchKernelGGL((score_tiles_shared_kernel<DD, NR>), grid, dim3(256), 0, st, qp, kp, g, ws); \
+        if (g.sb_tokens == 32)                                                                       \
+            hipLaunchKernelGGL((score_tiles_shared_kernel<DD, 1>), grid, dim3(256), 0, st, qp, kp, g, ws); \
+        else if (g.sb_tokens == 16)                                                                  \
+            hipLaunchKernelGGL((score_tiles_shared_kernel<DD, 2>), grid, dim3(256), 0, st, qp, kp, g, ws); \
         else                                                                                         \
-            hipLaunchKernelGGL((score_tiles_kernel<DD, NR>), grid, dim3(256), 0, st, qp, kp, g, ws);  \
+            hipLaunchKernelGGL((score_tiles_shared_kernel<DD, 4>), grid, dim3(256), 0, st, qp, kp, g, ws); \
     } while (0)
+#define KV_SCORE_DIRECT(DD, NR) \
+    hipLaunchKernelGGL((score_tiles_kernel<DD, NR>), grid, dim3(256), 0, st, qp, kp, g, ws)
     const int D = shape->head_dim;
-    if (D == 64 && nrbw == 1) KV_SCORE_LAUNCH(64, 1);
-    else if (D == 64) KV_SCORE_LAUNCH(64, 2);
-    else if (D == 128 && nrbw == 1) KV_SCORE_LAUNCH(128, 1);
-    else if (D == 128) KV_SCORE_LAUNCH(128, 2);
-    else if (nrbw == 1) KV_SCORE_LAUNCH(256, 1);
-    else KV_SCORE_LAUNCH(256, 2);
-#undef KV_SCORE_LAUNCH
+    if (g.rg_per_wg > 1) {          // several row groups per kv head: two row blocks per wavefront
+        if (D == 64) KV_SCORE_SHARED(64);
+        else if (D == 128) KV_SCORE_SHARED(128);
+        else KV_SCORE_SHARED(256);
+    } else if (D == 64 && nrbw == 1) KV_SCORE_DIRECT(64, 1);
+    else if (D == 64) KV_SCORE_DIRECT(64, 2);
+    else if (D == 128 && nrbw == 1) KV_SCORE_DIRECT(128, 1);
+    else if (D == 128) KV_SCORE_DIRECT(128, 2);
+    else if (nrbw == 1) KV_SCORE_DIRECT(256, 1);
+    else KV_SCORE_DIRECT(256, 2);
+#undef KV_SCORE_SHARED
+#undef KV_SCORE_DIRECT
     if (int rc = launch_status("score_tiles_kernel launch")) return rc;
     hipLaunchKernelGGL(score_combine_kernel, dim3(g.L * g.Hq), dim3(256), 0, st, g, ws, chunk_mass);
     if (int rc = launch_status("score_combine_kernel launch")) return rc;

@@ -41,6 +41,7 @@ struct ScoreGeom {
     int32_t n_runs;       // ceil(n_tiles / run_len): runs per (layer, head)
     int32_t norm_mode;    // 0: divide each column by its number of visible rows; 1: plain sums
     float   scale_log2e;  // log2(e) / sqrt(D)
+    float   inv_R;        // 1 / R
 };
 
 // Workspace planes (floats), row index fastest:
@@ -56,11 +57,20 @@ struct ScoreWs {
 
 // Softmax partials of one 32-token tile for one block of 32 query rows.
 // acc[v] = raw logit of (token tile*32 + 8*(v/4) + 4*half + v%4, query row of this lane);
-// row < 0 marks a padding row.  Writes the tile maximum and the weighted
-// sub-block sums, and folds the tile into the run's maximum / denominator.
+// row < 0 marks a padding row.  Writes the tile's reference exponent and the
+// weighted sub-block sums, and folds the tile into the run's reference / denominator.
+//
+// Every row keeps ONE reference exponent m_ref for a whole run of tiles: the
+// maximum of the run's first tile.  Later tiles are exponentiated against it
+// without a maximum pass of their own; should a tile's sum leave the safe range
+// (a logit more than 60 binary orders above the reference) the tile is redone
+// against its own maximum, which becomes the new reference.  The partials only
+// promise "sum of w * 2^(s - m_tile)" for the m_tile stored beside them.
+constexpr float kRefOverflow = 1.152921504606846976e18f;   // 2^60
+
 __device__ __forceinline__ void tile_epilogue(const v16f_t& acc, const ScoreGeom& g, const ScoreWs& ws,
-                                              int tile, int row, int lh, int half, float& m_run,
-                                              float& l_run) {
+                                              int tile, int row, int lh, int half, bool first,
+                                              float& m_ref, float& l_run) {
     const int t0 = tile * 32;
     const int first_q_pos = g.N - g.R;
     const bool tail = (t0 + 31 > first_q_pos);   // wave-uniform: some entry may be masked
@@ -68,17 +78,34 @@ __device__ __forceinline__ void tile_epilogue(const v16f_t& acc, const ScoreGeom
     // q4[k]: (weighted) sum over the lane's tokens 8k..8k+7 of the tile; l4[k]: unweighted
     float q4[4] = {0.0f, 0.0f, 0.0f, 0.0f};
     float l4[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    float lsum;
     if (!tail) {
         // every entry is visible and every column has the same weight
-        float mloc = acc[0];
+        bool own_max = first;
+        for (;;) {
+            if (own_max) {
+                float mloc = acc[0];
 #pragma unroll
-        for (int v = 1; v < 16; ++v) mloc = fmaxf(mloc, acc[v]);
-        mloc = xhalf_max(mloc);
-        m_t = mloc * g.scale_log2e;
+                for (int v = 1; v < 16; ++v) mloc = fmaxf(mloc, acc[v]);
+                // the reference never decreases, so the rescaling factor is at most 1
+                // (a padding row has logits 0: its reference is 0, its sums are never stored)
+                const float m_new = fmaxf(m_ref, xhalf_max(mloc) * g.scale_log2e);
+                l_run = (m_ref == -INFINITY) ? 0.0f : l_run * __builtin_amdgcn_exp2f(m_ref - m_new);
+                m_ref = m_new;
+            }
 #pragma unroll
-        for (int v = 0; v < 16; ++v)
-            l4[v / 4] += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[v], g.scale_log2e, -m_t));
-        const float w_const = (g.norm_mode == 0) ? 1.0f / static_cast<float>(g.R) : 1.0f;
+            for (int k = 0; k < 4; ++k) l4[k] = 0.0f;
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                l4[v / 4] += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[v], g.scale_log2e, -m_ref));
+            lsum = xhalf_sum((l4[0] + l4[1]) + (l4[2] + l4[3]));
+            // wave-uniform: redo the tile against its own maximum if any row left the safe range
+            if (own_max || !__any(!(lsum < kRefOverflow))) break;
+            own_max = true;
+        }
+        m_t = m_ref;
+        l_run += lsum;
+        const float w_const = (g.norm_mode == 0) ? g.inv_R : 1.0f;
 #pragma unroll
         for (int k = 0; k < 4; ++k) q4[k] = l4[k] * w_const;
     } else {
@@ -103,10 +130,13 @@ __device__ __forceinline__ void tile_epilogue(const v16f_t& acc, const ScoreGeom
             if (g.norm_mode == 0) w = 1.0f / static_cast<float>(g.N - max(tk, first_q_pos));
             q4[v / 4] += e * w;
         }
+        lsum = xhalf_sum((l4[0] + l4[1]) + (l4[2] + l4[3]));
+        // this tile keeps its own maximum; the run's reference moves to the larger of the two
+        const float m_new = fmaxf(m_ref, m_t);
+        const float m_safe = (m_new == -INFINITY) ? 0.0f : m_new;
+        l_run = l_run * __builtin_amdgcn_exp2f(m_ref - m_safe) + lsum * __builtin_amdgcn_exp2f(m_t - m_safe);
+        m_ref = m_new;
     }
-    // the lane's partial denominator, then both halves of the wavefront together
-    float lsum = (l4[0] + l4[1]) + (l4[2] + l4[3]);
-    lsum = xhalf_sum(lsum);
     // sub-block sums: 8, 16 or 32 tokens each (uniform branch), both halves together
     float esub[4];
     int n_sub;
@@ -125,13 +155,6 @@ __device__ __forceinline__ void tile_epilogue(const v16f_t& acc, const ScoreGeom
         const float a = (q4[0] + q4[1]) + (q4[2] + q4[3]);
         esub[0] = xhalf_sum(a);
         esub[1] = esub[2] = esub[3] = 0.0f;
-    }
-    // running maximum / denominator of this run
-    {
-        const float m_new = fmaxf(m_run, m_t);
-        const float m_safe = (m_new == -INFINITY) ? 0.0f : m_new;
-        l_run = l_run * __builtin_amdgcn_exp2f(m_run - m_safe) + lsum * __builtin_amdgcn_exp2f(m_t - m_safe);
-        m_run = m_new;
     }
     if (half == 0 && row >= 0) {
         const int n_sb = g.N / g.sb_tokens;
@@ -217,7 +240,7 @@ __global__ __launch_bounds__(256) void score_tiles_kernel(const _Float16* __rest
 #pragma unroll
         for (int u = 0; u < NRBW; ++u) {
             if (rg * NRBW + u >= g.n_rb) break;
-            tile_epilogue(acc[u], g, ws, tile, row[u], lh[u], half, m_run[u], l_run[u]);
+            tile_epilogue(acc[u], g, ws, tile, row[u], lh[u], half, tile == tile_begin, m_run[u], l_run[u]);
         }
     }
 #pragma unroll
@@ -230,25 +253,83 @@ __global__ __launch_bounds__(256) void score_tiles_kernel(const _Float16* __rest
     }
 }
 
+// Partials of a tile whose entries are all visible, against the row's current
+// reference, with no branch and no maximum pass: straight-line code that can be
+// interleaved with the MFMAs of the next tile.  Both halves of the wavefront
+// store the same values to the same slots; padding rows have slots of their own
+// (rows_p per tile).  `bad` collects rows whose sum left the safe range: the
+// caller then redoes the tile through tile_epilogue.
+//   SBT = sub-blocks per tile (32 / sb_tokens); mt, es = this lane's slots of the tile.
+template <int SBT>
+__device__ __forceinline__ void fast_epilogue(const v16f_t& acc, float scale_log2e, float w,
+                                              float m_ref, float& l_run, uint32_t& bad,
+                                              float* __restrict__ mt, float* __restrict__ es, int rows_p) {
+    float l4[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        float a = __builtin_amdgcn_exp2f(__builtin_fmaf(acc[4 * k], scale_log2e, -m_ref));
+#pragma unroll
+        for (int i = 1; i < 4; ++i)
+            a += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[4 * k + i], scale_log2e, -m_ref));
+        l4[k] = a;
+    }
+    float sub[SBT];
+    float lsum;
+    if constexpr (SBT == 1) {
+        sub[0] = xhalf_sum((l4[0] + l4[1]) + (l4[2] + l4[3]));
+        lsum = sub[0];
+    } else if constexpr (SBT == 2) {
+        sub[0] = xhalf_sum(l4[0] + l4[1]);
+        sub[1] = xhalf_sum(l4[2] + l4[3]);
+        lsum = sub[0] + sub[1];
+    } else {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) sub[k] = xhalf_sum(l4[k]);
+        lsum = (sub[0] + sub[1]) + (sub[2] + sub[3]);
+    }
+    l_run += lsum;
+    bad |= (lsum < kRefOverflow) ? 0u : 1u;
+    mt[0] = m_ref;
+#pragma unroll
+    for (int k = 0; k < SBT; ++k) es[k * rows_p] = sub[k] * w;
+}
+
 // Variant for grouped-query attention: the 2-4 wavefronts of a workgroup hold
-// the row blocks of different query heads that read the SAME kv head, so the K
-// tile is fetched once per workgroup (fully coalesced, 16 bytes per thread and
-// access), staged in LDS (double-buffered, rows padded by 16 bytes so that the
-// operand reads are bank-conflict free) and read from there by every wavefront.
-template <int D, int NRBW>
-__global__ __launch_bounds__(256) void score_tiles_shared_kernel(const _Float16* __restrict__ q,
-                                                                 const _Float16* __restrict__ kv,
-                                                                 ScoreGeom g, ScoreWs ws) {
+// the row blocks (two each) of different query heads that read the SAME kv head,
+// so K is fetched once per workgroup (fully coalesced, 16 bytes per thread and
+// access), staged in LDS (two buffers of two tiles; the 16-byte pieces of a row
+// are permuted by its row number so that the operand reads are bank-conflict
+// free) and read from there by every wavefront: one barrier per 64 tokens.
+//
+// A run is processed in up to three passes over its tiles:
+//  - the fast pass over the tiles below the causal diagonal.  The row references
+//    come from the run's first tile; the loads of a stage are issued two stages
+//    ahead (two register sets used in turn), and inside a wavefront the MFMAs of
+//    a tile are interleaved, instruction by instruction, with the softmax
+//    partials (fast_epilogue) of the tile before it (two accumulator sets used in
+//    turn), so that the matrix pipe and the VALU work overlap;
+//  - the general pass (tile_epilogue) over the tiles that reach the diagonal;
+//  - the general pass over the whole fast range again if some sum left the safe
+//    range there (workgroup-wide decision), or instead of the fast pass if a
+//    wavefront holds only one row block.
+template <int D, int SBT>
+__global__ __launch_bounds__(256, 2) void score_tiles_shared_kernel(const _Float16* __restrict__ q,
+                                                                    const _Float16* __restrict__ kv,
+                                                                    ScoreGeom g, ScoreWs ws) {
+    constexpr int NRBW = 2;
     constexpr int KS = D / 16;
     constexpr int kRowPieces = D / 8;               // 16-byte pieces per token row
-    constexpr int kLdsRow = kRowPieces + 1;         // padded row, in pieces
     constexpr int kTilePieces = 32 * kRowPieces;
-    constexpr int kPerThread = kTilePieces / 256;   // 1, 2 or 4
+    constexpr int TS = D <= 128 ? 2 : 1;                 // tiles per LDS stage (two 32 KiB buffers at most)
+    constexpr int kPerThread = TS * kTilePieces / 256;   // 16-byte loads per thread and stage
     typedef unsigned int su4_t __attribute__((ext_vector_type(4)));
-    __shared__ su4_t ktile[2][32 * kLdsRow];
+    __shared__ su4_t kstage[2][TS * 32 * kRowPieces];
+    // piece c of stage row r sits at r * kRowPieces + (c ^ swz(r)): 16 consecutive rows of one
+    // piece column fall into 16 different 16-byte bank groups
+    auto swz = [](int r) __attribute__((always_inline)) { return D == 64 ? (r >> 1) & 7 : r & 15; };
 
     const int tid = threadIdx.x;
-    const int wave = tid >> 6, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int lrow = lane & 31, half = lane >> 5;
     const int run = blockIdx.x;
     const int tile_begin = run * g.run_len;
@@ -258,20 +339,30 @@ __global__ __launch_bounds__(256) void score_tiles_shared_kernel(const _Float16*
     const bool active = wave < g.rg_per_wg && rg < g.n_rg;
     const int l = blockIdx.z / g.Hkv, kvh = blockIdx.z % g.Hkv;
     const int qh_per_kv = g.Hq / g.Hkv;
+    // tiles from here on touch the causal diagonal
+    const int first_tail_tile = (g.N - g.R + 1) / 32;
+    const bool two_blocks = rg * NRBW + 1 < g.n_rb;
+    // the fast pass needs both row blocks in every wavefront (workgroup-uniform)
+    const int fast_end = (g.n_rb % NRBW == 0) ? min(tile_end, max(first_tail_tile, tile_begin)) : tile_begin;
 
     v8h_t qreg[NRBW][KS];
     int row[NRBW], lh[NRBW];
     float m_run[NRBW], l_run[NRBW];
+    float* mt_base[NRBW];     // this lane's slot of tile 0 in m_tile / e_sub
+    float* es_base[NRBW];
 #pragma unroll
     for (int u = 0; u < NRBW; ++u) {
         const int rb = rg * NRBW + u;
-        const int head = kvh * qh_per_kv + rb / g.RB;
-        const int r = (rb % g.RB) * 32 + lrow;
-        const bool ok = active && rb < g.n_rb && r < g.R;
+        const bool exists = active && rb < g.n_rb;
+        const int head = kvh * qh_per_kv + (exists ? rb / g.RB : 0);
+        const int r = (rb % g.RB) * 32 + lrow;          // slot inside the head: < rows_p
+        const bool ok = exists && r < g.R;
         row[u] = ok ? r : -1;
-        lh[u] = l * g.Hq + ((active && rb < g.n_rb) ? head : 0);
+        lh[u] = l * g.Hq + head;
         m_run[u] = -INFINITY;
         l_run[u] = 0.0f;
+        mt_base[u] = ws.m_tile + static_cast<int64_t>(lh[u]) * g.n_tiles * g.rows_p + r;
+        es_base[u] = ws.e_sub + static_cast<int64_t>(lh[u]) * g.n_tiles * SBT * g.rows_p + r;
         const _Float16* qp = q + (static_cast<int64_t>(lh[u]) * g.R + (ok ? r : 0)) * D + half * 8;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
@@ -283,51 +374,154 @@ __global__ __launch_bounds__(256) void score_tiles_shared_kernel(const _Float16*
 
     const su4_t* kbase = reinterpret_cast<const su4_t*>(
         kv + (static_cast<int64_t>(l) * 2 * g.Hkv + kvh) * g.N * D);
-    su4_t stage[kPerThread];
+    // pieces of the stage that starts at tile t (< stop).  Loads are unconditional so that they
+    // stay in flight: a tile at or beyond `stop` is replaced by tile stop - 1 and never used.
+    auto fetch = [&](su4_t (&st)[kPerThread], int t, int stop) __attribute__((always_inline)) {
 #pragma unroll
-    for (int i = 0; i < kPerThread; ++i)
-        stage[i] = kbase[static_cast<int64_t>(tile_begin) * kTilePieces + i * 256 + tid];
-#pragma unroll
-    for (int i = 0; i < kPerThread; ++i) {
-        const int p = i * 256 + tid;
-        ktile[0][(p / kRowPieces) * kLdsRow + (p % kRowPieces)] = stage[i];
-    }
-    __syncthreads();
-    for (int tile = tile_begin; tile < tile_end; ++tile) {
-        const int buf = (tile - tile_begin) & 1;
-        const bool more = tile + 1 < tile_end;
-        if (more) {
-#pragma unroll
-            for (int i = 0; i < kPerThread; ++i)
-                stage[i] = kbase[static_cast<int64_t>(tile + 1) * kTilePieces + i * 256 + tid];
+        for (int i = 0; i < kPerThread; ++i) {
+            const int p = i * 256 + tid;
+            const int tile = min(t + p / kTilePieces, stop - 1);
+            st[i] = kbase[static_cast<int64_t>(tile) * kTilePieces + p % kTilePieces];
         }
+    };
+    auto park = [&](const su4_t (&st)[kPerThread], int buf) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < kPerThread; ++i) {
+            const int p = i * 256 + tid;
+            const int r = p / kRowPieces, c = p % kRowPieces;
+            kstage[buf][r * kRowPieces + (c ^ swz(r))] = st[i];
+        }
+    };
+    // K operand of tile j (0 or 1) of a stage, then the logits of both row blocks
+    auto logits = [&](v16f_t (&a)[NRBW], int buf, int j) __attribute__((always_inline)) {
+        v8h_t kreg[KS];
+        const int r = j * 32 + lrow;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+            kreg[ks] = __builtin_bit_cast(v8h_t, kstage[buf][r * kRowPieces + ((2 * ks + half) ^ swz(r))]);
+#pragma unroll
+        for (int u = 0; u < NRBW; ++u) a[u] = v16f_t{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+        // independent accumulators interleaved: consecutive MFMAs do not depend on each other
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+            for (int u = 0; u < NRBW; ++u)
+                a[u] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kreg[ks], qreg[u][ks], a[u], 0, 0, 0);
+    };
+
+    // General pass over tiles [from, to): plain double buffering, partials right behind the MFMAs.
+    auto general_pass = [&](int from, int to) __attribute__((always_inline)) {
+        su4_t st[kPerThread];
+        fetch(st, from, to);
+        park(st, 0);
+        __syncthreads();
+        for (int t = from; t < to; t += TS) {
+            const int buf = ((t - from) / TS) & 1;
+            const bool more = t + TS < to;
+            if (more) fetch(st, t + TS, to);
+            if (active) {
+                for (int j = 0; j < TS && t + j < to; ++j) {
+                    v16f_t a[NRBW];
+                    logits(a, buf, j);
+#pragma unroll
+                    for (int u = 0; u < NRBW; ++u) {
+                        if (u == 1 && !two_blocks) break;
+                        tile_epilogue(a[u], g, ws, t + j, row[u], lh[u], half, t + j == tile_begin,
+                                      m_run[u], l_run[u]);
+                    }
+                }
+            }
+            if (more) park(st, buf ^ 1);
+            __syncthreads();
+        }
+    };
+
+    int dirty = 0;
+    if (fast_end > tile_begin) {
+        const float w_const = (g.norm_mode == 0) ? g.inv_R : 1.0f;
+        su4_t sa[kPerThread], sb[kPerThread];   // stages in flight: sa holds odd stages, sb even ones
+        fetch(sb, tile_begin, fast_end);
+        park(sb, 0);
+        fetch(sa, tile_begin + TS, fast_end);
+        __syncthreads();
+        v16f_t acc[2][NRBW];
+        uint32_t bad = 0;
         if (active) {
-            v8h_t kreg[KS];
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-                kreg[ks] = __builtin_bit_cast(v8h_t, ktile[buf][lrow * kLdsRow + 2 * ks + half]);
-            v16f_t acc[NRBW];
-#pragma unroll
-            for (int u = 0; u < NRBW; ++u) acc[u] = v16f_t{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-                for (int u = 0; u < NRBW; ++u)
-                    acc[u] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kreg[ks], qreg[u][ks], acc[u], 0, 0, 0);
+            // row references: the maxima of the first tile
+            logits(acc[0], 0, 0);
 #pragma unroll
             for (int u = 0; u < NRBW; ++u) {
-                if (rg * NRBW + u >= g.n_rb) break;
-                tile_epilogue(acc[u], g, ws, tile, row[u], lh[u], half, m_run[u], l_run[u]);
-            }
-        }
-        if (more) {
+                float mloc = acc[0][u][0];
 #pragma unroll
-            for (int i = 0; i < kPerThread; ++i) {
-                const int p = i * 256 + tid;
-                ktile[buf ^ 1][(p / kRowPieces) * kLdsRow + (p % kRowPieces)] = stage[i];
+                for (int v = 1; v < 16; ++v) mloc = fmaxf(mloc, acc[0][u][v]);
+                m_run[u] = xhalf_max(mloc) * g.scale_log2e;
             }
         }
-        __syncthreads();
+        // the MFMAs of tile `tile` (set cur) interleaved with the partials of tile - 1 (set cur ^ 1)
+        auto fast_tile = [&](int cur, int buf, int j, int tile) __attribute__((always_inline)) {
+            if (tile == tile_begin) {
+                logits(acc[cur], buf, j);
+                return;
+            }
+            logits(acc[cur], buf, j);
+#pragma unroll
+            for (int u = 0; u < NRBW; ++u)
+                fast_epilogue<SBT>(acc[cur ^ 1][u], g.scale_log2e, w_const, m_run[u], l_run[u], bad,
+                                   mt_base[u] + static_cast<int64_t>(tile - 1) * g.rows_p,
+                                   es_base[u] + static_cast<int64_t>(tile - 1) * SBT * g.rows_p, g.rows_p);
+            // one MFMA, then a share of the VALU work, and so on
+#pragma unroll
+            for (int i = 0; i < KS * NRBW; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x402, (2 * (66 + 2 * SBT)) / (KS * NRBW) + 1, 0);
+            }
+        };
+        // stage s (TS tiles from t) is in kstage[s & 1]; `next` holds stage s + 1, `far` receives
+        // stage s + 2.  Tiles use the accumulator sets in turn: set = (tile - tile_begin) & 1.
+        auto fast_stage = [&](int t, int buf, su4_t (&next)[kPerThread], su4_t (&far)[kPerThread])
+                              __attribute__((always_inline)) {
+            if (t + 2 * TS < fast_end) fetch(far, t + 2 * TS, fast_end);
+            if (active) {
+                if constexpr (TS == 2) {
+                    fast_tile(0, buf, 0, t);
+                    if (t + 1 < fast_end) fast_tile(1, buf, 1, t + 1);
+                } else {
+                    fast_tile(buf, buf, 0, t);
+                }
+            }
+            if (t + TS < fast_end) park(next, buf ^ 1);
+            __syncthreads();
+        };
+        for (int t = tile_begin; t < fast_end; t += 2 * TS) {
+            fast_stage(t, 0, sa, sb);
+            if (t + TS < fast_end) fast_stage(t + TS, 1, sb, sa);
+        }
+        if (active) {
+            // partials of the last tile of the pass
+            const int last = fast_end - 1;
+            const int set = (last - tile_begin) & 1;
+#pragma unroll
+            for (int u = 0; u < NRBW; ++u) {
+                float* mt = mt_base[u] + static_cast<int64_t>(last) * g.rows_p;
+                float* es = es_base[u] + static_cast<int64_t>(last) * SBT * g.rows_p;
+                if (set == 0) fast_epilogue<SBT>(acc[0][u], g.scale_log2e, w_const, m_run[u], l_run[u], bad, mt, es, g.rows_p);
+                else fast_epilogue<SBT>(acc[1][u], g.scale_log2e, w_const, m_run[u], l_run[u], bad, mt, es, g.rows_p);
+            }
+        }
+        dirty = __syncthreads_or(static_cast<int>(bad));
+    }
+    if (dirty) {
+        // start over through the general path (which writes every slot of these tiles again)
+#pragma unroll
+        for (int u = 0; u < NRBW; ++u) {
+            m_run[u] = -INFINITY;
+            l_run[u] = 0.0f;
+        }
+    }
+    for (int pass = dirty ? 0 : 1; pass < 2; ++pass) {
+        const int from = pass == 0 ? tile_begin : fast_end;
+        const int to = pass == 0 ? fast_end : tile_end;
+        if (from < to) general_pass(from, to);
     }
     if (active) {
 #pragma unroll
