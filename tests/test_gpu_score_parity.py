@@ -62,6 +62,41 @@ def test_peaked_and_huge_logits():
     np.testing.assert_allclose(d, d_want, rtol=RTOL, atol=1e-30)
 
 
+@pytest.mark.parametrize("geom,R", [
+    ((1, 1, 4, 128, 1184, 32, 128), 40),   # 37 tiles in one run (odd), two row blocks per head
+    ((1, 2, 4, 64, 4160, 16, 64), 32),     # 130 tiles: runs of 64, 64 and 2
+    ((1, 1, 2, 256, 2080, 8, 64), 64),     # head_dim 256: one tile per LDS stage, 65 tiles
+    ((1, 1, 3, 128, 640, 16, 64), 32),     # three row blocks per kv head: a wavefront with one block
+])
+def test_grouped_query_long_runs(geom, R):
+    """Several heads per kv head over many tiles: the pipelined pass of the shared-K kernel."""
+    g = synth.Geometry(*geom)
+    ks, os_ = both_shapes(g)
+    kv = synth.make_kv(g, 23, "cpu", 1, 4.0)
+    q = (synth.make_q(g, 23, R).float() * 5).to(torch.float16)
+    for norm in (oracle.NORM_VISIBLE, oracle.NORM_NONE):
+        cm_want, d_want = oracle.score_chunks(os_, q.numpy(), kv.numpy(), norm)
+        cm, d = gpu_score(ks, q.to(DEV), kv.to(DEV), norm)
+        assert_close(cm, cm_want, "chunk_mass")
+        assert_close(d, d_want, "density")
+
+
+@pytest.mark.parametrize("hot_token", [5, 200, 2300])
+def test_grouped_query_huge_logit_late_in_a_run(hot_token):
+    """A key far above the row references taken from a run's first tile: the sums of the
+    pipelined pass leave their safe range and the run is redone through the general path."""
+    g = synth.Geometry(1, 1, 4, 128, 4096, 16, 64)
+    ks, os_ = both_shapes(g)
+    kv = (synth.make_kv(g, 29, "cpu").float() * 0.05).to(torch.float16)
+    kv[0, 0, 0, hot_token] = 20.0
+    q = torch.full((1, 4, 32, 128), 2.0, dtype=torch.float16)
+    cm_want, d_want = oracle.score_chunks(os_, q.numpy(), kv.numpy(), oracle.NORM_NONE)
+    cm, d = gpu_score(ks, q.to(DEV), kv.to(DEV), oracle.NORM_NONE)
+    assert cm[0, 0, hot_token // 16] == pytest.approx(32.0, rel=1e-5)
+    np.testing.assert_allclose(cm, cm_want, rtol=RTOL, atol=1e-30)
+    np.testing.assert_allclose(d, d_want, rtol=RTOL, atol=1e-30)
+
+
 def test_zero_queries_closed_form():
     """Q = 0 gives uniform attention: harmonic-number column masses (checked against
     the closed form directly, no oracle involved)."""
