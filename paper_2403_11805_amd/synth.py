@@ -64,7 +64,7 @@ WORKLOADS = (
 )
 
 (_STREAM_KV, _STREAM_OUTLIER, _STREAM_Q, _STREAM_BITS, _STREAM_SUBSET, _STREAM_SCORES,
- _STREAM_KV_I8) = range(7)
+ _STREAM_KV_I8, _STREAM_WEIGHTS, _STREAM_HIDDEN) = range(9)
 
 
 def _gen(seed: int, stream: int, device="cpu", context: int = 0) -> torch.Generator:
@@ -143,3 +143,36 @@ def draw_subset(n_chunks: int, k: int, seed: int, draw: int = 0) -> torch.Tensor
     """int32 [k]: k distinct chunk indices, ascending."""
     g = _gen(seed, _STREAM_SUBSET, "cpu", draw)
     return torch.randperm(n_chunks, generator=g)[:k].sort().values.to(torch.int32)
+
+
+LAYER_WEIGHTS = ("w_norm1", "wq", "wk", "wv", "wo", "w_norm2", "w_gate", "w_up", "w_down")
+
+
+def make_layer_weights(d_model: int, n_q_heads: int, n_kv_heads: int, head_dim: int, d_ff: int,
+                       seed: int, device="cpu", layer: int = 0) -> dict:
+    """Seeded random weights of one Llama-style block, fp16, stored [in][out]: projections
+    ~ N(0, 1/sqrt(in)), norm gains ~ 1 + 0.1 N(0,1).  They stand in for trained weights, which
+    are not available; only the shapes are those of the paper's models."""
+    dev = torch.device(device)
+    g = _gen(seed, _STREAM_WEIGHTS, dev, layer)
+    shapes = {"w_norm1": (d_model,), "wq": (d_model, n_q_heads * head_dim),
+              "wk": (d_model, n_kv_heads * head_dim), "wv": (d_model, n_kv_heads * head_dim),
+              "wo": (n_q_heads * head_dim, d_model), "w_norm2": (d_model,),
+              "w_gate": (d_model, d_ff), "w_up": (d_model, d_ff), "w_down": (d_ff, d_model)}
+    out = {}
+    for name in LAYER_WEIGHTS:
+        shp = shapes[name]
+        x = torch.randn(shp, generator=g, device=dev, dtype=torch.float32)
+        if len(shp) == 1:
+            x.mul_(0.1).add_(1.0)
+        else:
+            x.mul_(1.0 / math.sqrt(shp[0]))
+        out[name] = x.to(torch.float16)
+    return out
+
+
+def make_hidden(n_tokens: int, d_model: int, seed: int, device="cpu") -> torch.Tensor:
+    """fp16 hidden states [n_tokens][d_model] ~ N(0,1): the layer inputs of a token sequence."""
+    dev = torch.device(device)
+    g = _gen(seed, _STREAM_HIDDEN, dev)
+    return torch.randn((n_tokens, d_model), generator=g, device=dev, dtype=torch.float32).to(torch.float16)
