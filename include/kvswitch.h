@@ -262,6 +262,71 @@ int32_t kv_swapout_aot(const void* packed_dev, void* packed_pinned,
                        uint64_t begin, uint64_t end,
                        void* producer_stream, void* copy_stream);
 
+/* ------------------------------------ recompute of interleaved chunks (Sec. 3.3) */
+
+/* The paper recovers missing chunks either from their swapped-out records or by
+ * recomputing them from their tokens while other chunks are loaded (Sec. 3.3,
+ * swapping-recompute pipeline).  "Making interleaved chunks recomputable" (Sec. 3.3
+ * and its six-token example): the tokens of the missing chunks go through a layer with
+ * their GLOBAL positions in the rotary encoding of q and k; the recomputed K/V are
+ * inserted between the resident K/V of the layer; the recomputed queries attend to the
+ * recovered K/V under a causal mask by global position; the result is the input of the
+ * next layer for these tokens.  kv_recompute_layer does this for ONE Llama-style block
+ * (the paper's example uses a Llama2-7B layer):
+ *   xn = rmsnorm(x; w_norm1);  q, k, v = xn wq, xn wk, xn wv;
+ *   q, k = rope(q, k; global position, pairs (i, i + head_dim/2), angle pos * rope_base^(-2i/head_dim));
+ *   cache[layer][K|V][kv head][position][:] = fp16(k), fp16(v);
+ *   o = softmax(q K^T / sqrt(head_dim), keys at positions <= the query's) V   per query head,
+ *       query head h reading kv head h / (n_q_heads / n_kv_heads);
+ *   x1 = x + o wo;  y = x1 + (silu(rmsnorm(x1; w_norm2) w_gate) * (rmsnorm(x1; w_norm2) w_up)) w_down.
+ * Heads, head_dim, cache geometry and chunk size come from kv_shape_t (format 0,
+ * head_dim 64 or 128).  Weights are fp16, row-major [in][out], 16-byte aligned, device. */
+typedef struct {
+    int32_t d_model;      /* hidden size, multiple of 8 */
+    int32_t d_ff;         /* feed-forward width, multiple of 8 */
+    float   rope_base;    /* e.g. 10000 */
+    float   rms_eps;      /* e.g. 1e-5 */
+} kv_layer_dims_t;
+
+typedef struct {
+    const void* w_norm1;  /* [d_model]                       */
+    const void* wq;       /* [d_model][n_q_heads * head_dim]  */
+    const void* wk;       /* [d_model][n_kv_heads * head_dim] */
+    const void* wv;       /* [d_model][n_kv_heads * head_dim] */
+    const void* wo;       /* [n_q_heads * head_dim][d_model]  */
+    const void* w_norm2;  /* [d_model]                       */
+    const void* w_gate;   /* [d_model][d_ff]                  */
+    const void* w_up;     /* [d_model][d_ff]                  */
+    const void* w_down;   /* [d_ff][d_model]                  */
+} kv_layer_weights_t;
+
+/* Handle of the recompute path: owns the dense-GEMM library handle (rocBLAS, loaded on
+ * creation; its own device workspace lives until kv_recompute_destroy).  NULL on failure
+ * (kv_last_error has the text).  One handle serves one stream at a time. */
+typedef struct kv_recompute kv_recompute_t;
+kv_recompute_t* kv_recompute_create(void);
+void            kv_recompute_destroy(kv_recompute_t* rc);
+
+/* Bytes of device workspace kv_recompute_layer needs for n_missing chunks; 0 on invalid arguments. */
+uint64_t kv_recompute_workspace_bytes(const kv_shape_t* shape, const kv_layer_dims_t* dims,
+                                      int32_t n_missing);
+
+/* One block over the tokens of n_missing chunks (1 <= n_missing <= n_chunks).
+ *   chunk_idx_dev dev i32 [n_missing], strictly ascending chunk indices (trusted, like the
+ *                 gather lists: an index outside the cache makes the kernels write outside it);
+ *   x_in   dev fp16 [n_missing * chunk_tokens][d_model]: the layer inputs of these tokens,
+ *          chunk by chunk in the order of chunk_idx_dev;
+ *   kv     dev fp16 cache; the K and V planes of `layer` must hold every resident chunk that
+ *          lies before the last recomputed token; the recomputed chunks' entries are written;
+ *   x_out  dev fp16, same shape as x_in: the layer outputs (may not alias x_in);
+ *   workspace dev, >= kv_recompute_workspace_bytes(), 256-byte aligned, contents scratch.
+ * Enqueues on `stream` and returns; nothing is launched if a host argument is invalid. */
+int32_t kv_recompute_layer(kv_recompute_t* rc, const kv_shape_t* shape, const kv_layer_dims_t* dims,
+                           const kv_layer_weights_t* weights, int32_t layer,
+                           const int32_t* chunk_idx_dev, int32_t n_missing, const void* x_in,
+                           void* kv, void* x_out, void* workspace, uint64_t workspace_bytes,
+                           void* stream);
+
 /* -------------------------------------------- host lifecycle (Sec. 3.4 ii) */
 
 /* LCTRU queue: concatenated sub-queues, one per bit-width, least compressed

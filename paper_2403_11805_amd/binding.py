@@ -82,6 +82,10 @@ _SIGNATURES = {
     "kv_swapin_chunks": (_i32, [_vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp]),
     "kv_swapin_pinned": (_i32, [_vp, _vp, _vp, _vp, _vp, _i32, _vp, _u64, _i32, _vp, _vp, _vp]),
     "kv_swapout_aot": (_i32, [_vp, _vp, _u64, _u64, _vp, _vp]),
+    "kv_recompute_create": (_vp, []),
+    "kv_recompute_destroy": (None, [_vp]),
+    "kv_recompute_workspace_bytes": (_u64, [_vp, _vp, _i32]),
+    "kv_recompute_layer": (_i32, [_vp, _vp, _vp, _vp, _i32, _vp, _i32, _vp, _vp, _vp, _vp, _u64, _vp]),
     "kv_lctru_create": (_vp, []),
     "kv_lctru_destroy": (None, [_vp]),
     "kv_lctru_insert": (_i32, [_vp, _i32, _i32, _i32, _u64, _u64]),
@@ -145,6 +149,76 @@ def _stream(stream) -> int:
     if isinstance(stream, torch.cuda.Stream):
         return stream.cuda_stream
     return int(stream)
+
+
+# ------------------------------------------------- recompute of interleaved chunks
+
+class kv_layer_dims_t(ctypes.Structure):
+    _fields_ = [("d_model", ctypes.c_int32), ("d_ff", ctypes.c_int32),
+                ("rope_base", ctypes.c_float), ("rms_eps", ctypes.c_float)]
+
+
+LAYER_WEIGHTS = ("w_norm1", "wq", "wk", "wv", "wo", "w_norm2", "w_gate", "w_up", "w_down")
+
+
+class kv_layer_weights_t(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in LAYER_WEIGHTS]
+
+
+class LayerDims(NamedTuple):
+    d_model: int
+    d_ff: int
+    rope_base: float = 10000.0
+    rms_eps: float = 1e-5
+
+    def c(self) -> kv_layer_dims_t:
+        return kv_layer_dims_t(*self)
+
+
+def kv_recompute_workspace_bytes(shape: Shape, dims: LayerDims, n_missing: int) -> int:
+    s, d = shape.c(), dims.c()
+    n = int(lib().kv_recompute_workspace_bytes(ctypes.byref(s), ctypes.byref(d), n_missing))
+    if n == 0:
+        raise KvError(KV_EINVAL, kv_last_error())
+    return n
+
+
+class Recompute:
+    """Handle of the recompute path (kv_recompute_create / kv_recompute_destroy)."""
+
+    def __init__(self):
+        self._h = lib().kv_recompute_create()
+        if not self._h:
+            raise KvError(KV_EHIP, kv_last_error())
+
+    def close(self):
+        if self._h:
+            lib().kv_recompute_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def layer(self, shape: Shape, dims: LayerDims, weights: dict, layer: int, chunk_idx_dev: torch.Tensor,
+              x_in: torch.Tensor, kv: torch.Tensor, x_out: torch.Tensor, workspace: torch.Tensor,
+              stream=None) -> None:
+        """kv_recompute_layer: argument marshalling only."""
+        s, d = shape.c(), dims.c()
+        n_missing = chunk_idx_dev.numel()
+        rows = n_missing * shape.chunk_tokens
+        if tuple(x_in.shape) != (rows, dims.d_model) or tuple(x_out.shape) != (rows, dims.d_model):
+            raise ValueError("x_in / x_out must be [n_missing * chunk_tokens][d_model]")
+        if tuple(kv.shape) != shape.kv_dims:
+            raise ValueError("kv must be [L][2][Hkv][N][D]")
+        w = kv_layer_weights_t(*[_dev(weights[n], torch.float16) for n in LAYER_WEIGHTS])
+        _check(lib().kv_recompute_layer(self._h, ctypes.byref(s), ctypes.byref(d), ctypes.byref(w), layer,
+                                        _dev(chunk_idx_dev, torch.int32), n_missing,
+                                        _dev(x_in, torch.float16), _dev(kv, torch.float16),
+                                        _dev(x_out, torch.float16), _dev(workspace),
+                                        workspace.numel() * workspace.element_size(), _stream(stream)))
 
 
 # ------------------------------------------------------------------ host, pure

@@ -9,7 +9,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(_HERE), "include")
 LIB_PATH = os.path.join(_HERE, "libkvswitch.so")
-SOURCES = ("kv_host.cpp", "kv_lctru.cpp", "kv_device.hip")
+SOURCES = ("kv_host.cpp", "kv_lctru.cpp", "kv_device.hip", "kv_recompute.hip")
 
 
 def hipcc() -> str:
@@ -31,7 +31,7 @@ def build_library(verbose: bool = False) -> str:
     cmd += os.environ.get("KVS_EXTRA_FLAGS", "").split()
     cmd += [os.path.join(CSRC, s) for s in SOURCES]
     tmp = LIB_PATH + ".tmp"
-    cmd += ["-o", tmp]
+    cmd += ["-ldl", "-o", tmp]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if verbose or res.returncode:
         noise = "packed-fp32-ops"

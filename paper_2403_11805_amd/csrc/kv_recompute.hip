@@ -1,0 +1,236 @@
+// libkvswitch: recompute of interleaved chunks through one Llama-style block
+// (Sec. 3.3, "Making interleaved chunks recomputable").  Host side: argument
+// checks, the workspace plan, the dense projections as rocBLAS GEMMs (loaded at
+// run time, so the rest of the library does not depend on it) and the launches
+// of the kernels in kv_recompute_kernels.hpp.
+
+#include <dlfcn.h>
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+#include <new>
+
+#include "kv_internal.h"
+#include "kv_recompute_kernels.hpp"
+
+using namespace kvs;
+
+namespace {
+
+// The few rocBLAS entry points used, with the library's published C signatures and enum values.
+typedef void* rb_handle;
+typedef int (*rb_create_fn)(rb_handle*);
+typedef int (*rb_destroy_fn)(rb_handle);
+typedef int (*rb_set_stream_fn)(rb_handle, hipStream_t);
+typedef int (*rb_gemm_ex_fn)(rb_handle, int, int, int, int, int, const void*, const void*, int, int,
+                             const void*, int, int, const void*, const void*, int, int, void*, int, int,
+                             int, int, int32_t, uint32_t);
+constexpr int kRbOpNone = 111;        // rocblas_operation_none
+constexpr int kRbF16 = 150;           // rocblas_datatype_f16_r
+constexpr int kRbF32 = 151;           // rocblas_datatype_f32_r
+constexpr int kRbAlgoStandard = 0;    // rocblas_gemm_algo_standard
+
+uint64_t align256(uint64_t v) { return (v + 255) & ~static_cast<uint64_t>(255); }
+
+struct Plan {
+    uint64_t xn, q32, k32, v32, q16, attn, x1, gate, up, total;
+};
+
+Plan plan_workspace(const kv_shape_t& s, const kv_layer_dims_t& d, int64_t M) {
+    const uint64_t dq = static_cast<uint64_t>(s.n_q_heads) * s.head_dim;
+    const uint64_t dkv = static_cast<uint64_t>(s.n_kv_heads) * s.head_dim;
+    Plan p;
+    uint64_t o = 0;
+    p.xn = o;   o += align256(M * d.d_model * 2u);
+    p.q32 = o;  o += align256(M * dq * 4u);
+    p.k32 = o;  o += align256(M * dkv * 4u);
+    p.v32 = o;  o += align256(M * dkv * 4u);
+    p.q16 = o;  o += align256(M * dq * 2u);
+    p.attn = o; o += align256(M * dq * 2u);
+    p.x1 = o;   o += align256(M * d.d_model * 2u);
+    p.gate = o; o += align256(M * static_cast<uint64_t>(d.d_ff) * 2u);
+    p.up = o;   o += align256(M * static_cast<uint64_t>(d.d_ff) * 2u);
+    p.total = o;
+    return p;
+}
+
+int check_layer(const kv_shape_t* shape, const kv_layer_dims_t* dims, int32_t n_missing) {
+    if (int rc = check_shape(shape)) return rc;
+    if (!dims) return fail(KV_EINVAL, "dims is NULL");
+    if (shape->format != KV_FMT_F16_GROUPS) return fail(KV_ESHAPE, "recompute needs the fp16 cache format");
+    if (shape->head_dim != 64 && shape->head_dim != 128)
+        return fail(KV_ESHAPE, "recompute needs head_dim 64 or 128, got %d", shape->head_dim);
+    if (dims->d_model <= 0 || dims->d_model % 8 || dims->d_ff <= 0 || dims->d_ff % 8)
+        return fail(KV_ESHAPE, "d_model %d and d_ff %d must be positive multiples of 8", dims->d_model, dims->d_ff);
+    if (!(dims->rope_base > 1.0f) || !(dims->rms_eps >= 0.0f))
+        return fail(KV_EINVAL, "rope_base must exceed 1 and rms_eps must not be negative");
+    const int32_t n_chunks = shape->n_tokens / shape->chunk_tokens;
+    if (n_missing < 1 || n_missing > n_chunks)
+        return fail(KV_EINVAL, "n_missing %d outside [1,%d]", n_missing, n_chunks);
+    return KV_OK;
+}
+
+}  // namespace
+
+struct kv_recompute {
+    void* lib = nullptr;
+    rb_handle handle = nullptr;
+    rb_destroy_fn destroy = nullptr;
+    rb_set_stream_fn set_stream = nullptr;
+    rb_gemm_ex_fn gemm_ex = nullptr;
+};
+
+namespace {
+
+// Row-major C[M][N] = A[M][K] * B[K][N] (+ Cin if given), fp16 operands, binary32 accumulation.
+int gemm(kv_recompute* rc, int64_t M, int64_t N, int64_t K, const void* A, const void* B,
+         const void* Cin, void* Cout, bool out_f32, const char* what) {
+    const float alpha = 1.0f, beta = Cin ? 1.0f : 0.0f;
+    const int ct = out_f32 ? kRbF32 : kRbF16;
+    // column-major view: Cout^T [N][M] = B^T [N][K] * A^T [K][M]
+    const int st = rc->gemm_ex(rc->handle, kRbOpNone, kRbOpNone, static_cast<int>(N), static_cast<int>(M),
+                               static_cast<int>(K), &alpha, B, kRbF16, static_cast<int>(N), A, kRbF16,
+                               static_cast<int>(K), &beta, Cin ? Cin : Cout, ct, static_cast<int>(N), Cout, ct,
+                               static_cast<int>(N), kRbF32, kRbAlgoStandard, 0, 0);
+    if (st != 0) return fail(KV_EHIP, "rocblas_gemm_ex (%s) failed with status %d", what, st);
+    return KV_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+kv_recompute_t* kv_recompute_create(void) {
+    clear_error();
+    kv_recompute* rc = new (std::nothrow) kv_recompute();
+    if (!rc) {
+        fail(KV_ENOMEM, "out of host memory");
+        return nullptr;
+    }
+    rc->lib = dlopen("librocblas.so.5", RTLD_NOW | RTLD_LOCAL);
+    if (!rc->lib) rc->lib = dlopen("librocblas.so", RTLD_NOW | RTLD_LOCAL);
+    if (!rc->lib) {
+        fail(KV_EHIP, "rocBLAS not found: %s", dlerror());
+        delete rc;
+        return nullptr;
+    }
+    rb_create_fn create = reinterpret_cast<rb_create_fn>(dlsym(rc->lib, "rocblas_create_handle"));
+    rc->destroy = reinterpret_cast<rb_destroy_fn>(dlsym(rc->lib, "rocblas_destroy_handle"));
+    rc->set_stream = reinterpret_cast<rb_set_stream_fn>(dlsym(rc->lib, "rocblas_set_stream"));
+    rc->gemm_ex = reinterpret_cast<rb_gemm_ex_fn>(dlsym(rc->lib, "rocblas_gemm_ex"));
+    if (!create || !rc->destroy || !rc->set_stream || !rc->gemm_ex) {
+        fail(KV_EHIP, "rocBLAS lacks a required entry point");
+        dlclose(rc->lib);
+        delete rc;
+        return nullptr;
+    }
+    const int st = create(&rc->handle);
+    if (st != 0 || !rc->handle) {
+        fail(KV_EHIP, "rocblas_create_handle failed with status %d", st);
+        dlclose(rc->lib);
+        delete rc;
+        return nullptr;
+    }
+    return rc;
+}
+
+void kv_recompute_destroy(kv_recompute_t* rc) {
+    if (!rc) return;
+    if (rc->handle) rc->destroy(rc->handle);
+    // the library stays loaded: other users in the process may share it
+    delete rc;
+}
+
+uint64_t kv_recompute_workspace_bytes(const kv_shape_t* shape, const kv_layer_dims_t* dims, int32_t n_missing) {
+    if (check_layer(shape, dims, n_missing) != KV_OK) return 0;
+    return plan_workspace(*shape, *dims, static_cast<int64_t>(n_missing) * shape->chunk_tokens).total;
+}
+
+int32_t kv_recompute_layer(kv_recompute_t* rc, const kv_shape_t* shape, const kv_layer_dims_t* dims,
+                           const kv_layer_weights_t* w, int32_t layer, const int32_t* chunk_idx_dev,
+                           int32_t n_missing, const void* x_in, void* kv, void* x_out, void* workspace,
+                           uint64_t workspace_bytes, void* stream) {
+    if (!rc) return fail(KV_EINVAL, "handle is NULL");
+    if (int st = check_layer(shape, dims, n_missing)) return st;
+    if (layer < 0 || layer >= shape->n_layers) return fail(KV_EINVAL, "layer %d outside [0,%d)", layer, shape->n_layers);
+    if (!w || !w->w_norm1 || !w->wq || !w->wk || !w->wv || !w->wo || !w->w_norm2 || !w->w_gate || !w->w_up ||
+        !w->w_down)
+        return fail(KV_EINVAL, "a weight pointer is NULL");
+    if (!chunk_idx_dev || !x_in || !kv || !x_out || !workspace) return fail(KV_EINVAL, "NULL device pointer");
+    if (!aligned(x_in, 16) || !aligned(x_out, 16) || !aligned(kv, 16) || !aligned(workspace, 256) ||
+        !aligned(chunk_idx_dev, 4))
+        return fail(KV_EINVAL, "x_in/x_out/kv must be 16-byte aligned, workspace 256-byte aligned");
+    const void* ws_ptrs[] = {w->w_norm1, w->wq, w->wk, w->wv, w->wo, w->w_norm2, w->w_gate, w->w_up, w->w_down};
+    for (const void* p : ws_ptrs)
+        if (!aligned(p, 16)) return fail(KV_EINVAL, "weights must be 16-byte aligned");
+    const kv_shape_t& s = *shape;
+    const int64_t M = static_cast<int64_t>(n_missing) * s.chunk_tokens;
+    const Plan p = plan_workspace(s, *dims, M);
+    if (workspace_bytes < p.total)
+        return fail(KV_ENOMEM, "workspace %llu bytes, %llu needed", static_cast<unsigned long long>(workspace_bytes),
+                    static_cast<unsigned long long>(p.total));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (rc->set_stream(rc->handle, st) != 0) return fail(KV_EHIP, "rocblas_set_stream failed");
+
+    uint8_t* base = static_cast<uint8_t*>(workspace);
+    _Float16* xn = reinterpret_cast<_Float16*>(base + p.xn);
+    float* q32 = reinterpret_cast<float*>(base + p.q32);
+    float* k32 = reinterpret_cast<float*>(base + p.k32);
+    float* v32 = reinterpret_cast<float*>(base + p.v32);
+    _Float16* q16 = reinterpret_cast<_Float16*>(base + p.q16);
+    _Float16* attn = reinterpret_cast<_Float16*>(base + p.attn);
+    _Float16* x1 = reinterpret_cast<_Float16*>(base + p.x1);
+    _Float16* gate = reinterpret_cast<_Float16*>(base + p.gate);
+    _Float16* up = reinterpret_cast<_Float16*>(base + p.up);
+    const _Float16* xin = static_cast<const _Float16*>(x_in);
+    const int D = s.head_dim, Hq = s.n_q_heads, Hkv = s.n_kv_heads;
+    const int64_t dq = static_cast<int64_t>(Hq) * D, dkv = static_cast<int64_t>(Hkv) * D;
+    _Float16* k_plane = static_cast<_Float16*>(kv) + (static_cast<int64_t>(layer) * 2 + 0) * Hkv * s.n_tokens * D;
+    _Float16* v_plane = k_plane + static_cast<int64_t>(Hkv) * s.n_tokens * D;
+    const dim3 rows(static_cast<uint32_t>((M + 3) / 4));
+
+    // 1. norm, q/k/v projections (binary32 results, rounded once after the rotation)
+    hipLaunchKernelGGL(rmsnorm_kernel, rows, dim3(256), 0, st, xin, static_cast<const _Float16*>(w->w_norm1), xn,
+                       static_cast<int32_t>(M), dims->d_model, dims->rms_eps);
+    if (int e = gemm(rc, M, dq, dims->d_model, xn, w->wq, nullptr, q32, true, "q")) return e;
+    if (int e = gemm(rc, M, dkv, dims->d_model, xn, w->wk, nullptr, k32, true, "k")) return e;
+    if (int e = gemm(rc, M, dkv, dims->d_model, xn, w->wv, nullptr, v32, true, "v")) return e;
+    // 2. global position encoding; the recomputed K/V go to their places in the cache
+    RopeTable tab;
+    for (int i = 0; i < D / 2; ++i) tab.theta[i] = std::pow(static_cast<double>(dims->rope_base), -2.0 * i / D);
+    hipLaunchKernelGGL(rope_scatter_kernel, dim3(static_cast<uint32_t>(M)), dim3(256), 0, st, q32, k32, v32,
+                       chunk_idx_dev, q16, k_plane, v_plane, tab, s.chunk_tokens, s.n_tokens, Hq, Hkv, D);
+    // 3. causal attention over the recovered K/V
+    AttnGeom g;
+    g.M = static_cast<int32_t>(M);
+    g.T = s.chunk_tokens;
+    g.N = s.n_tokens;
+    g.Hq = Hq;
+    g.Hkv = Hkv;
+    g.n_rb = static_cast<int32_t>((M + 31) / 32);
+    g.pairs = (Hq / Hkv) * g.n_rb;
+    g.scale_log2e = static_cast<float>(1.4426950408889634 / std::sqrt(static_cast<double>(D)));
+    const dim3 agrid(static_cast<uint32_t>((g.pairs + 3) / 4), static_cast<uint32_t>(Hkv));
+    if (D == 64)
+        hipLaunchKernelGGL(recompute_attention_kernel<64>, agrid, dim3(256), 0, st, q16, k_plane, v_plane,
+                           chunk_idx_dev, attn, g);
+    else
+        hipLaunchKernelGGL(recompute_attention_kernel<128>, agrid, dim3(256), 0, st, q16, k_plane, v_plane,
+                           chunk_idx_dev, attn, g);
+    // 4. output projection + residual, feed-forward + residual
+    if (int e = gemm(rc, M, dims->d_model, dq, attn, w->wo, xin, x1, false, "o")) return e;
+    hipLaunchKernelGGL(rmsnorm_kernel, rows, dim3(256), 0, st, x1, static_cast<const _Float16*>(w->w_norm2), xn,
+                       static_cast<int32_t>(M), dims->d_model, dims->rms_eps);
+    if (int e = gemm(rc, M, dims->d_ff, dims->d_model, xn, w->w_gate, nullptr, gate, false, "gate")) return e;
+    if (int e = gemm(rc, M, dims->d_ff, dims->d_model, xn, w->w_up, nullptr, up, false, "up")) return e;
+    const int64_t n8 = M * dims->d_ff / 8;
+    hipLaunchKernelGGL(silu_mul_kernel, dim3(static_cast<uint32_t>((n8 + 255) / 256)), dim3(256), 0, st, gate, up,
+                       gate, n8);
+    if (int e = gemm(rc, M, dims->d_model, dims->d_ff, gate, w->w_down, x1, x_out, false, "down")) return e;
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(KV_EHIP, "recompute launch: %s", hipGetErrorString(e));
+    return KV_OK;
+}
+
+}  // extern "C"

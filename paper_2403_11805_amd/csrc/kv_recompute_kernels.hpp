@@ -1,0 +1,303 @@
+// gfx950 kernels for the recompute of interleaved chunks (Sec. 3.3, "Making
+// interleaved chunks recomputable"): the tokens of the missing chunks go through
+// one Llama-style block; q and k are encoded with the tokens' GLOBAL positions,
+// the recomputed K/V are inserted between the resident K/V of the cache, and the
+// recomputed queries attend to the recovered K/V under a causal mask by global
+// position.  The dense projections are library GEMMs; everything else is here.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "kv_lane_ops.hpp"
+
+namespace kvs {
+
+typedef _Float16 rv8h_t __attribute__((ext_vector_type(8)));
+typedef _Float16 rv4h_t __attribute__((ext_vector_type(4)));
+typedef float rv16f_t __attribute__((ext_vector_type(16)));
+typedef unsigned int ru4_t __attribute__((ext_vector_type(4)));
+
+// Global position of recomputed token m: chunks of T tokens, chunk_idx ascending.
+__device__ __forceinline__ int global_position(const int32_t* __restrict__ chunk_idx, int T, int m) {
+    return chunk_idx[m / T] * T + m % T;
+}
+
+// xn[m][:] = x[m][:] / sqrt(mean(x[m][:]^2) + eps) * w[:]      (fp16 in/out, binary32 inside)
+// One wavefront per row; d_model % 8 == 0.
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const _Float16* __restrict__ x,
+                                                      const _Float16* __restrict__ w,
+                                                      _Float16* __restrict__ xn, int32_t M,
+                                                      int32_t d_model, float eps) {
+    const int lane = threadIdx.x & 63;
+    const int m = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (m >= M) return;
+    const rv8h_t* row = reinterpret_cast<const rv8h_t*>(x + static_cast<int64_t>(m) * d_model);
+    const int pieces = d_model / 8;
+    float ss = 0.0f;
+    for (int p = lane; p < pieces; p += 64) {
+        const rv8h_t v = row[p];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) ss += static_cast<float>(v[k]) * static_cast<float>(v[k]);
+    }
+#pragma unroll
+    for (int o = 16; o >= 1; o >>= 1) ss += __shfl_xor(ss, o);
+    ss = xhalf_sum(ss);
+    const float r = 1.0f / sqrtf(ss / static_cast<float>(d_model) + eps);
+    const rv8h_t* wp = reinterpret_cast<const rv8h_t*>(w);
+    rv8h_t* out = reinterpret_cast<rv8h_t*>(xn + static_cast<int64_t>(m) * d_model);
+    for (int p = lane; p < pieces; p += 64) {
+        const rv8h_t v = row[p], g = wp[p];
+        rv8h_t o;
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            o[k] = static_cast<_Float16>(static_cast<float>(v[k]) * r * static_cast<float>(g[k]));
+        out[p] = o;
+    }
+}
+
+// Rotary angles: theta[i] = base^(-2i/D) in double, computed on the host.
+struct RopeTable {
+    double theta[128];      // head_dim / 2 <= 128
+};
+
+// One workgroup per recomputed token m at global position p:
+//   q16[m][h][:]            = rope(q32[m][h][:], p)                       (fp16)
+//   K plane [g][p][:]       = rope(k32[m][g][:], p)   V plane [g][p][:] = v32[m][g][:]   (fp16 cache)
+// The pair (i, i + D/2) is rotated by p * theta[i]; sine and cosine are taken in
+// double (positions reach tens of thousands of radians).
+__global__ __launch_bounds__(256) void rope_scatter_kernel(const float* __restrict__ q32,
+                                                           const float* __restrict__ k32,
+                                                           const float* __restrict__ v32,
+                                                           const int32_t* __restrict__ chunk_idx,
+                                                           _Float16* __restrict__ q16,
+                                                           _Float16* __restrict__ k_plane,
+                                                           _Float16* __restrict__ v_plane,
+                                                           RopeTable tab, int32_t T, int32_t N,
+                                                           int32_t Hq, int32_t Hkv, int32_t D) {
+    __shared__ float cs[2][128];
+    const int m = blockIdx.x;
+    const int p = global_position(chunk_idx, T, m);
+    const int half = D / 2;
+    for (int i = threadIdx.x; i < half; i += blockDim.x) {
+        double s, c;
+        sincos(static_cast<double>(p) * tab.theta[i], &s, &c);
+        cs[0][i] = static_cast<float>(c);
+        cs[1][i] = static_cast<float>(s);
+    }
+    __syncthreads();
+    const float* qrow = q32 + static_cast<int64_t>(m) * Hq * D;
+    _Float16* qout = q16 + static_cast<int64_t>(m) * Hq * D;
+    for (int e = threadIdx.x; e < Hq * half; e += blockDim.x) {
+        const int h = e / half, i = e % half;
+        const float a = qrow[h * D + i], b = qrow[h * D + i + half];
+        const float c = cs[0][i], s = cs[1][i];
+        qout[h * D + i] = static_cast<_Float16>(a * c - b * s);
+        qout[h * D + i + half] = static_cast<_Float16>(b * c + a * s);
+    }
+    const float* krow = k32 + static_cast<int64_t>(m) * Hkv * D;
+    const float* vrow = v32 + static_cast<int64_t>(m) * Hkv * D;
+    for (int e = threadIdx.x; e < Hkv * half; e += blockDim.x) {
+        const int g = e / half, i = e % half;
+        const float a = krow[g * D + i], b = krow[g * D + i + half];
+        const float c = cs[0][i], s = cs[1][i];
+        _Float16* dst = k_plane + (static_cast<int64_t>(g) * N + p) * D;
+        dst[i] = static_cast<_Float16>(a * c - b * s);
+        dst[i + half] = static_cast<_Float16>(b * c + a * s);
+    }
+    for (int e = threadIdx.x; e < Hkv * D; e += blockDim.x) {
+        const int g = e / D, d = e % D;
+        v_plane[(static_cast<int64_t>(g) * N + p) * D + d] = static_cast<_Float16>(vrow[e]);
+    }
+}
+
+// act = silu(gate) * up, elementwise, 8 elements per thread (n % 8 == 0).
+// (act may be gate: each thread reads its elements before it writes them)
+__global__ __launch_bounds__(256) void silu_mul_kernel(const _Float16* gate, const _Float16* up,
+                                                       _Float16* act, int64_t n8) {
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i >= n8) return;
+    const rv8h_t g = reinterpret_cast<const rv8h_t*>(gate)[i], u = reinterpret_cast<const rv8h_t*>(up)[i];
+    rv8h_t o;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const float x = static_cast<float>(g[k]);
+        o[k] = static_cast<_Float16>(x / (1.0f + __expf(-x)) * static_cast<float>(u[k]));
+    }
+    reinterpret_cast<rv8h_t*>(act)[i] = o;
+}
+
+struct AttnGeom {
+    int32_t M;        // recomputed tokens
+    int32_t T;        // chunk tokens
+    int32_t N;        // cache tokens
+    int32_t Hq, Hkv;
+    int32_t n_rb;     // ceil(M / 32): blocks of 32 query rows
+    int32_t pairs;    // (Hq / Hkv) * n_rb: (row block, query head) pairs per kv head
+    float scale_log2e;
+};
+
+// Causal attention of the recomputed queries over the recovered K/V of one layer.
+// A wavefront owns one (block of 32 query rows, query head) pair: S^T = K_tile Q^T
+// with mfma_f32_32x32x16_f16 (a lane owns one query row and 16 of the tile's 32
+// tokens), online softmax per row, O^T += V_tile^T P^T with the probabilities
+// rounded to fp16 as the B operand straight from the registers (the contraction
+// index is permuted the same way on both operands).  The four wavefronts of a
+// workgroup take four consecutive pairs of ONE kv head, so K and V tiles are
+// fetched once per workgroup (coalesced 16-byte loads, one tile ahead) and shared
+// through LDS: K with its row pieces permuted by the row number, V transposed.
+// Tokens after a row's global position are masked; a wavefront skips the tiles
+// that lie entirely behind its last row.
+template <int D>
+__global__ __launch_bounds__(256) void recompute_attention_kernel(const _Float16* __restrict__ q16,
+                                                                  const _Float16* __restrict__ k_plane,
+                                                                  const _Float16* __restrict__ v_plane,
+                                                                  const int32_t* __restrict__ chunk_idx,
+                                                                  _Float16* __restrict__ out, AttnGeom g) {
+    constexpr int KS = D / 16;
+    constexpr int DB = D / 32;                      // 32-wide blocks of the head dimension
+    constexpr int kRowPieces = D / 8;
+    constexpr int kPer = 32 * kRowPieces / 256;     // 16-byte pieces per thread and tile
+    constexpr int kVtStride = 36;                   // halfs per transposed V row (32 tokens + padding)
+    __shared__ ru4_t ktile[2][32 * kRowPieces];
+    __shared__ __align__(16) _Float16 vt[2][D * kVtStride];
+    auto swz = [](int r) __attribute__((always_inline)) { return D == 64 ? (r >> 1) & 7 : r & 15; };
+
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int lrow = lane & 31, half = lane >> 5;
+    const int kvh = blockIdx.y;
+    const int per = g.Hq / g.Hkv;
+    const int pair = blockIdx.x * 4 + wave;
+    const bool valid = pair < g.pairs;
+    const int head = kvh * per + (valid ? pair % per : 0);
+    const int rb = valid ? pair / per : 0;
+    const int m = rb * 32 + lrow;
+    const bool ok = valid && m < g.M;
+    const int pos = ok ? global_position(chunk_idx, g.T, m) : -1;
+    // rows ascend in position: first and last row of this wavefront, last row of the workgroup
+    const int min_pos = valid ? global_position(chunk_idx, g.T, rb * 32) : -1;
+    const int max_pos = valid ? global_position(chunk_idx, g.T, min(rb * 32 + 31, g.M - 1)) : -1;
+    const int rb_hi = min(blockIdx.x * 4 + 3, g.pairs - 1) / per;
+    const int wg_max_pos = global_position(chunk_idx, g.T, min(rb_hi * 32 + 31, g.M - 1));
+    const int n_tiles = wg_max_pos / 32 + 1;
+
+    rv8h_t qreg[KS];
+    {
+        const _Float16* qp = q16 + (static_cast<int64_t>(ok ? m : 0) * g.Hq + head) * D + half * 8;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            rv8h_t v = {0, 0, 0, 0, 0, 0, 0, 0};
+            if (ok) v = *reinterpret_cast<const rv8h_t*>(qp + ks * 16);
+            qreg[ks] = v;
+        }
+    }
+    const ru4_t* kbase = reinterpret_cast<const ru4_t*>(k_plane + static_cast<int64_t>(kvh) * g.N * D);
+    const ru4_t* vbase = reinterpret_cast<const ru4_t*>(v_plane + static_cast<int64_t>(kvh) * g.N * D);
+    ru4_t kst[kPer], vst[kPer];
+    auto fetch = [&](int t) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) {
+            const int p = i * 256 + tid;
+            const int token = min(t * 32 + p / kRowPieces, g.N - 1);      // rows past the cache are masked anyway
+            const int64_t src = static_cast<int64_t>(token) * kRowPieces + p % kRowPieces;
+            kst[i] = kbase[src];
+            vst[i] = vbase[src];
+        }
+    };
+    auto park = [&](int buf) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) {
+            const int p = i * 256 + tid;
+            const int r = p / kRowPieces, c = p % kRowPieces;
+            ktile[buf][r * kRowPieces + (c ^ swz(r))] = kst[i];
+            const rv8h_t v = __builtin_bit_cast(rv8h_t, vst[i]);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) vt[buf][(c * 8 + j) * kVtStride + r] = v[j];
+        }
+    };
+
+    rv16f_t o_acc[DB];
+#pragma unroll
+    for (int b = 0; b < DB; ++b) o_acc[b] = rv16f_t{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+    float m_run = -INFINITY, l_run = 0.0f;
+
+    fetch(0);
+    park(0);
+    __syncthreads();
+    for (int t = 0; t < n_tiles; ++t) {
+        const int buf = t & 1;
+        const bool more = t + 1 < n_tiles;
+        if (more) fetch(t + 1);
+        if (t * 32 <= max_pos) {            // wave-uniform
+            rv8h_t kreg[KS];
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+                kreg[ks] = __builtin_bit_cast(rv8h_t, ktile[buf][lrow * kRowPieces + ((2 * ks + half) ^ swz(lrow))]);
+            rv16f_t acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(kreg[ks], qreg[ks], acc, 0, 0, 0);
+            // acc[v]: token t*32 + 8*(v/4) + 4*half + v%4 against this lane's query row
+            float s[16];
+            const bool masked = t * 32 + 31 > min_pos;     // wave-uniform
+            float mloc = -INFINITY;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int tk = t * 32 + 8 * (v / 4) + 4 * half + (v % 4);
+                float x = acc[v] * g.scale_log2e;
+                if (masked && tk > pos) x = -INFINITY;
+                s[v] = x;
+                mloc = fmaxf(mloc, x);
+            }
+            const float m_new = fmaxf(m_run, xhalf_max(mloc));
+            const float m_safe = (m_new == -INFINITY) ? 0.0f : m_new;
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
+            float psum = 0.0f;
+            rv8h_t pb[2];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const float pv = __builtin_amdgcn_exp2f(s[v] - m_safe);
+                psum += pv;
+                pb[v / 8][v % 8] = static_cast<_Float16>(pv);
+            }
+            l_run = l_run * alpha + xhalf_sum(psum);
+            m_run = m_new;
+#pragma unroll
+            for (int b = 0; b < DB; ++b)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) o_acc[b][v] *= alpha;
+            // contraction slot (half, e) of step st holds token 16*st + 4*half + e (e < 4) or
+            // 16*st + 8 + 4*half + e - 4: the order of acc[8*st .. 8*st+7] on the P side
+#pragma unroll
+            for (int b = 0; b < DB; ++b) {
+#pragma unroll
+                for (int st = 0; st < 2; ++st) {
+                    const _Float16* vr = &vt[buf][(32 * b + lrow) * kVtStride + 16 * st + 4 * half];
+                    const rv4h_t lo = *reinterpret_cast<const rv4h_t*>(vr);
+                    const rv4h_t hi = *reinterpret_cast<const rv4h_t*>(vr + 8);
+                    const rv8h_t a = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                    o_acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, pb[st], o_acc[b], 0, 0, 0);
+                }
+            }
+        }
+        if (more) park(buf ^ 1);
+        __syncthreads();
+    }
+    if (ok) {
+        // o_acc[b][v]: head dimension 32*b + 8*(v/4) + 4*half + v%4 of this lane's query row
+        const float inv = 1.0f / l_run;         // a row sees at least its own token
+        _Float16* dst = out + (static_cast<int64_t>(m) * g.Hq + head) * D;
+#pragma unroll
+        for (int b = 0; b < DB; ++b)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                rv4h_t o4;
+#pragma unroll
+                for (int k = 0; k < 4; ++k) o4[k] = static_cast<_Float16>(o_acc[b][4 * j + k] * inv);
+                *reinterpret_cast<rv4h_t*>(dst + 32 * b + 8 * j + 4 * half) = o4;
+            }
+    }
+}
+
+}  // namespace kvs

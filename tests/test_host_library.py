@@ -72,6 +72,31 @@ def test_int8_channel_format_sizes_offsets_and_validation():
         kvs.kv_score_workspace_bytes(good, 8)
 
 
+def test_recompute_entry_points_validate_on_the_host():
+    """Workspace size by hand; bad geometry and NULL handles are refused before any launch."""
+    shape = kvs.Shape(32, 32, 32, 128, 4096, 16, 64)
+    dims = binding.LayerDims(4096, 11008)
+    M, dq = 8 * 16, 32 * 128
+
+    def up(n):
+        return (n + 255) // 256 * 256
+    want = (up(M * 4096 * 2) + 3 * up(M * dq * 4) + 2 * up(M * dq * 2) + up(M * 4096 * 2) + 2 * up(M * 11008 * 2))
+    assert kvs.kv_recompute_workspace_bytes(shape, dims, 8) == want
+    for bad_shape, bad_dims, n in ((shape._replace(head_dim=256, group=64), dims, 8),
+                                   (shape._replace(format=1), dims, 8),
+                                   (shape, dims._replace(d_model=4100), 8),
+                                   (shape, dims._replace(d_ff=0), 8),
+                                   (shape, dims._replace(rope_base=1.0), 8),
+                                   (shape, dims, 0), (shape, dims, 257)):
+        with pytest.raises(kvs.KvError):
+            kvs.kv_recompute_workspace_bytes(bad_shape, bad_dims, n)
+    s, d = shape.c(), dims.c()
+    w = binding.kv_layer_weights_t()
+    assert binding.lib().kv_recompute_layer(None, ctypes.byref(s), ctypes.byref(d), ctypes.byref(w), 0, None, 8,
+                                            None, None, None, None, 0, None) == binding.KV_EINVAL
+    binding.lib().kv_recompute_destroy(None)      # a no-op
+
+
 def test_bits_from_scores_matches_oracle_including_ties():
     rng = np.random.default_rng(0)
     for n in (1, 2, 3, 7, 256, 1024):
