@@ -442,6 +442,88 @@ def run_i8(wl, args, dev):
     }
 
 
+def run_recompute(wl, args, dev):
+    """Recompute of interleaved chunks (Sec. 3.3) on the workload's geometry with a Llama-2-7B-sized
+    block and seeded random weights: one layer over x of the context's chunks (seeded interleaved
+    subsets), timed per x; the line T_re(x) fitted through the points (Sec. 3.3 i) and, with a
+    measured host-to-device line, a plan for loading the whole context (Eq. 4)."""
+    g = wl.geom
+    d_model, d_ff = g.Hq * g.D, args.d_ff
+    shape = kvs.Shape(1, g.Hkv, g.Hq, g.D, g.N, g.T, g.G)          # one layer's planes are enough
+    dims = kvs.LayerDims(d_model, d_ff)
+    w = synth.make_layer_weights(d_model, g.Hq, g.Hkv, g.D, d_ff, wl.seed, dev)
+    kv = synth.make_kv(synth.Geometry(1, g.Hkv, g.Hq, g.D, g.N, g.T, g.G), wl.seed, dev)
+    rc = kvs.Recompute()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    points = []
+    per = g.Hq // g.Hkv
+    for x in [c for c in (8, 16, 32, 64, 102, 154, 256) if c <= g.n_chunks]:
+        idx = synth.draw_subset(g.n_chunks, x, wl.seed, draw=1000 + x)
+        idx_dev = idx.to(dev)
+        M = x * g.T
+        x_in = synth.make_hidden(M, d_model, wl.seed, dev)
+        x_out = torch.empty_like(x_in)
+        ws = torch.empty(kvs.kv_recompute_workspace_bytes(shape, dims, x), dtype=torch.uint8, device=dev)
+        ms = []
+        for it in range(args.warmup + args.steps):
+            ev0.record()
+            rc.layer(shape, dims, w, 0, idx_dev, x_in, kv, x_out, ws)
+            ev1.record()
+            torch.cuda.synchronize()
+            if it >= args.warmup:
+                ms.append(ev0.elapsed_time(ev1))
+        pos = (idx.numpy()[:, None].astype(np.int64) * g.T + np.arange(g.T)[None, :]).reshape(-1)
+        gemm_flop = 2.0 * M * (d_model * (g.Hq + 2 * g.Hkv) * g.D + g.Hq * g.D * d_model + 3 * d_model * d_ff)
+        attn_flop = 4.0 * float((pos + 1).sum()) * g.D * g.Hq
+        t = float(np.mean(ms))
+        points.append({"chunks": x, "tokens": M, "ms": round(t, 4), "ms_min": round(float(np.min(ms)), 4),
+                       "gemm_gflop": round(gemm_flop / 1e9, 1), "attention_gflop": round(attn_flop / 1e9, 1),
+                       "tflops": round((gemm_flop + attn_flop) / t / 1e9, 1)})
+        del ws, x_in, x_out
+    rc.close()
+    slope, icpt = kvs.kv_fit_line([float(p["chunks"]) for p in points], [p["ms"] * 1e-3 for p in points])
+    # IO line: pinned host -> device copies of a few sizes (as in the streaming workload)
+    pinned = torch.empty(256 << 20, dtype=torch.uint8).pin_memory()
+    stage = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+    sizes, times = [], []
+    for mib in (1, 4, 16, 64, 256):
+        for rep in range(3):
+            ev0.record()
+            stage[:mib << 20].copy_(pinned[:mib << 20], non_blocking=True)
+            ev1.record()
+            torch.cuda.synchronize()
+        sizes.append(float(mib << 20)); times.append(ev0.elapsed_time(ev1) * 1e-3)
+    io_per_byte, io_fixed = kvs.kv_fit_line(sizes, times)
+    full = kvs.Shape(g.L, g.Hkv, g.Hq, g.D, g.N, g.T, g.G)
+    rec = [kvs.kv_record_bytes(full, b) for b in (8, 4, 2)]
+    bits = kvs.kv_bits_from_scores(synth.draw_scores(g.n_chunks, wl.seed).numpy(), 1, 1, 3)
+    missing = [int((bits == b).sum()) for b in (8, 4, 2)]
+    # a recomputed chunk passes through all L layers; the fitted per-layer line is scaled by L
+    model = (max(slope, 0.0) * g.L, max(icpt, 0.0) * g.L, max(io_per_byte, 0.0), max(io_fixed, 0.0))
+    recompute, delay = kvs.kv_plan_pipeline(model, missing, rec)
+    io_only = model[2] * sum(m * r for m, r in zip(missing, rec)) + model[3]
+    big = points[-1]
+    return {
+        "metric": "recompute of interleaved chunks, one layer (Sec. 3.3): ms per layer against recomputed chunks",
+        "value": big["tflops"], "unit": "TFLOP/s (GEMMs + attention, largest point)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": big["ms"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16 (f32 accumulate)",
+        "data": "synthetic",
+        "config": {"workload": f"{wl.name} geometry, Llama-2-7B-sized block: d_model {d_model}, {g.Hq} heads of {g.D} "
+                               f"({g.Hkv} kv heads), d_ff {d_ff}, cache of {g.N} tokens, chunk {g.T}; seeded weights",
+                   "step": "kv_recompute_layer over x interleaved chunks"},
+        "points": points,
+        "recompute_model": {"seconds_per_chunk_per_layer": slope, "fixed_seconds_per_layer": icpt},
+        "io_model": {"seconds_per_byte": io_per_byte, "fixed_seconds": io_fixed, "gbps": round(1e-9 / io_per_byte, 2)},
+        "plan": {"missing_8_4_2": missing, "record_bytes_8_4_2": rec, "layers": g.L,
+                 "recompute_8_4_2": list(recompute), "planned_delay_ms": round(delay * 1e3, 3),
+                 "io_only_delay_ms": round(io_only * 1e3, 3)},
+        "roofline": {"kernel": "kv_recompute_layer (rocBLAS GEMMs + recompute_attention_kernel)", "bound": "mfma",
+                     "achieved": big["tflops"], "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(big["tflops"] / MFMA_F16_PEAK_TFLOPS, 4), "traffic": None},
+    }
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -453,6 +535,10 @@ def main():
                     help="i8: the int8 channel-wise record format on the workload's geometry (compress + swap-in)")
     ap.add_argument("--sweep-chunk-tokens", action="store_true",
                     help="instead of the benchmark: compress / swap-in rates for chunk sizes 4..256")
+    ap.add_argument("--recompute", action="store_true",
+                    help="instead of the benchmark: one-layer recompute of interleaved chunks (Sec. 3.3) on the "
+                         "workload's geometry, T_re fit and an Eq. 4 plan")
+    ap.add_argument("--d-ff", type=int, default=11008, help="--recompute: feed-forward width")
     ap.add_argument("--contexts", type=int, default=0, help="pool workload: number of contexts (default: all)")
     ap.add_argument("--stream-buffers", type=int, default=4)
     ap.add_argument("--stream-slot-mib", type=int, default=64)
@@ -475,6 +561,9 @@ def main():
         return
     if args.format == "i8":
         print(json.dumps(run_i8(wl, args, dev)))
+        return
+    if args.recompute:
+        print(json.dumps(run_recompute(wl, args, dev)))
         return
     if wl.n_contexts > 1:
         print(json.dumps(run_pool(wl, args, dev)))
