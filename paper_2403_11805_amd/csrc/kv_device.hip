@@ -69,6 +69,32 @@ QuantGeom quant_geom_i8(const kv_shape_t& s, int* ppl) {
     return g;
 }
 
+I8View i8_view(const kv_shape_t& s) {
+    I8View v;
+    v.head_dim = s.head_dim;
+    v.group_lanes = s.head_dim / 4 < 64 ? s.head_dim / 4 : 64;
+    v.share_log2 = 6 - ilog2(v.group_lanes);
+    return v;
+}
+
+// Calls LAUNCH(NDW, GPL) for the int8 format's (dwords per lane, channel groups per lane).
+#define KV_I8_DISPATCH(ppl, head_dim, LAUNCH)                                   \
+    do {                                                                        \
+        const int gpl_ = (head_dim) > 256 ? (head_dim) / 256 : 1;               \
+        switch ((ppl) * 4 * 8 + gpl_) {                                         \
+            case 4 * 8 + 1: LAUNCH(4, 1); break;                                \
+            case 4 * 8 + 2: LAUNCH(4, 2); break;                                \
+            case 4 * 8 + 4: LAUNCH(4, 4); break;                                \
+            case 8 * 8 + 1: LAUNCH(8, 1); break;                                \
+            case 8 * 8 + 2: LAUNCH(8, 2); break;                                \
+            case 8 * 8 + 4: LAUNCH(8, 4); break;                                \
+            case 16 * 8 + 1: LAUNCH(16, 1); break;                              \
+            case 16 * 8 + 2: LAUNCH(16, 2); break;                              \
+            case 16 * 8 + 4: LAUNCH(16, 4); break;                              \
+            default: return fail(KV_ESHAPE, "int8 format: unsupported unit");   \
+        }                                                                       \
+    } while (0)
+
 // Pieces per lane of a wavefront task (the largest of 4, 2, 1 that is at most
 // max_ppl and divides the unit) and the resulting tasks per unit.
 int plan_tasks(QuantGeom* g, int max_ppl) {
@@ -116,27 +142,11 @@ int32_t kv_compress_chunks(const kv_shape_t* shape, const void* kv, const uint8_
     const u4_t* src = static_cast<const u4_t*>(kv);
     uint8_t* dst = static_cast<uint8_t*>(packed_out);
     if (i8) {
-        I8View v;
-        v.head_dim = shape->head_dim;
-        v.group_lanes = shape->head_dim / 4 < 64 ? shape->head_dim / 4 : 64;
-        v.share_log2 = 6 - ilog2(v.group_lanes);
-        const int gpl = shape->head_dim > 256 ? shape->head_dim / 256 : 1;   // 1, 2 or 4
+        const I8View v = i8_view(*shape);
 #define KV_LAUNCH_I8(NDW, GPL)                                                                          \
         hipLaunchKernelGGL((compress_i8_kernel<NDW, GPL>), grid, dim3(256), 0, st, src, bits_dev, off_dev, \
                            dst, g, v, n_chunks)
-        const int key = ppl * 4 * 8 + gpl;          // dwords per lane, channel groups per lane
-        switch (key) {
-            case 4 * 8 + 1: KV_LAUNCH_I8(4, 1); break;
-            case 4 * 8 + 2: KV_LAUNCH_I8(4, 2); break;
-            case 4 * 8 + 4: KV_LAUNCH_I8(4, 4); break;
-            case 8 * 8 + 1: KV_LAUNCH_I8(8, 1); break;
-            case 8 * 8 + 2: KV_LAUNCH_I8(8, 2); break;
-            case 8 * 8 + 4: KV_LAUNCH_I8(8, 4); break;
-            case 16 * 8 + 1: KV_LAUNCH_I8(16, 1); break;
-            case 16 * 8 + 2: KV_LAUNCH_I8(16, 2); break;
-            case 16 * 8 + 4: KV_LAUNCH_I8(16, 4); break;
-            default: return fail(KV_ESHAPE, "int8 format: unit of %d pieces with head_dim %d", g.pieces, shape->head_dim);
-        }
+        KV_I8_DISPATCH(ppl, shape->head_dim, KV_LAUNCH_I8);
 #undef KV_LAUNCH_I8
         return launch_status("compress_i8_kernel launch");
     }
@@ -168,9 +178,12 @@ int32_t kv_swapin_chunks(const kv_shape_t* shape, const void* packed, const uint
     const uint8_t* src = static_cast<const uint8_t*>(packed);
     u4_t* dst = static_cast<u4_t*>(kv_out);
     if (i8) {
-        if (ppl == 4) hipLaunchKernelGGL(swapin_i8_kernel<4>, grid, dim3(256), 0, st, src, src_off_dev, dst_tok_dev, sel_bits_dev, dst, g, n_sel);
-        else if (ppl == 2) hipLaunchKernelGGL(swapin_i8_kernel<2>, grid, dim3(256), 0, st, src, src_off_dev, dst_tok_dev, sel_bits_dev, dst, g, n_sel);
-        else hipLaunchKernelGGL(swapin_i8_kernel<1>, grid, dim3(256), 0, st, src, src_off_dev, dst_tok_dev, sel_bits_dev, dst, g, n_sel);
+        const I8View v = i8_view(*shape);
+#define KV_LAUNCH_I8(NDW, GPL)                                                                       \
+        hipLaunchKernelGGL((swapin_i8_kernel<NDW, GPL>), grid, dim3(256), 0, st, src, src_off_dev,   \
+                           dst_tok_dev, sel_bits_dev, dst, g, v, n_sel)
+        KV_I8_DISPATCH(ppl, shape->head_dim, KV_LAUNCH_I8);
+#undef KV_LAUNCH_I8
         return launch_status("swapin_i8_kernel launch");
     }
     if (ppl == 4) hipLaunchKernelGGL(swapin_kernel<4>, grid, dim3(256), 0, st, src, src_off_dev, dst_tok_dev, sel_bits_dev, dst, g, n_sel);
@@ -400,10 +413,13 @@ int32_t kv_swapin_pinned(const kv_shape_t* shape, const void* packed_pinned, con
         if (e != hipSuccess) { rc = hip_fail(e, "event record/wait"); break; }
         const dim3 grid = task_grid(g, list.n);
         u4_t* dst = static_cast<u4_t*>(kv_out);
-        if (i8 && ppl == 4) hipLaunchKernelGGL(swapin_i8_batch_kernel<4>, grid, dim3(256), 0, ks, slot_dev, list, dst, g);
-        else if (i8 && ppl == 2) hipLaunchKernelGGL(swapin_i8_batch_kernel<2>, grid, dim3(256), 0, ks, slot_dev, list, dst, g);
-        else if (i8) hipLaunchKernelGGL(swapin_i8_batch_kernel<1>, grid, dim3(256), 0, ks, slot_dev, list, dst, g);
-        else if (ppl == 4) hipLaunchKernelGGL(swapin_batch_kernel<4>, grid, dim3(256), 0, ks, slot_dev, list, dst, g);
+        if (i8) {
+            const I8View v = i8_view(*shape);
+#define KV_LAUNCH_I8(NDW, GPL) \
+            hipLaunchKernelGGL((swapin_i8_batch_kernel<NDW, GPL>), grid, dim3(256), 0, ks, slot_dev, list, dst, g, v)
+            KV_I8_DISPATCH(ppl, shape->head_dim, KV_LAUNCH_I8);
+#undef KV_LAUNCH_I8
+        } else if (ppl == 4) hipLaunchKernelGGL(swapin_batch_kernel<4>, grid, dim3(256), 0, ks, slot_dev, list, dst, g);
         else if (ppl == 2) hipLaunchKernelGGL(swapin_batch_kernel<2>, grid, dim3(256), 0, ks, slot_dev, list, dst, g);
         else hipLaunchKernelGGL(swapin_batch_kernel<1>, grid, dim3(256), 0, ks, slot_dev, list, dst, g);
         rc = launch_status("swapin_batch_kernel launch");

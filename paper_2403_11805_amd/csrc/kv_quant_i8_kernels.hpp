@@ -246,61 +246,98 @@ __global__ __launch_bounds__(256) void compress_i8_kernel(const u4_t* __restrict
 }
 
 // ------------------------------------------------------------------ swap-in
+//
+// The same transposed view as compress, the other way round: the unit's codes are
+// loaded in record order (one coalesced access per lane), parked in LDS and read
+// back by the lane that holds 4 adjacent channels of a token row; that lane loads
+// the parameters of its channels itself (two 16-byte loads per channel group
+// instead of the 32 parameters of a 16-channel piece per piece), dequantises,
+// packs four bytes and parks them in LDS in cache order, from where they leave as
+// coalesced 16-byte stores.
 
-template <int BITS, int PPL>
-__device__ __forceinline__ void swapin_i8_unit(const uint8_t* __restrict__ codes,
-                                               const float* __restrict__ scale_in,
-                                               const float* __restrict__ mn_in,
-                                               u4_t* __restrict__ dst, int rp_log2, int lane) {
-    constexpr uint32_t kMask = (1u << BITS) - 1u;
-    u2_t w[PPL];
+template <int BYTES>
+__device__ __forceinline__ void copy_in(const uint8_t* __restrict__ src, uint8_t* __restrict__ img, int lane) {
+    if constexpr (BYTES >= 16) {
 #pragma unroll
-    for (int u = 0; u < PPL; ++u) {
-        const int p = u * 64 + lane;
-        w[u] = u2_t{0u, 0u};
-        if constexpr (BITS == 4) w[u] = stream_load<KVS_NT_CODE_LOAD>(reinterpret_cast<const u2_t*>(codes) + p);
-        else if constexpr (BITS == 2) w[u].x = stream_load<KVS_NT_CODE_LOAD>(reinterpret_cast<const uint32_t*>(codes) + p);
-        else w[u].x = stream_load<KVS_NT_CODE_LOAD>(reinterpret_cast<const uint16_t*>(codes) + p);
-    }
-    const int cb = lane & ((1 << rp_log2) - 1);        // which 16 channels this lane holds
-    float sc[16], mn[16];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const u4_t sv = reinterpret_cast<const u4_t*>(scale_in)[cb * 4 + j];
-        const u4_t mv = reinterpret_cast<const u4_t*>(mn_in)[cb * 4 + j];
-        const uint32_t s4[4] = {sv.x, sv.y, sv.z, sv.w}, m4[4] = {mv.x, mv.y, mv.z, mv.w};
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            sc[4 * j + k] = __builtin_bit_cast(float, s4[k]);
-            mn[4 * j + k] = __builtin_bit_cast(float, m4[k]);
-        }
-    }
-#pragma unroll
-    for (int u = 0; u < PPL; ++u) {
-        uint32_t out[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            uint32_t word = 0;
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const int e = 4 * j + k;                  // element of the piece
-                const int bitpos = e * BITS;
-                const uint32_t c = ((bitpos < 32 ? w[u].x : w[u].y) >> (bitpos & 31)) & kMask;
-                const float prod = static_cast<float>(c) * sc[e];    // rounded product, then rounded sum
-                float v = __builtin_rintf(prod + mn[e]);
-                v = __builtin_fminf(__builtin_fmaxf(v, -128.0f), 127.0f);
-                word = __builtin_amdgcn_cvt_pk_u8_f32(v + 128.0f, k, word);
-            }
-            out[j] = word ^ 0x80808080u;                 // back to two's complement bytes
-        }
-        const u4_t v4 = {out[0], out[1], out[2], out[3]};
-        stream_store<KVS_NT_CACHE_STORE>(v4, dst + u * 64 + lane);
+        for (int u = 0; u < BYTES / 16; ++u)
+            reinterpret_cast<u4_t*>(img)[u * 64 + lane] =
+                stream_load<KVS_NT_CODE_LOAD>(reinterpret_cast<const u4_t*>(src) + u * 64 + lane);
+    } else if constexpr (BYTES == 8) {
+        reinterpret_cast<u2_t*>(img)[lane] = stream_load<KVS_NT_CODE_LOAD>(reinterpret_cast<const u2_t*>(src) + lane);
+    } else if constexpr (BYTES == 4) {
+        reinterpret_cast<uint32_t*>(img)[lane] =
+            stream_load<KVS_NT_CODE_LOAD>(reinterpret_cast<const uint32_t*>(src) + lane);
+    } else {
+        reinterpret_cast<uint16_t*>(img)[lane] =
+            stream_load<KVS_NT_CODE_LOAD>(reinterpret_cast<const uint16_t*>(src) + lane);
     }
 }
 
-template <int PPL>
+// x = int8(clamp(rint(code * scale + mn), -128, 127)): product and sum rounded separately; the
+// saturating conversion of x + 128 to an unsigned byte is the clamp (x is an integer after rint).
+template <int BITS, int NDW, int GPL>
+__device__ __forceinline__ void swapin_i8_unit(const uint8_t* __restrict__ codes,
+                                               const float* __restrict__ scale_in,
+                                               const float* __restrict__ mn_in, uint8_t* __restrict__ code_img,
+                                               uint8_t* __restrict__ raw_img, u4_t* __restrict__ dst,
+                                               const I8View& v, int lane) {
+    constexpr int PPL = NDW / 4;
+    constexpr int RPL = NDW / GPL;
+    constexpr uint32_t kMask = (1u << BITS) - 1u;
+    copy_in<NDW * BITS / 2>(codes, code_img, lane);
+    const int c = lane & (v.group_lanes - 1);
+    const int rpart = lane >> (6 - v.share_log2);
+    const int row0 = rpart * RPL;
+    u4_t sv[GPL], mv[GPL];
+#pragma unroll
+    for (int j = 0; j < GPL; ++j) {
+        sv[j] = reinterpret_cast<const u4_t*>(scale_in)[c + 64 * j];
+        mv[j] = reinterpret_cast<const u4_t*>(mn_in)[c + 64 * j];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+    for (int j = 0; j < GPL; ++j) {
+        const int g4 = c + 64 * j;
+        const uint32_t s4[4] = {sv[j].x, sv[j].y, sv[j].z, sv[j].w};
+        const uint32_t m4[4] = {mv[j].x, mv[j].y, mv[j].z, mv[j].w};
+#pragma unroll
+        for (int k = 0; k < RPL; ++k) {
+            const int row = row0 + k;
+            uint32_t cw;                   // the four codes of (row, channel group), lowest channel lowest
+            if constexpr (BITS == 4) {
+                cw = *reinterpret_cast<const uint16_t*>(code_img + row * (v.head_dim >> 1) + 2 * g4);
+            } else if constexpr (BITS == 2) {
+                cw = code_img[row * (v.head_dim >> 2) + g4];
+            } else {
+                cw = code_img[row * (v.head_dim >> 3) + (g4 >> 1)];
+                cw >>= 4 * (g4 & 1);
+            }
+            uint32_t word = 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t code = (cw >> (i * BITS)) & kMask;
+                const float prod = static_cast<float>(code) * __builtin_bit_cast(float, s4[i]);
+                const float x = __builtin_rintf(prod + __builtin_bit_cast(float, m4[i]));
+                word = __builtin_amdgcn_cvt_pk_u8_f32(x + 128.0f, i, word);
+            }
+            *reinterpret_cast<uint32_t*>(raw_img + row * v.head_dim + 4 * g4) = word ^ 0x80808080u;
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+    for (int u = 0; u < PPL; ++u)
+        stream_store<KVS_NT_CACHE_STORE>(reinterpret_cast<const u4_t*>(raw_img)[u * 64 + lane], dst + u * 64 + lane);
+}
+
+template <int NDW, int GPL>
 __device__ __forceinline__ void swapin_i8_task(const uint8_t* __restrict__ base, int b, int slab,
-                                               u4_t* __restrict__ dst, const QuantGeom& g, int lane) {
+                                               u4_t* __restrict__ dst, const QuantGeom& g, const I8View& v,
+                                               uint8_t* __restrict__ lds_wave, int lane) {
+    constexpr int PPL = NDW / 4;
     if (b == 8) {
         const u4_t* src = reinterpret_cast<const u4_t*>(base) + static_cast<uint64_t>(slab) * g.pieces;
         u4_t raw[PPL];
@@ -311,41 +348,48 @@ __device__ __forceinline__ void swapin_i8_task(const uint8_t* __restrict__ base,
         return;
     }
     const uint64_t code_bytes = static_cast<uint64_t>(g.pieces) * 2 * b;
-    const uint32_t channels = static_cast<uint32_t>(g.row_pieces) * 16;
+    const uint32_t channels = static_cast<uint32_t>(v.head_dim);
     const uint8_t* codes = base + slab * code_bytes;
     const float* scale = reinterpret_cast<const float*>(base + g.slabs * code_bytes) +
                          static_cast<uint64_t>(slab) * channels;
     const float* mn = scale + static_cast<uint64_t>(g.slabs) * channels;
-    if (b == 4) swapin_i8_unit<4, PPL>(codes, scale, mn, dst, g.lpg_log2, lane);
-    else if (b == 2) swapin_i8_unit<2, PPL>(codes, scale, mn, dst, g.lpg_log2, lane);
-    else swapin_i8_unit<1, PPL>(codes, scale, mn, dst, g.lpg_log2, lane);
+    uint8_t* raw_img = lds_wave;
+    uint8_t* code_img = lds_wave + NDW * 256;
+    if (b == 4) swapin_i8_unit<4, NDW, GPL>(codes, scale, mn, code_img, raw_img, dst, v, lane);
+    else if (b == 2) swapin_i8_unit<2, NDW, GPL>(codes, scale, mn, code_img, raw_img, dst, v, lane);
+    else swapin_i8_unit<1, NDW, GPL>(codes, scale, mn, code_img, raw_img, dst, v, lane);
 }
 
-template <int PPL>
+// LDS per wavefront as in compress_i8_kernel: the unit (NDW * 256 bytes) and its codes.
+template <int NDW, int GPL>
 __global__ __launch_bounds__(256) void swapin_i8_kernel(const uint8_t* __restrict__ packed,
                                                         const uint64_t* __restrict__ src_off,
                                                         const int32_t* __restrict__ dst_tok,
                                                         const uint8_t* __restrict__ sel_bits,
-                                                        u4_t* __restrict__ kv_out, QuantGeom g,
+                                                        u4_t* __restrict__ kv_out, QuantGeom g, I8View v,
                                                         int32_t n_sel) {
+    __shared__ __align__(16) uint8_t lds[kWavesPerBlock][NDW * 256 + NDW * 128];
     const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6));
     int j, slab, p0;
-    if (!wave_task(g, n_sel, PPL, j, slab, p0)) return;
+    if (!wave_task(g, n_sel, NDW / 4, j, slab, p0)) return;
     u4_t* dst = kv_out + (static_cast<uint64_t>(slab) * g.n_tokens +
                           static_cast<uint64_t>(dst_tok[j])) * g.row_pieces;
-    swapin_i8_task<PPL>(packed + src_off[j], uniform_byte(sel_bits, j), slab, dst, g, lane);
+    swapin_i8_task<NDW, GPL>(packed + src_off[j], uniform_byte(sel_bits, j), slab, dst, g, v, lds[wave], lane);
 }
 
-template <int PPL>
+template <int NDW, int GPL>
 __global__ __launch_bounds__(256) void swapin_i8_batch_kernel(const uint8_t* __restrict__ staged,
                                                               SwapinBatch list,
-                                                              u4_t* __restrict__ kv_out, QuantGeom g) {
+                                                              u4_t* __restrict__ kv_out, QuantGeom g, I8View v) {
+    __shared__ __align__(16) uint8_t lds[kWavesPerBlock][NDW * 256 + NDW * 128];
     const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6));
     int j, slab, p0;
-    if (!wave_task(g, list.n, PPL, j, slab, p0)) return;
+    if (!wave_task(g, list.n, NDW / 4, j, slab, p0)) return;
     u4_t* dst = kv_out + (static_cast<uint64_t>(slab) * g.n_tokens +
                           static_cast<uint64_t>(list.dst_tok[j])) * g.row_pieces;
-    swapin_i8_task<PPL>(staged + list.src_off[j], list.bits[j], slab, dst, g, lane);
+    swapin_i8_task<NDW, GPL>(staged + list.src_off[j], list.bits[j], slab, dst, g, v, lds[wave], lane);
 }
 
 }  // namespace kvs
