@@ -211,13 +211,13 @@ int32_t kv_recompute_layer(kv_recompute_t* rc, const kv_shape_t* shape, const kv
     g.n_rb = static_cast<int32_t>((M + 31) / 32);
     g.pairs = (Hq / Hkv) * g.n_rb;
     g.scale_log2e = static_cast<float>(1.4426950408889634 / std::sqrt(static_cast<double>(D)));
-    const dim3 agrid(static_cast<uint32_t>((g.pairs + 3) / 4), static_cast<uint32_t>(Hkv));
+    const dim3 agrid(static_cast<uint32_t>((g.pairs + kAttnWaves - 1) / kAttnWaves), static_cast<uint32_t>(Hkv));
     if (D == 64)
-        hipLaunchKernelGGL(recompute_attention_kernel<64>, agrid, dim3(256), 0, st, q16, k_plane, v_plane,
-                           chunk_idx_dev, attn, g);
+        hipLaunchKernelGGL(recompute_attention_kernel<64>, agrid, dim3(64 * kAttnWaves), 0, st, q16, k_plane,
+                           v_plane, chunk_idx_dev, attn, g);
     else
-        hipLaunchKernelGGL(recompute_attention_kernel<128>, agrid, dim3(256), 0, st, q16, k_plane, v_plane,
-                           chunk_idx_dev, attn, g);
+        hipLaunchKernelGGL(recompute_attention_kernel<128>, agrid, dim3(64 * kAttnWaves), 0, st, q16, k_plane,
+                           v_plane, chunk_idx_dev, attn, g);
     // 4. output projection + residual, feed-forward + residual
     if (int e = gemm(rc, M, dims->d_model, dq, attn, w->wo, xin, x1, false, "o")) return e;
     hipLaunchKernelGGL(rmsnorm_kernel, rows, dim3(256), 0, st, x1, static_cast<const _Float16*>(w->w_norm2), xn,

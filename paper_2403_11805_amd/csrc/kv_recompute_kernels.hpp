@@ -142,33 +142,41 @@ struct AttnGeom {
 // with mfma_f32_32x32x16_f16 (a lane owns one query row and 16 of the tile's 32
 // tokens), online softmax per row, O^T += V_tile^T P^T with the probabilities
 // rounded to fp16 as the B operand straight from the registers (the contraction
-// index is permuted the same way on both operands).  The four wavefronts of a
-// workgroup take four consecutive pairs of ONE kv head, so K and V tiles are
-// fetched once per workgroup (coalesced 16-byte loads, one tile ahead) and shared
-// through LDS: K with its row pieces permuted by the row number, V transposed.
-// Tokens after a row's global position are masked; a wavefront skips the tiles
-// that lie entirely behind its last row.
+// index is permuted the same way on both operands).  The eight wavefronts of a
+// workgroup take eight consecutive pairs of ONE kv head, so K and V tiles are
+// fetched once per workgroup (coalesced 16-byte loads, two tiles ahead) and shared
+// through LDS: K with its row pieces permuted by the row number, V transposed
+// (token groups of a row permuted by the row's channel block, which spreads the
+// 2-byte transposing writes over the banks).  Tokens after a row's global position
+// are masked; a wavefront skips the tiles that lie entirely behind its last row,
+// and the output accumulators are rescaled only when some row's maximum moved.
+constexpr int kAttnWaves = 8;
+
 template <int D>
-__global__ __launch_bounds__(256) void recompute_attention_kernel(const _Float16* __restrict__ q16,
-                                                                  const _Float16* __restrict__ k_plane,
-                                                                  const _Float16* __restrict__ v_plane,
-                                                                  const int32_t* __restrict__ chunk_idx,
-                                                                  _Float16* __restrict__ out, AttnGeom g) {
+__global__ __launch_bounds__(64 * kAttnWaves) void recompute_attention_kernel(
+    const _Float16* __restrict__ q16, const _Float16* __restrict__ k_plane,
+    const _Float16* __restrict__ v_plane, const int32_t* __restrict__ chunk_idx,
+    _Float16* __restrict__ out, AttnGeom g) {
     constexpr int KS = D / 16;
     constexpr int DB = D / 32;                      // 32-wide blocks of the head dimension
     constexpr int kRowPieces = D / 8;
-    constexpr int kPer = 32 * kRowPieces / 256;     // 16-byte pieces per thread and tile
-    constexpr int kVtStride = 36;                   // halfs per transposed V row (32 tokens + padding)
+    constexpr int kThreads = 64 * kAttnWaves;
+    constexpr int kTilePieces = 32 * kRowPieces;    // 16-byte pieces of a K (or V) tile
+    constexpr int kPer = (kTilePieces + kThreads - 1) / kThreads;
     __shared__ ru4_t ktile[2][32 * kRowPieces];
-    __shared__ __align__(16) _Float16 vt[2][D * kVtStride];
+    __shared__ __align__(16) _Float16 vt[2][D * 32];       // [channel][token], 64 bytes per channel
     auto swz = [](int r) __attribute__((always_inline)) { return D == 64 ? (r >> 1) & 7 : r & 15; };
+    // token t of channel d sits at vt[d * 32 + (t ^ vswz(d))]: groups of 4 tokens stay together
+    auto vswz = [](int d) __attribute__((always_inline)) { return ((d >> 3) & 7) << 2; };
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int lrow = lane & 31, half = lane >> 5;
     const int kvh = blockIdx.y;
     const int per = g.Hq / g.Hkv;
-    const int pair = blockIdx.x * 4 + wave;
+    // workgroups with the longest key ranges are dispatched first
+    const int bx = static_cast<int>(gridDim.x) - 1 - static_cast<int>(blockIdx.x);
+    const int pair = bx * kAttnWaves + wave;
     const bool valid = pair < g.pairs;
     const int head = kvh * per + (valid ? pair % per : 0);
     const int rb = valid ? pair / per : 0;
@@ -178,7 +186,7 @@ __global__ __launch_bounds__(256) void recompute_attention_kernel(const _Float16
     // rows ascend in position: first and last row of this wavefront, last row of the workgroup
     const int min_pos = valid ? global_position(chunk_idx, g.T, rb * 32) : -1;
     const int max_pos = valid ? global_position(chunk_idx, g.T, min(rb * 32 + 31, g.M - 1)) : -1;
-    const int rb_hi = min(blockIdx.x * 4 + 3, g.pairs - 1) / per;
+    const int rb_hi = min(bx * kAttnWaves + kAttnWaves - 1, g.pairs - 1) / per;
     const int wg_max_pos = global_position(chunk_idx, g.T, min(rb_hi * 32 + 31, g.M - 1));
     const int n_tiles = wg_max_pos / 32 + 1;
 
@@ -194,26 +202,27 @@ __global__ __launch_bounds__(256) void recompute_attention_kernel(const _Float16
     }
     const ru4_t* kbase = reinterpret_cast<const ru4_t*>(k_plane + static_cast<int64_t>(kvh) * g.N * D);
     const ru4_t* vbase = reinterpret_cast<const ru4_t*>(v_plane + static_cast<int64_t>(kvh) * g.N * D);
-    ru4_t kst[kPer], vst[kPer];
-    auto fetch = [&](int t) __attribute__((always_inline)) {
+    // tiles in flight: set 0 holds even tiles, set 1 odd ones (loads are issued two tiles ahead)
+    ru4_t kst[2][kPer], vst[2][kPer];
+    auto fetch = [&](int set, int t) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < kPer; ++i) {
-            const int p = i * 256 + tid;
+            const int p = min(i * kThreads + tid, kTilePieces - 1);       // surplus threads repeat the last piece
             const int token = min(t * 32 + p / kRowPieces, g.N - 1);      // rows past the cache are masked anyway
             const int64_t src = static_cast<int64_t>(token) * kRowPieces + p % kRowPieces;
-            kst[i] = kbase[src];
-            vst[i] = vbase[src];
+            kst[set][i] = kbase[src];
+            vst[set][i] = vbase[src];
         }
     };
-    auto park = [&](int buf) __attribute__((always_inline)) {
+    auto park = [&](int set, int buf) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < kPer; ++i) {
-            const int p = i * 256 + tid;
+            const int p = min(i * kThreads + tid, kTilePieces - 1);
             const int r = p / kRowPieces, c = p % kRowPieces;
-            ktile[buf][r * kRowPieces + (c ^ swz(r))] = kst[i];
-            const rv8h_t v = __builtin_bit_cast(rv8h_t, vst[i]);
+            ktile[buf][r * kRowPieces + (c ^ swz(r))] = kst[set][i];
+            const rv8h_t v = __builtin_bit_cast(rv8h_t, vst[set][i]);
 #pragma unroll
-            for (int j = 0; j < 8; ++j) vt[buf][(c * 8 + j) * kVtStride + r] = v[j];
+            for (int j = 0; j < 8; ++j) vt[buf][(c * 8 + j) * 32 + (r ^ vswz(c * 8 + j))] = v[j];
         }
     };
 
@@ -222,13 +231,9 @@ __global__ __launch_bounds__(256) void recompute_attention_kernel(const _Float16
     for (int b = 0; b < DB; ++b) o_acc[b] = rv16f_t{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
     float m_run = -INFINITY, l_run = 0.0f;
 
-    fetch(0);
-    park(0);
-    __syncthreads();
-    for (int t = 0; t < n_tiles; ++t) {
-        const int buf = t & 1;
-        const bool more = t + 1 < n_tiles;
-        if (more) fetch(t + 1);
+    // one tile: the arithmetic on LDS buffer `buf` (tile t), then tile t + 1 (fetched two steps ago
+    // into the other register set) goes to the other buffer and its set fetches tile t + 3
+    auto step = [&](int t, int buf) __attribute__((always_inline)) {
         if (t * 32 <= max_pos) {            // wave-uniform
             rv8h_t kreg[KS];
 #pragma unroll
@@ -239,50 +244,65 @@ __global__ __launch_bounds__(256) void recompute_attention_kernel(const _Float16
             for (int ks = 0; ks < KS; ++ks)
                 acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(kreg[ks], qreg[ks], acc, 0, 0, 0);
             // acc[v]: token t*32 + 8*(v/4) + 4*half + v%4 against this lane's query row
-            float s[16];
+            // maxima on the raw logits (the scale is positive), the scale folded into the exponent
             const bool masked = t * 32 + 31 > min_pos;     // wave-uniform
             float mloc = -INFINITY;
+            if (masked) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int tk = t * 32 + 8 * (v / 4) + 4 * half + (v % 4);
-                float x = acc[v] * g.scale_log2e;
-                if (masked && tk > pos) x = -INFINITY;
-                s[v] = x;
-                mloc = fmaxf(mloc, x);
+                for (int v = 0; v < 16; ++v) {
+                    const int tk = t * 32 + 8 * (v / 4) + 4 * half + (v % 4);
+                    if (tk > pos) acc[v] = -INFINITY;
+                }
             }
-            const float m_new = fmaxf(m_run, xhalf_max(mloc));
+#pragma unroll
+            for (int v = 0; v < 16; ++v) mloc = fmaxf(mloc, acc[v]);
+            const float m_new = fmaxf(m_run, xhalf_max(mloc) * g.scale_log2e);
             const float m_safe = (m_new == -INFINITY) ? 0.0f : m_new;
             const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
             float psum = 0.0f;
             rv8h_t pb[2];
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const float pv = __builtin_amdgcn_exp2f(s[v] - m_safe);
+                const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(acc[v], g.scale_log2e, -m_safe));
                 psum += pv;
                 pb[v / 8][v % 8] = static_cast<_Float16>(pv);
             }
             l_run = l_run * alpha + xhalf_sum(psum);
+            const bool moved = m_new != m_run;
             m_run = m_new;
+            if (__any(moved)) {             // wave-uniform: some row's maximum moved
 #pragma unroll
-            for (int b = 0; b < DB; ++b)
+                for (int b = 0; b < DB; ++b)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) o_acc[b][v] *= alpha;
+                    for (int v = 0; v < 16; ++v) o_acc[b][v] *= alpha;
+            }
             // contraction slot (half, e) of step st holds token 16*st + 4*half + e (e < 4) or
             // 16*st + 8 + 4*half + e - 4: the order of acc[8*st .. 8*st+7] on the P side
 #pragma unroll
             for (int b = 0; b < DB; ++b) {
+                const int d = 32 * b + lrow;
+                const _Float16* vrow = &vt[buf][d * 32];
 #pragma unroll
                 for (int st = 0; st < 2; ++st) {
-                    const _Float16* vr = &vt[buf][(32 * b + lrow) * kVtStride + 16 * st + 4 * half];
-                    const rv4h_t lo = *reinterpret_cast<const rv4h_t*>(vr);
-                    const rv4h_t hi = *reinterpret_cast<const rv4h_t*>(vr + 8);
+                    const rv4h_t lo = *reinterpret_cast<const rv4h_t*>(vrow + ((16 * st + 4 * half) ^ vswz(d)));
+                    const rv4h_t hi = *reinterpret_cast<const rv4h_t*>(vrow + ((16 * st + 8 + 4 * half) ^ vswz(d)));
                     const rv8h_t a = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
                     o_acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, pb[st], o_acc[b], 0, 0, 0);
                 }
             }
         }
-        if (more) park(buf ^ 1);
+        if (t + 1 < n_tiles) park(buf ^ 1, buf ^ 1);
+        if (t + 3 < n_tiles) fetch(buf ^ 1, t + 3);
         __syncthreads();
+    };
+    fetch(0, 0);
+    park(0, 0);
+    fetch(1, min(1, n_tiles - 1));
+    fetch(0, min(2, n_tiles - 1));
+    __syncthreads();
+    for (int t = 0; t < n_tiles; t += 2) {
+        step(t, 0);
+        if (t + 1 < n_tiles) step(t + 1, 1);
     }
     if (ok) {
         // o_acc[b][v]: head dimension 32*b + 8*(v/4) + 4*half + v%4 of this lane's query row
