@@ -68,9 +68,12 @@ struct ScoreWs {
 // promise "sum of w * 2^(s - m_tile)" for the m_tile stored beside them.
 constexpr float kRefOverflow = 1.152921504606846976e18f;   // 2^60
 
+// stage_m / stage_e (both or neither): LDS slots of this tile, [32] and [n_sub][32] floats indexed by
+// the row inside its block; the caller copies them to the workspace later.  NULL: store directly.
 __device__ __forceinline__ void tile_epilogue(const v16f_t& acc, const ScoreGeom& g, const ScoreWs& ws,
                                               int tile, int row, int lh, int half, bool first,
-                                              float& m_ref, float& l_run) {
+                                              float& m_ref, float& l_run, float* stage_m = nullptr,
+                                              float* stage_e = nullptr) {
     const int t0 = tile * 32;
     const int first_q_pos = g.N - g.R;
     const bool tail = (t0 + 31 > first_q_pos);   // wave-uniform: some entry may be masked
@@ -157,12 +160,19 @@ __device__ __forceinline__ void tile_epilogue(const v16f_t& acc, const ScoreGeom
         esub[1] = esub[2] = esub[3] = 0.0f;
     }
     if (half == 0 && row >= 0) {
-        const int n_sb = g.N / g.sb_tokens;
-        ws.m_tile[(static_cast<int64_t>(lh) * g.n_tiles + tile) * g.rows_p + row] = m_t;
+        if (stage_m) {
+            stage_m[row & 31] = m_t;
 #pragma unroll
-        for (int k = 0; k < 4; ++k)
-            if (k < n_sub)
-                ws.e_sub[(static_cast<int64_t>(lh) * n_sb + tile * n_sub + k) * g.rows_p + row] = esub[k];
+            for (int k = 0; k < 4; ++k)
+                if (k < n_sub) stage_e[k * 32 + (row & 31)] = esub[k];
+        } else {
+            const int n_sb = g.N / g.sb_tokens;
+            ws.m_tile[(static_cast<int64_t>(lh) * g.n_tiles + tile) * g.rows_p + row] = m_t;
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                if (k < n_sub)
+                    ws.e_sub[(static_cast<int64_t>(lh) * n_sb + tile * n_sub + k) * g.rows_p + row] = esub[k];
+        }
     }
 }
 
@@ -171,6 +181,11 @@ __global__ __launch_bounds__(256) void score_tiles_kernel(const _Float16* __rest
                                                           const _Float16* __restrict__ kv,
                                                           ScoreGeom g, ScoreWs ws) {
     constexpr int KS = D / 16;
+    constexpr int kMaxRun = 8;       // tiles per run at most (host: run_len <= 8 for this kernel)
+    // Partials of a run are collected in LDS and written out after the run: stores issued between
+    // the K loads would hold back every wait for the next tile (one counter tracks both).
+    __shared__ float stage_m[4][NRBW][kMaxRun][32];
+    __shared__ float stage_e[4][NRBW][kMaxRun * 4][32];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int lrow = lane & 31, half = lane >> 5;
     const int rg_local = wave % g.rg_per_wg, tpar = wave / g.rg_per_wg;
@@ -183,6 +198,7 @@ __global__ __launch_bounds__(256) void score_tiles_kernel(const _Float16* __rest
     const int tile_end = min(tile_begin + g.run_len, g.n_tiles);
     const int l = blockIdx.z / g.Hkv, kvh = blockIdx.z % g.Hkv;
     const int qh_per_kv = g.Hq / g.Hkv;
+    const int n_sub_tile = 32 / g.sb_tokens;         // sub-blocks per tile: 1, 2 or 4
 
     // query rows of this wave, resident for the whole run
     v8h_t qreg[NRBW][KS];
@@ -240,11 +256,34 @@ __global__ __launch_bounds__(256) void score_tiles_kernel(const _Float16* __rest
 #pragma unroll
         for (int u = 0; u < NRBW; ++u) {
             if (rg * NRBW + u >= g.n_rb) break;
-            tile_epilogue(acc[u], g, ws, tile, row[u], lh[u], half, tile == tile_begin, m_run[u], l_run[u]);
+            const int tl = tile - tile_begin;
+            tile_epilogue(acc[u], g, ws, tile, row[u], lh[u], half, tile == tile_begin, m_run[u], l_run[u],
+                          stage_m[wave][u][tl], stage_e[wave][u][tl * n_sub_tile]);
         }
     }
+    // the wavefront's own LDS writes are ordered before its reads below
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const int ntl = tile_end - tile_begin;
+    const int n_sb = g.N / g.sb_tokens;
 #pragma unroll
     for (int u = 0; u < NRBW; ++u) {
+        const int rb = rg * NRBW + u;
+        if (rb >= g.n_rb) break;
+        const int row_base = (rb % g.RB) * 32;          // first row of this block inside its head
+        for (int i = lane; i < ntl * 32; i += 64) {
+            const int r = row_base + (i & 31);
+            if (r < g.R)
+                ws.m_tile[(static_cast<int64_t>(lh[u]) * g.n_tiles + tile_begin + (i >> 5)) * g.rows_p + r] =
+                    stage_m[wave][u][i >> 5][i & 31];
+        }
+        for (int i = lane; i < ntl * n_sub_tile * 32; i += 64) {
+            const int r = row_base + (i & 31);
+            if (r < g.R)
+                ws.e_sub[(static_cast<int64_t>(lh[u]) * n_sb + tile_begin * n_sub_tile + (i >> 5)) * g.rows_p + r] =
+                    stage_e[wave][u][i >> 5][i & 31];
+        }
         if (half == 0 && row[u] >= 0) {
             const int64_t ri = (static_cast<int64_t>(lh[u]) * g.n_runs + run) * g.rows_p + row[u];
             ws.m_run[ri] = m_run[u];
