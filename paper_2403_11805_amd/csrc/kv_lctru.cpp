@@ -4,6 +4,7 @@
 // One ordered set keyed by (more bits first, older last-access first, ctx,
 // chunk) realises the concatenation of per-bit-width sub-queues, each in
 // least-recently-used order.
+#include <cstddef>
 #include <map>
 #include <new>
 #include <set>

@@ -98,3 +98,46 @@ def test_llama_like_layer_sampled_positions():
     recomputed): the oracle's whole-sequence route is the reference."""
     run_case(1, 8, 8, 128, 2048, 16, 1024, 2816, 0,
              sorted(np.random.default_rng(7).choice(128, size=51, replace=False).tolist()), seed=43)
+
+
+def test_long_cache_positions_near_32768():
+    """Chunks at the start, the middle and the very end of a 32768-token cache (one kv head, four
+    query heads): rotary angles of tens of thousands of radians and attention over the whole
+    cache.  The resident K/V are seeded random values; the oracle's recompute procedure is the
+    reference."""
+    L, Hkv, Hq, D, N, T, d_model, d_ff = 1, 1, 4, 128, 32768, 32, 512, 1024
+    missing = [0, 511, 1022, 1023]
+    shape = kvs.Shape(L, Hkv, Hq, D, N, T, 128)
+    dims_o = orc.LayerDims(d_model, Hq, Hkv, D, d_ff)
+    dims = binding.LayerDims(d_model, d_ff, dims_o.rope_base, dims_o.rms_eps)
+    w = synth.make_layer_weights(d_model, Hq, Hkv, D, d_ff, 47)
+    w_np = {k: v.numpy() for k, v in w.items()}
+    kv = synth.make_kv(synth.Geometry(L, Hkv, Hq, D, N, T, 128), 47, "cpu")
+    rows = np.concatenate([np.arange(c * T, (c + 1) * T) for c in missing])
+    x = synth.make_hidden(len(rows), d_model, 47)
+    k_ref, v_ref = kv[0, 0].numpy().copy(), kv[0, 1].numpy().copy()
+    y_ref = orc.recompute_layer(x.numpy(), missing, T, k_ref, v_ref, w_np, dims_o)
+    kv_dev = kv.to(DEV)
+    x_out = torch.full((len(rows), d_model), float("nan"), dtype=torch.float16, device=DEV)
+    ws = torch.empty(kvs.kv_recompute_workspace_bytes(shape, dims, len(missing)), dtype=torch.uint8, device=DEV)
+    rc = kvs.Recompute()
+    rc.layer(shape, dims, {k: v.to(DEV) for k, v in w.items()}, 0,
+             torch.tensor(missing, dtype=torch.int32, device=DEV), x.to(DEV), kv_dev, x_out, ws)
+    torch.cuda.synchronize()
+    # twice: identical bytes
+    x_out2 = torch.empty_like(x_out)
+    kv_dev2 = kv.to(DEV)
+    rc.layer(shape, dims, {k: v.to(DEV) for k, v in w.items()}, 0,
+             torch.tensor(missing, dtype=torch.int32, device=DEV), x.to(DEV), kv_dev2, x_out2, ws)
+    torch.cuda.synchronize()
+    rc.close()
+    assert torch.equal(x_out.view(torch.int16), x_out2.view(torch.int16))
+    assert torch.equal(kv_dev.view(torch.int16), kv_dev2.view(torch.int16))
+    got = kv_dev.cpu().numpy()
+    close(got[0, 0][:, rows], k_ref[:, rows], 2e-3, 2e-3, "recomputed K")
+    close(got[0, 1][:, rows], v_ref[:, rows], 2e-3, 2e-3, "recomputed V")
+    keep = np.ones(N, dtype=bool)
+    keep[rows] = False
+    assert np.array_equal(got[0][:, :, keep].view(np.uint16), kv[0].numpy()[:, :, keep].view(np.uint16))
+    err = close(x_out.cpu().numpy(), y_ref, 1e-2, 1e-2, "layer output")
+    assert err < 3e-3
