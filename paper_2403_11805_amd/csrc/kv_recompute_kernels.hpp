@@ -172,10 +172,19 @@ __global__ __launch_bounds__(64 * kAttnWaves) void recompute_attention_kernel(
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int lrow = lane & 31, half = lane >> 5;
-    const int kvh = blockIdx.y;
+    // Workgroups are handed to the 8 XCDs in turn (linear id modulo 8), each with an L2 of its
+    // own: the workgroups of one kv head are placed on one XCD, so that its K/V planes are
+    // fetched into one L2 only.  Needs n_kv_heads % 8 == 0, otherwise the plain order is kept.
+    int kvh = blockIdx.y, bxi = blockIdx.x;
+    if (g.Hkv % 8 == 0) {
+        const int lin = blockIdx.y * gridDim.x + blockIdx.x;
+        const int per_xcd = lin >> 3;                       // position among this XCD's workgroups
+        kvh = (lin & 7) + 8 * (per_xcd / static_cast<int>(gridDim.x));
+        bxi = per_xcd % static_cast<int>(gridDim.x);
+    }
     const int per = g.Hq / g.Hkv;
     // workgroups with the longest key ranges are dispatched first
-    const int bx = static_cast<int>(gridDim.x) - 1 - static_cast<int>(blockIdx.x);
+    const int bx = static_cast<int>(gridDim.x) - 1 - bxi;
     const int pair = bx * kAttnWaves + wave;
     const bool valid = pair < g.pairs;
     const int head = kvh * per + (valid ? pair % per : 0);
