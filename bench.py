@@ -43,7 +43,7 @@ def find_workload(name):
 class Path:
     """Device buffers and the per-step call sequence for one context."""
 
-    def __init__(self, wl, dev):
+    def __init__(self, wl, dev, host_plan=False):
         g = wl.geom
         self.wl, self.g, self.dev = wl, g, dev
         self.shape = kvs.Shape(g.L, g.Hkv, g.Hq, g.D, g.N, g.T, g.G)
@@ -77,9 +77,17 @@ class Path:
         self.lists_dev = torch.empty_like(self.lists_host, device=dev)
         self.all_chunks = np.arange(g.n_chunks, dtype=np.int32)
         self.ev = {k: (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-                   for k in ("score", "compress", "swapin")}
+                   for k in ("score", "plan", "compress", "swapin")}
         self.packed_bytes = 0
         self.bits = None
+        # widths, offsets and the gather list of the whole cache stay on the device when the
+        # widths come from the scores: the step then has no host round trip
+        self.device_plan = bool(self.R) and not host_plan
+        if self.device_plan:
+            n = g.n_chunks
+            self.bits_d = torch.empty(n, dtype=torch.uint8, device=dev)
+            self.off_d = torch.empty(n + 1, dtype=torch.int64, device=dev)
+            self.dst_d = torch.empty(n, dtype=torch.int32, device=dev)
 
     def _upload_lists(self, bits, off, src, dst, sb):
         """One pinned staging buffer, one async copy: bits | off | src_off | dst_tok | sel_bits."""
@@ -106,6 +114,23 @@ class Path:
         k = self.step_no % self.n_sets
         self.step_no += 1
         self.kv, self.packed, self.kv_out = self.kv_sets[k], self.packed_sets[k], self.out_sets[k]
+        if self.device_plan:
+            n = self.g.n_chunks
+            self.ev["score"][0].record()
+            kvs.kv_score_chunks(s, self.q, self.kv, kvs.KV_NORM_VISIBLE, self.ws, self.chunk_mass,
+                                self.density)
+            self.ev["score"][1].record()
+            self.ev["plan"][0].record()
+            kvs.kv_plan_chunks_dev(s, self.density, *FRACTIONS[self.wl.bits_rule], self.bits_d, self.off_d,
+                                   self.dst_d)
+            self.ev["plan"][1].record()
+            self.ev["compress"][0].record()
+            kvs.kv_compress_chunks(s, self.kv, self.bits_d, self.off_d, self.packed)
+            self.ev["compress"][1].record()
+            self.ev["swapin"][0].record()
+            kvs.kv_swapin_chunks(s, self.packed, self.off_d[:n], self.dst_d, self.bits_d, self.kv_out)
+            self.ev["swapin"][1].record()
+            return
         if self.R:
             self.ev["score"][0].record()
             kvs.kv_score_chunks(s, self.q, self.kv, kvs.KV_NORM_VISIBLE, self.ws, self.chunk_mass,
@@ -129,7 +154,15 @@ class Path:
         self.bits = bits
 
     def kernel_ms(self):
-        return {k: a.elapsed_time(b) for k, (a, b) in self.ev.items() if k != "score" or self.R}
+        return {k: a.elapsed_time(b) for k, (a, b) in self.ev.items()
+                if (k != "score" or self.R) and (k != "plan" or self.device_plan)}
+
+    def fetch_plan(self):
+        """After the last step: the widths and the packed size the device planned."""
+        if self.device_plan:
+            torch.cuda.synchronize()
+            self.bits = self.bits_d.cpu().numpy()
+            self.packed_bytes = int(self.off_d[-1])
 
 
 def cpu_baseline(path, budget_s=20.0):
@@ -275,7 +308,7 @@ def run_stream(wl, args, dev):
     on another).  Reports the kernel-only rate, the bare copy rate and the overlap."""
     g = wl.geom
     shape = kvs.Shape(g.L, g.Hkv, g.Hq, g.D, g.N, g.T, g.G)
-    path = Path(wl, dev)
+    path = Path(wl, dev, host_plan=True)     # the host owns the pinned pool: it needs the offsets
     copy_s, comp_s = torch.cuda.Stream(), torch.cuda.Stream()
     path.step()                                  # score + compress (+ resident swap-in)
     torch.cuda.synchronize()
@@ -544,6 +577,9 @@ def main():
     ap.add_argument("--stream-slot-mib", type=int, default=64)
     ap.add_argument("--re-us-per-chunk", type=float, default=50.0,
                     help="streaming workload: assumed recompute cost per chunk for the Eq. 4 plan example")
+    ap.add_argument("--host-plan", action="store_true",
+                    help="widths, offsets and gather list on the host between scoring and compression "
+                         "(default: on the device, no host round trip)")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="N",
                     help="instead of the benchmark, run N pass-through (16-bit) compress launches: "
                          "a plain copy of the whole cache, used to scale rocprofv3 byte counters")
@@ -571,7 +607,7 @@ def main():
     if wl.name == "llama3-8b-32k" and not args.calibrate_copy:
         print(json.dumps(run_stream(wl, args, dev)))
         return
-    path = Path(wl, dev)
+    path = Path(wl, dev, host_plan=args.host_plan)
     g = wl.geom
 
     if args.calibrate_copy:
@@ -599,12 +635,14 @@ def main():
     wall = time.perf_counter() - t0
     ms_per_step = wall / args.steps * 1e3
 
+    path.fetch_plan()
     cache_bytes = g.elements * 2
     alg = {"compress": cache_bytes + path.packed_bytes, "swapin": cache_bytes + path.packed_bytes}
     if path.R:
         alg["score"] = (g.L * g.Hkv * g.N * g.D * 2 + g.L * g.Hq * path.R * g.D * 2 +
                         g.L * g.Hq * g.n_chunks * 4)
     kernels = {}
+    plan_ms = sums.pop("plan", None)
     for k, v in sums.items():
         ms = float(np.mean(v))
         gbps = alg[k] / ms / 1e6
@@ -633,13 +671,17 @@ def main():
         "config": {"workload": f"{wl.name}: [L={g.L},K/V,Hkv={g.Hkv},N={g.N},D={g.D}] fp16, "
                                f"chunk {g.T}, group {g.G}, R={path.R}, widths {wl.bits_rule}",
                    "cache_bytes": cache_bytes, "packed_bytes": path.packed_bytes,
-                   "step": "score + bits/offsets (host) + compress + gather list (host) + swap-in"},
+                   "step": ("score + widths/offsets/gather list (device) + compress + swap-in, one stream, no "
+                            "host round trip" if path.device_plan else
+                            "score + bits/offsets (host) + compress + gather list (host) + swap-in")},
         "ms_per_4k_ctx_switch": kernels["swapin"]["ms"],
         "compress_pct_hbm_peak": round(100 * kernels["compress"]["hbm_frac"], 2),
         "swapin_pct_hbm_peak": round(100 * kernels["swapin"]["hbm_frac"], 2),
         "kernels": kernels,
         "roofline": roofline,
     }
+    if plan_ms is not None:
+        out["plan_ms"] = round(float(np.mean(plan_ms)), 4)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(path)
     print(json.dumps(out))

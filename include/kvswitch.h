@@ -214,6 +214,27 @@ int32_t kv_score_chunks(const kv_shape_t* shape, const void* q, int32_t n_querie
                         void* workspace, uint64_t workspace_bytes,
                         float* chunk_mass, float* density, void* stream);
 
+/* Widths, record offsets and the whole-cache gather list computed on the device
+ * (Sec. 3.2, Eq. 2 with fixed thresholds; Sec. 3.1 primitive 3), for callers that
+ * keep scoring, compression and swap-in on one stream with no host round trip.
+ * The results equal, bit for bit, those of kv_bits_from_scores(density, n_chunks,
+ * num8, num4, den) followed by kv_chunk_offsets and by kv_build_gather over all
+ * chunks:
+ *   density_dev dev fp32 [n_chunks], finite (e.g. kv_score_chunks' output on the
+ *               same stream);
+ *   bits_dev    dev u8  [n_chunks]    widths; also the sel_bits list;
+ *   off_dev     dev u64 [n_chunks+1]  record offsets; its first n_chunks entries
+ *               are the src_off list, off_dev[n_chunks] the packed size;
+ *   dst_tok_dev dev i32 [n_chunks]    i * chunk_tokens.
+ * Fractions as for kv_bits_from_scores (else KV_EINVAL); n_chunks <= 65536 (else
+ * KV_ESHAPE).  The packed pool must hold the worst case, n_chunks records of 8
+ * bits, since the host does not learn the packed size before it enqueues the
+ * compression. */
+int32_t kv_plan_chunks_dev(const kv_shape_t* shape, const float* density_dev,
+                           int32_t num8, int32_t num4, int32_t den,
+                           uint8_t* bits_dev, uint64_t* off_dev, int32_t* dst_tok_dev,
+                           void* stream);
+
 /* Quantise and bit-pack every chunk at its bit-width (Sec. 3.2 "Compressing
  * chunks"; Sec. 4 bit-shift packing).
  *   kv dev fp16 cache (read only); bits_dev dev u8 [n_chunks];

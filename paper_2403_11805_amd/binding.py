@@ -80,6 +80,7 @@ _SIGNATURES = {
     "kv_score_chunks": (_i32, [_vp, _vp, _i32, _vp, _i32, _vp, _u64, _vp, _vp, _vp]),
     "kv_compress_chunks": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp]),
     "kv_swapin_chunks": (_i32, [_vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp]),
+    "kv_plan_chunks_dev": (_i32, [_vp, _vp, _i32, _i32, _i32, _vp, _vp, _vp, _vp]),
     "kv_swapin_pinned": (_i32, [_vp, _vp, _vp, _vp, _vp, _i32, _vp, _u64, _i32, _vp, _vp, _vp]),
     "kv_swapout_aot": (_i32, [_vp, _vp, _u64, _u64, _vp, _vp]),
     "kv_recompute_create": (_vp, []),
@@ -337,6 +338,18 @@ def kv_compress_chunks(shape: Shape, kv: torch.Tensor, bits_dev: torch.Tensor,
     _check(lib().kv_compress_chunks(ctypes.byref(s), _dev(kv, shape.cache_dtype),
                                     _dev(bits_dev, torch.uint8), _dev(off_dev, torch.int64),
                                     _dev(packed_out, torch.uint8), _stream(stream)))
+
+
+def kv_plan_chunks_dev(shape: Shape, density_dev: torch.Tensor, num8: int, num4: int, den: int,
+                       bits_dev: torch.Tensor, off_dev: torch.Tensor, dst_tok_dev: torch.Tensor,
+                       stream=None) -> None:
+    s = shape.c()
+    n = shape.n_chunks
+    if density_dev.numel() != n or bits_dev.numel() != n or dst_tok_dev.numel() != n or off_dev.numel() != n + 1:
+        raise ValueError("need density/bits/dst_tok of n_chunks entries and off of n_chunks + 1")
+    _check(lib().kv_plan_chunks_dev(ctypes.byref(s), _dev(density_dev, torch.float32), num8, num4, den,
+                                    _dev(bits_dev, torch.uint8), _dev(off_dev, torch.int64),
+                                    _dev(dst_tok_dev, torch.int32), _stream(stream)))
 
 
 def kv_swapin_chunks(shape: Shape, packed: torch.Tensor, src_off_dev: torch.Tensor,

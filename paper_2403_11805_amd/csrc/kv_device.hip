@@ -10,6 +10,7 @@
 #include "kv_internal.h"
 #include "kv_quant_kernels.hpp"
 #include "kv_quant_i8_kernels.hpp"
+#include "kv_plan_kernels.hpp"
 #include "kv_score_kernels.hpp"
 
 using namespace kvs;
@@ -304,6 +305,42 @@ int32_t kv_score_chunks(const kv_shape_t* shape, const void* q, int32_t n_querie
     hipLaunchKernelGGL(score_density_kernel, dim3((n_chunks + 63) / 64), dim3(1024), 0, st,
                        chunk_mass, density, g.L * g.Hq, n_chunks, inv_norm);
     return launch_status("score_density_kernel launch");
+}
+
+// --------------------------------------------------------------------- widths and offsets on the device
+
+int32_t kv_plan_chunks_dev(const kv_shape_t* shape, const float* density_dev, int32_t num8,
+                           int32_t num4, int32_t den, uint8_t* bits_dev, uint64_t* off_dev,
+                           int32_t* dst_tok_dev, void* stream) {
+    if (int rc = check_shape(shape)) return rc;
+    if (!density_dev || !bits_dev || !off_dev || !dst_tok_dev) return fail(KV_EINVAL, "NULL device pointer");
+    if (!aligned(density_dev, 4) || !aligned(off_dev, 8) || !aligned(dst_tok_dev, 4))
+        return fail(KV_EINVAL, "density_dev/dst_tok_dev must be 4-byte aligned, off_dev 8-byte aligned");
+    if (den <= 0 || num8 < 0 || num4 < 0 || num8 + num4 > den)
+        return fail(KV_EINVAL, "need den > 0, 0 <= num8, 0 <= num4, num8+num4 <= den");
+    const int32_t n = shape->n_tokens / shape->chunk_tokens;
+    if (n > 65536) return fail(KV_ESHAPE, "device planning handles at most 65536 chunks, not %d", n);
+    const int k8 = static_cast<int>(static_cast<int64_t>(n) * num8 / den);
+    const int k84 = static_cast<int>(static_cast<int64_t>(n) * (num8 + num4) / den);
+    RecordBytes rec;
+    const bool i8 = shape->format == KV_FMT_I8_CHANNELS;
+    rec.w16 = i8 ? 0 : kv_record_bytes(shape, 16);
+    rec.w8 = kv_record_bytes(shape, 8);
+    rec.w4 = kv_record_bytes(shape, 4);
+    rec.w2 = kv_record_bytes(shape, 2);
+    rec.w1 = i8 ? kv_record_bytes(shape, 1) : 0;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (n <= kPlanScanThreads) {
+        hipLaunchKernelGGL(plan_small_kernel, dim3(1), dim3(kPlanScanThreads), 0, st, density_dev, n, k8, k84,
+                           shape->chunk_tokens, rec, bits_dev, off_dev, dst_tok_dev);
+        return launch_status("plan_small_kernel launch");
+    }
+    hipLaunchKernelGGL(plan_bits_kernel, dim3((n + kPlanRankThreads - 1) / kPlanRankThreads),
+                       dim3(kPlanRankThreads), 0, st, density_dev, n, k8, k84, shape->chunk_tokens,
+                       bits_dev, dst_tok_dev);
+    if (int rc = launch_status("plan_bits_kernel launch")) return rc;
+    hipLaunchKernelGGL(plan_offsets_kernel, dim3(1), dim3(kPlanScanThreads), 0, st, bits_dev, n, rec, off_dev);
+    return launch_status("plan_offsets_kernel launch");
 }
 
 // --------------------------------------------------------------------- streaming Load / AoT swap-out

@@ -160,6 +160,13 @@ def test_device_entry_points_validate_before_touching_the_gpu():
     assert L.kv_swapout_aot(None, None, 0, 0, None, None) == binding.KV_EINVAL
     bad = kvs.Shape(2, 4, 4, 64, 500, 16, 64).c()
     assert L.kv_compress_chunks(ctypes.byref(bad), None, None, None, None, None) == binding.KV_ESHAPE
+    assert L.kv_plan_chunks_dev(ctypes.byref(s), None, 1, 1, 3, None, None, None, None) == binding.KV_EINVAL
+    assert L.kv_plan_chunks_dev(ctypes.byref(bad), None, 1, 1, 3, None, None, None, None) == binding.KV_ESHAPE
+    fake = ctypes.c_void_p(4096)         # never dereferenced: the fractions are refused first
+    for fr in ((1, 1, 0), (-1, 1, 3), (1, -1, 3), (2, 2, 3)):
+        assert L.kv_plan_chunks_dev(ctypes.byref(s), fake, *fr, fake, fake, fake, None) == binding.KV_EINVAL
+    many = kvs.Shape(1, 1, 1, 64, 8 * 65537, 8, 64).c()
+    assert L.kv_plan_chunks_dev(ctypes.byref(many), fake, 1, 1, 3, fake, fake, fake, None) == binding.KV_ESHAPE
 
 
 def replay(ops):
