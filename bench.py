@@ -76,8 +76,9 @@ class Path:
         self.lists_host = torch.empty(g.n_chunks * 32 + 64, dtype=torch.uint8).pin_memory()
         self.lists_dev = torch.empty_like(self.lists_host, device=dev)
         self.all_chunks = np.arange(g.n_chunks, dtype=np.int32)
-        self.ev = {k: (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-                   for k in ("score", "plan", "compress", "swapin")}
+        # one set of events per step in flight, read back after the timed region
+        self.ev_sets = [self._event_set()]
+        self.ev = self.ev_sets[0]
         self.packed_bytes = 0
         self.bits = None
         # widths, offsets and the gather list of the whole cache stay on the device when the
@@ -88,6 +89,16 @@ class Path:
             self.bits_d = torch.empty(n, dtype=torch.uint8, device=dev)
             self.off_d = torch.empty(n + 1, dtype=torch.int64, device=dev)
             self.dst_d = torch.empty(n, dtype=torch.int32, device=dev)
+
+    @staticmethod
+    def _event_set():
+        return {k: (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+                for k in ("score", "plan", "compress", "swapin")}
+
+    def reserve_event_sets(self, n):
+        """Steps numbered modulo n record into event sets of their own (kernel_ms(i) reads them later)."""
+        while len(self.ev_sets) < n:
+            self.ev_sets.append(self._event_set())
 
     def _upload_lists(self, bits, off, src, dst, sb):
         """One pinned staging buffer, one async copy: bits | off | src_off | dst_tok | sel_bits."""
@@ -112,6 +123,7 @@ class Path:
     def step(self):
         s = self.shape
         k = self.step_no % self.n_sets
+        self.ev = self.ev_sets[self.step_no % len(self.ev_sets)]
         self.step_no += 1
         self.kv, self.packed, self.kv_out = self.kv_sets[k], self.packed_sets[k], self.out_sets[k]
         if self.device_plan:
@@ -153,8 +165,9 @@ class Path:
         self.packed_bytes = int(off[-1])
         self.bits = bits
 
-    def kernel_ms(self):
-        return {k: a.elapsed_time(b) for k, (a, b) in self.ev.items()
+    def kernel_ms(self, step=None):
+        ev = self.ev if step is None else self.ev_sets[step % len(self.ev_sets)]
+        return {k: a.elapsed_time(b) for k, (a, b) in ev.items()
                 if (k != "score" or self.R) and (k != "plan" or self.device_plan)}
 
     def fetch_plan(self):
@@ -624,16 +637,21 @@ def main():
     for _ in range(args.warmup):
         path.step()
         torch.cuda.synchronize()
-    sums = {}
+    # the K timed steps are enqueued back to back (the host-plan route synchronises inside each
+    # step to read the densities); the per-kernel events are read after the timed region
+    path.reserve_event_sets(args.steps)
+    torch.cuda.synchronize()
+    first = path.step_no
     t0 = time.perf_counter()
     for _ in range(args.steps):
         path.step()
-        torch.cuda.synchronize()
-        for k, v in path.kernel_ms().items():
-            sums.setdefault(k, []).append(v)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall / args.steps * 1e3
+    sums = {}
+    for i in range(args.steps):
+        for k, v in path.kernel_ms(first + i).items():
+            sums.setdefault(k, []).append(v)
 
     path.fetch_plan()
     cache_bytes = g.elements * 2
