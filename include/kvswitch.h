@@ -256,6 +256,18 @@ int32_t kv_swapin_chunks(const kv_shape_t* shape, const void* packed,
                          const uint8_t* sel_bits_dev, int32_t n_sel,
                          void* kv_out, void* stream);
 
+/* The Load primitive in one call (Sec. 3.1 primitive 3; the Fault primitive with
+ * n_sel == 1): kv_build_gather + kv_swapin_chunks with the gather list carried in
+ * the kernel arguments (up to 64 records per launch), so no list is uploaded and
+ * no device list buffers are needed; the shortest route for a few chunks.
+ *   packed dev pool; off HOST u64 [n_chunks+1]; bits HOST u8 [n_chunks];
+ *   chunk_idx HOST i32 [n_sel], strictly ascending (else KV_EINDEX); kv_out dev
+ *   cache.  The whole list is checked before the first launch; n_sel == 0 is a
+ *   no-op.  The host arrays may be reused as soon as the call returns. */
+int32_t kv_load_chunks(const kv_shape_t* shape, const void* packed, const uint64_t* off,
+                       const uint8_t* bits, const int32_t* chunk_idx, int32_t n_sel,
+                       void* kv_out, void* stream);
+
 /* Streaming Load from pinned host memory: the IO half of the swapping-
  * recompute pipeline (Sec. 3.3), with the dequantise kernel in the place of
  * the recompute stage.  The listed records are copied host->device in batches

@@ -80,6 +80,7 @@ _SIGNATURES = {
     "kv_score_chunks": (_i32, [_vp, _vp, _i32, _vp, _i32, _vp, _u64, _vp, _vp, _vp]),
     "kv_compress_chunks": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp]),
     "kv_swapin_chunks": (_i32, [_vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp]),
+    "kv_load_chunks": (_i32, [_vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp]),
     "kv_plan_chunks_dev": (_i32, [_vp, _vp, _i32, _i32, _i32, _vp, _vp, _vp, _vp]),
     "kv_swapin_pinned": (_i32, [_vp, _vp, _vp, _vp, _vp, _i32, _vp, _u64, _i32, _vp, _vp, _vp]),
     "kv_swapout_aot": (_i32, [_vp, _vp, _u64, _u64, _vp, _vp]),
@@ -367,6 +368,19 @@ def kv_swapin_chunks(shape: Shape, packed: torch.Tensor, src_off_dev: torch.Tens
                                   _dev(src_off_dev, torch.int64), _dev(dst_tok_dev, torch.int32),
                                   _dev(sel_bits_dev, torch.uint8), n_sel,
                                   _dev(kv_out, shape.cache_dtype), _stream(stream)))
+
+
+def kv_load_chunks(shape: Shape, packed: torch.Tensor, off, bits, chunk_idx, kv_out: torch.Tensor,
+                   stream=None) -> None:
+    s = shape.c()
+    off, bits, chunk_idx = _np(off, np.uint64), _np(bits, np.uint8), _np(chunk_idx, np.int32)
+    if len(off) != shape.n_chunks + 1 or len(bits) != shape.n_chunks:
+        raise ValueError("need off of n_chunks + 1 entries and bits of n_chunks entries")
+    if tuple(kv_out.shape) != shape.kv_dims:
+        raise ValueError("kv_out must be [L][2][Hkv][N][D]")
+    _check(lib().kv_load_chunks(ctypes.byref(s), _dev(packed, torch.uint8), _hp(off), _hp(bits),
+                                _hp(chunk_idx), len(chunk_idx), _dev(kv_out, shape.cache_dtype),
+                                _stream(stream)))
 
 
 def kv_swapin_pinned(shape: Shape, packed_pinned: torch.Tensor, src_off, dst_tok, sel_bits,

@@ -120,6 +120,23 @@ int launch_status(const char* what) {
     return KV_OK;
 }
 
+// One launch of the Load kernel whose (short) gather list travels in the kernel
+// arguments; offsets in the list are relative to `base`.
+int launch_swapin_batch(const kv_shape_t& shape, const QuantGeom& g, int ppl, const uint8_t* base,
+                        const SwapinBatch& list, u4_t* dst, hipStream_t st) {
+    const dim3 grid = task_grid(g, list.n);
+    if (shape.format == KV_FMT_I8_CHANNELS) {
+        const I8View v = i8_view(shape);
+#define KV_LAUNCH_I8(NDW, GPL) \
+        hipLaunchKernelGGL((swapin_i8_batch_kernel<NDW, GPL>), grid, dim3(256), 0, st, base, list, dst, g, v)
+        KV_I8_DISPATCH(ppl, shape.head_dim, KV_LAUNCH_I8);
+#undef KV_LAUNCH_I8
+    } else if (ppl == 4) hipLaunchKernelGGL(swapin_batch_kernel<4>, grid, dim3(256), 0, st, base, list, dst, g);
+    else if (ppl == 2) hipLaunchKernelGGL(swapin_batch_kernel<2>, grid, dim3(256), 0, st, base, list, dst, g);
+    else hipLaunchKernelGGL(swapin_batch_kernel<1>, grid, dim3(256), 0, st, base, list, dst, g);
+    return launch_status("swapin_batch_kernel launch");
+}
+
 }  // namespace
 
 extern "C" {
@@ -307,6 +324,46 @@ int32_t kv_score_chunks(const kv_shape_t* shape, const void* q, int32_t n_querie
     return launch_status("score_density_kernel launch");
 }
 
+int32_t kv_load_chunks(const kv_shape_t* shape, const void* packed, const uint64_t* off,
+                       const uint8_t* bits, const int32_t* chunk_idx, int32_t n_sel, void* kv_out,
+                       void* stream) {
+    if (int rc = check_shape(shape)) return rc;
+    const int32_t n_chunks = shape->n_tokens / shape->chunk_tokens;
+    if (n_sel < 0 || n_sel > n_chunks) return fail(KV_EINVAL, "n_sel %d outside [0,%d]", n_sel, n_chunks);
+    if (n_sel == 0) return KV_OK;
+    if (!packed || !off || !bits || !chunk_idx || !kv_out) return fail(KV_EINVAL, "NULL pointer");
+    if (!aligned(packed, 16) || !aligned(kv_out, 16))
+        return fail(KV_EINVAL, "packed/kv_out must be 16-byte aligned");
+    // the whole list is checked before the first launch
+    std::vector<uint64_t> src_off(static_cast<size_t>(n_sel));
+    std::vector<int32_t> dst_tok(static_cast<size_t>(n_sel));
+    std::vector<uint8_t> sel_bits(static_cast<size_t>(n_sel));
+    if (int rc = kv_build_gather(shape, off, bits, chunk_idx, n_sel, src_off.data(), dst_tok.data(),
+                                 sel_bits.data()))
+        return rc;
+    for (int32_t j = 0; j < n_sel; ++j)
+        if (src_off[static_cast<size_t>(j)] % 16) return fail(KV_EINVAL, "record offset of chunk %d not 16-byte aligned", chunk_idx[j]);
+    const bool i8 = shape->format == KV_FMT_I8_CHANNELS;
+    int ppl = 0;
+    QuantGeom g = i8 ? quant_geom_i8(*shape, &ppl) : quant_geom(*shape);
+    if (!i8) ppl = plan_tasks(&g, kSwapinPiecesPerLane);
+    if (g.slabs > 65535) return fail(KV_ESHAPE, "more than 65535 slabs exceed the launch grid");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    for (int32_t j = 0; j < n_sel; j += kBatchMax) {
+        SwapinBatch list;
+        list.n = std::min<int32_t>(kBatchMax, n_sel - j);
+        for (int32_t k = 0; k < list.n; ++k) {
+            list.src_off[k] = src_off[static_cast<size_t>(j + k)];
+            list.dst_tok[k] = dst_tok[static_cast<size_t>(j + k)];
+            list.bits[k] = sel_bits[static_cast<size_t>(j + k)];
+        }
+        if (int rc = launch_swapin_batch(*shape, g, ppl, static_cast<const uint8_t*>(packed), list,
+                                         static_cast<u4_t*>(kv_out), st))
+            return rc;
+    }
+    return KV_OK;
+}
+
 // --------------------------------------------------------------------- widths and offsets on the device
 
 int32_t kv_plan_chunks_dev(const kv_shape_t* shape, const float* density_dev, int32_t num8,
@@ -448,18 +505,7 @@ int32_t kv_swapin_pinned(const kv_shape_t* shape, const void* packed_pinned, con
         hipError_t e = hipEventRecord(copied[b], cs);
         if (e == hipSuccess) e = hipStreamWaitEvent(ks, copied[b], 0);
         if (e != hipSuccess) { rc = hip_fail(e, "event record/wait"); break; }
-        const dim3 grid = task_grid(g, list.n);
-        u4_t* dst = static_cast<u4_t*>(kv_out);
-        if (i8) {
-            const I8View v = i8_view(*shape);
-#define KV_LAUNCH_I8(NDW, GPL) \
-            hipLaunchKernelGGL((swapin_i8_batch_kernel<NDW, GPL>), grid, dim3(256), 0, ks, slot_dev, list, dst, g, v)
-            KV_I8_DISPATCH(ppl, shape->head_dim, KV_LAUNCH_I8);
-#undef KV_LAUNCH_I8
-        } else if (ppl == 4) hipLaunchKernelGGL(swapin_batch_kernel<4>, grid, dim3(256), 0, ks, slot_dev, list, dst, g);
-        else if (ppl == 2) hipLaunchKernelGGL(swapin_batch_kernel<2>, grid, dim3(256), 0, ks, slot_dev, list, dst, g);
-        else hipLaunchKernelGGL(swapin_batch_kernel<1>, grid, dim3(256), 0, ks, slot_dev, list, dst, g);
-        rc = launch_status("swapin_batch_kernel launch");
+        rc = launch_swapin_batch(*shape, g, ppl, slot_dev, list, static_cast<u4_t*>(kv_out), ks);
         if (rc != KV_OK) break;
         e = hipEventRecord(consumed[b], ks);
         if (e != hipSuccess) { rc = hip_fail(e, "hipEventRecord"); break; }

@@ -165,6 +165,13 @@ def test_device_entry_points_validate_before_touching_the_gpu():
     fake = ctypes.c_void_p(4096)         # never dereferenced: the fractions are refused first
     for fr in ((1, 1, 0), (-1, 1, 3), (1, -1, 3), (2, 2, 3)):
         assert L.kv_plan_chunks_dev(ctypes.byref(s), fake, *fr, fake, fake, fake, None) == binding.KV_EINVAL
+    assert L.kv_load_chunks(ctypes.byref(s), None, None, None, None, 3, None, None) == binding.KV_EINVAL
+    assert L.kv_load_chunks(ctypes.byref(s), None, None, None, None, 0, None, None) == binding.KV_OK
+    off = (ctypes.c_uint64 * 33)(*range(0, 33 * 4096, 4096))
+    b8 = (ctypes.c_uint8 * 32)(*([8] * 32))
+    for idx in ((2, 1), (5, 5), (0, 32)):                 # refused on the host: nothing is launched
+        ci = (ctypes.c_int32 * 2)(*idx)
+        assert L.kv_load_chunks(ctypes.byref(s), fake, off, b8, ci, 2, fake, None) == binding.KV_EINDEX
     many = kvs.Shape(1, 1, 1, 64, 8 * 65537, 8, 64).c()
     assert L.kv_plan_chunks_dev(ctypes.byref(many), fake, 1, 1, 3, fake, fake, fake, None) == binding.KV_ESHAPE
 
