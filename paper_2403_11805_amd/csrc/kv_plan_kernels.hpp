@@ -77,27 +77,32 @@ __global__ __launch_bounds__(kPlanScanThreads) void plan_offsets_kernel(
     if (tid == kPlanScanThreads - 1) off[n] = part[tid];
 }
 
-// Both steps in one workgroup for up to kPlanScanThreads chunks (one chunk per thread):
-// a single launch between scoring and compression.
+// Both steps in one workgroup for up to kPlanScanThreads chunks (one chunk per thread,
+// launched with n rounded up to whole wavefronts): a single launch between scoring and
+// compression.
 __global__ __launch_bounds__(kPlanScanThreads) void plan_small_kernel(
     const float* __restrict__ density, int n, int k8, int k84, int chunk_tokens, RecordBytes rec,
     uint8_t* __restrict__ bits, uint64_t* __restrict__ off, int32_t* __restrict__ dst_tok) {
-    __shared__ float dens[kPlanScanThreads];
+    __shared__ __attribute__((aligned(16))) float dens[kPlanScanThreads];
     __shared__ uint64_t part[kPlanScanThreads];
     const int i = threadIdx.x;
+    const int width = blockDim.x;
     const float di = density[i < n ? i : n - 1];
-    dens[i] = di;
+    dens[i] = i < n ? di : -__builtin_inff();          // padding never comes before a chunk
     __syncthreads();
     int rank = 0;
-    for (int j = 0; j < n; ++j) {
-        const float dj = dens[j];
-        rank += (dj > di || (!(di > dj) && j < i)) ? 1 : 0;
+    for (int j = 0; j < width; j += 4) {
+        const float4 d4 = *reinterpret_cast<const float4*>(dens + j);
+        rank += (d4.x > di || (!(di > d4.x) && j + 0 < i)) ? 1 : 0;
+        rank += (d4.y > di || (!(di > d4.y) && j + 1 < i)) ? 1 : 0;
+        rank += (d4.z > di || (!(di > d4.z) && j + 2 < i)) ? 1 : 0;
+        rank += (d4.w > di || (!(di > d4.w) && j + 3 < i)) ? 1 : 0;
     }
     const int b = rank < k8 ? 8 : (rank < k84 ? 4 : 2);
     const uint64_t own = i < n ? rec.of(b) : 0;
     part[i] = own;
     __syncthreads();
-    for (int d = 1; d < kPlanScanThreads; d <<= 1) {
+    for (int d = 1; d < width; d <<= 1) {
         const uint64_t add = i >= d ? part[i - d] : 0;
         __syncthreads();
         part[i] += add;
