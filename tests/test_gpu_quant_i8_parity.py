@@ -179,3 +179,12 @@ def test_streaming_from_pinned_host_equals_resident_path():
     want = oracle.compress_chunks_i8(os_, kv.numpy(), bits, off)
     oracle.swapin_chunks_i8(os_, want, *oracle.build_gather(os_, off, bits, idx), ref)
     assert np.array_equal(out.cpu().numpy(), ref)
+
+
+def test_more_chunks_than_a_grid_dimension():
+    """70 000 chunks of the int8 format (the second grid dimension holds at most 65 535)."""
+    g = synth.Geometry(1, 1, 1, 64, 16 * 70000, 16, 64)
+    kv = synth.make_kv_i8(g, 22, "cpu").numpy()
+    bits = synth.draw_bits_uniform(g.n_chunks, 22, widths=(8, 4, 2, 1)).numpy()
+    check_full(g, kv, bits)
+    check_full(g, kv, bits, select=[1, 65535, 65536, 69998])

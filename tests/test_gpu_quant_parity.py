@@ -211,3 +211,14 @@ def test_determinism():
     a, _ = gpu_compress(ks, kv_dev, bits)
     b, _ = gpu_compress(ks, kv_dev, bits)
     assert torch.equal(a, b)
+
+
+def test_more_chunks_than_a_grid_dimension():
+    """70 000 chunks: the launch grid cannot carry the chunk index in its second dimension
+    (limit 65 535), so compression walks the chunks of one slab instead.  Bit-exact records
+    and cache for every chunk, and for a subset that starts beyond chunk 65 535."""
+    g = synth.Geometry(1, 1, 1, 64, 8 * 70000, 8, 64)
+    kv = synth.make_kv(g, 21, "cpu", 1, 10.0).numpy()
+    bits = synth.draw_bits_uniform(g.n_chunks, 21, widths=(16, 8, 4, 2)).numpy()
+    check_full(g, kv, bits)
+    check_full(g, kv, bits, select=[0, 65535, 65536, 69999])
