@@ -120,12 +120,21 @@ class Path:
         return (cut("bits", torch.uint8), cut("off", torch.int64), cut("src", torch.int64),
                 cut("dst", torch.int32), cut("sb", torch.uint8))
 
-    def step(self):
+    def step(self, record_events=True):
         s = self.shape
         k = self.step_no % self.n_sets
         self.ev = self.ev_sets[self.step_no % len(self.ev_sets)]
         self.step_no += 1
         self.kv, self.packed, self.kv_out = self.kv_sets[k], self.packed_sets[k], self.out_sets[k]
+        if self.device_plan and not record_events:
+            n = self.g.n_chunks
+            kvs.kv_score_chunks(s, self.q, self.kv, kvs.KV_NORM_VISIBLE, self.ws, self.chunk_mass,
+                                self.density)
+            kvs.kv_plan_chunks_dev(s, self.density, *FRACTIONS[self.wl.bits_rule], self.bits_d, self.off_d,
+                                   self.dst_d)
+            kvs.kv_compress_chunks(s, self.kv, self.bits_d, self.off_d, self.packed)
+            kvs.kv_swapin_chunks(s, self.packed, self.off_d[:n], self.dst_d, self.bits_d, self.kv_out)
+            return
         if self.device_plan:
             n = self.g.n_chunks
             self.ev["score"][0].record()
@@ -176,6 +185,31 @@ class Path:
             torch.cuda.synchronize()
             self.bits = self.bits_d.cpu().numpy()
             self.packed_bytes = int(self.off_d[-1])
+
+
+def graph_ms_per_step(path, args):
+    """The device-planned step captured in a HIP graph (one per rotating buffer set) and replayed
+    K times between two synchronisations.  The path records no events while capturing."""
+    side = torch.cuda.Stream()
+    graphs = []
+    saved, path.ev_sets = path.ev_sets, [None]
+    try:
+        for k in range(path.n_sets):
+            path.step_no = k
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=side):
+                path.step(record_events=False)
+            graphs.append(graph)
+    finally:
+        path.ev_sets = saved
+    for i in range(args.warmup):
+        graphs[i % len(graphs)].replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        graphs[i % len(graphs)].replay()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / args.steps * 1e3
 
 
 def cpu_baseline(path, budget_s=20.0):
@@ -581,6 +615,8 @@ def main():
     ap.add_argument("--stream-slot-mib", type=int, default=64)
     ap.add_argument("--re-us-per-chunk", type=float, default=50.0,
                     help="streaming workload: assumed recompute cost per chunk for the Eq. 4 plan example")
+    ap.add_argument("--graph", action="store_true",
+                    help="additionally time the device-planned step replayed from a HIP graph")
     ap.add_argument("--host-plan", action="store_true",
                     help="widths, offsets and gather list on the host between scoring and compression "
                          "(default: on the device, no host round trip)")
@@ -691,6 +727,9 @@ def main():
     }
     if plan_ms is not None:
         out["plan_ms"] = round(float(np.mean(plan_ms)), 4)
+    if args.graph and path.device_plan:
+        out["hip_graph"] = {"ms_per_step": round(graph_ms_per_step(path, args), 4),
+                            "note": "the same step captured once per buffer set and replayed; no events inside"}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(path)
     print(json.dumps(out))

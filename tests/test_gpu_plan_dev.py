@@ -118,3 +118,55 @@ def test_switch_without_host_round_trip():
     assert torch.equal(packed[:total], ref_packed[:total])
     ref_out = gpu_swapin(ks, ref_packed, off, bits, np.arange(n, dtype=np.int32), torch.zeros_like(kv))
     assert torch.equal(out.view(torch.int16), ref_out.view(torch.int16))
+
+
+def test_switch_replayed_from_a_hip_graph():
+    """The device path allocates nothing, clears nothing and never synchronises, so a whole
+    switch (score, plan, compress, swap-in) can be captured once and replayed.  Every replay,
+    with the inputs changed and eager work in between, must equal the eager result."""
+    g = synth.Geometry(2, 2, 4, 128, 1024, 16, 64)
+    ks, _ = both_shapes(g)
+    n = ks.n_chunks
+    kv = synth.make_kv(g, 5).to(DEV)
+    q = synth.make_q(g, 5, 32).to(DEV)
+    ws = torch.empty(kvs.kv_score_workspace_bytes(ks, 32), dtype=torch.uint8, device=DEV)
+    cm = torch.empty((g.L, g.Hq, n), dtype=torch.float32, device=DEV)
+    dens = torch.empty(n, dtype=torch.float32, device=DEV)
+    bits_d = torch.empty(n, dtype=torch.uint8, device=DEV)
+    off_d = torch.empty(n + 1, dtype=torch.int64, device=DEV)
+    dst_d = torch.empty(n, dtype=torch.int32, device=DEV)
+    packed = torch.zeros(kvs.kv_record_bytes(ks, 8) * n, dtype=torch.uint8, device=DEV)
+    out = torch.zeros_like(kv)
+
+    def switch():
+        kvs.kv_score_chunks(ks, q, kv, kvs.KV_NORM_VISIBLE, ws, cm, dens)
+        kvs.kv_plan_chunks_dev(ks, dens, 1, 1, 3, bits_d, off_d, dst_d)
+        kvs.kv_compress_chunks(ks, kv, bits_d, off_d, packed)
+        kvs.kv_swapin_chunks(ks, packed, off_d[:n], dst_d, bits_d, out)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        switch()                                    # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        switch()
+    for rep in range(4):
+        kv.copy_(synth.make_kv(g, 50 + rep).to(DEV))        # new cache and queries for this replay
+        q.copy_(synth.make_q(g, 50 + rep, 32).to(DEV))
+        for t in (dens, bits_d, off_d, dst_d, packed, out):
+            t.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [t.clone() for t in (dens, bits_d, off_d, dst_d, packed, out)]
+        for t in (dens, bits_d, off_d, dst_d, packed, out):
+            t.zero_()
+        switch()                                    # the same switch, eagerly
+        torch.cuda.synchronize()
+        for a, b, name in zip(got, (dens, bits_d, off_d, dst_d, packed, out),
+                              ("density", "bits", "offsets", "dst_tok", "pool", "cache")):
+            assert torch.equal(a.view(torch.uint8), b.view(torch.uint8)), f"replay {rep}: {name} differs"
+        assert int(off_d[n]) > 0 and bool(out.any())
