@@ -50,7 +50,8 @@ class Shape:
     N: int
     T: int
     G: int
-    fmt: int = 0    # 0: fp16 cache, groups of G along head_dim; 1: int8 cache, channel-wise
+    fmt: int = 0    # 0: fp16 cache, groups of G along head_dim; 1: int8 cache, channel-wise;
+                    # 2: as 1 with binary16 parameters
 
     @property
     def n_chunks(self) -> int:
@@ -203,7 +204,7 @@ def swapin_chunks(shape: Shape, packed: np.ndarray, src_off, dst_tok, sel_bits,
 def compress_chunks_i8(shape: Shape, kv, bits: np.ndarray, off: np.ndarray) -> np.ndarray:
     """Channel-wise quantise + pack of an int8 cache (format 1) -> uint8 pool."""
     kv = np.ascontiguousarray(kv, dtype=np.int8)
-    assert shape.fmt == 1 and kv.shape == (shape.L, 2, shape.Hkv, shape.N, shape.D)
+    assert shape.fmt in (1, 2) and kv.shape == (shape.L, 2, shape.Hkv, shape.N, shape.D)
     bits = np.ascontiguousarray(bits, dtype=np.uint8)
     off = np.ascontiguousarray(off, dtype=np.uint64)
     assert bits.shape == (shape.n_chunks,) and off.shape == (shape.n_chunks + 1,)
@@ -220,7 +221,7 @@ def swapin_chunks_i8(shape: Shape, packed, src_off, dst_tok, sel_bits, kv_out: n
     src_off = np.ascontiguousarray(src_off, dtype=np.uint64)
     dst_tok = np.ascontiguousarray(dst_tok, dtype=np.int32)
     sel_bits = np.ascontiguousarray(sel_bits, dtype=np.uint8)
-    assert shape.fmt == 1 and kv_out.flags["C_CONTIGUOUS"] and kv_out.dtype == np.int8
+    assert shape.fmt in (1, 2) and kv_out.flags["C_CONTIGUOUS"] and kv_out.dtype == np.int8
     assert kv_out.shape == (shape.L, 2, shape.Hkv, shape.N, shape.D)
     cs = shape.c()
     rc = lib().orc_swapin_chunks_i8(ctypes.byref(cs), _p(packed), _p(src_off), _p(dst_tok),

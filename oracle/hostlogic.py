@@ -17,14 +17,17 @@ VALID_BITS_I8 = (8, 4, 2, 1)
 def record_bytes(shape, bits: int) -> int:
     """Bytes of one chunk's packed record.  fp16 format: b < 16: every token row of
     every slab holds D*b/8 code bytes plus one fp32 scale and one fp32 minimum per
-    group of G elements; b = 16: the raw fp16 bytes.  int8 channel-wise format: b < 8:
-    T*D*b/8 code bytes per slab plus one scale and one minimum per channel; b = 8: raw."""
+    group of G elements; b = 16: the raw fp16 bytes.  int8 channel-wise formats: b < 8:
+    T*D*b/8 code bytes per slab plus one scale and one minimum per channel (fp32, or
+    binary16 in format 2); b = 8: raw."""
     slabs = shape.L * 2 * shape.Hkv
-    if getattr(shape, "fmt", 0) == 1:
+    fmt = getattr(shape, "fmt", 0)
+    if fmt in (1, 2):
         assert bits in VALID_BITS_I8
         if bits == 8:
             return slabs * shape.T * shape.D
-        return slabs * (shape.T * shape.D * bits // 8 + 8 * shape.D)
+        meta = 8 if fmt == 1 else 4            # fp32 or binary16 (scale, minimum) per channel
+        return slabs * (shape.T * shape.D * bits // 8 + meta * shape.D)
     assert bits in VALID_BITS
     if bits == 16:
         return slabs * shape.T * shape.D * 2

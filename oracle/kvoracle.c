@@ -28,7 +28,8 @@
 
 typedef struct {
     int32_t L, Hkv, Hq, D, N, T, G;
-    int32_t fmt;   /* 0: fp16 cache, groups of G along head_dim; 1: int8 cache, channel-wise */
+    int32_t fmt;   /* 0: fp16 cache, groups of G along head_dim; 1: int8 cache, channel-wise;
+                      2: as 1 with the parameters stored (and used) in binary16 */
 } orc_shape;
 
 int orc_threads(void)
@@ -199,9 +200,10 @@ int orc_score_chunks(const orc_shape* s, const uint16_t* q, int R, const uint16_
 uint64_t orc_record_bytes(const orc_shape* s, int bits)
 {
     const uint64_t slabs = (uint64_t)s->L * 2 * s->Hkv;
-    if (s->fmt == 1) {
+    if (s->fmt == 1 || s->fmt == 2) {
+        const uint64_t meta = s->fmt == 1 ? 8 : 4;      /* scale + minimum per channel */
         if (bits == 8) return slabs * s->T * s->D;
-        return slabs * ((uint64_t)s->T * s->D * bits / 8 + 8ull * s->D);
+        return slabs * ((uint64_t)s->T * s->D * bits / 8 + meta * s->D);
     }
     if (bits == 16) return slabs * s->T * s->D * 2;
     return slabs * s->T * ((uint64_t)s->D * bits / 8 + 8ull * (s->D / s->G));
@@ -307,6 +309,9 @@ int orc_compress_chunks(const orc_shape* s, const uint16_t* kv, const uint8_t* b
  *   code = scale == 0 ? 0 : clamp(rintf((x - mn) / scale), 0, 2^b - 1)   (binary32)
  * b in {4, 2, 1}; b = 8 copies the int8 bytes.  Record: codes [slab][T][D*b/8]
  * (lowest-index element in the least-significant bits), scale [slab][D], mn [slab][D].
+ * fmt 2 keeps the parameters in binary16: the scale is rounded to binary16 (nearest even)
+ * BEFORE the codes are computed, so that quantisation and reconstruction use the same
+ * value; mn is an integer in [-128, 127] and needs no rounding.
  */
 int orc_compress_chunks_i8(const orc_shape* s, const int8_t* kv, const uint8_t* bits,
                            const uint64_t* off, uint8_t* packed)
@@ -331,8 +336,12 @@ int orc_compress_chunks_i8(const orc_shape* s, const int8_t* kv, const uint8_t* 
             const int per_byte = 8 / b;
             const float levels = (float)((1 << b) - 1);
             uint8_t* codes = rec + (size_t)sl * s->T * row_bytes;
-            float* scale = (float*)(rec + (size_t)slabs * s->T * row_bytes) + (size_t)sl * s->D;
+            const int half = s->fmt == 2;
+            uint8_t* meta = rec + (size_t)slabs * s->T * row_bytes;
+            float* scale = (float*)meta + (size_t)sl * s->D;
             float* mn_out = scale + (size_t)slabs * s->D;
+            uint16_t* scale_h = (uint16_t*)meta + (size_t)sl * s->D;
+            uint16_t* mn_h = scale_h + (size_t)slabs * s->D;
             memset(codes, 0, (size_t)s->T * row_bytes);
             for (int d = 0; d < s->D; ++d) {
                 float mn = (float)src[d], mx = mn;
@@ -344,9 +353,15 @@ int orc_compress_chunks_i8(const orc_shape* s, const int8_t* kv, const uint8_t* 
                 mn = mn + 0.0f;
                 mx = mx + 0.0f;
                 const float range = mx - mn;
-                const float sc = range / levels;
-                scale[d] = sc;
-                mn_out[d] = mn;
+                float sc = range / levels;
+                if (half) {
+                    scale_h[d] = orc_float_to_half(sc);
+                    sc = orc_half_to_float(scale_h[d]);
+                    mn_h[d] = orc_float_to_half(mn);
+                } else {
+                    scale[d] = sc;
+                    mn_out[d] = mn;
+                }
                 for (int t = 0; t < s->T; ++t) {
                     float c = 0.0f;
                     if (sc != 0.0f) {
@@ -389,13 +404,19 @@ int orc_swapin_chunks_i8(const orc_shape* s, const uint8_t* packed, const uint64
             const int per_byte = 8 / b;
             const unsigned mask = (1u << b) - 1u;
             const uint8_t* codes = rec + (size_t)sl * s->T * row_bytes;
-            const float* scale = (const float*)(rec + (size_t)slabs * s->T * row_bytes) + (size_t)sl * s->D;
+            const int half = s->fmt == 2;
+            const uint8_t* meta = rec + (size_t)slabs * s->T * row_bytes;
+            const float* scale = (const float*)meta + (size_t)sl * s->D;
             const float* mn = scale + (size_t)slabs * s->D;
+            const uint16_t* scale_h = (const uint16_t*)meta + (size_t)sl * s->D;
+            const uint16_t* mn_h = scale_h + (size_t)slabs * s->D;
             for (int t = 0; t < s->T; ++t) {
                 for (int d = 0; d < s->D; ++d) {
                     const unsigned code = (codes[(size_t)t * row_bytes + d / per_byte] >> ((d % per_byte) * b)) & mask;
-                    const float prod = (float)code * scale[d];
-                    float v = rintf(prod + mn[d]);
+                    const float sc = half ? orc_half_to_float(scale_h[d]) : scale[d];
+                    const float m = half ? orc_half_to_float(mn_h[d]) : mn[d];
+                    const float prod = (float)code * sc;
+                    float v = rintf(prod + m);
                     if (v < -128.0f) v = -128.0f;
                     if (v > 127.0f) v = 127.0f;
                     dst[(size_t)t * s->D + d] = (int8_t)v;

@@ -171,3 +171,105 @@ def test_vectorised_float32_cross_check():
         assert np.array_equal(codes, ref.astype(np.uint8))
         deq = np.clip(np.rint(code.astype(np.float32) * scale + mn), -128, 127).astype(np.int8)
         assert np.array_equal(out.reshape(shape.slabs, shape.n_chunks, shape.T, shape.D)[:, i], deq)
+
+
+# ------------------------------------------------------------------ binary16 parameters (format 2)
+
+def sections_h(shape, rec, b):
+    n_codes = shape.slabs * shape.T * shape.D * b // 8
+    n_meta = shape.slabs * shape.D
+    assert len(rec) == n_codes + 4 * n_meta
+    codes = rec[:n_codes].reshape(shape.slabs, shape.T, shape.D * b // 8)
+    scale = rec[n_codes:n_codes + 2 * n_meta].view(np.float16).reshape(shape.slabs, shape.D)
+    mn = rec[n_codes + 2 * n_meta:].view(np.float16).reshape(shape.slabs, shape.D)
+    return codes, scale, mn
+
+
+def test_half_parameter_record_sizes_by_hand():
+    s = oracle.Shape(32, 32, 32, 128, 4096, 16, 64, 2)
+    assert oracle.record_bytes(s, 8) == 4194304
+    assert oracle.record_bytes(s, 4) == 2048 * (1024 + 4 * 128) == 3145728
+    assert oracle.record_bytes(s, 2) == 2048 * (512 + 512) == 2097152
+    assert oracle.record_bytes(s, 1) == 2048 * (256 + 512) == 1572864
+    bits = np.array([8, 4, 2, 1] * 64, dtype=np.uint8)
+    assert int(oracle.chunk_offsets(s, bits)[-1]) == 64 * (4194304 + 3145728 + 2097152 + 1572864)
+
+
+@pytest.mark.parametrize("b", [4, 2, 1])
+def test_half_parameters_equal_format_one_when_the_scale_is_a_half(b):
+    """A range that is a multiple of the level count gives an integer scale, exact in binary16:
+    codes and reconstruction must then equal those of the fp32-parameter format."""
+    rng = np.random.default_rng(40 + b)
+    levels = (1 << b) - 1
+    s1 = oracle.Shape(1, 2, 2, 64, 32, 16, 64, 1)
+    s2 = oracle.Shape(1, 2, 2, 64, 32, 16, 64, 2)
+    k = rng.integers(1, 255 // levels + 1, size=(1, 2, 2, 1, 64))                # the scale of a channel
+    base = rng.integers(-128, 128 - k * levels)
+    step = rng.integers(0, k * levels + 1, size=(1, 2, 2, 32, 64))
+    step[..., 0::16, :] = 0                                                      # both ends in every chunk
+    step[..., 1::16, :] = k * levels
+    kv = (base + step).astype(np.int8)
+    assert np.array_equal(kv.astype(np.int64), base + step)
+    bits = np.full(2, b, dtype=np.uint8)
+    o1, o2 = oracle.chunk_offsets(s1, bits), oracle.chunk_offsets(s2, bits)
+    p1, p2 = oracle.compress_chunks_i8(s1, kv, bits, o1), oracle.compress_chunks_i8(s2, kv, bits, o2)
+    for i in range(2):
+        c1, sc1, m1 = sections(s1, p1[int(o1[i]):int(o1[i + 1])], b)
+        c2, sc2, m2 = sections_h(s2, p2[int(o2[i]):int(o2[i + 1])], b)
+        assert np.array_equal(c1, c2)
+        assert np.array_equal(sc1, sc2.astype(np.float32)) and np.array_equal(m1, m2.astype(np.float32))
+        assert np.array_equal(sc1[0], k.reshape(4, 64)[0].astype(np.float32))
+    a, h = np.zeros(kv.shape, np.int8), np.zeros(kv.shape, np.int8)
+    oracle.swapin_chunks_i8(s1, p1, *oracle.build_gather(s1, o1, bits, [0, 1]), a)
+    oracle.swapin_chunks_i8(s2, p2, *oracle.build_gather(s2, o2, bits, [0, 1]), h)
+    assert np.array_equal(a, h)
+
+
+def test_half_parameters_vectorised_cross_check_and_error_bound():
+    """Independent numpy route: scale = binary16(float32 range / levels) (numpy's cast rounds to
+    nearest even), codes against that rounded scale, reconstruction from the stored halves; and
+    the error bound with the rounded scale: |x' - x| <= scale_h / 2 + 1/2."""
+    rng = np.random.default_rng(77)
+    shape = oracle.Shape(2, 2, 2, 128, 64, 16, 64, 2)
+    kv = np.clip(np.rint(rng.normal(size=(2, 2, 2, 64, 128)) * 25), -128, 127).astype(np.int8)
+    kv[..., 9] = -3                                              # a constant channel
+    kv[0, 0, 0, :16, 11] = np.arange(-128, 128, 16)              # widest range: 240
+    kv[0, 0, 0, 1, 11] = 127
+    bits = np.array([4, 2, 1, 8], dtype=np.uint8)
+    off = oracle.chunk_offsets(shape, bits)
+    packed = oracle.compress_chunks_i8(shape, kv, bits, off)
+    out = np.zeros(kv.shape, dtype=np.int8)
+    oracle.swapin_chunks_i8(shape, packed, *oracle.build_gather(shape, off, bits, [0, 1, 2, 3]), out)
+    x = kv.astype(np.float32).reshape(shape.slabs, shape.n_chunks, shape.T, shape.D)
+    y = out.reshape(x.shape)
+    assert np.array_equal(y[:, 3], kv.reshape(x.shape)[:, 3])     # 8 bits: pass-through
+    n_inexact = 0
+    for i in range(3):
+        b = int(bits[i])
+        levels = np.float32((1 << b) - 1)
+        xi = x[:, i]
+        mn = xi.min(axis=1, keepdims=True)
+        mx = xi.max(axis=1, keepdims=True)
+        exact = (mx - mn) / levels                                # float32
+        scale_h = exact.astype(np.float16)
+        scale = scale_h.astype(np.float32)
+        n_inexact += int((scale != exact).sum())
+        with np.errstate(divide="ignore", invalid="ignore"):
+            code = np.where(scale == 0, 0, np.clip(np.rint((xi - mn) / scale), 0, levels)).astype(np.uint32)
+        codes, s_got, m_got = sections_h(shape, packed[int(off[i]):int(off[i + 1])], b)
+        assert np.array_equal(s_got.view(np.uint16), scale_h[:, 0].view(np.uint16))
+        assert np.array_equal(m_got.astype(np.float32), mn[:, 0])
+        per = 8 // b
+        ref = np.zeros((shape.slabs, shape.T, shape.D // per), dtype=np.uint32)
+        for k in range(per):
+            ref |= code[..., k::per] << (k * b)
+        assert np.array_equal(codes, ref.astype(np.uint8))
+        deq = np.clip(np.rint(code.astype(np.float32) * scale + mn), -128, 127).astype(np.int8)
+        assert np.array_equal(y[:, i], deq)
+        # both ends of every non-constant channel keep their codes; error bound with the stored scale
+        assert np.all(code[np.arange(shape.slabs)[:, None], np.argmax(xi, axis=1), np.arange(shape.D)][scale[:, 0] > 0] == levels)
+        assert np.all(code[np.arange(shape.slabs)[:, None], np.argmin(xi, axis=1), np.arange(shape.D)] == 0)
+        err = np.abs(y[:, i].astype(np.float64) - xi.astype(np.float64))
+        assert np.all(err <= scale.astype(np.float64) / 2 + 0.5 + 1e-3)
+        assert np.all(y[:, i][..., 9] == -3)
+    assert n_inexact > 100, "the test must exercise scales that binary16 cannot hold exactly"
