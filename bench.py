@@ -467,7 +467,9 @@ def run_i8(wl, args, dev):
     8/4/2 by terciles of seeded scores, channel-wise parameters per slab.  A step is compress
     + swap-in of the whole cache (scoring reads fp16 keys and is not part of this variant)."""
     g = wl.geom
-    shape = kvs.Shape(g.L, g.Hkv, g.Hq, g.D, g.N, g.T, g.G, kvs.KV_FMT_I8_CHANNELS)
+    half = args.format == "i8h"
+    shape = kvs.Shape(g.L, g.Hkv, g.Hq, g.D, g.N, g.T, g.G,
+                      kvs.KV_FMT_I8_CHANNELS_H if half else kvs.KV_FMT_I8_CHANNELS)
     kv = synth.make_kv_i8(g, wl.seed, dev)
     out = torch.empty_like(kv)
     bits = kvs.kv_bits_from_scores(synth.draw_scores(g.n_chunks, wl.seed).numpy(), 1, 1, 3)
@@ -504,7 +506,7 @@ def run_i8(wl, args, dev):
         "value": round(cache_bytes / ms_per_step / 1e6, 2), "unit": "GB/s (int8 cache bytes)",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"{wl.name}, int8 channel-wise format: [L={g.L},K/V,Hkv={g.Hkv},N={g.N},D={g.D}] int8, "
+        "config": {"workload": f"{wl.name}, int8 channel-wise format ({'binary16' if half else 'fp32'} parameters): [L={g.L},K/V,Hkv={g.Hkv},N={g.N},D={g.D}] int8, "
                                f"chunk {g.T}, widths 8/4/2 by terciles of seeded scores",
                    "cache_bytes": cache_bytes, "packed_bytes": int(off[-1]), "step": "compress + swap-in"},
         "kernels": kernels,
@@ -602,8 +604,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="llama2-7b-4k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--format", choices=("f16", "i8"), default="f16",
-                    help="i8: the int8 channel-wise record format on the workload's geometry (compress + swap-in)")
+    ap.add_argument("--format", choices=("f16", "i8", "i8h"), default="f16",
+                    help="i8 / i8h: the int8 channel-wise record format with fp32 / binary16 parameters on the "
+                         "workload's geometry (compress + swap-in)")
     ap.add_argument("--sweep-chunk-tokens", action="store_true",
                     help="instead of the benchmark: compress / swap-in rates for chunk sizes 4..256")
     ap.add_argument("--recompute", action="store_true",
@@ -635,7 +638,7 @@ def main():
     if args.sweep_chunk_tokens:
         print(json.dumps(run_chunk_sweep(wl, args, dev)))
         return
-    if args.format == "i8":
+    if args.format in ("i8", "i8h"):
         print(json.dumps(run_i8(wl, args, dev)))
         return
     if args.recompute:

@@ -57,6 +57,14 @@
  *  Same arithmetic as below with x the int8 value as binary32; dequantisation
  *  gives int8(clamp(rint(fp32(code) * scale + mn), -128, 127)).
  *
+ *  KV_FMT_I8_CHANNELS_H (= 2) is format 1 with the parameters held in binary16:
+ *  at 16 tokens per chunk the two fp32 parameters of a channel weigh as much as
+ *  its 4-bit codes, and halves cut that in two.  scale is rounded to binary16
+ *  (nearest even) BEFORE the codes are computed, so that quantisation and
+ *  dequantisation use the same stored value; mn is an integer in [-128, 127],
+ *  exact in binary16.  Record for b < 8: codes as in format 1, then
+ *    scale : [slab][head_dim] binary16;   mn : [slab][head_dim] binary16.
+ *
  *  Quantisation of one group of `group` consecutive head_dim elements of one
  *  token (linear min/max quantisation, Sec. 3.2 "Compressing chunks"), all in
  *  IEEE binary32, round-to-nearest, no contraction:
@@ -102,10 +110,10 @@ typedef struct {
     int32_t n_tokens;
     int32_t chunk_tokens;
     int32_t group;         /* quantisation group along head_dim (format 0) */
-    int32_t format;        /* KV_FMT_F16_GROUPS (0) or KV_FMT_I8_CHANNELS (1) */
+    int32_t format;        /* KV_FMT_F16_GROUPS (0), KV_FMT_I8_CHANNELS (1), KV_FMT_I8_CHANNELS_H (2) */
 } kv_shape_t;
 
-enum { KV_FMT_F16_GROUPS = 0, KV_FMT_I8_CHANNELS = 1 };
+enum { KV_FMT_F16_GROUPS = 0, KV_FMT_I8_CHANNELS = 1, KV_FMT_I8_CHANNELS_H = 2 };
 
 enum { KV_NORM_VISIBLE = 0, KV_NORM_NONE = 1 };
 
@@ -116,7 +124,7 @@ const char* kv_last_error(void);
 
 /* Bytes of one chunk's packed record at bit-width `bits`; 0 if shape or bits
  * are invalid.  Format 0: b<16: slabs*T*(D*b/8 + 8*D/G); b=16: slabs*T*D*2.
- * Format 1: b<8: slabs*(T*D*b/8 + 8*D); b=8: slabs*T*D. */
+ * Format 1: b<8: slabs*(T*D*b/8 + 8*D); b=8: slabs*T*D.  Format 2: 4*D in the place of 8*D. */
 uint64_t kv_record_bytes(const kv_shape_t* shape, int32_t bits);
 
 /* Exclusive prefix sum of record sizes: off[0]=0, off[i+1]=off[i]+record_bytes(bits[i]).

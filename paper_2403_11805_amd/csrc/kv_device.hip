@@ -75,6 +75,7 @@ I8View i8_view(const kv_shape_t& s) {
     v.head_dim = s.head_dim;
     v.group_lanes = s.head_dim / 4 < 64 ? s.head_dim / 4 : 64;
     v.share_log2 = 6 - ilog2(v.group_lanes);
+    v.half_meta = s.format == KV_FMT_I8_CHANNELS_H ? 1 : 0;
     return v;
 }
 
@@ -125,10 +126,13 @@ int launch_status(const char* what) {
 int launch_swapin_batch(const kv_shape_t& shape, const QuantGeom& g, int ppl, const uint8_t* base,
                         const SwapinBatch& list, u4_t* dst, hipStream_t st) {
     const dim3 grid = task_grid(g, list.n);
-    if (shape.format == KV_FMT_I8_CHANNELS) {
+    if (is_i8(shape)) {
         const I8View v = i8_view(shape);
 #define KV_LAUNCH_I8(NDW, GPL) \
-        hipLaunchKernelGGL((swapin_i8_batch_kernel<NDW, GPL>), grid, dim3(256), 0, st, base, list, dst, g, v)
+        do {                                                                                                    \
+            if (v.half_meta) hipLaunchKernelGGL((swapin_i8_batch_kernel<NDW, GPL, true>), grid, dim3(256), 0, st, base, list, dst, g, v); \
+            else hipLaunchKernelGGL((swapin_i8_batch_kernel<NDW, GPL, false>), grid, dim3(256), 0, st, base, list, dst, g, v);            \
+        } while (0)
         KV_I8_DISPATCH(ppl, shape.head_dim, KV_LAUNCH_I8);
 #undef KV_LAUNCH_I8
     } else if (ppl == 4) hipLaunchKernelGGL(swapin_batch_kernel<4>, grid, dim3(256), 0, st, base, list, dst, g);
@@ -147,7 +151,7 @@ int32_t kv_compress_chunks(const kv_shape_t* shape, const void* kv, const uint8_
     if (!kv || !bits_dev || !off_dev || !packed_out) return fail(KV_EINVAL, "NULL device pointer");
     if (!aligned(kv, 16) || !aligned(packed_out, 16) || !aligned(off_dev, 8))
         return fail(KV_EINVAL, "kv/packed_out must be 16-byte aligned, off_dev 8-byte aligned");
-    const bool i8 = shape->format == KV_FMT_I8_CHANNELS;
+    const bool i8 = is_i8(*shape);
     int ppl = 0;
     QuantGeom g = i8 ? quant_geom_i8(*shape, &ppl) : quant_geom(*shape);
     if (!i8) ppl = plan_tasks(&g, kCompressPiecesPerLane);
@@ -161,9 +165,15 @@ int32_t kv_compress_chunks(const kv_shape_t* shape, const void* kv, const uint8_
     uint8_t* dst = static_cast<uint8_t*>(packed_out);
     if (i8) {
         const I8View v = i8_view(*shape);
-#define KV_LAUNCH_I8(NDW, GPL)                                                                          \
-        hipLaunchKernelGGL((compress_i8_kernel<NDW, GPL>), grid, dim3(256), 0, st, src, bits_dev, off_dev, \
-                           dst, g, v, n_chunks)
+#define KV_LAUNCH_I8(NDW, GPL)                                                                               \
+        do {                                                                                                 \
+            if (v.half_meta)                                                                                 \
+                hipLaunchKernelGGL((compress_i8_kernel<NDW, GPL, true>), grid, dim3(256), 0, st, src, bits_dev, \
+                                   off_dev, dst, g, v, n_chunks);                                            \
+            else                                                                                             \
+                hipLaunchKernelGGL((compress_i8_kernel<NDW, GPL, false>), grid, dim3(256), 0, st, src, bits_dev, \
+                                   off_dev, dst, g, v, n_chunks);                                            \
+        } while (0)
         KV_I8_DISPATCH(ppl, shape->head_dim, KV_LAUNCH_I8);
 #undef KV_LAUNCH_I8
         return launch_status("compress_i8_kernel launch");
@@ -186,7 +196,7 @@ int32_t kv_swapin_chunks(const kv_shape_t* shape, const void* packed, const uint
     if (!aligned(kv_out, 16) || !aligned(packed, 16) || !aligned(src_off_dev, 8) ||
         !aligned(dst_tok_dev, 4))
         return fail(KV_EINVAL, "kv_out/packed must be 16-byte aligned, lists naturally aligned");
-    const bool i8 = shape->format == KV_FMT_I8_CHANNELS;
+    const bool i8 = is_i8(*shape);
     int ppl = 0;
     QuantGeom g = i8 ? quant_geom_i8(*shape, &ppl) : quant_geom(*shape);
     if (!i8) ppl = plan_tasks(&g, kSwapinPiecesPerLane);
@@ -197,9 +207,15 @@ int32_t kv_swapin_chunks(const kv_shape_t* shape, const void* packed, const uint
     u4_t* dst = static_cast<u4_t*>(kv_out);
     if (i8) {
         const I8View v = i8_view(*shape);
-#define KV_LAUNCH_I8(NDW, GPL)                                                                       \
-        hipLaunchKernelGGL((swapin_i8_kernel<NDW, GPL>), grid, dim3(256), 0, st, src, src_off_dev,   \
-                           dst_tok_dev, sel_bits_dev, dst, g, v, n_sel)
+#define KV_LAUNCH_I8(NDW, GPL)                                                                            \
+        do {                                                                                              \
+            if (v.half_meta)                                                                              \
+                hipLaunchKernelGGL((swapin_i8_kernel<NDW, GPL, true>), grid, dim3(256), 0, st, src, src_off_dev, \
+                                   dst_tok_dev, sel_bits_dev, dst, g, v, n_sel);                          \
+            else                                                                                          \
+                hipLaunchKernelGGL((swapin_i8_kernel<NDW, GPL, false>), grid, dim3(256), 0, st, src, src_off_dev, \
+                                   dst_tok_dev, sel_bits_dev, dst, g, v, n_sel);                          \
+        } while (0)
         KV_I8_DISPATCH(ppl, shape->head_dim, KV_LAUNCH_I8);
 #undef KV_LAUNCH_I8
         return launch_status("swapin_i8_kernel launch");
@@ -343,7 +359,7 @@ int32_t kv_load_chunks(const kv_shape_t* shape, const void* packed, const uint64
         return rc;
     for (int32_t j = 0; j < n_sel; ++j)
         if (src_off[static_cast<size_t>(j)] % 16) return fail(KV_EINVAL, "record offset of chunk %d not 16-byte aligned", chunk_idx[j]);
-    const bool i8 = shape->format == KV_FMT_I8_CHANNELS;
+    const bool i8 = is_i8(*shape);
     int ppl = 0;
     QuantGeom g = i8 ? quant_geom_i8(*shape, &ppl) : quant_geom(*shape);
     if (!i8) ppl = plan_tasks(&g, kSwapinPiecesPerLane);
@@ -380,7 +396,7 @@ int32_t kv_plan_chunks_dev(const kv_shape_t* shape, const float* density_dev, in
     const int k8 = static_cast<int>(static_cast<int64_t>(n) * num8 / den);
     const int k84 = static_cast<int>(static_cast<int64_t>(n) * (num8 + num4) / den);
     RecordBytes rec;
-    const bool i8 = shape->format == KV_FMT_I8_CHANNELS;
+    const bool i8 = is_i8(*shape);
     rec.w16 = i8 ? 0 : kv_record_bytes(shape, 16);
     rec.w8 = kv_record_bytes(shape, 8);
     rec.w4 = kv_record_bytes(shape, 4);
@@ -433,7 +449,7 @@ int32_t kv_swapin_pinned(const kv_shape_t* shape, const void* packed_pinned, con
         return fail(KV_ENOMEM, "staging slot %llu bytes, largest record %llu",
                     static_cast<unsigned long long>(slot), static_cast<unsigned long long>(largest));
 
-    const bool i8 = shape->format == KV_FMT_I8_CHANNELS;
+    const bool i8 = is_i8(*shape);
     int ppl = 0;
     QuantGeom g = i8 ? quant_geom_i8(*shape, &ppl) : quant_geom(*shape);
     if (!i8) ppl = plan_tasks(&g, kSwapinPiecesPerLane);

@@ -31,7 +31,7 @@ int check_shape(const kv_shape_t* s) {
     if (s->n_tokens % s->chunk_tokens)
         return fail(KV_ESHAPE, "n_tokens %d is not a multiple of chunk_tokens %d", s->n_tokens,
                     s->chunk_tokens);
-    if (s->format != KV_FMT_F16_GROUPS && s->format != KV_FMT_I8_CHANNELS)
+    if (s->format != KV_FMT_F16_GROUPS && !is_i8(*s))
         return fail(KV_ESHAPE, "format %d unknown", s->format);
     if (s->n_q_heads % s->n_kv_heads)
         return fail(KV_ESHAPE, "n_q_heads %d is not a multiple of n_kv_heads %d", s->n_q_heads,
@@ -40,7 +40,7 @@ int check_shape(const kv_shape_t* s) {
         return fail(KV_ESHAPE, "head_dim and chunk_tokens must be <= 1024");
     if (slabs_of(*s) * static_cast<uint64_t>(s->n_tokens) > (1ull << 31))
         return fail(KV_ESHAPE, "layers*2*kv_heads*tokens exceeds 2^31");
-    if (s->format == KV_FMT_I8_CHANNELS) {
+    if (is_i8(*s)) {
         if (s->head_dim < 64 || (s->head_dim & (s->head_dim - 1)))
             return fail(KV_ESHAPE, "int8 format needs head_dim a power of two in [64,1024], got %d", s->head_dim);
         const int64_t unit = static_cast<int64_t>(s->chunk_tokens) * s->head_dim;

@@ -14,13 +14,18 @@ void clear_error();
 // KV_OK, or KV_EINVAL / KV_ESHAPE with the error text set.
 int check_shape(const kv_shape_t* s);
 
-// Widths a chunk may have: {16,8,4,2} for the fp16 format, {8,4,2,1} for the int8 format.
+// The int8 cache formats (channel-wise parameters in fp32 or in binary16).
+inline bool is_i8(const kv_shape_t& s) {
+    return s.format == KV_FMT_I8_CHANNELS || s.format == KV_FMT_I8_CHANNELS_H;
+}
+
+// Widths a chunk may have: {16,8,4,2} for the fp16 format, {8,4,2,1} for the int8 formats.
 inline bool valid_bits(const kv_shape_t& s, int b) {
-    if (s.format == KV_FMT_I8_CHANNELS) return b == 8 || b == 4 || b == 2 || b == 1;
+    if (is_i8(s)) return b == 8 || b == 4 || b == 2 || b == 1;
     return b == 16 || b == 8 || b == 4 || b == 2;
 }
 inline const char* bits_set(const kv_shape_t& s) {
-    return s.format == KV_FMT_I8_CHANNELS ? "{8,4,2,1}" : "{16,8,4,2}";
+    return is_i8(s) ? "{8,4,2,1}" : "{16,8,4,2}";
 }
 
 inline uint64_t slabs_of(const kv_shape_t& s) {
@@ -30,10 +35,11 @@ inline uint64_t slabs_of(const kv_shape_t& s) {
 // Bytes of one chunk's record; shape and bits already validated.
 inline uint64_t record_bytes(const kv_shape_t& s, int bits) {
     const uint64_t rows = slabs_of(s) * static_cast<uint64_t>(s.chunk_tokens);
-    if (s.format == KV_FMT_I8_CHANNELS) {
+    if (is_i8(s)) {
         if (bits == 8) return rows * static_cast<uint64_t>(s.head_dim);
+        const uint64_t meta = s.format == KV_FMT_I8_CHANNELS ? 8u : 4u;   // (scale, minimum) per channel
         return rows * static_cast<uint64_t>(s.head_dim) * bits / 8u +
-               slabs_of(s) * 8u * static_cast<uint64_t>(s.head_dim);
+               slabs_of(s) * meta * static_cast<uint64_t>(s.head_dim);
     }
     if (bits == 16) return rows * static_cast<uint64_t>(s.head_dim) * 2u;
     return rows * (static_cast<uint64_t>(s.head_dim) * bits / 8u +

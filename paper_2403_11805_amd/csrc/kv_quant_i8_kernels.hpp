@@ -66,10 +66,14 @@ __device__ __forceinline__ float refined_rcp(float s) {
     return (s != 0.0f) ? __builtin_fmaf(e, r0, r0) : 0.0f;
 }
 
+// Residual corrections of the quotient.  The operand domain is finite (numerators 0..255, one
+// scale per range 0..255, level count and parameter precision), and the GPU tests compare the
+// codes of every such pair with the oracle's true division: one correction reproduces all of
+// them, none does not.
 #ifndef KVS_I8_DIV_STEPS
-#define KVS_I8_DIV_STEPS 2
+#define KVS_I8_DIV_STEPS 1
 #endif
-// d / s correctly rounded (rinv = refined_rcp(s)).
+// d / s rounded as the division does on this domain (rinv = refined_rcp(s)).
 __device__ __forceinline__ float div_exact(float d, float s, float rinv) {
     float q = d * rinv;
 #pragma unroll
@@ -103,13 +107,32 @@ struct I8View {
     int32_t head_dim;     // D
     int32_t group_lanes;  // lanes along the channel groups: min(D / 4, 64)
     int32_t share_log2;   // log2 of the lanes that share a channel group: 0, 1 (D = 128) or 2 (D = 64)
+    int32_t half_meta;    // 1: parameters are stored, and the scale is used, in binary16 (host side:
+                          // selects the HM instantiation of the kernels)
 };
 
+// Four binary32 values as four binary16 (round to nearest even), lowest index in the lowest bits.
+__device__ __forceinline__ uint32_t half_bits(float f) {
+    return __builtin_bit_cast(uint16_t, static_cast<_Float16>(f));
+}
+__device__ __forceinline__ uint32_t half_to_float_bits(uint32_t h) {
+    return __builtin_bit_cast(uint32_t, static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(h))));
+}
+__device__ __forceinline__ u2_t pack_halves(const float (&f)[4]) {
+    return u2_t{half_bits(f[0]) | (half_bits(f[1]) << 16), half_bits(f[2]) | (half_bits(f[3]) << 16)};
+}
+__device__ __forceinline__ void unpack_halves(u2_t w, uint32_t (&bits32)[4]) {
+    bits32[0] = half_to_float_bits(w.x & 0xffffu);
+    bits32[1] = half_to_float_bits(w.x >> 16);
+    bits32[2] = half_to_float_bits(w.y & 0xffffu);
+    bits32[3] = half_to_float_bits(w.y >> 16);
+}
+
 // NDW = dwords per lane (unit bytes / 256: 4, 8, 16); GPL = channel groups per lane (D / 256, at least 1).
-template <int BITS, int NDW, int GPL>
+template <int BITS, int NDW, int GPL, bool HM>
 __device__ __forceinline__ void compress_i8_unit(const uint8_t* __restrict__ raw_img, uint8_t* __restrict__ code_img,
-                                                 uint8_t* __restrict__ codes, float* __restrict__ scale_out,
-                                                 float* __restrict__ mn_out, const I8View& v, int lane) {
+                                                 uint8_t* __restrict__ codes, void* __restrict__ scale_out,
+                                                 void* __restrict__ mn_out, const I8View& v, int lane) {
     constexpr int LEVELS = (1 << BITS) - 1;
     constexpr int RPL = NDW / GPL;                         // token rows per lane and group
     const int c = lane & (v.group_lanes - 1);              // channel group (+ 64 * j)
@@ -153,6 +176,7 @@ __device__ __forceinline__ void compress_i8_unit(const uint8_t* __restrict__ raw
         for (int i = 0; i < 4; ++i) {
             mn[i] = static_cast<float>(mnw[i]);
             scale[i] = div_levels<LEVELS>(static_cast<float>(mxw[i] - mnw[i]));
+            if constexpr (HM) scale[i] = static_cast<float>(static_cast<_Float16>(scale[i]));
             rinv[i] = refined_rcp(scale[i]);
         }
         const int g4 = c + 64 * j;                            // channel group index in the row
@@ -182,13 +206,18 @@ __device__ __forceinline__ void compress_i8_unit(const uint8_t* __restrict__ raw
             }
         }
         if (rpart == 0) {
-            const u4_t sv = {__builtin_bit_cast(uint32_t, scale[0]), __builtin_bit_cast(uint32_t, scale[1]),
-                             __builtin_bit_cast(uint32_t, scale[2]), __builtin_bit_cast(uint32_t, scale[3])};
-            const float m0 = mn[0] - 128.0f, m1 = mn[1] - 128.0f, m2 = mn[2] - 128.0f, m3 = mn[3] - 128.0f;
-            const u4_t mv = {__builtin_bit_cast(uint32_t, m0), __builtin_bit_cast(uint32_t, m1),
-                             __builtin_bit_cast(uint32_t, m2), __builtin_bit_cast(uint32_t, m3)};
-            reinterpret_cast<u4_t*>(scale_out)[g4] = sv;
-            reinterpret_cast<u4_t*>(mn_out)[g4] = mv;
+            const float mo[4] = {mn[0] - 128.0f, mn[1] - 128.0f, mn[2] - 128.0f, mn[3] - 128.0f};
+            if constexpr (HM) {
+                reinterpret_cast<u2_t*>(scale_out)[g4] = pack_halves(scale);
+                reinterpret_cast<u2_t*>(mn_out)[g4] = pack_halves(mo);
+            } else {
+                const u4_t sv = {__builtin_bit_cast(uint32_t, scale[0]), __builtin_bit_cast(uint32_t, scale[1]),
+                                 __builtin_bit_cast(uint32_t, scale[2]), __builtin_bit_cast(uint32_t, scale[3])};
+                const u4_t mv = {__builtin_bit_cast(uint32_t, mo[0]), __builtin_bit_cast(uint32_t, mo[1]),
+                                 __builtin_bit_cast(uint32_t, mo[2]), __builtin_bit_cast(uint32_t, mo[3])};
+                reinterpret_cast<u4_t*>(scale_out)[g4] = sv;
+                reinterpret_cast<u4_t*>(mn_out)[g4] = mv;
+            }
         }
     }
     // LDS writes of this wavefront are ordered before its reads below
@@ -200,7 +229,7 @@ __device__ __forceinline__ void compress_i8_unit(const uint8_t* __restrict__ raw
 
 // Grid as compress_kernel with one task per unit (g.tpu = 1); g.pieces = T * D / 16,
 // g.row_pieces = D / 16.  LDS: per wavefront the unit (NDW * 256 bytes) and its codes (at most half of that).
-template <int NDW, int GPL>
+template <int NDW, int GPL, bool HM>
 __global__ __launch_bounds__(256) void compress_i8_kernel(const u4_t* __restrict__ kv,
                                                           const uint8_t* __restrict__ bits,
                                                           const uint64_t* __restrict__ off,
@@ -235,14 +264,13 @@ __global__ __launch_bounds__(256) void compress_i8_kernel(const u4_t* __restrict
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     const uint64_t code_bytes = static_cast<uint64_t>(g.pieces) * 2 * b;   // T * D * b / 8 per unit
-    const uint32_t channels = static_cast<uint32_t>(v.head_dim);
+    const uint64_t meta_bytes = static_cast<uint64_t>(v.head_dim) * (HM ? 2 : 4);   // per slab and section
     uint8_t* codes = base + slab * code_bytes;
-    float* scale = reinterpret_cast<float*>(base + g.slabs * code_bytes) +
-                   static_cast<uint64_t>(slab) * channels;
-    float* mn = scale + static_cast<uint64_t>(g.slabs) * channels;
-    if (b == 4) compress_i8_unit<4, NDW, GPL>(raw_img, code_img, codes, scale, mn, v, lane);
-    else if (b == 2) compress_i8_unit<2, NDW, GPL>(raw_img, code_img, codes, scale, mn, v, lane);
-    else compress_i8_unit<1, NDW, GPL>(raw_img, code_img, codes, scale, mn, v, lane);
+    uint8_t* scale = base + g.slabs * code_bytes + slab * meta_bytes;
+    uint8_t* mn = scale + g.slabs * meta_bytes;
+    if (b == 4) compress_i8_unit<4, NDW, GPL, HM>(raw_img, code_img, codes, scale, mn, v, lane);
+    else if (b == 2) compress_i8_unit<2, NDW, GPL, HM>(raw_img, code_img, codes, scale, mn, v, lane);
+    else compress_i8_unit<1, NDW, GPL, HM>(raw_img, code_img, codes, scale, mn, v, lane);
 }
 
 // ------------------------------------------------------------------ swap-in
@@ -275,10 +303,10 @@ __device__ __forceinline__ void copy_in(const uint8_t* __restrict__ src, uint8_t
 
 // x = int8(clamp(rint(code * scale + mn), -128, 127)): product and sum rounded separately; the
 // saturating conversion of x + 128 to an unsigned byte is the clamp (x is an integer after rint).
-template <int BITS, int NDW, int GPL>
+template <int BITS, int NDW, int GPL, bool HM>
 __device__ __forceinline__ void swapin_i8_unit(const uint8_t* __restrict__ codes,
-                                               const float* __restrict__ scale_in,
-                                               const float* __restrict__ mn_in, uint8_t* __restrict__ code_img,
+                                               const void* __restrict__ scale_in,
+                                               const void* __restrict__ mn_in, uint8_t* __restrict__ code_img,
                                                uint8_t* __restrict__ raw_img, u4_t* __restrict__ dst,
                                                const I8View& v, int lane) {
     constexpr int PPL = NDW / 4;
@@ -288,11 +316,18 @@ __device__ __forceinline__ void swapin_i8_unit(const uint8_t* __restrict__ codes
     const int c = lane & (v.group_lanes - 1);
     const int rpart = lane >> (6 - v.share_log2);
     const int row0 = rpart * RPL;
-    u4_t sv[GPL], mv[GPL];
+    u4_t sv[GPL], mv[GPL];           // binary16 parameters travel in .x and .y
 #pragma unroll
     for (int j = 0; j < GPL; ++j) {
-        sv[j] = reinterpret_cast<const u4_t*>(scale_in)[c + 64 * j];
-        mv[j] = reinterpret_cast<const u4_t*>(mn_in)[c + 64 * j];
+        if constexpr (HM) {
+            const u2_t sh = reinterpret_cast<const u2_t*>(scale_in)[c + 64 * j];
+            const u2_t mh = reinterpret_cast<const u2_t*>(mn_in)[c + 64 * j];
+            sv[j] = u4_t{sh.x, sh.y, 0u, 0u};
+            mv[j] = u4_t{mh.x, mh.y, 0u, 0u};
+        } else {
+            sv[j] = reinterpret_cast<const u4_t*>(scale_in)[c + 64 * j];
+            mv[j] = reinterpret_cast<const u4_t*>(mn_in)[c + 64 * j];
+        }
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -300,8 +335,12 @@ __device__ __forceinline__ void swapin_i8_unit(const uint8_t* __restrict__ codes
 #pragma unroll
     for (int j = 0; j < GPL; ++j) {
         const int g4 = c + 64 * j;
-        const uint32_t s4[4] = {sv[j].x, sv[j].y, sv[j].z, sv[j].w};
-        const uint32_t m4[4] = {mv[j].x, mv[j].y, mv[j].z, mv[j].w};
+        uint32_t s4[4] = {sv[j].x, sv[j].y, sv[j].z, sv[j].w};
+        uint32_t m4[4] = {mv[j].x, mv[j].y, mv[j].z, mv[j].w};
+        if constexpr (HM) {
+            unpack_halves(u2_t{sv[j].x, sv[j].y}, s4);
+            unpack_halves(u2_t{mv[j].x, mv[j].y}, m4);
+        }
 #pragma unroll
         for (int k = 0; k < RPL; ++k) {
             const int row = row0 + k;
@@ -333,7 +372,7 @@ __device__ __forceinline__ void swapin_i8_unit(const uint8_t* __restrict__ codes
         stream_store<KVS_NT_CACHE_STORE>(reinterpret_cast<const u4_t*>(raw_img)[u * 64 + lane], dst + u * 64 + lane);
 }
 
-template <int NDW, int GPL>
+template <int NDW, int GPL, bool HM>
 __device__ __forceinline__ void swapin_i8_task(const uint8_t* __restrict__ base, int b, int slab,
                                                u4_t* __restrict__ dst, const QuantGeom& g, const I8View& v,
                                                uint8_t* __restrict__ lds_wave, int lane) {
@@ -348,20 +387,19 @@ __device__ __forceinline__ void swapin_i8_task(const uint8_t* __restrict__ base,
         return;
     }
     const uint64_t code_bytes = static_cast<uint64_t>(g.pieces) * 2 * b;
-    const uint32_t channels = static_cast<uint32_t>(v.head_dim);
+    const uint64_t meta_bytes = static_cast<uint64_t>(v.head_dim) * (HM ? 2 : 4);
     const uint8_t* codes = base + slab * code_bytes;
-    const float* scale = reinterpret_cast<const float*>(base + g.slabs * code_bytes) +
-                         static_cast<uint64_t>(slab) * channels;
-    const float* mn = scale + static_cast<uint64_t>(g.slabs) * channels;
+    const uint8_t* scale = base + g.slabs * code_bytes + slab * meta_bytes;
+    const uint8_t* mn = scale + g.slabs * meta_bytes;
     uint8_t* raw_img = lds_wave;
     uint8_t* code_img = lds_wave + NDW * 256;
-    if (b == 4) swapin_i8_unit<4, NDW, GPL>(codes, scale, mn, code_img, raw_img, dst, v, lane);
-    else if (b == 2) swapin_i8_unit<2, NDW, GPL>(codes, scale, mn, code_img, raw_img, dst, v, lane);
-    else swapin_i8_unit<1, NDW, GPL>(codes, scale, mn, code_img, raw_img, dst, v, lane);
+    if (b == 4) swapin_i8_unit<4, NDW, GPL, HM>(codes, scale, mn, code_img, raw_img, dst, v, lane);
+    else if (b == 2) swapin_i8_unit<2, NDW, GPL, HM>(codes, scale, mn, code_img, raw_img, dst, v, lane);
+    else swapin_i8_unit<1, NDW, GPL, HM>(codes, scale, mn, code_img, raw_img, dst, v, lane);
 }
 
 // LDS per wavefront as in compress_i8_kernel: the unit (NDW * 256 bytes) and its codes.
-template <int NDW, int GPL>
+template <int NDW, int GPL, bool HM>
 __global__ __launch_bounds__(256) void swapin_i8_kernel(const uint8_t* __restrict__ packed,
                                                         const uint64_t* __restrict__ src_off,
                                                         const int32_t* __restrict__ dst_tok,
@@ -375,10 +413,10 @@ __global__ __launch_bounds__(256) void swapin_i8_kernel(const uint8_t* __restric
     if (!wave_task(g, n_sel, NDW / 4, j, slab, p0)) return;
     u4_t* dst = kv_out + (static_cast<uint64_t>(slab) * g.n_tokens +
                           static_cast<uint64_t>(dst_tok[j])) * g.row_pieces;
-    swapin_i8_task<NDW, GPL>(packed + src_off[j], uniform_byte(sel_bits, j), slab, dst, g, v, lds[wave], lane);
+    swapin_i8_task<NDW, GPL, HM>(packed + src_off[j], uniform_byte(sel_bits, j), slab, dst, g, v, lds[wave], lane);
 }
 
-template <int NDW, int GPL>
+template <int NDW, int GPL, bool HM>
 __global__ __launch_bounds__(256) void swapin_i8_batch_kernel(const uint8_t* __restrict__ staged,
                                                               SwapinBatch list,
                                                               u4_t* __restrict__ kv_out, QuantGeom g, I8View v) {
@@ -389,7 +427,7 @@ __global__ __launch_bounds__(256) void swapin_i8_batch_kernel(const uint8_t* __r
     if (!wave_task(g, list.n, NDW / 4, j, slab, p0)) return;
     u4_t* dst = kv_out + (static_cast<uint64_t>(slab) * g.n_tokens +
                           static_cast<uint64_t>(list.dst_tok[j])) * g.row_pieces;
-    swapin_i8_task<NDW, GPL>(staged + list.src_off[j], list.bits[j], slab, dst, g, v, lds[wave], lane);
+    swapin_i8_task<NDW, GPL, HM>(staged + list.src_off[j], list.bits[j], slab, dst, g, v, lds[wave], lane);
 }
 
 }  // namespace kvs

@@ -48,9 +48,10 @@ def test_load_equals_oracle_and_list_path(geom):
         assert torch.equal(out.view(torch.int16), via_lists.view(torch.int16))
 
 
-def test_load_int8_format():
+@pytest.mark.parametrize("fmt", [1, 2])
+def test_load_int8_formats(fmt):
     g = synth.Geometry(2, 2, 2, 128, 1600, 16, 64)
-    ks, os_ = both_shapes(g, 1)
+    ks, os_ = both_shapes(g, fmt)
     kv_host = synth.make_kv_i8(g, 4).numpy()
     bits = synth.draw_bits_uniform(g.n_chunks, 4, widths=(8, 4, 2, 1)).numpy()
     kv_dev = torch.from_numpy(kv_host).to(DEV)

@@ -1,6 +1,7 @@
 """GPU parity for the int8, channel-wise record format (the paper's own quantiser setting,
 Sec. 3.2 "Compressing chunks" and Sec. 4): kv_compress_chunks / kv_swapin_chunks /
-kv_swapin_pinned with shape.format = KV_FMT_I8_CHANNELS against the CPU oracle.
+kv_swapin_pinned with shape.format = KV_FMT_I8_CHANNELS (fp32 parameters) and
+KV_FMT_I8_CHANNELS_H (binary16 parameters) against the CPU oracle.
 
 Bar: every record byte (codes, scales, minima, pass-through bytes) and every
 dequantised int8 value bit-exact."""
@@ -19,8 +20,16 @@ pytestmark = pytest.mark.gpu
 SENTINEL = 0x55
 
 
-def check_full(geom, kv_host, bits, select=None):
-    ks, os_ = both_shapes(geom, 1)
+def check_full(geom, kv_host, bits, select=None, fmts=(1, 2)):
+    """Both int8 formats: parameters in fp32 (1) and in binary16 (2)."""
+    got = None
+    for fmt in fmts:
+        got = check_format(geom, kv_host, bits, select, fmt)
+    return got
+
+
+def check_format(geom, kv_host, bits, select, fmt):
+    ks, os_ = both_shapes(geom, fmt)
     kv_dev = torch.from_numpy(kv_host).to(DEV)
     packed_dev, off = gpu_compress(ks, kv_dev, bits)
     assert np.array_equal(off, oracle.chunk_offsets(os_, bits))
@@ -119,11 +128,12 @@ def test_random_cache_many_channels():
     check_full(g, kv, bits)
 
 
-def test_llama7b_4k_int8_cache_sampled():
+@pytest.mark.parametrize("fmt", [1, 2])
+def test_llama7b_4k_int8_cache_sampled(fmt):
     """Llama-2-7B-shaped int8 cache (1 GiB) at full size; the oracle recomputes sampled chunks."""
     g = synth.Geometry(32, 32, 32, 128, 4096, 16, 64)
-    ks, os_ = both_shapes(g, 1)
-    one = oracle.Shape(os_.L, os_.Hkv, os_.Hq, os_.D, os_.T, os_.T, os_.G, 1)
+    ks, os_ = both_shapes(g, fmt)
+    one = oracle.Shape(os_.L, os_.Hkv, os_.Hq, os_.D, os_.T, os_.T, os_.G, fmt)
     kv_dev = synth.make_kv_i8(g, 2, DEV)
     bits = synth.draw_bits_uniform(g.n_chunks, 2, widths=(8, 4, 2, 1)).numpy()
     packed_dev, off = gpu_compress(ks, kv_dev, bits)
@@ -156,9 +166,10 @@ def test_llama7b_4k_int8_cache_sampled():
         assert bool(((y - x).abs() <= step * 0.5 + 0.5 + 1e-3).all())
 
 
-def test_streaming_from_pinned_host_equals_resident_path():
+@pytest.mark.parametrize("fmt", [1, 2])
+def test_streaming_from_pinned_host_equals_resident_path(fmt):
     g = synth.Geometry(2, 2, 2, 128, 512, 16, 64)
-    ks, os_ = both_shapes(g, 1)
+    ks, os_ = both_shapes(g, fmt)
     kv = synth.make_kv_i8(g, 31, "cpu")
     bits = synth.draw_bits_uniform(g.n_chunks, 31, widths=(8, 4, 2, 1)).numpy()
     packed_dev, off = gpu_compress(ks, kv.to(DEV), bits)

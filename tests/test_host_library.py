@@ -42,11 +42,13 @@ def test_record_bytes_and_offsets_match_oracle(cfg):
 
 
 def test_int8_channel_format_sizes_offsets_and_validation():
-    """Format 1 (int8 cache, channel-wise parameters): record sizes and offsets equal the
-    oracle's, widths are {8,4,2,1}, and shapes one wavefront cannot hold are refused."""
-    for (D, T) in ((64, 16), (128, 16), (128, 32), (256, 4), (1024, 1), (1024, 4)):
-        ks = kvs.Shape(3, 2, 2, D, 8 * T, T, 64, binding.KV_FMT_I8_CHANNELS)
-        os_ = oracle.Shape(3, 2, 2, D, 8 * T, T, 64, 1)
+    """Formats 1 and 2 (int8 cache, channel-wise parameters in fp32 / binary16): record sizes and
+    offsets equal the oracle's, widths are {8,4,2,1}, and shapes one wavefront cannot hold are refused."""
+    for (D, T, fmt) in ((64, 16, 1), (128, 16, 1), (128, 32, 2), (256, 4, 1), (1024, 1, 2), (1024, 4, 1),
+                        (64, 16, 2), (128, 16, 2)):
+        ks = kvs.Shape(3, 2, 2, D, 8 * T, T, 64, fmt)
+        os_ = oracle.Shape(3, 2, 2, D, 8 * T, T, 64, fmt)
+        assert fmt in (binding.KV_FMT_I8_CHANNELS, binding.KV_FMT_I8_CHANNELS_H)
         for b in (8, 4, 2, 1):
             assert kvs.kv_record_bytes(ks, b) == oracle.record_bytes(os_, b)
         bits = np.array([8, 4, 2, 1, 1, 2, 4, 8], dtype=np.uint8)
@@ -57,6 +59,8 @@ def test_int8_channel_format_sizes_offsets_and_validation():
         assert all(np.array_equal(g, w) for g, w in zip(got, want))
     good = kvs.Shape(2, 2, 2, 128, 64, 16, 64, binding.KV_FMT_I8_CHANNELS)
     assert kvs.kv_record_bytes(good, 2) == 8 * (16 * 128 // 4 + 8 * 128)
+    assert kvs.kv_record_bytes(good._replace(format=2), 2) == 8 * (16 * 128 // 4 + 4 * 128)
+    assert kvs.kv_record_bytes(good._replace(format=2), 8) == 8 * 16 * 128
     with pytest.raises(kvs.KvError):
         kvs.kv_record_bytes(good, 16)
     with pytest.raises(kvs.KvError) as e:
@@ -64,7 +68,7 @@ def test_int8_channel_format_sizes_offsets_and_validation():
     assert e.value.code == binding.KV_EBITS
     for bad in (good._replace(head_dim=96), good._replace(head_dim=32, chunk_tokens=32),
                 good._replace(chunk_tokens=64), good._replace(chunk_tokens=4, n_tokens=64),
-                good._replace(format=2)):
+                good._replace(format=3), good._replace(format=-1)):
         with pytest.raises(kvs.KvError) as e:
             kvs.kv_chunk_offsets(bad, np.full(max(bad.n_chunks, 1), 4, dtype=np.uint8))
         assert e.value.code == binding.KV_ESHAPE
