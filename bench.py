@@ -537,6 +537,7 @@ def run_recompute(wl, args, dev):
         x_in = synth.make_hidden(M, d_model, wl.seed, dev)
         x_out = torch.empty_like(x_in)
         ws = torch.empty(kvs.kv_recompute_workspace_bytes(shape, dims, x), dtype=torch.uint8, device=dev)
+        improved = 0 if args.no_tune else rc.tune(shape, dims, w, x, ws)
         ms = []
         for it in range(args.warmup + args.steps):
             ev0.record()
@@ -551,7 +552,7 @@ def run_recompute(wl, args, dev):
         t = float(np.mean(ms))
         points.append({"chunks": x, "tokens": M, "ms": round(t, 4), "ms_min": round(float(np.min(ms)), 4),
                        "gemm_gflop": round(gemm_flop / 1e9, 1), "attention_gflop": round(attn_flop / 1e9, 1),
-                       "tflops": round((gemm_flop + attn_flop) / t / 1e9, 1)})
+                       "tflops": round((gemm_flop + attn_flop) / t / 1e9, 1), "gemm_shapes_retuned": improved})
         del ws, x_in, x_out
     rc.close()
     slope, icpt = kvs.kv_fit_line([float(p["chunks"]) for p in points], [p["ms"] * 1e-3 for p in points])
@@ -618,6 +619,8 @@ def main():
     ap.add_argument("--stream-slot-mib", type=int, default=64)
     ap.add_argument("--re-us-per-chunk", type=float, default=50.0,
                     help="streaming workload: assumed recompute cost per chunk for the Eq. 4 plan example")
+    ap.add_argument("--no-tune", action="store_true",
+                    help="--recompute: keep the GEMM library's own choice of kernels (default: kv_recompute_tune first)")
     ap.add_argument("--graph", action="store_true",
                     help="additionally time the device-planned step replayed from a HIP graph")
     ap.add_argument("--host-plan", action="store_true",

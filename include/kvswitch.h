@@ -352,6 +352,21 @@ void            kv_recompute_destroy(kv_recompute_t* rc);
 uint64_t kv_recompute_workspace_bytes(const kv_shape_t* shape, const kv_layer_dims_t* dims,
                                       int32_t n_missing);
 
+/* Optional, once per (handle, n_missing): choose the GEMM library's kernels for the five projection
+ * shapes of a block over n_missing chunks by timing them on the caller's weights and workspace
+ * (Sec. 3.3 i profiles the recompute delay before planning; for a few hundred tokens the
+ * library's default kernels are far from the best it has).  Every listed kernel is timed back to
+ * back; the standard choice and the best few are timed again with cold weights, the other
+ * projections of the block running in between as in a layer; the winner is used by later
+ * kv_recompute_layer calls with the same n_missing if it beats the standard choice by more than
+ * 5 %.  Unlike every other device call this one SYNCHRONISES `stream`, takes of the order of a
+ * second, and overwrites the workspace.  n_improved (may be NULL) receives the number of shapes
+ * that got another kernel; 0 and KV_OK if the library cannot list its kernels.  Results are the
+ * same up to the summation order inside a GEMM. */
+int32_t kv_recompute_tune(kv_recompute_t* rc, const kv_shape_t* shape, const kv_layer_dims_t* dims,
+                          const kv_layer_weights_t* weights, int32_t n_missing, void* workspace,
+                          uint64_t workspace_bytes, void* stream, int32_t* n_improved);
+
 /* One block over the tokens of n_missing chunks (1 <= n_missing <= n_chunks).
  *   chunk_idx_dev dev i32 [n_missing], strictly ascending chunk indices (trusted, like the
  *                 gather lists: an index outside the cache makes the kernels write outside it);

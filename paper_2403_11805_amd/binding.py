@@ -87,6 +87,7 @@ _SIGNATURES = {
     "kv_recompute_create": (_vp, []),
     "kv_recompute_destroy": (None, [_vp]),
     "kv_recompute_workspace_bytes": (_u64, [_vp, _vp, _i32]),
+    "kv_recompute_tune": (_i32, [_vp, _vp, _vp, _vp, _i32, _vp, _u64, _vp, _vp]),
     "kv_recompute_layer": (_i32, [_vp, _vp, _vp, _vp, _i32, _vp, _i32, _vp, _vp, _vp, _vp, _u64, _vp]),
     "kv_lctru_create": (_vp, []),
     "kv_lctru_destroy": (None, [_vp]),
@@ -203,6 +204,17 @@ class Recompute:
             self.close()
         except Exception:
             pass
+
+    def tune(self, shape: Shape, dims: LayerDims, weights: dict, n_missing: int, workspace: torch.Tensor,
+             stream=None) -> int:
+        """kv_recompute_tune: synchronises the stream; returns the number of GEMM shapes that got another kernel."""
+        s, d = shape.c(), dims.c()
+        w = kv_layer_weights_t(*[_dev(weights[n], torch.float16) for n in LAYER_WEIGHTS])
+        improved = ctypes.c_int32(0)
+        _check(lib().kv_recompute_tune(self._h, ctypes.byref(s), ctypes.byref(d), ctypes.byref(w), n_missing,
+                                       _dev(workspace), workspace.numel() * workspace.element_size(),
+                                       _stream(stream), ctypes.byref(improved)))
+        return improved.value
 
     def layer(self, shape: Shape, dims: LayerDims, weights: dict, layer: int, chunk_idx_dev: torch.Tensor,
               x_in: torch.Tensor, kv: torch.Tensor, x_out: torch.Tensor, workspace: torch.Tensor,

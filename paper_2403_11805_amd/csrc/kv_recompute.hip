@@ -10,6 +10,7 @@
 #include <cmath>
 #include <cstdint>
 #include <new>
+#include <vector>
 
 #include "kv_internal.h"
 #include "kv_recompute_kernels.hpp"
@@ -30,6 +31,12 @@ constexpr int kRbOpNone = 111;        // rocblas_operation_none
 constexpr int kRbF16 = 150;           // rocblas_datatype_f16_r
 constexpr int kRbF32 = 151;           // rocblas_datatype_f32_r
 constexpr int kRbAlgoStandard = 0;    // rocblas_gemm_algo_standard
+constexpr int kRbAlgoSolution = 1;    // rocblas_gemm_algo_solution_index
+// Lists the library's kernels ("solutions") that can run a given gemm_ex call (same arguments,
+// then flags, list, list size; a NULL list returns the count).
+typedef int (*rb_get_solutions_fn)(rb_handle, int, int, int, int, int, const void*, const void*, int, int,
+                                   const void*, int, int, const void*, const void*, int, int, void*, int, int,
+                                   int, int, uint32_t, int*, int*);
 
 uint64_t align256(uint64_t v) { return (v + 255) & ~static_cast<uint64_t>(255); }
 
@@ -73,27 +80,149 @@ int check_layer(const kv_shape_t* shape, const kv_layer_dims_t* dims, int32_t n_
 
 }  // namespace
 
+// One projection of the block: row-major C[M][N] = A[M][K] * B[K][N] (+ Cin), fp16 operands.
+struct GemmShape {
+    int64_t M, N, K;
+    bool out_f32, add;
+    bool operator==(const GemmShape& o) const {
+        return M == o.M && N == o.N && K == o.K && out_f32 == o.out_f32 && add == o.add;
+    }
+};
+
 struct kv_recompute {
     void* lib = nullptr;
     rb_handle handle = nullptr;
     rb_destroy_fn destroy = nullptr;
     rb_set_stream_fn set_stream = nullptr;
     rb_gemm_ex_fn gemm_ex = nullptr;
+    rb_get_solutions_fn get_solutions = nullptr;     // optional
+    std::vector<std::pair<GemmShape, int>> tuned;    // shapes for which kv_recompute_tune found a faster kernel
 };
 
 namespace {
 
-// Row-major C[M][N] = A[M][K] * B[K][N] (+ Cin if given), fp16 operands, binary32 accumulation.
+// The GEMM library's status for C[M][N] = A * B (+ Cin) with the standard choice of kernel
+// (solution < 0) or a given one.  Column-major view: Cout^T [N][M] = B^T [N][K] * A^T [K][M].
+int gemm_status(kv_recompute* rc, const GemmShape& g, const void* A, const void* B, const void* Cin, void* Cout,
+                int solution) {
+    const float alpha = 1.0f, beta = g.add ? 1.0f : 0.0f;
+    const int ct = g.out_f32 ? kRbF32 : kRbF16;
+    return rc->gemm_ex(rc->handle, kRbOpNone, kRbOpNone, static_cast<int>(g.N), static_cast<int>(g.M),
+                       static_cast<int>(g.K), &alpha, B, kRbF16, static_cast<int>(g.N), A, kRbF16,
+                       static_cast<int>(g.K), &beta, g.add ? Cin : Cout, ct, static_cast<int>(g.N), Cout, ct,
+                       static_cast<int>(g.N), kRbF32, solution < 0 ? kRbAlgoStandard : kRbAlgoSolution,
+                       solution < 0 ? 0 : solution, 0);
+}
+
 int gemm(kv_recompute* rc, int64_t M, int64_t N, int64_t K, const void* A, const void* B,
          const void* Cin, void* Cout, bool out_f32, const char* what) {
-    const float alpha = 1.0f, beta = Cin ? 1.0f : 0.0f;
-    const int ct = out_f32 ? kRbF32 : kRbF16;
-    // column-major view: Cout^T [N][M] = B^T [N][K] * A^T [K][M]
-    const int st = rc->gemm_ex(rc->handle, kRbOpNone, kRbOpNone, static_cast<int>(N), static_cast<int>(M),
-                               static_cast<int>(K), &alpha, B, kRbF16, static_cast<int>(N), A, kRbF16,
-                               static_cast<int>(K), &beta, Cin ? Cin : Cout, ct, static_cast<int>(N), Cout, ct,
-                               static_cast<int>(N), kRbF32, kRbAlgoStandard, 0, 0);
+    const GemmShape g = {M, N, K, out_f32, Cin != nullptr};
+    int solution = -1;
+    for (const auto& t : rc->tuned)
+        if (t.first == g) solution = t.second;
+    const int st = gemm_status(rc, g, A, B, Cin, Cout, solution);
     if (st != 0) return fail(KV_EHIP, "rocblas_gemm_ex (%s) failed with status %d", what, st);
+    return KV_OK;
+}
+
+// One projection of a block with its operands.
+struct GemmJob {
+    GemmShape g;
+    const void* A;
+    const void* B;
+    const void* Cin;
+    void* Cout;
+};
+
+// Picks the kernel of jobs[which] in two passes.  Pass 1 times every kernel the library lists
+// back to back, which ranks them with the weights sitting in the last-level cache; pass 2 times
+// the standard choice and the best few of pass 1 with cold weights, as a layer meets them: the
+// other projections of the block (several hundred MB of weights) run in between.  The fastest of
+// pass 2 is remembered if it beats the standard choice by more than 5 %.  Synchronises `st`.
+int tune_gemm(kv_recompute* rc, const GemmJob* jobs, int n_jobs, int which, hipStream_t st, hipEvent_t e0,
+              hipEvent_t e1, int* improved) {
+    const GemmJob& job = jobs[which];
+    const GemmShape& g = job.g;
+    for (const auto& t : rc->tuned)
+        if (t.first == g) return KV_OK;                       // already tuned
+    const float alpha = 1.0f, beta = g.add ? 1.0f : 0.0f;
+    const int ct = g.out_f32 ? kRbF32 : kRbF16;
+    int n = 0;
+    auto list = [&](int* out, int* count) {
+        return rc->get_solutions(rc->handle, kRbOpNone, kRbOpNone, static_cast<int>(g.N), static_cast<int>(g.M),
+                                 static_cast<int>(g.K), &alpha, job.B, kRbF16, static_cast<int>(g.N), job.A, kRbF16,
+                                 static_cast<int>(g.K), &beta, g.add ? job.Cin : job.Cout, ct, static_cast<int>(g.N),
+                                 job.Cout, ct, static_cast<int>(g.N), kRbF32, kRbAlgoSolution, 0, out, count);
+    };
+    if (list(nullptr, &n) != 0 || n <= 0) return KV_OK;      // nothing to choose from
+    std::vector<int> sols(static_cast<size_t>(n));
+    if (list(sols.data(), &n) != 0) return KV_OK;
+    auto run = [&](int solution) { return gemm_status(rc, g, job.A, job.B, job.Cin, job.Cout, solution); };
+    // elapsed time of `reps` runs; 1: this kernel cannot run the problem; -1: the runtime failed
+    auto time_ms = [&](int solution, int reps, float* ms) -> int {
+        hipError_t e = hipEventRecord(e0, st);
+        for (int r = 0; r < reps && e == hipSuccess; ++r)
+            if (run(solution) != 0) return 1;
+        if (e == hipSuccess) e = hipEventRecord(e1, st);
+        if (e == hipSuccess) e = hipEventSynchronize(e1);
+        if (e == hipSuccess) e = hipEventElapsedTime(ms, e0, e1);
+        return e == hipSuccess ? 0 : -1;
+    };
+    constexpr int kKeep = 6;
+    int keep[kKeep];
+    float keep_ms[kKeep];
+    int n_keep = 0;
+    for (int i = 0; i < n; ++i) {
+        const int sol = sols[static_cast<size_t>(i)];
+        float t = 0.0f;
+        if (run(sol) != 0) continue;                          // warm-up, and "can it run"
+        const int rc_t = time_ms(sol, 3, &t);
+        if (rc_t < 0) return fail(KV_EHIP, "timing a GEMM kernel failed");
+        if (rc_t != 0) continue;
+        int at;                                               // insertion into the sorted short list
+        if (n_keep < kKeep) at = n_keep++;
+        else if (t < keep_ms[kKeep - 1]) at = kKeep - 1;
+        else continue;
+        while (at > 0 && keep_ms[at - 1] > t) {
+            keep[at] = keep[at - 1];
+            keep_ms[at] = keep_ms[at - 1];
+            --at;
+        }
+        keep[at] = sol;
+        keep_ms[at] = t;
+    }
+    auto cold_ms = [&](int solution, float* ms) -> int {
+        *ms = 1e30f;
+        for (int rep = 0; rep < 3; ++rep) {
+            for (int k = 0; k < n_jobs; ++k)                  // push this job's weights out of the cache
+                if (jobs[k].B != job.B) {
+                    const GemmJob& o = jobs[k];
+                    if (gemm_status(rc, o.g, o.A, o.B, o.Cin, o.Cout, -1) != 0) return -1;
+                }
+            float t = 0.0f;
+            const int rc_t = time_ms(solution, 1, &t);
+            if (rc_t != 0) return rc_t;
+            if (t < *ms) *ms = t;
+        }
+        return 0;
+    };
+    float t_std = 0.0f;
+    if (cold_ms(-1, &t_std) != 0) return fail(KV_EHIP, "timing the standard GEMM kernel failed");
+    float t_best = t_std;
+    int best = -1;
+    for (int i = 0; i < n_keep; ++i) {
+        float t = 0.0f;
+        const int rc_t = cold_ms(keep[i], &t);
+        if (rc_t < 0) return fail(KV_EHIP, "timing a GEMM kernel failed");
+        if (rc_t == 0 && t < t_best) {
+            t_best = t;
+            best = keep[i];
+        }
+    }
+    if (best >= 0 && t_best < 0.95f * t_std) {
+        rc->tuned.emplace_back(g, best);
+        ++*improved;
+    }
     return KV_OK;
 }
 
@@ -119,6 +248,7 @@ kv_recompute_t* kv_recompute_create(void) {
     rc->destroy = reinterpret_cast<rb_destroy_fn>(dlsym(rc->lib, "rocblas_destroy_handle"));
     rc->set_stream = reinterpret_cast<rb_set_stream_fn>(dlsym(rc->lib, "rocblas_set_stream"));
     rc->gemm_ex = reinterpret_cast<rb_gemm_ex_fn>(dlsym(rc->lib, "rocblas_gemm_ex"));
+    rc->get_solutions = reinterpret_cast<rb_get_solutions_fn>(dlsym(rc->lib, "rocblas_gemm_ex_get_solutions"));
     if (!create || !rc->destroy || !rc->set_stream || !rc->gemm_ex) {
         fail(KV_EHIP, "rocBLAS lacks a required entry point");
         dlclose(rc->lib);
@@ -145,6 +275,60 @@ void kv_recompute_destroy(kv_recompute_t* rc) {
 uint64_t kv_recompute_workspace_bytes(const kv_shape_t* shape, const kv_layer_dims_t* dims, int32_t n_missing) {
     if (check_layer(shape, dims, n_missing) != KV_OK) return 0;
     return plan_workspace(*shape, *dims, static_cast<int64_t>(n_missing) * shape->chunk_tokens).total;
+}
+
+int32_t kv_recompute_tune(kv_recompute_t* rc, const kv_shape_t* shape, const kv_layer_dims_t* dims,
+                          const kv_layer_weights_t* w, int32_t n_missing, void* workspace,
+                          uint64_t workspace_bytes, void* stream, int32_t* n_improved) {
+    if (n_improved) *n_improved = 0;
+    if (!rc) return fail(KV_EINVAL, "handle is NULL");
+    if (int st = check_layer(shape, dims, n_missing)) return st;
+    if (!w || !w->wq || !w->wk || !w->wv || !w->wo || !w->w_gate || !w->w_up || !w->w_down)
+        return fail(KV_EINVAL, "a weight pointer is NULL");
+    if (!workspace || !aligned(workspace, 256)) return fail(KV_EINVAL, "workspace must be a 256-byte aligned device pointer");
+    const kv_shape_t& s = *shape;
+    const int64_t M = static_cast<int64_t>(n_missing) * s.chunk_tokens;
+    const Plan p = plan_workspace(s, *dims, M);
+    if (workspace_bytes < p.total)
+        return fail(KV_ENOMEM, "workspace %llu bytes, %llu needed", static_cast<unsigned long long>(workspace_bytes),
+                    static_cast<unsigned long long>(p.total));
+    if (!rc->get_solutions) return KV_OK;                     // this GEMM library cannot list its kernels
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (rc->set_stream(rc->handle, st) != 0) return fail(KV_EHIP, "rocblas_set_stream failed");
+    // operands of ordinary magnitude and varied bits in every buffer a GEMM reads
+    const int64_t n_words = static_cast<int64_t>(p.total / 4);
+    hipLaunchKernelGGL(fill_noise_kernel, dim3(static_cast<uint32_t>((n_words + 255) / 256)), dim3(256), 0, st,
+                       static_cast<uint32_t*>(workspace), n_words);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(KV_EHIP, "fill_noise_kernel launch: %s", hipGetErrorString(e));
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    e = hipEventCreate(&e0);
+    if (e == hipSuccess) e = hipEventCreate(&e1);
+    if (e != hipSuccess) {
+        if (e0) (void)hipEventDestroy(e0);
+        return fail(KV_EHIP, "hipEventCreate: %s", hipGetErrorString(e));
+    }
+    uint8_t* base = static_cast<uint8_t*>(workspace);
+    void *xn = base + p.xn, *q32 = base + p.q32, *k32 = base + p.k32, *attn = base + p.attn, *x1 = base + p.x1,
+         *gate = base + p.gate;
+    const int64_t dq = static_cast<int64_t>(s.n_q_heads) * s.head_dim;
+    const int64_t dkv = static_cast<int64_t>(s.n_kv_heads) * s.head_dim;
+    void* up = base + p.up;
+    void* v32 = base + p.v32;
+    const GemmShape gq = {M, dq, dims->d_model, true, false}, gk = {M, dkv, dims->d_model, true, false};
+    const GemmShape go = {M, dims->d_model, dq, false, true}, gg = {M, dims->d_ff, dims->d_model, false, false};
+    const GemmShape gd = {M, dims->d_model, dims->d_ff, false, true};
+    const GemmJob jobs[7] = {{gq, xn, w->wq, nullptr, q32}, {gk, xn, w->wk, nullptr, k32}, {gk, xn, w->wv, nullptr, v32},
+                             {go, attn, w->wo, xn, x1},     {gg, xn, w->w_gate, nullptr, gate},
+                             {gg, xn, w->w_up, nullptr, up}, {gd, gate, w->w_down, x1, xn}};
+    int improved = 0;
+    int rcode = KV_OK;
+    for (int which : {0, 1, 3, 4, 6})
+        if (!rcode) rcode = tune_gemm(rc, jobs, 7, which, st, e0, e1, &improved);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (n_improved) *n_improved = improved;
+    return rcode;
 }
 
 int32_t kv_recompute_layer(kv_recompute_t* rc, const kv_shape_t* shape, const kv_layer_dims_t* dims,

@@ -98,6 +98,10 @@ def test_recompute_entry_points_validate_on_the_host():
     w = binding.kv_layer_weights_t()
     assert binding.lib().kv_recompute_layer(None, ctypes.byref(s), ctypes.byref(d), ctypes.byref(w), 0, None, 8,
                                             None, None, None, None, 0, None) == binding.KV_EINVAL
+    improved = ctypes.c_int32(7)
+    assert binding.lib().kv_recompute_tune(None, ctypes.byref(s), ctypes.byref(d), ctypes.byref(w), 8, None, 0,
+                                           None, ctypes.byref(improved)) == binding.KV_EINVAL
+    assert improved.value == 0
     binding.lib().kv_recompute_destroy(None)      # a no-op
 
 
