@@ -7,6 +7,7 @@
 #include <dlfcn.h>
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdint>
 #include <new>
@@ -41,8 +42,24 @@ typedef int (*rb_get_solutions_fn)(rb_handle, int, int, int, int, int, const voi
 uint64_t align256(uint64_t v) { return (v + 255) & ~static_cast<uint64_t>(255); }
 
 struct Plan {
-    uint64_t xn, q32, k32, v32, q16, attn, x1, gate, up, total;
+    uint64_t xn, q32, k32, v32, q16, attn, x1, gate, up, part_o, part_ml, total;
+    int splits;          // workgroups that share the key range of one attention row block (1: no split)
 };
+
+// With few recomputed rows the attention kernel has too few workgroups to fill 256 CUs: the key
+// range is then divided among up to 16 workgroups (one workgroup per CU in total: measured, more
+// shares cost more in partial results than they gain; at least four key tiles per share, at most
+// 64 MiB of partial results).
+int attention_splits(const kv_shape_t& s, int64_t M) {
+    const int64_t pairs = static_cast<int64_t>(s.n_q_heads / s.n_kv_heads) * ((M + 31) / 32);
+    const int64_t base = (pairs + kAttnWaves - 1) / kAttnWaves * s.n_kv_heads;
+    int64_t splits = 256 / base;
+    splits = std::min<int64_t>(splits, (s.n_tokens + 31) / 32 / 4);
+    splits = std::min<int64_t>(splits, kMaxSplits);
+    const int64_t per_split = M * s.n_q_heads * (s.head_dim + 2) * 4;
+    splits = std::min<int64_t>(splits, (64ll << 20) / per_split);
+    return static_cast<int>(std::max<int64_t>(splits, 1));
+}
 
 Plan plan_workspace(const kv_shape_t& s, const kv_layer_dims_t& d, int64_t M) {
     const uint64_t dq = static_cast<uint64_t>(s.n_q_heads) * s.head_dim;
@@ -58,6 +75,11 @@ Plan plan_workspace(const kv_shape_t& s, const kv_layer_dims_t& d, int64_t M) {
     p.x1 = o;   o += align256(M * d.d_model * 2u);
     p.gate = o; o += align256(M * static_cast<uint64_t>(d.d_ff) * 2u);
     p.up = o;   o += align256(M * static_cast<uint64_t>(d.d_ff) * 2u);
+    p.splits = attention_splits(s, M);
+    p.part_o = o;
+    if (p.splits > 1) o += align256(static_cast<uint64_t>(p.splits) * M * dq * 4u);
+    p.part_ml = o;
+    if (p.splits > 1) o += align256(static_cast<uint64_t>(p.splits) * M * s.n_q_heads * 8u);
     p.total = o;
     return p;
 }
@@ -96,7 +118,7 @@ struct kv_recompute {
     rb_set_stream_fn set_stream = nullptr;
     rb_gemm_ex_fn gemm_ex = nullptr;
     rb_get_solutions_fn get_solutions = nullptr;     // optional
-    std::vector<std::pair<GemmShape, int>> tuned;    // shapes for which kv_recompute_tune found a faster kernel
+    std::vector<std::pair<GemmShape, int>> tuned;    // shapes kv_recompute_tune examined: kernel, or -1 = standard
 };
 
 namespace {
@@ -219,10 +241,9 @@ int tune_gemm(kv_recompute* rc, const GemmJob* jobs, int n_jobs, int which, hipS
             best = keep[i];
         }
     }
-    if (best >= 0 && t_best < 0.95f * t_std) {
-        rc->tuned.emplace_back(g, best);
-        ++*improved;
-    }
+    const bool better = best >= 0 && t_best < 0.95f * t_std;
+    rc->tuned.emplace_back(g, better ? best : -1);            // examined: not timed again
+    if (better) ++*improved;
     return KV_OK;
 }
 
@@ -395,13 +416,34 @@ int32_t kv_recompute_layer(kv_recompute_t* rc, const kv_shape_t* shape, const kv
     g.n_rb = static_cast<int32_t>((M + 31) / 32);
     g.pairs = (Hq / Hkv) * g.n_rb;
     g.scale_log2e = static_cast<float>(1.4426950408889634 / std::sqrt(static_cast<double>(D)));
-    const dim3 agrid(static_cast<uint32_t>((g.pairs + kAttnWaves - 1) / kAttnWaves), static_cast<uint32_t>(Hkv));
-    if (D == 64)
-        hipLaunchKernelGGL(recompute_attention_kernel<64>, agrid, dim3(64 * kAttnWaves), 0, st, q16, k_plane,
-                           v_plane, chunk_idx_dev, attn, g);
-    else
-        hipLaunchKernelGGL(recompute_attention_kernel<128>, agrid, dim3(64 * kAttnWaves), 0, st, q16, k_plane,
-                           v_plane, chunk_idx_dev, attn, g);
+    const uint32_t pair_blocks = static_cast<uint32_t>((g.pairs + kAttnWaves - 1) / kAttnWaves);
+    if (p.splits > 1) {
+        float* part_o = reinterpret_cast<float*>(base + p.part_o);
+        float* part_ml = reinterpret_cast<float*>(base + p.part_ml);
+        const int n_tiles = (s.n_tokens + 31) / 32;
+        const int per_split = (n_tiles + p.splits - 1) / p.splits;
+        const dim3 agrid(pair_blocks, static_cast<uint32_t>(Hkv), static_cast<uint32_t>(p.splits));
+        const int64_t rows = M * Hq;
+        if (D == 64) {
+            hipLaunchKernelGGL((recompute_attention_kernel<64, true>), agrid, dim3(64 * kAttnWaves), 0, st, q16,
+                               k_plane, v_plane, chunk_idx_dev, attn, g, part_o, part_ml, per_split);
+            hipLaunchKernelGGL(attention_combine_kernel<64>, dim3(static_cast<uint32_t>((rows * 16 + 255) / 256)),
+                               dim3(256), 0, st, part_o, part_ml, attn, rows, p.splits);
+        } else {
+            hipLaunchKernelGGL((recompute_attention_kernel<128, true>), agrid, dim3(64 * kAttnWaves), 0, st, q16,
+                               k_plane, v_plane, chunk_idx_dev, attn, g, part_o, part_ml, per_split);
+            hipLaunchKernelGGL(attention_combine_kernel<128>, dim3(static_cast<uint32_t>((rows * 32 + 255) / 256)),
+                               dim3(256), 0, st, part_o, part_ml, attn, rows, p.splits);
+        }
+    } else {
+        const dim3 agrid(pair_blocks, static_cast<uint32_t>(Hkv));
+        if (D == 64)
+            hipLaunchKernelGGL((recompute_attention_kernel<64, false>), agrid, dim3(64 * kAttnWaves), 0, st, q16,
+                               k_plane, v_plane, chunk_idx_dev, attn, g, nullptr, nullptr, 0);
+        else
+            hipLaunchKernelGGL((recompute_attention_kernel<128, false>), agrid, dim3(64 * kAttnWaves), 0, st, q16,
+                               k_plane, v_plane, chunk_idx_dev, attn, g, nullptr, nullptr, 0);
+    }
     // 4. output projection + residual, feed-forward + residual
     if (int e = gemm(rc, M, dims->d_model, dq, attn, w->wo, xin, x1, false, "o")) return e;
     hipLaunchKernelGGL(rmsnorm_kernel, rows, dim3(256), 0, st, x1, static_cast<const _Float16*>(w->w_norm2), xn,

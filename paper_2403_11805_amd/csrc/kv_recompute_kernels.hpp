@@ -16,6 +16,7 @@ namespace kvs {
 typedef _Float16 rv8h_t __attribute__((ext_vector_type(8)));
 typedef _Float16 rv4h_t __attribute__((ext_vector_type(4)));
 typedef float rv16f_t __attribute__((ext_vector_type(16)));
+typedef float rv4f_t __attribute__((ext_vector_type(4)));
 typedef unsigned int ru4_t __attribute__((ext_vector_type(4)));
 
 // Global position of recomputed token m: chunks of T tokens, chunk_idx ascending.
@@ -162,12 +163,20 @@ struct AttnGeom {
 // are masked; a wavefront skips the tiles that lie entirely behind its last row,
 // and the output accumulators are rescaled only when some row's maximum moved.
 constexpr int kAttnWaves = 8;
+constexpr int kMaxSplits = 16;     // workgroups that may share the key range of a row block
 
-template <int D>
+//
+// SPLIT: with few recomputed rows there are too few workgroups to fill the chip and each walks
+// the whole key range alone.  The key tiles are then divided among gridDim.z workgroups per
+// (pairs, kv head); each writes the unnormalised output, running maximum and denominator of its
+// share (part_o [split][row][head][D], part_ml [split][row][head][2], binary32) and
+// attention_combine_kernel merges the shares in a fixed order.
+template <int D, bool SPLIT>
 __global__ __launch_bounds__(64 * kAttnWaves) void recompute_attention_kernel(
     const _Float16* __restrict__ q16, const _Float16* __restrict__ k_plane,
     const _Float16* __restrict__ v_plane, const int32_t* __restrict__ chunk_idx,
-    _Float16* __restrict__ out, AttnGeom g) {
+    _Float16* __restrict__ out, AttnGeom g, float* __restrict__ part_o, float* __restrict__ part_ml,
+    int tiles_per_split) {
     constexpr int KS = D / 16;
     constexpr int DB = D / 32;                      // 32-wide blocks of the head dimension
     constexpr int kRowPieces = D / 8;
@@ -187,7 +196,7 @@ __global__ __launch_bounds__(64 * kAttnWaves) void recompute_attention_kernel(
     // own: the workgroups of one kv head are placed on one XCD, so that its K/V planes are
     // fetched into one L2 only.  Needs n_kv_heads % 8 == 0, otherwise the plain order is kept.
     int kvh = blockIdx.y, bxi = blockIdx.x;
-    if (g.Hkv % 8 == 0) {
+    if (!SPLIT && g.Hkv % 8 == 0) {
         const int lin = blockIdx.y * gridDim.x + blockIdx.x;
         const int per_xcd = lin >> 3;                       // position among this XCD's workgroups
         kvh = (lin & 7) + 8 * (per_xcd / static_cast<int>(gridDim.x));
@@ -208,7 +217,9 @@ __global__ __launch_bounds__(64 * kAttnWaves) void recompute_attention_kernel(
     const int max_pos = valid ? global_position(chunk_idx, g.T, min(rb * 32 + 31, g.M - 1)) : -1;
     const int rb_hi = min(bx * kAttnWaves + kAttnWaves - 1, g.pairs - 1) / per;
     const int wg_max_pos = global_position(chunk_idx, g.T, min(rb_hi * 32 + 31, g.M - 1));
-    const int n_tiles = wg_max_pos / 32 + 1;
+    // key tiles [t_first, n_tiles) of this workgroup
+    const int t_first = SPLIT ? static_cast<int>(blockIdx.z) * tiles_per_split : 0;
+    const int n_tiles = SPLIT ? min(wg_max_pos / 32 + 1, t_first + tiles_per_split) : wg_max_pos / 32 + 1;
 
     rv8h_t qreg[KS];
     {
@@ -315,14 +326,35 @@ __global__ __launch_bounds__(64 * kAttnWaves) void recompute_attention_kernel(
         if (t + 3 < n_tiles) fetch(buf ^ 1, t + 3);
         __syncthreads();
     };
-    fetch(0, 0);
-    park(0, 0);
-    fetch(1, min(1, n_tiles - 1));
-    fetch(0, min(2, n_tiles - 1));
-    __syncthreads();
-    for (int t = 0; t < n_tiles; t += 2) {
-        step(t, 0);
-        if (t + 1 < n_tiles) step(t + 1, 1);
+    if (t_first < n_tiles) {            // uniform per workgroup
+        fetch(0, t_first);
+        park(0, 0);
+        fetch(1, min(t_first + 1, n_tiles - 1));
+        fetch(0, min(t_first + 2, n_tiles - 1));
+        __syncthreads();
+        for (int t = t_first; t < n_tiles; t += 2) {
+            step(t, 0);
+            if (t + 1 < n_tiles) step(t + 1, 1);
+        }
+    }
+    if constexpr (SPLIT) {
+        if (ok) {
+            // the share of this workgroup: an empty one has m = -inf, l = 0 and zeros
+            const int64_t row = (static_cast<int64_t>(blockIdx.z) * g.M + m) * g.Hq + head;
+            if (half == 0) {
+                part_ml[row * 2] = m_run;
+                part_ml[row * 2 + 1] = l_run;
+            }
+            float* dst = part_o + row * D;
+#pragma unroll
+            for (int b = 0; b < DB; ++b)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const rv4f_t o4 = {o_acc[b][4 * j], o_acc[b][4 * j + 1], o_acc[b][4 * j + 2], o_acc[b][4 * j + 3]};
+                    *reinterpret_cast<rv4f_t*>(dst + 32 * b + 8 * j + 4 * half) = o4;
+                }
+        }
+        return;
     }
     if (ok) {
         // o_acc[b][v]: head dimension 32*b + 8*(v/4) + 4*half + v%4 of this lane's query row
@@ -338,6 +370,57 @@ __global__ __launch_bounds__(64 * kAttnWaves) void recompute_attention_kernel(
                 *reinterpret_cast<rv4h_t*>(dst + 32 * b + 8 * j + 4 * half) = o4;
             }
     }
+}
+
+// Merges the shares of a split attention: out[row][head][:] = sum_s w_s o_s / sum_s w_s l_s with
+// w_s = 2^(m_s - max_s m_s), shares taken in ascending order.  One thread per 4 channels.
+template <int D>
+__global__ __launch_bounds__(256) void attention_combine_kernel(const float* __restrict__ part_o,
+                                                                const float* __restrict__ part_ml,
+                                                                _Float16* __restrict__ out, int64_t rows,
+                                                                int n_splits) {
+    constexpr int kQuads = D / 4;
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i >= rows * kQuads) return;
+    const int64_t row = i / kQuads;
+    const int quad = static_cast<int>(i % kQuads);
+    // all loads of a pass are issued before its arithmetic: up to kMaxSplits shares, a clamped
+    // index for the surplus slots (their weight is forced to zero)
+    float m_s[kMaxSplits], l_s[kMaxSplits];
+#pragma unroll
+    for (int s = 0; s < kMaxSplits; ++s) {
+        const int sc = s < n_splits ? s : n_splits - 1;
+        const float2 ml = *reinterpret_cast<const float2*>(part_ml + (sc * rows + row) * 2);
+        m_s[s] = s < n_splits ? ml.x : -INFINITY;
+        l_s[s] = ml.y;
+    }
+    float m_all = -INFINITY;
+#pragma unroll
+    for (int s = 0; s < kMaxSplits; ++s) m_all = fmaxf(m_all, m_s[s]);
+    float l_all = 0.0f;
+    rv4f_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+    for (int s0 = 0; s0 < kMaxSplits; s0 += 4) {
+        if (s0 >= n_splits) break;
+        rv4f_t o[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int sc = s0 + k < n_splits ? s0 + k : n_splits - 1;
+            o[k] = *reinterpret_cast<const rv4f_t*>(part_o + (sc * rows + row) * D + quad * 4);
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            // an empty share (m = -inf) and a surplus slot weigh nothing
+            const float w = m_s[s0 + k] == -INFINITY ? 0.0f : __builtin_amdgcn_exp2f(m_s[s0 + k] - m_all);
+            l_all += w * l_s[s0 + k];
+            acc += o[k] * w;
+        }
+    }
+    const float inv = 1.0f / l_all;                     // a row sees at least its own token
+    rv4h_t o4;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) o4[k] = static_cast<_Float16>(acc[k] * inv);
+    *reinterpret_cast<rv4h_t*>(out + row * D + quad * 4) = o4;
 }
 
 }  // namespace kvs
