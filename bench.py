@@ -705,7 +705,10 @@ def main():
         flops = 2.0 * path.R * g.N * g.D * g.L * g.Hq
         kernels["score"]["mfma_tflops"] = round(flops / kernels["score"]["ms"] / 1e9, 2)
         kernels["score"]["mfma_frac"] = round(kernels["score"]["mfma_tflops"] / MFMA_F16_PEAK_TFLOPS, 4)
-    names = {"compress": "compress_kernel", "swapin": "swapin_kernel", "score": "score_tiles_kernel"}
+    # a head with one block of query rows and >= 256 (layer, head) pairs is scored by score_head_kernel
+    one_block = g.Hq == g.Hkv and path.R <= 32 and g.L * g.Hkv >= 256
+    names = {"compress": "compress_kernel", "swapin": "swapin_kernel",
+             "score": "score_head_kernel" if one_block else "score_tiles_kernel"}
     dom = max(kernels, key=lambda k: kernels[k]["ms"])
     roofline = {"kernel": names[dom], "bound": "hbm", "achieved": kernels[dom]["hbm_gbps"],
                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": kernels[dom]["hbm_frac"],

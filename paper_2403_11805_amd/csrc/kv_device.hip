@@ -318,6 +318,24 @@ int32_t kv_score_chunks(const kv_shape_t* shape, const void* q, int32_t n_querie
 #define KV_SCORE_DIRECT(DD, NR) \
     hipLaunchKernelGGL((score_tiles_kernel<DD, NR>), grid, dim3(256), 0, st, qp, kp, g, ws)
     const int D = shape->head_dim;
+    // One block of query rows per head and at least one (layer, head) per CU: a workgroup scores a
+    // whole head, keeps the partials in LDS and writes the chunk masses itself (at most 40 KiB of
+    // LDS, so that four workgroups share a CU).
+    const uint64_t head_lds = (static_cast<uint64_t>(g.N / g.sb_tokens) * 32 + 2ull * g.n_runs * 32 + 4 * 5 * 32 + 64) *
+                              sizeof(float);
+    if (g.n_rb == 1 && g.L * g.Hkv >= 256 && head_lds <= 40960 && D <= 128) {
+        const dim3 hgrid(static_cast<uint32_t>(g.L * g.Hkv));
+        if (D == 64)
+            hipLaunchKernelGGL(score_head_kernel<64>, hgrid, dim3(256), head_lds, st, qp, kp, g, chunk_mass);
+        else
+            hipLaunchKernelGGL(score_head_kernel<128>, hgrid, dim3(256), head_lds, st, qp, kp, g, chunk_mass);
+        if (int rc = launch_status("score_head_kernel launch")) return rc;
+        const int n_chunks_h = g.N / g.T;
+        const float inv_norm_h = static_cast<float>(1.0 / (static_cast<double>(g.T) * g.L * g.Hq));
+        hipLaunchKernelGGL(score_density_kernel, dim3((n_chunks_h + 63) / 64), dim3(1024), 0, st, chunk_mass, density,
+                           g.L * g.Hq, n_chunks_h, inv_norm_h);
+        return launch_status("score_density_kernel launch");
+    }
     if (g.rg_per_wg > 1) {          // several row groups per kv head: two row blocks per wavefront
         if (D == 64) KV_SCORE_SHARED(64);
         else if (D == 128) KV_SCORE_SHARED(128);

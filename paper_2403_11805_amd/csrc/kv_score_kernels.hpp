@@ -574,6 +574,147 @@ __global__ __launch_bounds__(256, 2) void score_tiles_shared_kernel(const _Float
     }
 }
 
+// One workgroup per (layer, head) when a head has a single block of query rows and many heads
+// are scored (multi-head attention, R <= 32): the four wavefronts take the runs of tiles in
+// turn, the partial results stay in LDS, relative to ONE reference per (row, run), and the
+// workgroup itself turns them into the chunk masses.  No partials travel through HBM and no
+// combine launch is needed.  Dynamic LDS (floats), rows fastest:
+//   e_all [n_sb][32]   weighted sub-block sums relative to the run's final reference
+//   m_run, l_run [n_runs][32]
+//   tmp [4 wavefronts][5][32]   the slots tile_epilogue fills for one tile
+//   row_m, row_f [32]
+template <int D>
+__global__ __launch_bounds__(256, 4) void score_head_kernel(const _Float16* __restrict__ q,
+                                                         const _Float16* __restrict__ kv, ScoreGeom g,
+                                                         float* __restrict__ chunk_mass) {
+    constexpr int KS = D / 16;
+    extern __shared__ float score_head_lds[];
+    const int n_sub_tile = 32 / g.sb_tokens;
+    const int n_sb = g.n_tiles * n_sub_tile;
+    float* e_all = score_head_lds;
+    float* m_run_l = e_all + n_sb * 32;
+    float* l_run_l = m_run_l + g.n_runs * 32;
+    float* tmp = l_run_l + g.n_runs * 32;
+    float* row_m = tmp + 4 * 5 * 32;
+    float* row_f = row_m + 32;
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63;
+    const int lrow = lane & 31, half = lane >> 5;
+    const int l = blockIdx.x / g.Hkv, kvh = blockIdx.x % g.Hkv;
+    const int lh = l * g.Hq + kvh;                    // one query head per kv head
+    const int row = lrow < g.R ? lrow : -1;
+    float* tmp_m = tmp + wave * 5 * 32;
+    float* tmp_e = tmp_m + 32;
+    const ScoreWs no_ws = {nullptr, nullptr, nullptr, nullptr};
+
+    v8h_t qreg[KS];
+    {
+        const _Float16* qp = q + (static_cast<int64_t>(lh) * g.R + (row >= 0 ? row : 0)) * D + half * 8;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            v8h_t v = {0, 0, 0, 0, 0, 0, 0, 0};
+            if (row >= 0) v = *reinterpret_cast<const v8h_t*>(qp + ks * 16);
+            qreg[ks] = v;
+        }
+    }
+    const _Float16* kbase = kv + (static_cast<int64_t>(l) * 2 * g.Hkv + kvh) * g.N * D;
+    // K tiles are double-buffered in registers across the tiles and runs of this wavefront
+    v8h_t knext[KS];
+    {
+        const int t_first = min(wave * g.run_len, g.n_tiles - 1);
+        const _Float16* kp = kbase + static_cast<int64_t>(t_first * 32 + lrow) * D + half * 8;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) knext[ks] = *reinterpret_cast<const v8h_t*>(kp + ks * 16);
+    }
+    for (int run = wave; run < g.n_runs; run += 4) {
+        const int tile_begin = run * g.run_len;
+        const int tile_end = min(tile_begin + g.run_len, g.n_tiles);
+        float m_ref = -INFINITY, l_run = 0.0f;
+        for (int tile = tile_begin; tile < tile_end; ++tile) {
+            v8h_t kreg[KS];
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) kreg[ks] = knext[ks];
+            {   // the next tile of the run, or the first tile of this wavefront's next run
+                int nt = tile + 1;
+                if (nt >= tile_end) nt = min((run + 4) * g.run_len, g.n_tiles - 1);
+                const _Float16* kp = kbase + static_cast<int64_t>(nt * 32 + lrow) * D + half * 8;
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) knext[ks] = *reinterpret_cast<const v8h_t*>(kp + ks * 16);
+            }
+            v16f_t acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(kreg[ks], qreg[ks], acc, 0, 0, 0);
+            const float m_before = m_ref;
+            tile_epilogue(acc, g, no_ws, tile, row, lh, half, tile == tile_begin, m_ref, l_run, tmp_m, tmp_e);
+            // the lane that owns a row wrote its slots and reads them back: same lane, in order
+            if (half == 0 && row >= 0) {
+                const float m_t = tmp_m[lrow];
+                const float f = (m_t == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(m_t - m_ref);
+                for (int k = 0; k < n_sub_tile; ++k)
+                    e_all[(tile * n_sub_tile + k) * 32 + lrow] = tmp_e[k * 32 + lrow] * f;
+                if (tile != tile_begin && m_ref != m_before) {
+                    // the reference of this row moved: earlier sums of the run follow it
+                    const float r = (m_before == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(m_before - m_ref);
+                    for (int i = tile_begin * n_sub_tile; i < tile * n_sub_tile; ++i) e_all[i * 32 + lrow] *= r;
+                }
+            }
+        }
+        if (half == 0 && row >= 0) {
+            m_run_l[run * 32 + lrow] = m_ref;
+            l_run_l[run * 32 + lrow] = l_run;
+        }
+    }
+    __syncthreads();
+    // row reference and denominator over the runs, in ascending order
+    if (tid < 32 && tid < g.R) {
+        float M = -INFINITY;
+        for (int r = 0; r < g.n_runs; ++r) M = fmaxf(M, m_run_l[r * 32 + tid]);
+        float Lr = 0.0f;
+        for (int r = 0; r < g.n_runs; ++r) {
+            const float mi = m_run_l[r * 32 + tid];
+            if (mi != -INFINITY) Lr += l_run_l[r * 32 + tid] * __builtin_amdgcn_exp2f(mi - M);
+        }
+        row_m[tid] = M;
+        row_f[tid] = 1.0f / Lr;          // every row sees at least its own token
+    }
+    __syncthreads();
+    // one factor per (run, row) takes a sum from its run's reference to the normalised row
+    // (kept where the run's denominator was); rows beyond R get 0
+    for (int i = tid; i < g.n_runs * 32; i += 256) {
+        const int r = i & 31;
+        const float mi = m_run_l[i];
+        l_run_l[i] = (r < g.R && mi != -INFINITY) ? __builtin_amdgcn_exp2f(mi - row_m[r]) * row_f[r] : 0.0f;
+    }
+    __syncthreads();
+    // chunk masses: 32 lanes per chunk, lane <-> row, fixed-order sums, two chunks in flight
+    const int n_chunks = g.N / g.T;
+    const int sb_per_chunk = g.T / g.sb_tokens;
+    const int sb_per_run = g.run_len * n_sub_tile;
+    const int grp = tid >> 5, gl = tid & 31;
+    const bool live = gl < g.R;
+    for (int c = grp; c < n_chunks; c += 16) {
+        const int c2 = min(c + 8, n_chunks - 1);
+        float a = 0.0f, b = 0.0f;
+        for (int k = 0; k < sb_per_chunk; ++k) {
+            const int sa = c * sb_per_chunk + k, sb2 = c2 * sb_per_chunk + k;
+            // padding rows hold no sums: their factor is 0, the product must not be NaN
+            const float ea = live ? e_all[sa * 32 + gl] : 0.0f, eb = live ? e_all[sb2 * 32 + gl] : 0.0f;
+            a += ea * l_run_l[(sa / sb_per_run) * 32 + gl];
+            b += eb * l_run_l[(sb2 / sb_per_run) * 32 + gl];
+        }
+#pragma unroll
+        for (int o = 16; o >= 1; o >>= 1) {
+            a += __shfl_xor(a, o);
+            b += __shfl_xor(b, o);
+        }
+        if (gl == 0) {
+            chunk_mass[static_cast<int64_t>(lh) * n_chunks + c] = a;
+            if (c + 8 < n_chunks) chunk_mass[static_cast<int64_t>(lh) * n_chunks + c + 8] = b;
+        }
+    }
+}
+
 // One workgroup per (layer, head): global row maximum and denominator from
 // the per-run partials, then the chunk masses from the per-tile partials.
 __global__ __launch_bounds__(256) void score_combine_kernel(ScoreGeom g, ScoreWs ws,

@@ -97,6 +97,45 @@ def test_grouped_query_huge_logit_late_in_a_run(hot_token):
     np.testing.assert_allclose(d, d_want, rtol=RTOL, atol=1e-30)
 
 
+@pytest.mark.parametrize("geom,R", [
+    ((16, 16, 16, 64, 256, 16, 64), 32),     # 8 tiles: one run, three wavefronts idle
+    ((8, 32, 32, 128, 288, 8, 64), 7),       # 9 tiles (runs of 8 and 1), four sub-blocks per tile, 7 rows
+    ((4, 64, 64, 128, 1056, 32, 128), 20),   # 33 tiles: five runs, a wavefront with two of them
+    ((16, 16, 16, 64, 1120, 16, 64), 32),    # 35 tiles, the diagonal crosses the last two tiles' boundary
+])
+def test_many_heads_one_row_block(geom, R):
+    """At least 256 (layer, head) pairs with one block of query rows each: a workgroup scores a
+    whole head, partials in LDS, no combine launch."""
+    g = synth.Geometry(*geom)
+    ks, os_ = both_shapes(g)
+    kv = synth.make_kv(g, 27, "cpu", 1, 4.0)
+    q = (synth.make_q(g, 27, R).float() * 5).to(torch.float16)
+    for norm in (oracle.NORM_VISIBLE, oracle.NORM_NONE):
+        cm_want, d_want = oracle.score_chunks(os_, q.numpy(), kv.numpy(), norm)
+        cm, d = gpu_score(ks, q.to(DEV), kv.to(DEV), norm)
+        assert_close(cm, cm_want, "chunk_mass")
+        assert_close(d, d_want, "density")
+        if norm == oracle.NORM_NONE:
+            np.testing.assert_allclose(cm.sum(axis=2), R, rtol=1e-5)
+
+
+@pytest.mark.parametrize("hot_token", [5, 200, 300, 1000, 1023])
+def test_many_heads_huge_logit_moves_a_run_reference(hot_token):
+    """A key far above the reference taken from its run's first tile: the tile is redone against
+    its own maximum and the sums the run has already parked in LDS follow the new reference."""
+    g = synth.Geometry(16, 16, 16, 128, 1024, 16, 64)
+    ks, os_ = both_shapes(g)
+    kv = (synth.make_kv(g, 31, "cpu").float() * 0.05).to(torch.float16)
+    kv[:, 0, :, hot_token] = 20.0
+    q = torch.full((16, 16, 32, 128), 2.0, dtype=torch.float16)
+    cm_want, d_want = oracle.score_chunks(os_, q.numpy(), kv.numpy(), oracle.NORM_NONE)
+    cm, d = gpu_score(ks, q.to(DEV), kv.to(DEV), oracle.NORM_NONE)
+    if hot_token <= g.N - 32:        # every row sees the hot key and gives it all its mass
+        assert cm[3, 5, hot_token // 16] == pytest.approx(32.0, rel=1e-5)
+    np.testing.assert_allclose(cm, cm_want, rtol=RTOL, atol=1e-30)
+    np.testing.assert_allclose(d, d_want, rtol=RTOL, atol=1e-30)
+
+
 def test_zero_queries_closed_form():
     """Q = 0 gives uniform attention: harmonic-number column masses (checked against
     the closed form directly, no oracle involved)."""
