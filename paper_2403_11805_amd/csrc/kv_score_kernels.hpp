@@ -12,8 +12,10 @@
 // local maximum, per (row, sub-block of min(T,32) tokens) the weighted sum, and
 // per (row, run) the running maximum and denominator of the run (kept in
 // registers, flash-attention style).  Kernel 2 combines them per (layer, head)
-// into chunk masses; kernel 3 averages over layers and heads.  All reductions
-// run in a fixed order: results are deterministic.
+// into chunk masses; kernel 3 averages over layers and heads.  Where a head has
+// one block of query rows and there are many heads, score_head_kernel does the
+// work of kernels 1 and 2 in one workgroup per head, with the partials in LDS.
+// All reductions run in a fixed order: results are deterministic.
 #pragma once
 
 #include <hip/hip_runtime.h>
