@@ -473,7 +473,7 @@ class Lctru:
         chunk = np.empty(max(cap, 1), dtype=np.int32)
         n = ctypes.c_int32()
         rc = fn(self._h, *head, _hp(ctx), _hp(chunk), cap, ctypes.byref(n))
-        return rc, [(int(ctx[i]), int(chunk[i])) for i in range(n.value)]
+        return rc, list(zip(ctx[:n.value].tolist(), chunk[:n.value].tolist()))
 
     def order(self):
         rc, out = self._lists(lib().kv_lctru_order)
