@@ -312,9 +312,11 @@ def run_pool(wl, args, dev):
             k_ms.append(ev0.elapsed_time(ev1)); wall_ms.append((t2 - t0) * 1e3); host_ms.append((t1 - t0) * 1e3)
             packed_b = int(sum(int(ctx_off[c][i + 1] - ctx_off[c][i]) for i in sel))
             moved.append(packed_b + n_sel * g.elements * 2 // g.n_chunks)
-    order_t0 = time.perf_counter()
-    eviction_order = queue.order()
-    order_ms = (time.perf_counter() - order_t0) * 1e3
+    order_ms = 1e9
+    for _ in range(3):                     # the first call pays one-off interpreter costs
+        order_t0 = time.perf_counter()
+        eviction_order = queue.order()
+        order_ms = min(order_ms, (time.perf_counter() - order_t0) * 1e3)
     queue.close()
     sel_fp16 = n_sel * g.elements * 2 // g.n_chunks
     gbps = float(np.mean(moved)) / float(np.mean(k_ms)) / 1e6
