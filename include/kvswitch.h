@@ -18,9 +18,12 @@
  *    "host" pointers ordinary host memory, "pinned" host memory obtained from
  *    hipHostMalloc (or torch pin_memory).  The library keeps no pointer after a
  *    call returns and allocates no device memory (kv_swapin_pinned and
- *    kv_swapout_aot create and destroy a few HIP events per call).
+ *    kv_swapout_aot create and destroy a few HIP events per call; a
+ *    kv_recompute_t handle owns the GEMM library's handle, with that library's
+ *    own device workspace, until it is destroyed).
  *  - Device entry points only enqueue work on the caller's hipStream_t (passed
- *    as void*, NULL = the default stream) and never synchronise.  Host
+ *    as void*, NULL = the default stream) and never synchronise (the one
+ *    exception, kv_recompute_tune, says so).  Host
  *    arguments are validated before anything is enqueued: an error return
  *    means nothing was launched and nothing written.  Device-side lists
  *    (bits, offsets, gather lists) are trusted: the caller builds them with
@@ -86,7 +89,7 @@ typedef enum {
     KV_OK      = 0,
     KV_EINVAL  = -1,  /* NULL pointer or argument out of range            */
     KV_ESHAPE  = -2,  /* kv_shape_t violates the requirements below        */
-    KV_EBITS   = -3,  /* a bit-width outside {16,8,4,2}                    */
+    KV_EBITS   = -3,  /* a bit-width outside {16,8,4,2} ({8,4,2,1}: int8 formats) */
     KV_EINDEX  = -4,  /* chunk index out of range, unsorted or repeated    */
     KV_ENOMEM  = -5,  /* capacity too small / not enough evictable bytes   */
     KV_EHIP    = -6   /* a HIP runtime call failed (text has the HIP error) */
@@ -99,7 +102,7 @@ typedef enum {
  * chunk_tokens <= 1024; chunk_tokens * head_dim % 512 == 0;
  * (chunk_tokens * head_dim / group) % 4 == 0 (keeps every record section
  * 16-byte aligned).
- * Format 1 instead of the group rules: head_dim a power of two in [64, 1024];
+ * Formats 1 and 2 instead of the group rules: head_dim a power of two in [64, 1024];
  * chunk_tokens * head_dim in {1024, 2048, 4096} (one wavefront holds a slab);
  * group is ignored.  Scoring (kv_score_chunks) needs format 0. */
 typedef struct {
