@@ -392,6 +392,16 @@ def run_pool(wl, args, dev):
             k_ms.append(ev0.elapsed_time(ev1)); wall_ms.append((t2 - t0) * 1e3); host_ms.append((t1 - t0) * 1e3)
             packed_b = int(sum(int(ctx_off[c][i + 1] - ctx_off[c][i]) for i in sel))
             moved.append(packed_b + n_sel * g.elements * 2 // g.n_chunks)
+    # the Fault primitive: Load of one chunk, issue to completion as the caller sees it
+    fault_wall = []
+    for it in range(64):
+        c = order_ctx[it % len(order_ctx)]
+        one = subsets[it % len(subsets)][it % n_sel:it % n_sel + 1]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        kvs.kv_load_chunks(shape, pools[c], ctx_off[c], ctx_bits[c], one, caches[it % len(caches)])
+        torch.cuda.synchronize()
+        fault_wall.append((time.perf_counter() - t0) * 1e3)
     order_ms = 1e9
     for _ in range(3):                     # the first call pays one-off interpreter costs
         order_t0 = time.perf_counter()
@@ -414,6 +424,8 @@ def run_pool(wl, args, dev):
                       "p99": round(pctl(wall_ms, 99), 4), "host_part_mean": round(float(np.mean(host_ms)), 4)},
         "swapin_kernel_ms": {"mean": round(float(np.mean(k_ms)), 4), "p50": round(pctl(k_ms, 50), 4),
                              "p99": round(pctl(k_ms, 99), 4)},
+        "fault_ms": {"p50": round(pctl(fault_wall[8:], 50), 4), "p99": round(pctl(fault_wall[8:], 99), 4),
+                     "note": "kv_load_chunks of one chunk (8 MiB of fp16 cache), call to completion"},
         "lctru": {"entries": len(eviction_order), "order_ms": round(order_ms, 3)},
         "pool_build_s": round(t_build, 2),
         "roofline": {"kernel": "swapin_batch_kernel", "bound": "hbm", "achieved": round(gbps, 1),
