@@ -255,6 +255,18 @@ int32_t kv_compress_chunks(const kv_shape_t* shape, const void* kv,
                            const uint8_t* bits_dev, const uint64_t* off_dev,
                            void* packed_out, void* stream);
 
+/* The same for n_sel listed chunks only (the chunks a call has added or changed are
+ * compressed and swapped out ahead of time when the call returns, Sec. 3.4 i): record
+ * i of the list is written at off_dev[idx_i] with width bits_dev[idx_i]; other records
+ * of the pool are not touched.
+ *   chunk_idx_dev dev i32 [n_sel], distinct indices in [0, n_chunks) (trusted like the
+ *   other device lists); bits_dev / off_dev as above, indexed by chunk.  n_sel == 0
+ *   is a no-op. */
+int32_t kv_compress_selected(const kv_shape_t* shape, const void* kv,
+                             const uint8_t* bits_dev, const uint64_t* off_dev,
+                             const int32_t* chunk_idx_dev, int32_t n_sel,
+                             void* packed_out, void* stream);
+
 /* Load primitive, data movement (Sec. 3.1 primitive 3; Sec. 3.3): unpack and
  * dequantise the n_sel listed records into tokens [dst_tok[j], dst_tok[j] +
  * chunk_tokens) of every slab of kv_out; other tokens are untouched.

@@ -80,6 +80,7 @@ _SIGNATURES = {
     "kv_score_chunks": (_i32, [_vp, _vp, _i32, _vp, _i32, _vp, _u64, _vp, _vp, _vp]),
     "kv_compress_chunks": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp]),
     "kv_swapin_chunks": (_i32, [_vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp]),
+    "kv_compress_selected": (_i32, [_vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp]),
     "kv_load_chunks": (_i32, [_vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp]),
     "kv_plan_chunks_dev": (_i32, [_vp, _vp, _i32, _i32, _i32, _vp, _vp, _vp, _vp]),
     "kv_swapin_pinned": (_i32, [_vp, _vp, _vp, _vp, _vp, _i32, _vp, _u64, _i32, _vp, _vp, _vp]),
@@ -351,6 +352,21 @@ def kv_compress_chunks(shape: Shape, kv: torch.Tensor, bits_dev: torch.Tensor,
     _check(lib().kv_compress_chunks(ctypes.byref(s), _dev(kv, shape.cache_dtype),
                                     _dev(bits_dev, torch.uint8), _dev(off_dev, torch.int64),
                                     _dev(packed_out, torch.uint8), _stream(stream)))
+
+
+def kv_compress_selected(shape: Shape, kv: torch.Tensor, bits_dev: torch.Tensor, off_dev: torch.Tensor,
+                         chunk_idx_dev: torch.Tensor, packed_out: torch.Tensor, stream=None) -> None:
+    s = shape.c()
+    if tuple(kv.shape) != shape.kv_dims:
+        raise ValueError("kv must be [L][2][Hkv][N][D]")
+    if bits_dev.numel() != shape.n_chunks or off_dev.numel() != shape.n_chunks + 1:
+        raise ValueError("need bits of n_chunks entries and off of n_chunks + 1")
+    n_sel = chunk_idx_dev.numel()
+    if n_sel == 0:
+        return
+    _check(lib().kv_compress_selected(ctypes.byref(s), _dev(kv, shape.cache_dtype), _dev(bits_dev, torch.uint8),
+                                      _dev(off_dev, torch.int64), _dev(chunk_idx_dev, torch.int32), n_sel,
+                                      _dev(packed_out, torch.uint8), _stream(stream)))
 
 
 def kv_plan_chunks_dev(shape: Shape, density_dev: torch.Tensor, num8: int, num4: int, den: int,

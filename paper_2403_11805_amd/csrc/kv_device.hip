@@ -145,21 +145,18 @@ int launch_swapin_batch(const kv_shape_t& shape, const QuantGeom& g, int ppl, co
 
 extern "C" {
 
-int32_t kv_compress_chunks(const kv_shape_t* shape, const void* kv, const uint8_t* bits_dev,
-                           const uint64_t* off_dev, void* packed_out, void* stream) {
-    if (int rc = check_shape(shape)) return rc;
-    if (!kv || !bits_dev || !off_dev || !packed_out) return fail(KV_EINVAL, "NULL device pointer");
-    if (!aligned(kv, 16) || !aligned(packed_out, 16) || !aligned(off_dev, 8))
-        return fail(KV_EINVAL, "kv/packed_out must be 16-byte aligned, off_dev 8-byte aligned");
+// Compression of all chunks (chunk_list NULL, n_units = n_chunks) or of the listed ones.
+static int32_t compress_launch(const kv_shape_t* shape, const void* kv, const uint8_t* bits_dev,
+                               const uint64_t* off_dev, const int32_t* chunk_list, int32_t n_units,
+                               void* packed_out, void* stream) {
     const bool i8 = is_i8(*shape);
     int ppl = 0;
     QuantGeom g = i8 ? quant_geom_i8(*shape, &ppl) : quant_geom(*shape);
     if (!i8) ppl = plan_tasks(&g, kCompressPiecesPerLane);
-    const int32_t n_chunks = shape->n_tokens / shape->chunk_tokens;
-    g.record_major = n_chunks <= 65535 ? 1 : 0;
+    g.record_major = n_units <= 65535 ? 1 : 0;
     if (!g.record_major && g.slabs > 65535)
         return fail(KV_ESHAPE, "more than 65535 chunks and slabs exceed the launch grid");
-    const dim3 grid = task_grid(g, n_chunks);
+    const dim3 grid = task_grid(g, n_units);
     hipStream_t st = static_cast<hipStream_t>(stream);
     const u4_t* src = static_cast<const u4_t*>(kv);
     uint8_t* dst = static_cast<uint8_t*>(packed_out);
@@ -169,19 +166,42 @@ int32_t kv_compress_chunks(const kv_shape_t* shape, const void* kv, const uint8_
         do {                                                                                                 \
             if (v.half_meta)                                                                                 \
                 hipLaunchKernelGGL((compress_i8_kernel<NDW, GPL, true>), grid, dim3(256), 0, st, src, bits_dev, \
-                                   off_dev, dst, g, v, n_chunks);                                            \
+                                   off_dev, dst, g, v, n_units, chunk_list);                                 \
             else                                                                                             \
                 hipLaunchKernelGGL((compress_i8_kernel<NDW, GPL, false>), grid, dim3(256), 0, st, src, bits_dev, \
-                                   off_dev, dst, g, v, n_chunks);                                            \
+                                   off_dev, dst, g, v, n_units, chunk_list);                                 \
         } while (0)
         KV_I8_DISPATCH(ppl, shape->head_dim, KV_LAUNCH_I8);
 #undef KV_LAUNCH_I8
         return launch_status("compress_i8_kernel launch");
     }
-    if (ppl == 4) hipLaunchKernelGGL(compress_kernel<4>, grid, dim3(256), 0, st, src, bits_dev, off_dev, dst, g, n_chunks);
-    else if (ppl == 2) hipLaunchKernelGGL(compress_kernel<2>, grid, dim3(256), 0, st, src, bits_dev, off_dev, dst, g, n_chunks);
-    else hipLaunchKernelGGL(compress_kernel<1>, grid, dim3(256), 0, st, src, bits_dev, off_dev, dst, g, n_chunks);
+    if (ppl == 4) hipLaunchKernelGGL(compress_kernel<4>, grid, dim3(256), 0, st, src, bits_dev, off_dev, dst, g, n_units, chunk_list);
+    else if (ppl == 2) hipLaunchKernelGGL(compress_kernel<2>, grid, dim3(256), 0, st, src, bits_dev, off_dev, dst, g, n_units, chunk_list);
+    else hipLaunchKernelGGL(compress_kernel<1>, grid, dim3(256), 0, st, src, bits_dev, off_dev, dst, g, n_units, chunk_list);
     return launch_status("compress_kernel launch");
+}
+
+int32_t kv_compress_chunks(const kv_shape_t* shape, const void* kv, const uint8_t* bits_dev,
+                           const uint64_t* off_dev, void* packed_out, void* stream) {
+    if (int rc = check_shape(shape)) return rc;
+    if (!kv || !bits_dev || !off_dev || !packed_out) return fail(KV_EINVAL, "NULL device pointer");
+    if (!aligned(kv, 16) || !aligned(packed_out, 16) || !aligned(off_dev, 8))
+        return fail(KV_EINVAL, "kv/packed_out must be 16-byte aligned, off_dev 8-byte aligned");
+    return compress_launch(shape, kv, bits_dev, off_dev, nullptr, shape->n_tokens / shape->chunk_tokens,
+                           packed_out, stream);
+}
+
+int32_t kv_compress_selected(const kv_shape_t* shape, const void* kv, const uint8_t* bits_dev,
+                             const uint64_t* off_dev, const int32_t* chunk_idx_dev, int32_t n_sel,
+                             void* packed_out, void* stream) {
+    if (int rc = check_shape(shape)) return rc;
+    const int32_t n_chunks = shape->n_tokens / shape->chunk_tokens;
+    if (n_sel < 0 || n_sel > n_chunks) return fail(KV_EINVAL, "n_sel %d outside [0,%d]", n_sel, n_chunks);
+    if (n_sel == 0) return KV_OK;
+    if (!kv || !bits_dev || !off_dev || !chunk_idx_dev || !packed_out) return fail(KV_EINVAL, "NULL device pointer");
+    if (!aligned(kv, 16) || !aligned(packed_out, 16) || !aligned(off_dev, 8) || !aligned(chunk_idx_dev, 4))
+        return fail(KV_EINVAL, "kv/packed_out must be 16-byte aligned, off_dev 8-byte, chunk_idx_dev 4-byte aligned");
+    return compress_launch(shape, kv, bits_dev, off_dev, chunk_idx_dev, n_sel, packed_out, stream);
 }
 
 int32_t kv_swapin_chunks(const kv_shape_t* shape, const void* packed, const uint64_t* src_off_dev,

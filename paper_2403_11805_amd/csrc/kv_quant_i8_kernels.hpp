@@ -234,13 +234,15 @@ __global__ __launch_bounds__(256) void compress_i8_kernel(const u4_t* __restrict
                                                           const uint8_t* __restrict__ bits,
                                                           const uint64_t* __restrict__ off,
                                                           uint8_t* __restrict__ packed, QuantGeom g,
-                                                          I8View v, int32_t n_chunks) {
+                                                          I8View v, int32_t n_chunks,
+                                                          const int32_t* __restrict__ chunk_list) {
     constexpr int PPL = NDW / 4;
     __shared__ __align__(16) uint8_t lds[kWavesPerBlock][NDW * 256 + NDW * 128];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6));
     int chunk, slab, p0;
     if (!wave_task(g, n_chunks, PPL, chunk, slab, p0)) return;
+    if (chunk_list) chunk = chunk_list[chunk];          // only the listed chunks
     const u4_t* src = kv + (static_cast<uint64_t>(slab) * g.n_tokens +
                             static_cast<uint64_t>(chunk) * g.chunk_tokens) * g.row_pieces;
     u4_t raw[PPL];

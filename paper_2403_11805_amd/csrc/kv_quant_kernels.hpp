@@ -233,15 +233,18 @@ __device__ __forceinline__ void compress_piece(const u4_t& raw, uint8_t* __restr
 
 // Grid (ceil(n_chunks * tpu / 4), slabs) or, record-major, (ceil(slabs * tpu / 4),
 // n_chunks); block 256 threads = 4 wavefront tasks of PPL * 64 pieces each.
+// chunk_list (may be NULL): the n_chunks chunk indices to compress instead of 0..n_chunks-1.
 template <int PPL>
 __global__ __launch_bounds__(64 * kWavesPerBlock) void compress_kernel(const u4_t* __restrict__ kv,
                                                        const uint8_t* __restrict__ bits,
                                                        const uint64_t* __restrict__ off,
                                                        uint8_t* __restrict__ packed, QuantGeom g,
-                                                       int32_t n_chunks) {
+                                                       int32_t n_chunks,
+                                                       const int32_t* __restrict__ chunk_list) {
     const int lane = threadIdx.x & 63;
     int chunk, slab, p0;
     if (!wave_task(g, n_chunks, PPL, chunk, slab, p0)) return;
+    if (chunk_list) chunk = chunk_list[chunk];          // only the listed chunks (uniform: a scalar load)
     const u4_t* src = kv + (static_cast<uint64_t>(slab) * g.n_tokens +
                             static_cast<uint64_t>(chunk) * g.chunk_tokens) * g.row_pieces;
     u4_t raw[PPL];

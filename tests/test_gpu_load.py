@@ -82,3 +82,35 @@ def test_bad_list_is_refused_before_anything_is_written():
     kvs.kv_load_chunks(ks, packed_dev, off, bits, [], out)           # nothing to load: a no-op
     torch.cuda.synchronize()
     assert bool((out.view(torch.int16) == SENTINEL).all())
+
+
+@pytest.mark.parametrize("fmt", [0, 1, 2])
+def test_compress_selected_writes_only_the_listed_records(fmt):
+    """kv_compress_selected (the chunks a call added, compressed when it returns, Sec. 3.4 i): the
+    listed records equal the oracle's bit for bit, every other byte of the pool keeps its value."""
+    g = synth.Geometry(2, 2, 2, 128, 1280, 16, 64)              # 80 chunks
+    ks, os_ = both_shapes(g, fmt)
+    if fmt == 0:
+        kv_host = synth.make_kv(g, 13, "cpu", 1, 10.0).numpy()
+        bits = synth.draw_bits_uniform(g.n_chunks, 13, widths=(16, 8, 4, 2)).numpy()
+    else:
+        kv_host = synth.make_kv_i8(g, 13).numpy()
+        bits = synth.draw_bits_uniform(g.n_chunks, 13, widths=(8, 4, 2, 1)).numpy()
+    off = kvs.kv_chunk_offsets(ks, bits)
+    want = oracle.compress_chunks(os_, kv_host, bits, off) if fmt == 0 else oracle.compress_chunks_i8(os_, kv_host, bits, off)
+    kv_dev = torch.from_numpy(kv_host).to(DEV)
+    bits_d = torch.from_numpy(bits).to(DEV)
+    off_d = torch.from_numpy(off.view(np.int64)).to(DEV)
+    for idx in ([79], [0, 1, 2], [5, 17, 18, 40, 77], list(range(0, 80, 3)), [63, 2, 30]):   # any order
+        pool = torch.full((int(off[-1]) + 64,), 0xA5, dtype=torch.uint8, device=DEV)
+        kvs.kv_compress_selected(ks, kv_dev, bits_d, off_d, torch.tensor(idx, dtype=torch.int32, device=DEV), pool)
+        torch.cuda.synchronize()
+        got = pool.cpu().numpy()
+        expect = np.full(len(got), 0xA5, dtype=np.uint8)
+        for i in idx:
+            expect[int(off[i]):int(off[i + 1])] = want[int(off[i]):int(off[i + 1])]
+        assert np.array_equal(got, expect), f"chunks {idx}: {(got != expect).sum()} pool bytes differ"
+    pool = torch.full((int(off[-1]),), 0xA5, dtype=torch.uint8, device=DEV)
+    kvs.kv_compress_selected(ks, kv_dev, bits_d, off_d, torch.empty(0, dtype=torch.int32, device=DEV), pool)
+    torch.cuda.synchronize()
+    assert bool((pool == 0xA5).all())

@@ -178,6 +178,9 @@ def test_device_entry_points_validate_before_touching_the_gpu():
     fake = ctypes.c_void_p(4096)         # never dereferenced: the fractions are refused first
     for fr in ((1, 1, 0), (-1, 1, 3), (1, -1, 3), (2, 2, 3)):
         assert L.kv_plan_chunks_dev(ctypes.byref(s), fake, *fr, fake, fake, fake, None) == binding.KV_EINVAL
+    assert L.kv_compress_selected(ctypes.byref(s), None, None, None, None, 3, None, None) == binding.KV_EINVAL
+    assert L.kv_compress_selected(ctypes.byref(s), None, None, None, None, 0, None, None) == binding.KV_OK
+    assert L.kv_compress_selected(ctypes.byref(s), None, None, None, None, 33, None, None) == binding.KV_EINVAL
     assert L.kv_load_chunks(ctypes.byref(s), None, None, None, None, 3, None, None) == binding.KV_EINVAL
     assert L.kv_load_chunks(ctypes.byref(s), None, None, None, None, 0, None, None) == binding.KV_OK
     off = (ctypes.c_uint64 * 33)(*range(0, 33 * 4096, 4096))
