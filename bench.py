@@ -696,7 +696,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="llama2-7b-4k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--format", choices=("f16", "i8", "i8h"), default="f16",
@@ -797,8 +797,8 @@ def main():
     for k, v in sums.items():
         ms = float(np.mean(v))
         gbps = alg[k] / ms / 1e6
-        kernels[k] = {"ms": round(ms, 4), "ms_min": round(float(np.min(v)), 4),
-                      "algorithmic_bytes": alg[k], "hbm_gbps": round(gbps, 1),
+        kernels[k] = {"ms": round(ms, 4), "ms_median": round(float(np.median(v)), 4),
+                      "ms_min": round(float(np.min(v)), 4), "algorithmic_bytes": alg[k], "hbm_gbps": round(gbps, 1),
                       "hbm_frac": round(gbps / HBM_PEAK_GBPS, 4),
                       "fp16_equiv_gbps": round(cache_bytes / ms / 1e6, 1)}
     if path.R:
