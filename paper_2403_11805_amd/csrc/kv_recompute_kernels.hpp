@@ -15,6 +15,7 @@ namespace kvs {
 
 typedef _Float16 rv8h_t __attribute__((ext_vector_type(8)));
 typedef _Float16 rv4h_t __attribute__((ext_vector_type(4)));
+typedef short rv4s_t __attribute__((ext_vector_type(4)));
 typedef float rv16f_t __attribute__((ext_vector_type(16)));
 typedef float rv4f_t __attribute__((ext_vector_type(4)));
 typedef unsigned int ru4_t __attribute__((ext_vector_type(4)));
@@ -157,9 +158,8 @@ struct AttnGeom {
 // index is permuted the same way on both operands).  The eight wavefronts of a
 // workgroup take eight consecutive pairs of ONE kv head, so K and V tiles are
 // fetched once per workgroup (coalesced 16-byte loads, two tiles ahead) and shared
-// through LDS: K with its row pieces permuted by the row number, V transposed
-// (token groups of a row permuted by the row's channel block, which spreads the
-// 2-byte transposing writes over the banks).  Tokens after a row's global position
+// through LDS: K with its row pieces permuted by the row number, V in cache order and
+// read through the LDS transpose read.  Tokens after a row's global position
 // are masked; a wavefront skips the tiles that lie entirely behind its last row,
 // and the output accumulators are rescaled only when some row's maximum moved.
 constexpr int kAttnWaves = 8;
@@ -184,10 +184,14 @@ __global__ __launch_bounds__(64 * kAttnWaves) void recompute_attention_kernel(
     constexpr int kTilePieces = 32 * kRowPieces;    // 16-byte pieces of a K (or V) tile
     constexpr int kPer = (kTilePieces + kThreads - 1) / kThreads;
     __shared__ ru4_t ktile[2][32 * kRowPieces];
-    __shared__ __align__(16) _Float16 vt[2][D * 32];       // [channel][token], 64 bytes per channel
+    // V stays in cache order, [token][channel] with 32 bytes of padding per token row; the
+    // operand of O^T += V^T P^T (a channel per lane, tokens along the contraction) is taken with
+    // the LDS transpose read (ds_read_b64_tr_b16): the 16 lanes of a group hand in the sixteen
+    // 8-byte pieces of a 4-token x 16-channel block, row by row, and lane i receives the four
+    // tokens of channel i.  The padding puts the four token rows of a block on different banks.
+    constexpr int kVPitch = D + 16;
+    __shared__ __align__(16) _Float16 vt[2][32 * kVPitch];
     auto swz = [](int r) __attribute__((always_inline)) { return D == 64 ? (r >> 1) & 7 : r & 15; };
-    // token t of channel d sits at vt[d * 32 + (t ^ vswz(d))]: groups of 4 tokens stay together
-    auto vswz = [](int d) __attribute__((always_inline)) { return ((d >> 3) & 7) << 2; };
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
@@ -251,9 +255,7 @@ __global__ __launch_bounds__(64 * kAttnWaves) void recompute_attention_kernel(
             const int p = min(i * kThreads + tid, kTilePieces - 1);
             const int r = p / kRowPieces, c = p % kRowPieces;
             ktile[buf][r * kRowPieces + (c ^ swz(r))] = kst[set][i];
-            const rv8h_t v = __builtin_bit_cast(rv8h_t, vst[set][i]);
-#pragma unroll
-            for (int j = 0; j < 8; ++j) vt[buf][(c * 8 + j) * 32 + (r ^ vswz(c * 8 + j))] = v[j];
+            *reinterpret_cast<ru4_t*>(&vt[buf][r * kVPitch + c * 8]) = vst[set][i];
         }
     };
 
@@ -311,13 +313,17 @@ __global__ __launch_bounds__(64 * kAttnWaves) void recompute_attention_kernel(
             // 16*st + 8 + 4*half + e - 4: the order of acc[8*st .. 8*st+7] on the P side
 #pragma unroll
             for (int b = 0; b < DB; ++b) {
-                const int d = 32 * b + lrow;
-                const _Float16* vrow = &vt[buf][d * 32];
+                // this lane's piece of the block of its 16-lane group: token row (lane % 16) / 4, channels
+                // 32 b + 16 (group % 2) + 4 (lane % 4) ..; the read returns channel 32 b + lane % 32
+                const _Float16* vblk = &vt[buf][((lane & 15) >> 2) * kVPitch + 32 * b + 16 * ((lane >> 4) & 1) + 4 * (lane & 3)];
 #pragma unroll
                 for (int st = 0; st < 2; ++st) {
-                    const rv4h_t lo = *reinterpret_cast<const rv4h_t*>(vrow + ((16 * st + 4 * half) ^ vswz(d)));
-                    const rv4h_t hi = *reinterpret_cast<const rv4h_t*>(vrow + ((16 * st + 8 + 4 * half) ^ vswz(d)));
-                    const rv8h_t a = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                    const rv4s_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        (__attribute__((address_space(3))) rv4s_t*)(vblk + (16 * st + 4 * half) * kVPitch));
+                    const rv4s_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        (__attribute__((address_space(3))) rv4s_t*)(vblk + (16 * st + 8 + 4 * half) * kVPitch));
+                    const rv4h_t lo_h = __builtin_bit_cast(rv4h_t, lo), hi_h = __builtin_bit_cast(rv4h_t, hi);
+                    const rv8h_t a = {lo_h[0], lo_h[1], lo_h[2], lo_h[3], hi_h[0], hi_h[1], hi_h[2], hi_h[3]};
                     o_acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, pb[st], o_acc[b], 0, 0, 0);
                 }
             }
