@@ -154,3 +154,46 @@ def test_long_cache_positions_near_32768():
     assert np.array_equal(got[0][:, :, keep].view(np.uint16), kv[0].numpy()[:, :, keep].view(np.uint16))
     err = close(x_out.cpu().numpy(), y_ref, 1e-2, 1e-2, "layer output")
     assert err < 3e-3
+
+
+def test_layer_chain_replayed_from_a_hip_graph():
+    """kv_recompute_layer allocates nothing and never synchronises, the GEMM library included: two
+    chained layers captured in a HIP graph give, on every replay, the bits of the eager run."""
+    L, Hkv, Hq, D, N, T, d_model, d_ff = 2, 2, 4, 128, 512, 16, 512, 1024
+    shape = kvs.Shape(L, Hkv, Hq, D, N, T, 64)
+    dims = binding.LayerDims(d_model, d_ff)
+    w = [{k: v.to(DEV) for k, v in synth.make_layer_weights(d_model, Hq, Hkv, D, d_ff, 53, layer=l).items()}
+         for l in range(L)]
+    missing = [1, 2, 9, 30]
+    idx = torch.tensor(missing, dtype=torch.int32, device=DEV)
+    kv0 = synth.make_kv(synth.Geometry(L, Hkv, Hq, D, N, T, 64), 53, DEV)
+    kv = kv0.clone()
+    x0 = synth.make_hidden(len(missing) * T, d_model, 53, DEV)
+    hid = [torch.empty_like(x0), torch.empty_like(x0)]
+    ws = torch.empty(kvs.kv_recompute_workspace_bytes(shape, dims, len(missing)), dtype=torch.uint8, device=DEV)
+    rc = kvs.Recompute()
+
+    def chain():
+        for l in range(L):
+            rc.layer(shape, dims, w[l], l, idx, x0 if l == 0 else hid[l & 1], kv, hid[(l + 1) & 1], ws)
+
+    chain()
+    torch.cuda.synchronize()
+    y_ref, kv_ref = hid[L & 1].clone(), kv.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        chain()                                     # warm-up on the capture stream
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        chain()
+    for rep in range(3):
+        kv.copy_(kv0)
+        hid[0].zero_(); hid[1].zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(hid[L & 1].view(torch.int16), y_ref.view(torch.int16)), f"replay {rep}: output differs"
+        assert torch.equal(kv.view(torch.int16), kv_ref.view(torch.int16)), f"replay {rep}: cache differs"
+    rc.close()
