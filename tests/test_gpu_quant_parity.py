@@ -222,3 +222,26 @@ def test_more_chunks_than_a_grid_dimension():
     bits = synth.draw_bits_uniform(g.n_chunks, 21, widths=(16, 8, 4, 2)).numpy()
     check_full(g, kv, bits)
     check_full(g, kv, bits, select=[0, 65535, 65536, 69999])
+
+
+def test_random_valid_geometries():
+    """Thirty seeded geometries drawn from everything the shape rules admit (head_dim 64..1024,
+    every group size that divides it, chunk sizes that keep a unit a whole number of wavefront
+    rows), random widths and a random subset each: records and cache bit for bit."""
+    rng = np.random.default_rng(2024)
+    done = 0
+    while done < 30:
+        D = int(rng.choice([64, 128, 192, 256, 384, 512, 1024]))
+        G = int(rng.choice([g_ for g_ in (64, 128, 256, 512) if D % g_ == 0]))
+        T = int(rng.choice([2, 4, 6, 8, 12, 16, 24, 32, 40, 64]))
+        if (T * D) % 512 or (T * D // G) % 4:
+            continue
+        L, Hkv = int(rng.integers(1, 3)), int(rng.integers(1, 4))
+        n_chunks = int(rng.integers(1, 8))
+        g = synth.Geometry(L, Hkv, Hkv, D, n_chunks * T, T, G)
+        kv = synth.make_kv(g, 100 + done, "cpu", 1, 10.0).numpy()
+        bits = rng.choice([16, 8, 4, 2], n_chunks).astype(np.uint8)
+        check_full(g, kv, bits)
+        sel = sorted(rng.choice(n_chunks, int(rng.integers(1, n_chunks + 1)), replace=False).tolist())
+        check_full(g, kv, bits, select=sel)
+        done += 1

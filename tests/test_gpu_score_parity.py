@@ -203,3 +203,29 @@ def test_determinism():
     a = gpu_score(ks, q, kv, oracle.NORM_VISIBLE)
     b = gpu_score(ks, q, kv, oracle.NORM_VISIBLE)
     assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+
+
+def test_random_valid_shapes():
+    """Sixteen seeded scoring shapes from everything the entry point admits: head_dim 64/128/256,
+    1..8 query heads per kv head, 1..256 query rows, chunk sizes 8..128, caches of 1..40 tiles."""
+    rng = np.random.default_rng(77)
+    for case in range(16):
+        D = int(rng.choice([64, 128, 256]))
+        Hkv = int(rng.integers(1, 3))
+        per = int(rng.choice([1, 1, 2, 3, 4, 8]))
+        T = int(rng.choice([8, 16, 32, 64, 128]))
+        n_tiles = int(rng.integers(1, 41))
+        N = -(-n_tiles * 32 // T) * T                      # a multiple of the chunk size and of 32
+        if N % 32:
+            N = N * 32 // np.gcd(N, 32)
+        R = int(min(N, rng.choice([1, 5, 31, 32, 33, 64, 100, 256])))
+        L = int(rng.integers(1, 3))
+        g = synth.Geometry(L, Hkv, Hkv * per, D, int(N), T, 64)
+        ks, os_ = both_shapes(g)
+        kv = synth.make_kv(g, 300 + case, "cpu", 1, 4.0)
+        q = (synth.make_q(g, 300 + case, R).float() * 4).to(torch.float16)
+        norm = oracle.NORM_VISIBLE if case % 2 == 0 else oracle.NORM_NONE
+        cm_want, d_want = oracle.score_chunks(os_, q.numpy(), kv.numpy(), norm)
+        cm, d = gpu_score(ks, q.to(DEV), kv.to(DEV), norm)
+        assert_close(cm, cm_want, f"case {case} {tuple(g)} R={R}: chunk_mass")
+        assert_close(d, d_want, f"case {case} {tuple(g)} R={R}: density")
