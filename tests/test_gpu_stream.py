@@ -106,3 +106,36 @@ def test_llama3_32k_workload_streamed_from_pinned_host():
         oracle.swapin_chunks(one, want, *oracle.build_gather(one, o1, b, [0]), ref)
         got = chunk_view(out, g.T, i).view(np.uint16)
         assert half_ulp_distance(got, ref).max() <= 1 and np.array_equal(got, ref)
+
+
+def test_records_survive_a_file_round_trip(tmp_path):
+    """The swapped-out records are the persistent form of a context (Sec. 2.2: contexts outlive the
+    app; Sec. 4: chunks are written to storage): a record pool written to a file together with its
+    widths, read back into fresh pinned memory and loaded, gives the same cache as the resident
+    path.  Nothing in a record depends on addresses."""
+    g = synth.Geometry(2, 2, 2, 128, 512, 16, 64)
+    ks, os_ = both_shapes(g)
+    kv = synth.make_kv(g, 71, "cpu", 1, 10.0)
+    bits = synth.draw_bits_uniform(g.n_chunks, 71, widths=(16, 8, 4, 2)).numpy()
+    packed_dev, off = gpu_compress(ks, kv.to(DEV), bits)
+    total = int(off[-1])
+    packed_dev[:total].cpu().numpy().tofile(tmp_path / "context.records")
+    np.save(tmp_path / "context.bits.npy", bits)
+    del packed_dev
+    # "another process": only the files and the shape are known
+    bits2 = np.load(tmp_path / "context.bits.npy")
+    off2 = kvs.kv_chunk_offsets(ks, bits2)
+    store = torch.from_numpy(np.fromfile(tmp_path / "context.records", dtype=np.uint8)).pin_memory()
+    assert store.numel() == int(off2[-1])
+    idx = list(range(g.n_chunks))
+    src, dst, sb = kvs.kv_build_gather(ks, off2, bits2, idx)
+    copy_s, comp_s = torch.cuda.Stream(), torch.cuda.Stream()
+    staging = torch.empty(2 * kvs.kv_record_bytes(ks, 16), dtype=torch.uint8, device=DEV)
+    out = torch.zeros(ks.kv_dims, dtype=torch.float16, device=DEV)
+    torch.cuda.synchronize()
+    kvs.kv_swapin_pinned(ks, store, src, dst, sb, staging, 2, out, copy_s, comp_s)
+    comp_s.synchronize(); copy_s.synchronize()
+    ref = np.zeros(kv.shape, dtype=np.uint16)
+    want = oracle.compress_chunks(os_, kv.numpy(), bits, off)
+    oracle.swapin_chunks(os_, want, *oracle.build_gather(os_, off, bits, idx), ref)
+    assert np.array_equal(out.cpu().numpy().view(np.uint16), ref)
