@@ -188,7 +188,7 @@ __global__ __launch_bounds__(256) void score_tiles_kernel(const _Float16* __rest
     // the K loads would hold back every wait for the next tile (one counter tracks both).
     __shared__ float stage_m[4][NRBW][kMaxRun][32];
     __shared__ float stage_e[4][NRBW][kMaxRun * 4][32];
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6)), lane = threadIdx.x & 63;
     const int lrow = lane & 31, half = lane >> 5;
     const int rg_local = wave % g.rg_per_wg, tpar = wave / g.rg_per_wg;
     if (tpar >= g.tile_par) return;
@@ -600,7 +600,7 @@ __global__ __launch_bounds__(256, 4) void score_head_kernel(const _Float16* __re
     float* row_m = tmp + 4 * 5 * 32;
     float* row_f = row_m + 32;
     const int tid = threadIdx.x;
-    const int wave = tid >> 6, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;   // uniform: run and tile bookkeeping in scalar registers
     const int lrow = lane & 31, half = lane >> 5;
     const int l = blockIdx.x / g.Hkv, kvh = blockIdx.x % g.Hkv;
     const int lh = l * g.Hq + kvh;                    // one query head per kv head
