@@ -201,6 +201,22 @@ def swapin_chunks(shape: Shape, packed: np.ndarray, src_off, dst_tok, sel_bits,
     return kv_out
 
 
+def swapin_layers(shape: Shape, packed, src_off, dst_tok, sel_bits, layer_begin: int, layer_end: int,
+                  kv_out: np.ndarray) -> np.ndarray:
+    """Layer-wise Load (Sec. 3.3: the chunks of one layer are loaded while another is recomputed): what
+    the Load of the listed records puts into the layers [layer_begin, layer_end); every other layer of
+    kv_out keeps its contents.  Written as its definition: the whole Load into a copy, of which the
+    layers in range are taken.  Any format (the cache's dtype says which)."""
+    assert 0 <= layer_begin <= layer_end <= shape.L
+    whole = kv_out.copy()
+    if shape.fmt == 0:
+        swapin_chunks(shape, packed, src_off, dst_tok, sel_bits, whole)
+    else:
+        swapin_chunks_i8(shape, packed, src_off, dst_tok, sel_bits, whole)
+    kv_out[layer_begin:layer_end] = whole[layer_begin:layer_end]
+    return kv_out
+
+
 def compress_chunks_i8(shape: Shape, kv, bits: np.ndarray, off: np.ndarray) -> np.ndarray:
     """Channel-wise quantise + pack of an int8 cache (format 1) -> uint8 pool."""
     kv = np.ascontiguousarray(kv, dtype=np.int8)

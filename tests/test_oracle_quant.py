@@ -252,6 +252,45 @@ def test_swapin_touches_only_selected_tokens():
     assert np.array_equal(out[..., 48:, :], full[..., 48:, :])
 
 
+def test_layer_wise_load_is_the_layer_share_of_each_record():
+    """Layer-wise Load (Sec. 3.3 pipeline): a record keeps its layers one after the other in every
+    section, so layer l of chunk c is slabs [l*2*Hkv, (l+1)*2*Hkv) of the three sections.  Decoded
+    here by hand from those pieces (independent bit decoder, numpy float32 arithmetic), it must be
+    what swapin_layers puts into layer l, and the other layers must keep their contents."""
+    shape = oracle.Shape(L=3, Hkv=2, Hq=2, D=64, N=48, T=16, G=64)
+    kv = random_cache(shape, 9)
+    bits = np.array([4, 8, 2], dtype=np.uint8)
+    off = oracle.chunk_offsets(shape, bits)
+    packed = oracle.compress_chunks(shape, kv, bits, off)
+    lists = oracle.build_gather(shape, off, bits, [0, 2])
+    sentinel = np.uint16(0x7bff)
+    for l in range(shape.L):
+        out = np.full(kv.shape, sentinel, dtype=np.uint16)
+        oracle.swapin_layers(shape, packed, *lists, l, l + 1, out)
+        others = [m for m in range(shape.L) if m != l]
+        assert np.all(out[others] == sentinel)
+        assert np.all(out[l][:, :, 16:32, :] == sentinel)          # chunk 1 is not listed
+        for c in (0, 2):
+            b = int(bits[c])
+            codes, scale, mn = sections(shape, packed[int(off[c]):int(off[c + 1])], b)
+            for kvsel in range(2):
+                for h in range(shape.Hkv):
+                    slab = (l * 2 + kvsel) * shape.Hkv + h
+                    for t in range(shape.T):
+                        q = unpack(codes[slab, t], b).astype(np.float32)
+                        want = (q * scale[slab, t, 0] + mn[slab, t, 0]).astype(np.float32).astype(np.float16)
+                        got = out[l, kvsel, h, c * shape.T + t].view(np.float16)
+                        assert np.array_equal(want.view(np.uint16), got.view(np.uint16))
+    # all layers one after the other = the whole Load; an empty range changes nothing
+    step = np.full(kv.shape, sentinel, dtype=np.uint16)
+    for l in range(shape.L):
+        oracle.swapin_layers(shape, packed, *lists, l, l + 1, step)
+    oracle.swapin_layers(shape, packed, *lists, 2, 2, step)
+    whole = np.full(kv.shape, sentinel, dtype=np.uint16)
+    oracle.swapin_chunks(shape, packed, *lists, whole)
+    assert np.array_equal(step, whole)
+
+
 def test_vectorised_float32_cross_check_on_tiny_workload():
     """The tiny benchmark configuration, re-derived with numpy float32 array arithmetic
     (numpy's float32 divide and rint are the IEEE operations the contract names)."""
