@@ -273,10 +273,29 @@ int32_t kv_compress_selected(const kv_shape_t* shape, const void* kv,
  *   packed dev pool; src_off_dev dev u64 [n_sel] (byte offsets into packed);
  *   dst_tok_dev dev i32 [n_sel]; sel_bits_dev dev u8 [n_sel]; kv_out dev fp16
  *   cache.  n_sel == 0 is a no-op.  The Fault primitive is this call with
- *   n_sel == 1. */
+ *   n_sel == 1.
+ * packed (here, in kv_swapin_layers and in kv_load_chunks) may also be PINNED HOST
+ * memory that the device can address (hipHostMalloc, torch pin_memory): the kernel
+ * then fetches the records over the host link itself, with no staging buffer and no
+ * copy engine (measured on MI355X: the link's full rate, 56.6 GB/s).  While such a
+ * launch runs its wavefronts wait on the link and hold their places on the compute
+ * units; kv_swapin_pinned keeps the compute units free instead. */
 int32_t kv_swapin_chunks(const kv_shape_t* shape, const void* packed,
                          const uint64_t* src_off_dev, const int32_t* dst_tok_dev,
                          const uint8_t* sel_bits_dev, int32_t n_sel,
+                         void* kv_out, void* stream);
+
+/* Layer-wise Load (Sec. 3.3, swapping-recompute pipeline: the chunks of the next layer
+ * are loaded while the current layer is recomputed): kv_swapin_chunks restricted to the
+ * layers [layer_begin, layer_end) of the listed records; the other layers of kv_out are
+ * untouched.  A record holds its layers one after the other in every section, so a
+ * layer's share is three contiguous pieces (codes, scale, mn) that the kernel addresses
+ * itself.  0 <= layer_begin <= layer_end <= n_layers (else KV_EINVAL); an empty range
+ * is a no-op; the full range is kv_swapin_chunks. */
+int32_t kv_swapin_layers(const kv_shape_t* shape, const void* packed,
+                         const uint64_t* src_off_dev, const int32_t* dst_tok_dev,
+                         const uint8_t* sel_bits_dev, int32_t n_sel,
+                         int32_t layer_begin, int32_t layer_end,
                          void* kv_out, void* stream);
 
 /* The Load primitive in one call (Sec. 3.1 primitive 3; the Fault primitive with

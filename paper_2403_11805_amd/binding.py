@@ -80,6 +80,7 @@ _SIGNATURES = {
     "kv_score_chunks": (_i32, [_vp, _vp, _i32, _vp, _i32, _vp, _u64, _vp, _vp, _vp]),
     "kv_compress_chunks": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp]),
     "kv_swapin_chunks": (_i32, [_vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp]),
+    "kv_swapin_layers": (_i32, [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _vp, _vp]),
     "kv_compress_selected": (_i32, [_vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp]),
     "kv_load_chunks": (_i32, [_vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp]),
     "kv_plan_chunks_dev": (_i32, [_vp, _vp, _i32, _i32, _i32, _vp, _vp, _vp, _vp]),
@@ -140,6 +141,19 @@ def _hp(a: np.ndarray):
 def _dev(t: torch.Tensor, dtype=None) -> int:
     if not t.is_cuda:
         raise TypeError("expected a device tensor")
+    if not t.is_contiguous():
+        raise TypeError("expected a contiguous tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"expected dtype {dtype}, got {t.dtype}")
+    return t.data_ptr()
+
+
+def _dev_or_pinned(t: torch.Tensor, dtype=None) -> int:
+    """A record pool: device memory, or pinned host memory that the kernels read over the host link."""
+    if t.is_cuda:
+        return _dev(t, dtype)
+    if not t.is_pinned():
+        raise TypeError("expected a device tensor or a pinned host tensor")
     if not t.is_contiguous():
         raise TypeError("expected a contiguous tensor")
     if dtype is not None and t.dtype != dtype:
@@ -392,9 +406,26 @@ def kv_swapin_chunks(shape: Shape, packed: torch.Tensor, src_off_dev: torch.Tens
         raise ValueError("kv_out must be [L][2][Hkv][N][D]")
     if n_sel == 0:
         return
-    _check(lib().kv_swapin_chunks(ctypes.byref(s), _dev(packed, torch.uint8),
+    _check(lib().kv_swapin_chunks(ctypes.byref(s), _dev_or_pinned(packed, torch.uint8),
                                   _dev(src_off_dev, torch.int64), _dev(dst_tok_dev, torch.int32),
                                   _dev(sel_bits_dev, torch.uint8), n_sel,
+                                  _dev(kv_out, shape.cache_dtype), _stream(stream)))
+
+
+def kv_swapin_layers(shape: Shape, packed: torch.Tensor, src_off_dev: torch.Tensor,
+                     dst_tok_dev: torch.Tensor, sel_bits_dev: torch.Tensor, layer_begin: int,
+                     layer_end: int, kv_out: torch.Tensor, stream=None) -> None:
+    s = shape.c()
+    n_sel = src_off_dev.numel()
+    if dst_tok_dev.numel() != n_sel or sel_bits_dev.numel() != n_sel:
+        raise ValueError("gather lists differ in length")
+    if tuple(kv_out.shape) != shape.kv_dims:
+        raise ValueError("kv_out must be [L][2][Hkv][N][D]")
+    _check(lib().kv_swapin_layers(ctypes.byref(s), _dev_or_pinned(packed, torch.uint8) if n_sel else None,
+                                  _dev(src_off_dev, torch.int64) if n_sel else None,
+                                  _dev(dst_tok_dev, torch.int32) if n_sel else None,
+                                  _dev(sel_bits_dev, torch.uint8) if n_sel else None, n_sel,
+                                  int(layer_begin), int(layer_end),
                                   _dev(kv_out, shape.cache_dtype), _stream(stream)))
 
 
@@ -406,7 +437,7 @@ def kv_load_chunks(shape: Shape, packed: torch.Tensor, off, bits, chunk_idx, kv_
         raise ValueError("need off of n_chunks + 1 entries and bits of n_chunks entries")
     if tuple(kv_out.shape) != shape.kv_dims:
         raise ValueError("kv_out must be [L][2][Hkv][N][D]")
-    _check(lib().kv_load_chunks(ctypes.byref(s), _dev(packed, torch.uint8), _hp(off), _hp(bits),
+    _check(lib().kv_load_chunks(ctypes.byref(s), _dev_or_pinned(packed, torch.uint8), _hp(off), _hp(bits),
                                 _hp(chunk_idx), len(chunk_idx), _dev(kv_out, shape.cache_dtype),
                                 _stream(stream)))
 

@@ -45,6 +45,8 @@ QuantGeom quant_geom(const kv_shape_t& s) {
     g.n_tokens = s.n_tokens;
     g.chunk_tokens = s.chunk_tokens;
     g.slabs = static_cast<int32_t>(slabs_of(s));
+    g.slab0 = 0;
+    g.slab_count = g.slabs;
     g.pieces = s.chunk_tokens * s.head_dim / 8;
     g.row_pieces = s.head_dim / 8;
     g.lpg_log2 = ilog2(s.group / 8);
@@ -60,6 +62,8 @@ QuantGeom quant_geom_i8(const kv_shape_t& s, int* ppl) {
     g.n_tokens = s.n_tokens;
     g.chunk_tokens = s.chunk_tokens;
     g.slabs = static_cast<int32_t>(slabs_of(s));
+    g.slab0 = 0;
+    g.slab_count = g.slabs;
     g.pieces = s.chunk_tokens * s.head_dim / 16;
     g.row_pieces = s.head_dim / 16;
     g.lpg_log2 = ilog2(g.row_pieces);
@@ -108,8 +112,8 @@ int plan_tasks(QuantGeom* g, int max_ppl) {
 }
 
 dim3 task_grid(const QuantGeom& g, int n_units) {
-    const int along_x = g.record_major ? g.slabs : n_units;
-    const int along_y = g.record_major ? n_units : g.slabs;
+    const int along_x = g.record_major ? g.slab_count : n_units;
+    const int along_y = g.record_major ? n_units : g.slab_count;
     const int64_t tasks = static_cast<int64_t>(along_x) * g.tpu;
     return dim3(static_cast<uint32_t>((tasks + kWavesPerBlock - 1) / kWavesPerBlock),
                 static_cast<uint32_t>(along_y));
@@ -204,13 +208,13 @@ int32_t kv_compress_selected(const kv_shape_t* shape, const void* kv, const uint
     return compress_launch(shape, kv, bits_dev, off_dev, chunk_idx_dev, n_sel, packed_out, stream);
 }
 
-int32_t kv_swapin_chunks(const kv_shape_t* shape, const void* packed, const uint64_t* src_off_dev,
-                         const int32_t* dst_tok_dev, const uint8_t* sel_bits_dev, int32_t n_sel,
-                         void* kv_out, void* stream) {
-    if (int rc = check_shape(shape)) return rc;
+// Load of the listed chunks into the cache, all layers or the layers [layer_begin, layer_end).
+static int32_t swapin_launch(const kv_shape_t* shape, const void* packed, const uint64_t* src_off_dev,
+                             const int32_t* dst_tok_dev, const uint8_t* sel_bits_dev, int32_t n_sel,
+                             int32_t layer_begin, int32_t layer_end, void* kv_out, void* stream) {
     const int32_t n_chunks = shape->n_tokens / shape->chunk_tokens;
     if (n_sel < 0 || n_sel > n_chunks) return fail(KV_EINVAL, "n_sel %d outside [0,%d]", n_sel, n_chunks);
-    if (n_sel == 0) return KV_OK;
+    if (n_sel == 0 || layer_begin == layer_end) return KV_OK;
     if (!packed || !src_off_dev || !dst_tok_dev || !sel_bits_dev || !kv_out)
         return fail(KV_EINVAL, "NULL device pointer");
     if (!aligned(kv_out, 16) || !aligned(packed, 16) || !aligned(src_off_dev, 8) ||
@@ -220,7 +224,9 @@ int32_t kv_swapin_chunks(const kv_shape_t* shape, const void* packed, const uint
     int ppl = 0;
     QuantGeom g = i8 ? quant_geom_i8(*shape, &ppl) : quant_geom(*shape);
     if (!i8) ppl = plan_tasks(&g, kSwapinPiecesPerLane);
-    if (g.slabs > 65535) return fail(KV_ESHAPE, "more than 65535 slabs exceed the launch grid");
+    g.slab0 = layer_begin * 2 * shape->n_kv_heads;
+    g.slab_count = (layer_end - layer_begin) * 2 * shape->n_kv_heads;
+    if (g.slab_count > 65535) return fail(KV_ESHAPE, "more than 65535 slabs exceed the launch grid");
     const dim3 grid = task_grid(g, n_sel);
     hipStream_t st = static_cast<hipStream_t>(stream);
     const uint8_t* src = static_cast<const uint8_t*>(packed);
@@ -244,6 +250,24 @@ int32_t kv_swapin_chunks(const kv_shape_t* shape, const void* packed, const uint
     else if (ppl == 2) hipLaunchKernelGGL(swapin_kernel<2>, grid, dim3(256), 0, st, src, src_off_dev, dst_tok_dev, sel_bits_dev, dst, g, n_sel);
     else hipLaunchKernelGGL(swapin_kernel<1>, grid, dim3(256), 0, st, src, src_off_dev, dst_tok_dev, sel_bits_dev, dst, g, n_sel);
     return launch_status("swapin_kernel launch");
+}
+
+int32_t kv_swapin_chunks(const kv_shape_t* shape, const void* packed, const uint64_t* src_off_dev,
+                         const int32_t* dst_tok_dev, const uint8_t* sel_bits_dev, int32_t n_sel,
+                         void* kv_out, void* stream) {
+    if (int rc = check_shape(shape)) return rc;
+    return swapin_launch(shape, packed, src_off_dev, dst_tok_dev, sel_bits_dev, n_sel, 0, shape->n_layers, kv_out,
+                         stream);
+}
+
+int32_t kv_swapin_layers(const kv_shape_t* shape, const void* packed, const uint64_t* src_off_dev,
+                         const int32_t* dst_tok_dev, const uint8_t* sel_bits_dev, int32_t n_sel,
+                         int32_t layer_begin, int32_t layer_end, void* kv_out, void* stream) {
+    if (int rc = check_shape(shape)) return rc;
+    if (layer_begin < 0 || layer_end < layer_begin || layer_end > shape->n_layers)
+        return fail(KV_EINVAL, "layers [%d,%d) outside [0,%d]", layer_begin, layer_end, shape->n_layers);
+    return swapin_launch(shape, packed, src_off_dev, dst_tok_dev, sel_bits_dev, n_sel, layer_begin, layer_end, kv_out,
+                         stream);
 }
 
 // --------------------------------------------------------------------- scoring

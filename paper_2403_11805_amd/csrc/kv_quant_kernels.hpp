@@ -28,7 +28,9 @@ typedef unsigned int u2_t __attribute__((ext_vector_type(2)));
 struct QuantGeom {
     int32_t n_tokens;      // N
     int32_t chunk_tokens;  // T
-    int32_t slabs;         // layers * 2 * kv_heads
+    int32_t slabs;         // layers * 2 * kv_heads (fixes the record layout)
+    int32_t slab0;         // the launch covers slabs [slab0, slab0 + slab_count): all of them, or
+    int32_t slab_count;    // those of a range of layers (layer-wise Load, Sec. 3.3)
     int32_t pieces;        // T * D / 8: 16-byte pieces per unit (multiple of 64)
     int32_t row_pieces;    // D / 8
     int32_t lpg_log2;      // log2(G / 8): lanes per quantisation group (3..6)
@@ -65,12 +67,12 @@ __device__ __forceinline__ bool wave_task(const QuantGeom& g, int n_chunks, int 
     }
     piece0 = sub * 64 * ppl;
     if (g.record_major) {
-        slab = unit;
+        slab = g.slab0 + unit;
         chunk = blockIdx.y;
-        return unit < g.slabs;
+        return unit < g.slab_count;
     }
     chunk = unit;
-    slab = blockIdx.y;
+    slab = g.slab0 + blockIdx.y;
     return unit < n_chunks;
 }
 

@@ -1,0 +1,136 @@
+"""GPU tests of the layer-wise Load (kv_swapin_layers; Sec. 3.3: the chunks of the next layer are
+loaded while the current one is recomputed) and of Loads whose record pool stays in pinned host
+memory (the kernels fetch the records over the host link themselves).  Compared with the oracle
+element by element; layers outside the range must keep their contents bit for bit."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2403_11805_amd as kvs
+from paper_2403_11805_amd import binding, synth
+
+from gpu_util import DEV, both_shapes, gpu_compress
+
+pytestmark = pytest.mark.gpu
+
+SENTINEL = 0x7bff
+
+
+def dev_gather(ks, off, bits, idx):
+    src, dst, sb = kvs.kv_build_gather(ks, off, bits, idx)
+    return (torch.from_numpy(src.view(np.int64)).to(DEV), torch.from_numpy(dst).to(DEV),
+            torch.from_numpy(sb).to(DEV))
+
+
+def make_case(geom, fmt, seed):
+    g = synth.Geometry(*geom)
+    ks, os_ = both_shapes(g, fmt)
+    if fmt == 0:
+        kv_host = synth.make_kv(g, seed, "cpu", 1, 10.0).numpy()
+        bits = synth.draw_bits_uniform(g.n_chunks, seed, widths=(16, 8, 4, 2)).numpy()
+    else:
+        kv_host = synth.make_kv_i8(g, seed).numpy()
+        bits = synth.draw_bits_uniform(g.n_chunks, seed, widths=(8, 4, 2, 1)).numpy()
+    packed_dev, off = gpu_compress(ks, torch.from_numpy(kv_host).to(DEV), bits)
+    return g, ks, os_, kv_host, bits, off, packed_dev
+
+
+def filled(ks, kv_host):
+    """A device cache and its host twin filled with a pattern no Load produces by accident."""
+    if kv_host.dtype == np.int8:
+        dev = torch.full(ks.kv_dims, 0x55, dtype=torch.int8, device=DEV)
+        return dev, np.full(kv_host.shape, 0x55, dtype=np.int8)
+    dev = torch.full(ks.kv_dims, SENTINEL, dtype=torch.int16, device=DEV).view(torch.float16)
+    return dev, np.full(kv_host.shape, SENTINEL, dtype=np.uint16)
+
+
+def as_bits(t):
+    a = t.cpu().numpy()
+    return a.view(np.uint16) if a.dtype == np.float16 else a
+
+
+@pytest.mark.parametrize("fmt,geom", [(0, (5, 2, 2, 128, 640, 16, 64)),     # 40 chunks, 5 layers
+                                      (0, (3, 1, 1, 256, 1600, 32, 128)),   # several wavefront tasks per unit
+                                      (0, (4, 3, 3, 64, 160, 16, 64)),      # head_dim 64, 3 kv heads
+                                      (1, (4, 2, 2, 128, 800, 16, 64)),
+                                      (2, (4, 2, 2, 128, 800, 16, 64))])
+def test_layer_ranges_equal_oracle(fmt, geom):
+    g, ks, os_, kv_host, bits, off, packed_dev = make_case(geom, fmt, 17)
+    packed = packed_dev[:int(off[-1])].cpu().numpy()
+    rng = np.random.default_rng(5)
+    idx = sorted(rng.choice(g.n_chunks, g.n_chunks // 2, replace=False).tolist())
+    lists_h = oracle.build_gather(os_, off, bits, idx)
+    lists_d = dev_gather(ks, off, bits, idx)
+    L = g.L
+    for (l0, l1) in [(0, 1), (L - 1, L), (1, 3), (0, L), (2, 2)]:
+        out, ref = filled(ks, kv_host)
+        kvs.kv_swapin_layers(ks, packed_dev, *lists_d, l0, l1, out)
+        torch.cuda.synchronize()
+        oracle.swapin_layers(os_, packed, *lists_h, l0, l1, ref)
+        got = as_bits(out)
+        assert np.array_equal(got, ref), f"layers [{l0},{l1}): {(got != ref).sum()} values differ from the oracle"
+
+
+def test_layer_by_layer_is_the_whole_load():
+    """The pipeline's order: one launch per layer; afterwards the cache is what one Load gives."""
+    g, ks, os_, kv_host, bits, off, packed_dev = make_case((6, 2, 2, 128, 1024, 16, 64), 0, 23)
+    idx = list(range(0, g.n_chunks, 3))
+    lists_d = dev_gather(ks, off, bits, idx)
+    step, _ = filled(ks, kv_host)
+    for l in range(g.L):
+        kvs.kv_swapin_layers(ks, packed_dev, *lists_d, l, l + 1, step)
+    whole, _ = filled(ks, kv_host)
+    kvs.kv_swapin_chunks(ks, packed_dev, *lists_d, whole)
+    torch.cuda.synchronize()
+    assert torch.equal(step.view(torch.int16), whole.view(torch.int16))
+
+
+@pytest.mark.parametrize("fmt", [0, 2])
+def test_records_read_straight_from_pinned_host_memory(fmt):
+    """The same kernels with the pool left in pinned host memory: list path, layer-wise path and
+    kv_load_chunks give the oracle's bytes."""
+    g, ks, os_, kv_host, bits, off, packed_dev = make_case((3, 2, 2, 128, 960, 16, 64), fmt, 31)
+    total = int(off[-1])
+    pool = torch.empty(total, dtype=torch.uint8).pin_memory()
+    pool.copy_(packed_dev[:total])
+    torch.cuda.synchronize()
+    del packed_dev
+    packed = pool.numpy()
+    idx = sorted(np.random.default_rng(2).choice(g.n_chunks, 25, replace=False).tolist())
+    lists_h = oracle.build_gather(os_, off, bits, idx)
+    lists_d = dev_gather(ks, off, bits, idx)
+    ref_whole = filled(ks, kv_host)[1]
+    (oracle.swapin_chunks if fmt == 0 else oracle.swapin_chunks_i8)(os_, packed, *lists_h, ref_whole)
+
+    out, _ = filled(ks, kv_host)
+    kvs.kv_swapin_chunks(ks, pool, *lists_d, out)
+    torch.cuda.synchronize()
+    assert np.array_equal(as_bits(out), ref_whole)
+
+    out, ref = filled(ks, kv_host)
+    kvs.kv_swapin_layers(ks, pool, *lists_d, 1, 2, out)
+    torch.cuda.synchronize()
+    oracle.swapin_layers(os_, packed, *lists_h, 1, 2, ref)
+    assert np.array_equal(as_bits(out), ref)
+
+    out, _ = filled(ks, kv_host)
+    kvs.kv_load_chunks(ks, pool, off, bits, idx, out)
+    torch.cuda.synchronize()
+    assert np.array_equal(as_bits(out), ref_whole)
+
+
+def test_bad_layer_ranges_launch_nothing():
+    g, ks, os_, kv_host, bits, off, packed_dev = make_case((3, 1, 1, 128, 256, 16, 64), 0, 3)
+    lists_d = dev_gather(ks, off, bits, [0, 5])
+    out, ref = filled(ks, kv_host)
+    for (l0, l1) in [(-1, 1), (2, 1), (0, 4), (3, 4)]:
+        with pytest.raises(binding.KvError) as e:
+            kvs.kv_swapin_layers(ks, packed_dev, *lists_d, l0, l1, out)
+        assert e.value.code == binding.KV_EINVAL
+    torch.cuda.synchronize()
+    assert np.array_equal(as_bits(out), ref)
+    with pytest.raises(TypeError):      # pageable host memory is not a record pool
+        kvs.kv_swapin_chunks(ks, torch.empty(int(off[-1]), dtype=torch.uint8), *lists_d, out)

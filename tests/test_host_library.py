@@ -169,6 +169,13 @@ def test_device_entry_points_validate_before_touching_the_gpu():
     assert L.kv_swapin_chunks(ctypes.byref(s), None, None, None, None, 3, None, None) == binding.KV_EINVAL
     assert L.kv_swapin_chunks(ctypes.byref(s), None, None, None, None, 0, None, None) == binding.KV_OK
     assert L.kv_swapin_chunks(ctypes.byref(s), None, None, None, None, 33, None, None) == binding.KV_EINVAL
+    # layer-wise Load: the layer range is checked on the host; empty ranges and empty lists are no-ops
+    assert L.kv_swapin_layers(ctypes.byref(s), None, None, None, None, 3, -1, 1, None, None) == binding.KV_EINVAL
+    assert L.kv_swapin_layers(ctypes.byref(s), None, None, None, None, 3, 2, 1, None, None) == binding.KV_EINVAL
+    assert L.kv_swapin_layers(ctypes.byref(s), None, None, None, None, 3, 0, 3, None, None) == binding.KV_EINVAL
+    assert L.kv_swapin_layers(ctypes.byref(s), None, None, None, None, 3, 1, 1, None, None) == binding.KV_OK
+    assert L.kv_swapin_layers(ctypes.byref(s), None, None, None, None, 0, 0, 2, None, None) == binding.KV_OK
+    assert L.kv_swapin_layers(ctypes.byref(s), None, None, None, None, 3, 0, 2, None, None) == binding.KV_EINVAL   # NULL pointers
     assert L.kv_score_chunks(ctypes.byref(s), None, 8, None, 0, None, 0, None, None, None) == binding.KV_EINVAL
     assert L.kv_swapout_aot(None, None, 0, 0, None, None) == binding.KV_EINVAL
     bad = kvs.Shape(2, 4, 4, 64, 500, 16, 64).c()
