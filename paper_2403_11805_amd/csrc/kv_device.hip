@@ -208,6 +208,21 @@ int32_t kv_compress_selected(const kv_shape_t* shape, const void* kv, const uint
     return compress_launch(shape, kv, bits_dev, off_dev, chunk_idx_dev, n_sel, packed_out, stream);
 }
 
+// Where a record pool lives: device memory (1), pinned host memory that the device addresses (2:
+// the Load kernels then read the records over the host link and are launched as a small strided
+// grid), or memory the runtime does not know, e.g. pageable host memory (0: a kernel must not
+// touch it).
+static int pool_kind(const void* p) {
+    hipPointerAttribute_t attr;
+    if (hipPointerGetAttributes(&attr, p) != hipSuccess) {
+        (void)hipGetLastError();
+        return 0;
+    }
+    if (attr.type == hipMemoryTypeHost) return 2;
+    if (attr.type == hipMemoryTypeUnregistered) return 0;
+    return 1;
+}
+
 // Load of the listed chunks into the cache, all layers or the layers [layer_begin, layer_end).
 static int32_t swapin_launch(const kv_shape_t* shape, const void* packed, const uint64_t* src_off_dev,
                              const int32_t* dst_tok_dev, const uint8_t* sel_bits_dev, int32_t n_sel,
@@ -231,6 +246,32 @@ static int32_t swapin_launch(const kv_shape_t* shape, const void* packed, const 
     hipStream_t st = static_cast<hipStream_t>(stream);
     const uint8_t* src = static_cast<const uint8_t*>(packed);
     u4_t* dst = static_cast<u4_t*>(kv_out);
+    const int kind = pool_kind(packed);
+    if (kind == 0) return fail(KV_EINVAL, "packed is neither device memory nor pinned host memory");
+    if (kind == 2) {
+        const uint64_t total = static_cast<uint64_t>(grid.x) * grid.y;
+        if (total > 0xffffffffull) return fail(KV_ESHAPE, "task grid of %llu workgroups", static_cast<unsigned long long>(total));
+        const dim3 lgrid(static_cast<uint32_t>(std::min<uint64_t>(total, kLinkBlocks)));
+        if (i8) {
+            const I8View v = i8_view(*shape);
+#define KV_LAUNCH_I8(NDW, GPL)                                                                            \
+            do {                                                                                          \
+                if (v.half_meta)                                                                          \
+                    hipLaunchKernelGGL((swapin_i8_link_kernel<NDW, GPL, true>), lgrid, dim3(256), 0, st, src,    \
+                                       src_off_dev, dst_tok_dev, sel_bits_dev, dst, g, v, n_sel, grid.x, grid.y); \
+                else                                                                                      \
+                    hipLaunchKernelGGL((swapin_i8_link_kernel<NDW, GPL, false>), lgrid, dim3(256), 0, st, src,   \
+                                       src_off_dev, dst_tok_dev, sel_bits_dev, dst, g, v, n_sel, grid.x, grid.y); \
+            } while (0)
+            KV_I8_DISPATCH(ppl, shape->head_dim, KV_LAUNCH_I8);
+#undef KV_LAUNCH_I8
+            return launch_status("swapin_i8_link_kernel launch");
+        }
+        if (ppl == 4) hipLaunchKernelGGL(swapin_link_kernel<4>, lgrid, dim3(256), 0, st, src, src_off_dev, dst_tok_dev, sel_bits_dev, dst, g, n_sel, grid.x, grid.y);
+        else if (ppl == 2) hipLaunchKernelGGL(swapin_link_kernel<2>, lgrid, dim3(256), 0, st, src, src_off_dev, dst_tok_dev, sel_bits_dev, dst, g, n_sel, grid.x, grid.y);
+        else hipLaunchKernelGGL(swapin_link_kernel<1>, lgrid, dim3(256), 0, st, src, src_off_dev, dst_tok_dev, sel_bits_dev, dst, g, n_sel, grid.x, grid.y);
+        return launch_status("swapin_link_kernel launch");
+    }
     if (i8) {
         const I8View v = i8_view(*shape);
 #define KV_LAUNCH_I8(NDW, GPL)                                                                            \

@@ -418,6 +418,28 @@ __global__ __launch_bounds__(256) void swapin_i8_kernel(const uint8_t* __restric
     swapin_i8_task<NDW, GPL, HM>(packed + src_off[j], uniform_byte(sel_bits, j), slab, dst, g, v, lds[wave], lane);
 }
 
+// Record pool in pinned host memory: a small grid that walks the task grid in strides (see
+// swapin_link_kernel).  A wavefront reuses its LDS region from task to task, in program order.
+template <int NDW, int GPL, bool HM>
+__global__ __launch_bounds__(256) void swapin_i8_link_kernel(const uint8_t* __restrict__ packed,
+                                                             const uint64_t* __restrict__ src_off,
+                                                             const int32_t* __restrict__ dst_tok,
+                                                             const uint8_t* __restrict__ sel_bits,
+                                                             u4_t* __restrict__ kv_out, QuantGeom g, I8View v,
+                                                             int32_t n_sel, uint32_t gx, uint32_t gy) {
+    __shared__ __align__(16) uint8_t lds[kWavesPerBlock][NDW * 256 + NDW * 128];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6));
+    const uint32_t total = gx * gy;
+    for (uint32_t w = blockIdx.x; w < total; w += gridDim.x) {
+        int j, slab, p0;
+        if (!wave_task_at(g, n_sel, NDW / 4, w % gx, w / gx, j, slab, p0)) continue;
+        u4_t* dst = kv_out + (static_cast<uint64_t>(slab) * g.n_tokens +
+                              static_cast<uint64_t>(dst_tok[j])) * g.row_pieces;
+        swapin_i8_task<NDW, GPL, HM>(packed + src_off[j], uniform_byte(sel_bits, j), slab, dst, g, v, lds[wave], lane);
+    }
+}
+
 template <int NDW, int GPL, bool HM>
 __global__ __launch_bounds__(256) void swapin_i8_batch_kernel(const uint8_t* __restrict__ staged,
                                                               SwapinBatch list,

@@ -53,10 +53,10 @@ __device__ __forceinline__ int uniform_byte(const uint8_t* list, int i) {
 // Wavefront task -> (chunk or list index, slab, first piece).  Task ids are uniform
 // per wavefront; readfirstlane keeps everything derived from them in SGPRs, so
 // the per-chunk list entries become scalar loads and the width branch is uniform.
-__device__ __forceinline__ bool wave_task(const QuantGeom& g, int n_chunks, int ppl, int& chunk,
-                                          int& slab, int& piece0) {
+__device__ __forceinline__ bool wave_task_at(const QuantGeom& g, int n_chunks, int ppl, uint32_t bx,
+                                             uint32_t by, int& chunk, int& slab, int& piece0) {
     const int wave = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6));
-    const int t = blockIdx.x * kWavesPerBlock + wave;
+    const int t = static_cast<int>(bx) * kWavesPerBlock + wave;
     int unit, sub;
     if (g.tpu_shift >= 0) {
         unit = t >> g.tpu_shift;
@@ -68,12 +68,17 @@ __device__ __forceinline__ bool wave_task(const QuantGeom& g, int n_chunks, int 
     piece0 = sub * 64 * ppl;
     if (g.record_major) {
         slab = g.slab0 + unit;
-        chunk = blockIdx.y;
+        chunk = static_cast<int>(by);
         return unit < g.slab_count;
     }
     chunk = unit;
-    slab = g.slab0 + blockIdx.y;
+    slab = g.slab0 + static_cast<int>(by);
     return unit < n_chunks;
+}
+
+__device__ __forceinline__ bool wave_task(const QuantGeom& g, int n_chunks, int ppl, int& chunk,
+                                          int& slab, int& piece0) {
+    return wave_task_at(g, n_chunks, ppl, blockIdx.x, blockIdx.y, chunk, slab, piece0);
 }
 
 // Streaming accesses: every byte is touched once.  Whether marking them
@@ -369,6 +374,32 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void swapin_kernel(const uint8
     u4_t* dst = kv_out + (static_cast<uint64_t>(slab) * g.n_tokens +
                           static_cast<uint64_t>(dst_tok[j])) * g.row_pieces;
     swapin_task<PPL>(packed + src_off[j], uniform_byte(sel_bits, j), slab, dst, g, p0, lane);
+}
+
+// The same Load for a record pool that stays in pinned host memory.  A wavefront of this
+// launch spends its time waiting for the host link, and a few hundred of them keep the link
+// full (measured on MI355X: 32 workgroups reach 60 % of the link's rate, 64 reach 96 %, 128 and
+// more all of it); so the launch is a small one-dimensional grid whose workgroups walk the task
+// grid (gx x gy workgroups of swapin_kernel) in strides, and most of the compute units' wavefront
+// slots stay free for kernels of other streams.
+constexpr uint32_t kLinkBlocks = 128;
+
+template <int PPL>
+__global__ __launch_bounds__(64 * kWavesPerBlock) void swapin_link_kernel(const uint8_t* __restrict__ packed,
+                                                          const uint64_t* __restrict__ src_off,
+                                                          const int32_t* __restrict__ dst_tok,
+                                                          const uint8_t* __restrict__ sel_bits,
+                                                          u4_t* __restrict__ kv_out, QuantGeom g,
+                                                          int32_t n_sel, uint32_t gx, uint32_t gy) {
+    const int lane = threadIdx.x & 63;
+    const uint32_t total = gx * gy;
+    for (uint32_t w = blockIdx.x; w < total; w += gridDim.x) {
+        int j, slab, p0;
+        if (!wave_task_at(g, n_sel, PPL, w % gx, w / gx, j, slab, p0)) continue;
+        u4_t* dst = kv_out + (static_cast<uint64_t>(slab) * g.n_tokens +
+                              static_cast<uint64_t>(dst_tok[j])) * g.row_pieces;
+        swapin_task<PPL>(packed + src_off[j], uniform_byte(sel_bits, j), slab, dst, g, p0, lane);
+    }
 }
 
 // Same work for one staged batch of the streaming Load: the (short) gather

@@ -132,5 +132,12 @@ def test_bad_layer_ranges_launch_nothing():
         assert e.value.code == binding.KV_EINVAL
     torch.cuda.synchronize()
     assert np.array_equal(as_bits(out), ref)
-    with pytest.raises(TypeError):      # pageable host memory is not a record pool
+    with pytest.raises(TypeError):      # pageable host memory is not a record pool: the binding says so,
         kvs.kv_swapin_chunks(ks, torch.empty(int(off[-1]), dtype=torch.uint8), *lists_d, out)
+    pageable = np.zeros(int(off[-1]) + 16, dtype=np.uint8)       # and so does the library, before any launch
+    addr = (pageable.ctypes.data + 15) & ~15
+    rc = binding.lib().kv_swapin_chunks(ctypes.byref(ks.c()), addr, lists_d[0].data_ptr(), lists_d[1].data_ptr(),
+                                        lists_d[2].data_ptr(), 2, out.data_ptr(), None)
+    assert rc == binding.KV_EINVAL and "pinned" in binding.kv_last_error()
+    torch.cuda.synchronize()
+    assert np.array_equal(as_bits(out), ref)
