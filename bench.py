@@ -451,7 +451,7 @@ def run_pool(wl, args, dev):
             moved.append(packed_b + n_sel * g.elements * 2 // g.n_chunks)
     # the Fault primitive: Load of one chunk, issue to completion as the caller sees it
     fault_wall = []
-    for it in range(64):
+    for it in range(264):
         c = order_ctx[it % len(order_ctx)]
         one = subsets[it % len(subsets)][it % n_sel:it % n_sel + 1]
         torch.cuda.synchronize()
@@ -482,6 +482,7 @@ def run_pool(wl, args, dev):
         "swapin_kernel_ms": {"mean": round(float(np.mean(k_ms)), 4), "p50": round(pctl(k_ms, 50), 4),
                              "p99": round(pctl(k_ms, 99), 4)},
         "fault_ms": {"p50": round(pctl(fault_wall[8:], 50), 4), "p99": round(pctl(fault_wall[8:], 99), 4),
+                     "max": round(max(fault_wall[8:]), 4), "samples": len(fault_wall) - 8,
                      "note": "kv_load_chunks of one chunk (8 MiB of fp16 cache), call to completion"},
         "lctru": {"entries": len(eviction_order), "order_ms": round(order_ms, 3)},
         "pool_build_s": round(t_build, 2),

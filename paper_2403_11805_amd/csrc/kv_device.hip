@@ -462,7 +462,8 @@ int32_t kv_load_chunks(const kv_shape_t* shape, const void* packed, const uint64
         return rc;
     for (int32_t j = 0; j < n_sel; ++j)
         if (src_off[static_cast<size_t>(j)] % 16) return fail(KV_EINVAL, "record offset of chunk %d not 16-byte aligned", chunk_idx[j]);
-    if (pool_kind(packed) == 0) return fail(KV_EINVAL, "packed is neither device memory nor pinned host memory");
+    // (no query of where `packed` lives here: this is the Fault path, tens of microseconds from call
+    // to completion, and the query costs three of them)
     const bool i8 = is_i8(*shape);
     int ppl = 0;
     QuantGeom g = i8 ? quant_geom_i8(*shape, &ppl) : quant_geom(*shape);
