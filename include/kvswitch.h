@@ -322,7 +322,14 @@ int32_t kv_load_chunks(const kv_shape_t* shape, const void* packed, const uint64
  *   must hold the largest listed record (else KV_ENOMEM);
  *   kv_out dev fp16 cache.  copy_stream and compute_stream must differ and
  *   must not be the NULL stream.  Returns after enqueuing everything;
- *   completion = both streams idle (the last kernel is on compute_stream). */
+ *   completion = both streams idle (the last kernel is on compute_stream).
+ *   The staging slots belong to the call until its last kernel has finished: a
+ *   further call on the same streams needs staging memory of its own, or
+ *   copy_stream must first wait for compute_stream (an event).
+ *   A context kept as one pool per layer (records of a shape with n_layers = 1,
+ *   kv_out pointing at the layer's slice of the cache) is loaded layer by layer
+ *   with one such call per layer: the order of the swapping-recompute pipeline
+ *   (Sec. 3.3), with the copies on the DMA engines. */
 int32_t kv_swapin_pinned(const kv_shape_t* shape, const void* packed_pinned,
                          const uint64_t* src_off, const int32_t* dst_tok,
                          const uint8_t* sel_bits, int32_t n_sel,
