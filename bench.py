@@ -517,6 +517,34 @@ def run_pool(wl, args, dev):
         kvs.kv_load_chunks(shape, pools[c], ctx_off[c], ctx_bits[c], one, caches[it % len(caches)])
         torch.cuda.synchronize()
         fault_wall.append((time.perf_counter() - t0) * 1e3)
+    # A context whose records were reclaimed to pinned host memory (Sec. 3.4: Reclaim moves no data, the
+    # records are already there): Fault and switch-sized Loads from the host, the kernel reading the
+    # pinned pool itself (in place) or kv_swapin_pinned staging it through the copy engines.
+    c0 = order_ctx[0]
+    host_pool = torch.empty(pools[c0].numel(), dtype=torch.uint8).pin_memory()
+    host_pool.copy_(pools[c0])
+    torch.cuda.synchronize()
+    hs_copy, hs_comp = torch.cuda.Stream(), torch.cuda.Stream()
+    stage = torch.empty(2 * (16 << 20), dtype=torch.uint8, device=dev)
+    from_host = []
+    for n in (1, n_sel):
+        t_place, t_staged, rec_bytes = [], [], []
+        for it in range(40):
+            sel = subsets[it % len(subsets)][:n]
+            rec_bytes.append(sum(int(ctx_off[c0][i + 1] - ctx_off[c0][i]) for i in sel))
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            kvs.kv_load_chunks(shape, host_pool, ctx_off[c0], ctx_bits[c0], sel, caches[0])
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            src, dst, sb = kvs.kv_build_gather(shape, ctx_off[c0], ctx_bits[c0], sel)
+            kvs.kv_swapin_pinned(shape, host_pool, src, dst, sb, stage, 2, caches[0], hs_copy, hs_comp)
+            hs_comp.synchronize(); hs_copy.synchronize()
+            t2 = time.perf_counter()
+            t_place.append((t1 - t0) * 1e3); t_staged.append((t2 - t1) * 1e3)
+        mb = float(np.mean(rec_bytes))
+        from_host.append({"chunks": n, "record_mib": round(mb / 2**20, 2), "in_place_ms_p50": round(pctl(t_place[8:], 50), 4),
+                          "staged_ms_p50": round(pctl(t_staged[8:], 50), 4), "link_ms_at_measured_rate": round(mb / 57e6, 4)})
     order_ms = 1e9
     for _ in range(3):                     # the first call pays one-off interpreter costs
         order_t0 = time.perf_counter()
@@ -542,6 +570,7 @@ def run_pool(wl, args, dev):
         "fault_ms": {"p50": round(pctl(fault_wall[8:], 50), 4), "p99": round(pctl(fault_wall[8:], 99), 4),
                      "max": round(max(fault_wall[8:]), 4), "samples": len(fault_wall) - 8,
                      "note": "kv_load_chunks of one chunk (8 MiB of fp16 cache), call to completion"},
+        "load_from_pinned_host": from_host,
         "lctru": {"entries": len(eviction_order), "order_ms": round(order_ms, 3)},
         "pool_build_s": round(t_build, 2),
         "roofline": {"kernel": "swapin_batch_kernel", "bound": "hbm", "achieved": round(gbps, 1),
