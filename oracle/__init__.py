@@ -50,7 +50,7 @@ class Shape:
     N: int
     T: int
     G: int
-    fmt: int = 0    # 0: fp16 cache, groups of G along head_dim; 1: int8 cache, channel-wise;
+    fmt: int = 0    # 0: fp16 cache, groups of G along head_dim (3: binary16 parameters); 1: int8 cache, channel-wise;
                     # 2: as 1 with binary16 parameters
 
     @property
@@ -209,7 +209,7 @@ def swapin_layers(shape: Shape, packed, src_off, dst_tok, sel_bits, layer_begin:
     layers in range are taken.  Any format (the cache's dtype says which)."""
     assert 0 <= layer_begin <= layer_end <= shape.L
     whole = kv_out.copy()
-    if shape.fmt == 0:
+    if shape.fmt in (0, 3):
         swapin_chunks(shape, packed, src_off, dst_tok, sel_bits, whole)
     else:
         swapin_chunks_i8(shape, packed, src_off, dst_tok, sel_bits, whole)

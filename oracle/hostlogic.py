@@ -17,7 +17,7 @@ VALID_BITS_I8 = (8, 4, 2, 1)
 def record_bytes(shape, bits: int) -> int:
     """Bytes of one chunk's packed record.  fp16 format: b < 16: every token row of
     every slab holds D*b/8 code bytes plus one fp32 scale and one fp32 minimum per
-    group of G elements; b = 16: the raw fp16 bytes.  int8 channel-wise formats: b < 8:
+    group of G elements (binary16 parameters in format 3); b = 16: the raw fp16 bytes.  int8 channel-wise formats: b < 8:
     T*D*b/8 code bytes per slab plus one scale and one minimum per channel (fp32, or
     binary16 in format 2); b = 8: raw."""
     slabs = shape.L * 2 * shape.Hkv
@@ -31,7 +31,8 @@ def record_bytes(shape, bits: int) -> int:
     assert bits in VALID_BITS
     if bits == 16:
         return slabs * shape.T * shape.D * 2
-    return slabs * shape.T * (shape.D * bits // 8 + 8 * (shape.D // shape.G))
+    meta = 4 if fmt == 3 else 8                # binary16 (format 3) or fp32 (scale, minimum) per group
+    return slabs * shape.T * (shape.D * bits // 8 + meta * (shape.D // shape.G))
 
 
 def chunk_offsets(shape, bits) -> np.ndarray:

@@ -28,7 +28,7 @@
 
 typedef struct {
     int32_t L, Hkv, Hq, D, N, T, G;
-    int32_t fmt;   /* 0: fp16 cache, groups of G along head_dim; 1: int8 cache, channel-wise;
+    int32_t fmt;   /* 0: fp16 cache, groups of G along head_dim (3: the same with binary16 parameters); 1: int8 cache, channel-wise;
                       2: as 1 with the parameters stored (and used) in binary16 */
 } orc_shape;
 
@@ -206,7 +206,8 @@ uint64_t orc_record_bytes(const orc_shape* s, int bits)
         return slabs * ((uint64_t)s->T * s->D * bits / 8 + meta * s->D);
     }
     if (bits == 16) return slabs * s->T * s->D * 2;
-    return slabs * s->T * ((uint64_t)s->D * bits / 8 + 8ull * (s->D / s->G));
+    /* scale + minimum per group: binary32 (fmt 0) or binary16 (fmt 3) */
+    return slabs * s->T * ((uint64_t)s->D * bits / 8 + (s->fmt == 3 ? 4ull : 8ull) * (s->D / s->G));
 }
 
 /* ----------------------------------------------------------------- compress (Sec. 3.2; Sec. 4 packing) */
@@ -217,7 +218,7 @@ uint64_t orc_record_bytes(const orc_shape* s, int bits)
  *   scale = (mx - mn) / (2^b - 1),
  *   code = scale == 0 ? 0 : clamp(rintf((x - mn) / scale), 0, 2^b - 1).
  */
-static void quantise_group(const uint16_t* x, int n, int b, uint8_t* code,
+static void quantise_group(const uint16_t* x, int n, int b, int half_params, uint8_t* code,
                            float* scale_out, float* mn_out)
 {
     float mn = orc_half_to_float(x[0]);
@@ -231,7 +232,10 @@ static void quantise_group(const uint16_t* x, int n, int b, uint8_t* code,
     mx = mx + 0.0f;
     const float levels = (float)((1 << b) - 1);
     const float range = mx - mn;
-    const float scale = range / levels;
+    float scale = range / levels;
+    /* parameters kept in binary16 (fmt 3): the scale is rounded to binary16 BEFORE the codes are
+     * computed, so that both directions use the stored value; mn is one of the inputs, exact */
+    if (half_params) scale = orc_half_to_float(orc_float_to_half(scale));
     for (int k = 0; k < n; ++k) {
         float c = 0.0f;
         if (scale != 0.0f) {
@@ -251,7 +255,7 @@ static void quantise_group(const uint16_t* x, int n, int b, uint8_t* code,
 /*
  * Compress every chunk i at bits[i] into packed + off[i].
  * Record: codes [slab][T][D*b/8], then scale [slab][T][D/G] fp32, then mn
- * (same shape).  Element d of a token row goes to byte d*b/8, bit position
+ * (same shape); fmt 3 keeps scale and mn in binary16.  Element d of a token row goes to byte d*b/8, bit position
  * (d mod (8/b))*b: the lowest-index element in the least-significant bits.
  * b = 16: the chunk's fp16 bytes, slab after slab, nothing else.
  */
@@ -276,17 +280,27 @@ int orc_compress_chunks(const orc_shape* s, const uint16_t* kv, const uint8_t* b
                 continue;
             }
             const size_t row_bytes = (size_t)s->D * b / 8;
+            const int half = s->fmt == 3;
             uint8_t* codes = rec + (size_t)sl * s->T * row_bytes;
-            float* scale = (float*)(rec + (size_t)slabs * s->T * row_bytes) +
-                           (size_t)sl * s->T * groups;
+            uint8_t* meta = rec + (size_t)slabs * s->T * row_bytes;     /* scale section, then mn section */
+            float* scale = (float*)meta + (size_t)sl * s->T * groups;
             float* mn = scale + (size_t)slabs * s->T * groups;
+            uint16_t* scale_h = (uint16_t*)meta + (size_t)sl * s->T * groups;
+            uint16_t* mn_h = scale_h + (size_t)slabs * s->T * groups;
             uint8_t tmp[1024];
             for (int t = 0; t < s->T; ++t) {
                 uint8_t* row = codes + (size_t)t * row_bytes;
                 memset(row, 0, row_bytes);
                 for (int j = 0; j < groups; ++j) {
-                    quantise_group(src + (size_t)t * s->D + (size_t)j * s->G, s->G, b, tmp,
-                                   &scale[t * groups + j], &mn[t * groups + j]);
+                    float sc, m;
+                    quantise_group(src + (size_t)t * s->D + (size_t)j * s->G, s->G, b, half, tmp, &sc, &m);
+                    if (half) {
+                        scale_h[t * groups + j] = orc_float_to_half(sc);
+                        mn_h[t * groups + j] = orc_float_to_half(m);
+                    } else {
+                        scale[t * groups + j] = sc;
+                        mn[t * groups + j] = m;
+                    }
                     for (int k = 0; k < s->G; ++k) {
                         const int d = j * s->G + k;
                         const int per_byte = 8 / b;
@@ -458,9 +472,12 @@ int orc_swapin_chunks(const orc_shape* s, const uint8_t* packed, const uint64_t*
             }
             const size_t row_bytes = (size_t)s->D * b / 8;
             const uint8_t* codes = rec + (size_t)sl * s->T * row_bytes;
-            const float* scale = (const float*)(rec + (size_t)slabs * s->T * row_bytes) +
-                                 (size_t)sl * s->T * groups;
+            const int half = s->fmt == 3;
+            const uint8_t* meta = rec + (size_t)slabs * s->T * row_bytes;
+            const float* scale = (const float*)meta + (size_t)sl * s->T * groups;
             const float* mn = scale + (size_t)slabs * s->T * groups;
+            const uint16_t* scale_h = (const uint16_t*)meta + (size_t)sl * s->T * groups;
+            const uint16_t* mn_h = scale_h + (size_t)slabs * s->T * groups;
             const int per_byte = 8 / b;
             const unsigned mask = (1u << b) - 1u;
             for (int t = 0; t < s->T; ++t) {
@@ -468,8 +485,10 @@ int orc_swapin_chunks(const orc_shape* s, const uint8_t* packed, const uint64_t*
                 for (int d = 0; d < s->D; ++d) {
                     const unsigned code = (row[d / per_byte] >> ((d % per_byte) * b)) & mask;
                     const int gidx = t * groups + d / s->G;
-                    const float prod = (float)code * scale[gidx];
-                    const float val = prod + mn[gidx];
+                    const float sc = half ? orc_half_to_float(scale_h[gidx]) : scale[gidx];
+                    const float m = half ? orc_half_to_float(mn_h[gidx]) : mn[gidx];
+                    const float prod = (float)code * sc;
+                    const float val = prod + m;
                     dst[(size_t)t * s->D + d] = orc_float_to_half(val);
                 }
             }

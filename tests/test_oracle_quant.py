@@ -291,6 +291,93 @@ def test_layer_wise_load_is_the_layer_share_of_each_record():
     assert np.array_equal(step, whole)
 
 
+# ------------------------------------------------------------------ format 3: binary16 parameters
+
+def sections_h(shape, rec, b):
+    """Split a format-3 record into (codes, scale binary16 bits [slabs][T][D/G], mn binary16 bits)."""
+    n_codes = shape.slabs * shape.T * shape.D * b // 8
+    n_meta = shape.slabs * shape.T * (shape.D // shape.G)
+    assert n_codes + 4 * n_meta == len(rec)
+    codes = rec[:n_codes].reshape(shape.slabs, shape.T, shape.D * b // 8)
+    scale = rec[n_codes:n_codes + 2 * n_meta].view(np.uint16).reshape(shape.slabs, shape.T, -1)
+    mn = rec[n_codes + 2 * n_meta:].view(np.uint16).reshape(shape.slabs, shape.T, -1)
+    return codes, scale, mn
+
+
+def test_format3_record_sizes_by_hand():
+    """Groups of 64 along head_dim 128, 16 tokens, 2 layers x K/V x 2 heads = 8 slabs: a token row holds
+    128*b/8 code bytes and two groups; the parameters weigh 2 x 2 bytes per group instead of 2 x 4."""
+    s3 = oracle.Shape(L=2, Hkv=2, Hq=2, D=128, N=64, T=16, G=64, fmt=3)
+    s0 = oracle.Shape(L=2, Hkv=2, Hq=2, D=128, N=64, T=16, G=64)
+    assert [oracle.record_bytes(s3, b) for b in (16, 8, 4, 2)] == [8 * 16 * 256, 8 * 16 * 136, 8 * 16 * 72, 8 * 16 * 40]
+    assert [oracle.record_bytes(s0, b) for b in (8, 4, 2)] == [8 * 16 * 144, 8 * 16 * 80, 8 * 16 * 48]
+    bits = np.array([4, 16, 2, 8], dtype=np.uint8)
+    assert oracle.chunk_offsets(s3, bits).tolist() == [0, 9216, 9216 + 32768, 9216 + 32768 + 5120, 9216 + 32768 + 5120 + 17408]
+
+
+@pytest.mark.parametrize("b", [8, 4, 2])
+def test_format3_equals_format0_when_the_scale_is_a_binary16_number(b):
+    """Values on the grid mn + k * 2^-3, k = 0 .. 2^b - 1 (every level present): the scale is exactly 2^-3,
+    a binary16 number, so rounding it changes nothing: same codes as format 0, same parameters after
+    widening, and the Load returns the inputs bit for bit."""
+    levels = (1 << b) - 1
+    rng = np.random.default_rng(b)
+    shape3 = shape_small(T=8, D=128, G=64, N=8)
+    shape3 = oracle.Shape(shape3.L, shape3.Hkv, shape3.Hq, shape3.D, shape3.N, shape3.T, shape3.G, 3)
+    shape0 = shape_small(T=8, D=128, G=64, N=8)
+    k = rng.integers(0, levels + 1, size=(1, 2, 1, 8, 128))
+    k[..., 0] = 0; k[..., 1] = levels; k[..., 64] = levels; k[..., 65] = 0       # both ends in every group
+    kv = (-3.0 + 0.125 * k).astype(np.float16)
+    rec3, bits, off3 = compress_one(shape3, kv, b)
+    rec0, _, off0 = compress_one(shape0, kv, b)
+    c3, sc3, mn3 = sections_h(shape3, rec3, b)
+    c0, sc0, mn0 = sections(shape0, rec0, b)
+    assert np.array_equal(c3, c0)
+    assert np.array_equal(sc3.view(np.float16).astype(np.float32), sc0) and np.all(sc0 == 0.125)
+    assert np.array_equal(mn3.view(np.float16).astype(np.float32), mn0) and np.all(mn0 == -3.0)
+    out = np.zeros(kv.shape, dtype=np.uint16)
+    oracle.swapin_chunks(shape3, rec3, *oracle.build_gather(shape3, off3, bits, [0]), out)
+    assert np.array_equal(out, kv.view(np.uint16))
+
+
+@pytest.mark.parametrize("b", [8, 4, 2])
+def test_format3_by_an_independent_route_and_its_error_bound(b):
+    """Random data with an outlier channel: the record's sections re-derived with numpy (float32 array
+    arithmetic, numpy's own binary16 rounding, the independent bit decoder).  The scale must have been
+    rounded to binary16 BEFORE the codes were computed: coding against the unrounded scale gives
+    different codes on this input (checked), so a swapped order cannot pass.  Then the error of the
+    round trip: half a step of the stored scale, the clamped top of the range (the rounded scale may
+    fall short of it by range * 2^-11), and the final binary16 rounding."""
+    levels = (1 << b) - 1
+    shape = oracle.Shape(L=1, Hkv=2, Hq=2, D=128, N=32, T=16, G=64, fmt=3)
+    kv = random_cache(shape, 40 + b)
+    rec, bits, off = compress_one(shape, kv, b)
+    codes, scale_bits, mn_bits = sections_h(shape, rec[:int(off[1])], b)
+    x = kv[:, :, :, 0:16, :].astype(np.float32).reshape(shape.slabs, 16, 2, 64)     # [slab][t][group][k]
+    mn = x.min(axis=-1, keepdims=True) + np.float32(0.0)
+    mx = x.max(axis=-1, keepdims=True) + np.float32(0.0)
+    scale32 = ((mx - mn) / np.float32(levels)).astype(np.float32)
+    scale16 = scale32.astype(np.float16)
+    assert np.array_equal(scale16.view(np.uint16)[..., 0], scale_bits)
+    assert np.array_equal(mn.astype(np.float16).view(np.uint16)[..., 0], mn_bits)
+    sc = scale16.astype(np.float32)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        want = np.where(sc != 0, np.clip(np.rint((x - mn) / sc), 0, levels), 0).astype(np.int64)
+        unrounded = np.where(scale32 != 0, np.clip(np.rint((x - mn) / scale32), 0, levels), 0).astype(np.int64)
+    got = np.stack([np.stack([unpack(codes[sl, t], b) for t in range(16)]) for sl in range(shape.slabs)])
+    assert np.array_equal(got.reshape(want.shape), want)
+    if b == 8:
+        assert (want != unrounded).any(), "input does not tell the two orders apart"
+    out = np.zeros(kv.shape, dtype=np.uint16)
+    oracle.swapin_chunks(shape, rec, *oracle.build_gather(shape, off, bits, [0, 1]), out)
+    deq = (want.astype(np.float32) * sc + mn).astype(np.float32).astype(np.float16)
+    assert np.array_equal(out[:, :, :, 0:16, :].reshape(deq.shape), deq.view(np.uint16))
+    err = np.abs(deq.astype(np.float64) - x)
+    rng_ = (mx - mn).astype(np.float64)
+    bound = sc.astype(np.float64) / 2 + rng_ * 2.0 ** -11 + np.abs(x) * 2.0 ** -11 + 1e-7
+    assert np.all(err <= bound)
+
+
 def test_vectorised_float32_cross_check_on_tiny_workload():
     """The tiny benchmark configuration, re-derived with numpy float32 array arithmetic
     (numpy's float32 divide and rint are the IEEE operations the contract names)."""
