@@ -43,10 +43,10 @@ def find_workload(name):
 class Path:
     """Device buffers and the per-step call sequence for one context."""
 
-    def __init__(self, wl, dev, host_plan=False):
+    def __init__(self, wl, dev, host_plan=False, fmt=0):
         g = wl.geom
         self.wl, self.g, self.dev = wl, g, dev
-        self.shape = kvs.Shape(g.L, g.Hkv, g.Hq, g.D, g.N, g.T, g.G)
+        self.shape = kvs.Shape(g.L, g.Hkv, g.Hq, g.D, g.N, g.T, g.G, fmt)
         self.kv = synth.make_kv(g, wl.seed, dev, wl.outlier_channels, wl.outlier_scale)
         # caches below ~640 MB would be served from the 256 MB Infinity Cache when reused every
         # step: rotate over enough independent copies that each step streams from HBM
@@ -584,8 +584,8 @@ def run_stream(wl, args, dev):
     swap-out to the host, then a streaming swap-in (H2D copies on one stream, dequantise kernel
     on another).  Reports the kernel-only rate, the bare copy rate and the overlap."""
     g = wl.geom
-    shape = kvs.Shape(g.L, g.Hkv, g.Hq, g.D, g.N, g.T, g.G)
-    path = Path(wl, dev, host_plan=True)     # the host owns the pinned pool: it needs the offsets
+    path = Path(wl, dev, host_plan=True, fmt=(3 if args.format == "f16h" else 0))     # the host owns the pinned pool: it needs the offsets
+    shape = path.shape
     copy_s, comp_s = torch.cuda.Stream(), torch.cuda.Stream()
     path.step()                                  # score + compress (+ resident swap-in)
     torch.cuda.synchronize()
@@ -652,7 +652,8 @@ def run_stream(wl, args, dev):
         "ms_per_step": round(mean["stream"], 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{wl.name}: [L={g.L},K/V,Hkv={g.Hkv},N={g.N},D={g.D}] fp16, chunk {g.T}, "
-                               f"group {g.G}, R={path.R}; records in pinned host memory",
+                               f"group {g.G}, R={path.R}; records in pinned host memory"
+                               + (", record parameters in binary16" if shape.format == 3 else ""),
                    "cache_bytes": cache_bytes, "packed_bytes": total,
                    "step": f"streaming swap-in from pinned host memory ({args.stream_buffers} staging slots of "
                            f"{args.stream_slot_mib} MiB); value includes the host link"},
@@ -853,8 +854,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="llama2-7b-4k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--format", choices=("f16", "i8", "i8h"), default="f16",
-                    help="i8 / i8h: the int8 channel-wise record format with fp32 / binary16 parameters on the "
+    ap.add_argument("--format", choices=("f16", "f16h", "i8", "i8h"), default="f16",
+                    help="f16h: the fp16 group format with binary16 parameters (the whole step, smaller records); "
+                         "i8 / i8h: the int8 channel-wise record format with fp32 / binary16 parameters on the "
                          "workload's geometry (compress + swap-in)")
     ap.add_argument("--sweep-chunk-tokens", action="store_true",
                     help="instead of the benchmark: compress / swap-in rates for chunk sizes 4..256")
@@ -907,7 +909,7 @@ def main():
     if wl.name == "llama3-8b-32k" and not args.calibrate_copy:
         print(json.dumps(run_stream(wl, args, dev)))
         return
-    path = Path(wl, dev, host_plan=args.host_plan)
+    path = Path(wl, dev, host_plan=args.host_plan, fmt=(3 if args.format == "f16h" else 0))
     g = wl.geom
 
     if args.calibrate_copy:
@@ -977,7 +979,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{wl.name}: [L={g.L},K/V,Hkv={g.Hkv},N={g.N},D={g.D}] fp16, "
-                               f"chunk {g.T}, group {g.G}, R={path.R}, widths {wl.bits_rule}",
+                               f"chunk {g.T}, group {g.G}, R={path.R}, widths {wl.bits_rule}"
+                               + (", record parameters in binary16" if path.shape.format == 3 else ""),
                    "cache_bytes": cache_bytes, "packed_bytes": path.packed_bytes,
                    "step": ("score + widths/offsets/gather list (device) + compress + swap-in, one stream, no "
                             "host round trip" if path.device_plan else

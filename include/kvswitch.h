@@ -68,6 +68,14 @@
  *  exact in binary16.  Record for b < 8: codes as in format 1, then
  *    scale : [slab][head_dim] binary16;   mn : [slab][head_dim] binary16.
  *
+ *  KV_FMT_F16_GROUPS_H (= 3) is format 0 with scale and mn held in binary16 (the
+ *  record's parameter sections shrink from 8 to 4 bytes per group: 8 % smaller
+ *  records at group 64 and terciles of 8/4/2 bits, which is what a Load over the
+ *  host link pays for).  As in format 2 the scale is rounded to binary16 (nearest
+ *  even) BEFORE the codes are computed; mn is one of the fp16 inputs, exact.  A
+ *  code may then saturate at 2^b - 1 where the rounded scale falls short of the
+ *  range (by at most range * 2^-11).
+ *
  *  Quantisation of one group of `group` consecutive head_dim elements of one
  *  token (linear min/max quantisation, Sec. 3.2 "Compressing chunks"), all in
  *  IEEE binary32, round-to-nearest, no contraction:
@@ -104,7 +112,7 @@ typedef enum {
  * 16-byte aligned).
  * Formats 1 and 2 instead of the group rules: head_dim a power of two in [64, 1024];
  * chunk_tokens * head_dim in {1024, 2048, 4096} (one wavefront holds a slab);
- * group is ignored.  Scoring (kv_score_chunks) needs format 0. */
+ * group is ignored.  Scoring (kv_score_chunks) needs an fp16 cache (format 0 or 3). */
 typedef struct {
     int32_t n_layers;
     int32_t n_kv_heads;
@@ -113,10 +121,10 @@ typedef struct {
     int32_t n_tokens;
     int32_t chunk_tokens;
     int32_t group;         /* quantisation group along head_dim (format 0) */
-    int32_t format;        /* KV_FMT_F16_GROUPS (0), KV_FMT_I8_CHANNELS (1), KV_FMT_I8_CHANNELS_H (2) */
+    int32_t format;        /* KV_FMT_F16_GROUPS (0), KV_FMT_I8_CHANNELS (1), KV_FMT_I8_CHANNELS_H (2), KV_FMT_F16_GROUPS_H (3) */
 } kv_shape_t;
 
-enum { KV_FMT_F16_GROUPS = 0, KV_FMT_I8_CHANNELS = 1, KV_FMT_I8_CHANNELS_H = 2 };
+enum { KV_FMT_F16_GROUPS = 0, KV_FMT_I8_CHANNELS = 1, KV_FMT_I8_CHANNELS_H = 2, KV_FMT_F16_GROUPS_H = 3 };
 
 enum { KV_NORM_VISIBLE = 0, KV_NORM_NONE = 1 };
 
@@ -127,7 +135,8 @@ const char* kv_last_error(void);
 
 /* Bytes of one chunk's packed record at bit-width `bits`; 0 if shape or bits
  * are invalid.  Format 0: b<16: slabs*T*(D*b/8 + 8*D/G); b=16: slabs*T*D*2.
- * Format 1: b<8: slabs*(T*D*b/8 + 8*D); b=8: slabs*T*D.  Format 2: 4*D in the place of 8*D. */
+ * Format 1: b<8: slabs*(T*D*b/8 + 8*D); b=8: slabs*T*D.  Format 2: 4*D in the place of 8*D.
+ * Format 3: format 0 with 4*D/G in the place of 8*D/G. */
 uint64_t kv_record_bytes(const kv_shape_t* shape, int32_t bits);
 
 /* Exclusive prefix sum of record sizes: off[0]=0, off[i+1]=off[i]+record_bytes(bits[i]).

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libkvswitch.so")
 
 KV_OK, KV_EINVAL, KV_ESHAPE, KV_EBITS, KV_EINDEX, KV_ENOMEM, KV_EHIP = 0, -1, -2, -3, -4, -5, -6
 KV_NORM_VISIBLE, KV_NORM_NONE = 0, 1
-KV_FMT_F16_GROUPS, KV_FMT_I8_CHANNELS, KV_FMT_I8_CHANNELS_H = 0, 1, 2
+KV_FMT_F16_GROUPS, KV_FMT_I8_CHANNELS, KV_FMT_I8_CHANNELS_H, KV_FMT_F16_GROUPS_H = 0, 1, 2, 3
 KV_OBJ_BITS_TO_DENSE, KV_OBJ_AS_PRINTED = 0, 1
 
 
@@ -42,7 +42,7 @@ class Shape(NamedTuple):
     n_tokens: int
     chunk_tokens: int
     group: int
-    format: int = 0      # KV_FMT_F16_GROUPS, KV_FMT_I8_CHANNELS or KV_FMT_I8_CHANNELS_H
+    format: int = 0      # KV_FMT_F16_GROUPS, KV_FMT_I8_CHANNELS, KV_FMT_I8_CHANNELS_H or KV_FMT_F16_GROUPS_H
 
     @property
     def cache_dtype(self):

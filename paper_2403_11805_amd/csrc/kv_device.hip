@@ -139,9 +139,18 @@ int launch_swapin_batch(const kv_shape_t& shape, const QuantGeom& g, int ppl, co
         } while (0)
         KV_I8_DISPATCH(ppl, shape.head_dim, KV_LAUNCH_I8);
 #undef KV_LAUNCH_I8
-    } else if (ppl == 4) hipLaunchKernelGGL(swapin_batch_kernel<4>, grid, dim3(256), 0, st, base, list, dst, g);
-    else if (ppl == 2) hipLaunchKernelGGL(swapin_batch_kernel<2>, grid, dim3(256), 0, st, base, list, dst, g);
-    else hipLaunchKernelGGL(swapin_batch_kernel<1>, grid, dim3(256), 0, st, base, list, dst, g);
+    } else {
+        const bool hp = shape.format == KV_FMT_F16_GROUPS_H;
+#define KV_LAUNCH_F16(PPL)                                                                                        \
+        do {                                                                                                      \
+            if (hp) hipLaunchKernelGGL((swapin_batch_kernel<PPL, true>), grid, dim3(256), 0, st, base, list, dst, g); \
+            else hipLaunchKernelGGL((swapin_batch_kernel<PPL, false>), grid, dim3(256), 0, st, base, list, dst, g);   \
+        } while (0)
+        if (ppl == 4) KV_LAUNCH_F16(4);
+        else if (ppl == 2) KV_LAUNCH_F16(2);
+        else KV_LAUNCH_F16(1);
+#undef KV_LAUNCH_F16
+    }
     return launch_status("swapin_batch_kernel launch");
 }
 
@@ -179,9 +188,16 @@ static int32_t compress_launch(const kv_shape_t* shape, const void* kv, const ui
 #undef KV_LAUNCH_I8
         return launch_status("compress_i8_kernel launch");
     }
-    if (ppl == 4) hipLaunchKernelGGL(compress_kernel<4>, grid, dim3(256), 0, st, src, bits_dev, off_dev, dst, g, n_units, chunk_list);
-    else if (ppl == 2) hipLaunchKernelGGL(compress_kernel<2>, grid, dim3(256), 0, st, src, bits_dev, off_dev, dst, g, n_units, chunk_list);
-    else hipLaunchKernelGGL(compress_kernel<1>, grid, dim3(256), 0, st, src, bits_dev, off_dev, dst, g, n_units, chunk_list);
+    const bool hp = shape->format == KV_FMT_F16_GROUPS_H;
+#define KV_LAUNCH_F16(PPL)                                                                                     \
+    do {                                                                                                       \
+        if (hp) hipLaunchKernelGGL((compress_kernel<PPL, true>), grid, dim3(256), 0, st, src, bits_dev, off_dev, dst, g, n_units, chunk_list); \
+        else hipLaunchKernelGGL((compress_kernel<PPL, false>), grid, dim3(256), 0, st, src, bits_dev, off_dev, dst, g, n_units, chunk_list);   \
+    } while (0)
+    if (ppl == 4) KV_LAUNCH_F16(4);
+    else if (ppl == 2) KV_LAUNCH_F16(2);
+    else KV_LAUNCH_F16(1);
+#undef KV_LAUNCH_F16
     return launch_status("compress_kernel launch");
 }
 
@@ -267,9 +283,16 @@ static int32_t swapin_launch(const kv_shape_t* shape, const void* packed, const 
 #undef KV_LAUNCH_I8
             return launch_status("swapin_i8_link_kernel launch");
         }
-        if (ppl == 4) hipLaunchKernelGGL(swapin_link_kernel<4>, lgrid, dim3(256), 0, st, src, src_off_dev, dst_tok_dev, sel_bits_dev, dst, g, n_sel, grid.x, grid.y);
-        else if (ppl == 2) hipLaunchKernelGGL(swapin_link_kernel<2>, lgrid, dim3(256), 0, st, src, src_off_dev, dst_tok_dev, sel_bits_dev, dst, g, n_sel, grid.x, grid.y);
-        else hipLaunchKernelGGL(swapin_link_kernel<1>, lgrid, dim3(256), 0, st, src, src_off_dev, dst_tok_dev, sel_bits_dev, dst, g, n_sel, grid.x, grid.y);
+        const bool hp = shape->format == KV_FMT_F16_GROUPS_H;
+#define KV_LAUNCH_F16(PPL)                                                                                     \
+        do {                                                                                                   \
+            if (hp) hipLaunchKernelGGL((swapin_link_kernel<PPL, true>), lgrid, dim3(256), 0, st, src, src_off_dev, dst_tok_dev, sel_bits_dev, dst, g, n_sel, grid.x, grid.y); \
+            else hipLaunchKernelGGL((swapin_link_kernel<PPL, false>), lgrid, dim3(256), 0, st, src, src_off_dev, dst_tok_dev, sel_bits_dev, dst, g, n_sel, grid.x, grid.y);   \
+        } while (0)
+        if (ppl == 4) KV_LAUNCH_F16(4);
+        else if (ppl == 2) KV_LAUNCH_F16(2);
+        else KV_LAUNCH_F16(1);
+#undef KV_LAUNCH_F16
         return launch_status("swapin_link_kernel launch");
     }
     if (i8) {
@@ -287,9 +310,16 @@ static int32_t swapin_launch(const kv_shape_t* shape, const void* packed, const 
 #undef KV_LAUNCH_I8
         return launch_status("swapin_i8_kernel launch");
     }
-    if (ppl == 4) hipLaunchKernelGGL(swapin_kernel<4>, grid, dim3(256), 0, st, src, src_off_dev, dst_tok_dev, sel_bits_dev, dst, g, n_sel);
-    else if (ppl == 2) hipLaunchKernelGGL(swapin_kernel<2>, grid, dim3(256), 0, st, src, src_off_dev, dst_tok_dev, sel_bits_dev, dst, g, n_sel);
-    else hipLaunchKernelGGL(swapin_kernel<1>, grid, dim3(256), 0, st, src, src_off_dev, dst_tok_dev, sel_bits_dev, dst, g, n_sel);
+    const bool hp = shape->format == KV_FMT_F16_GROUPS_H;
+#define KV_LAUNCH_F16(PPL)                                                                                     \
+    do {                                                                                                       \
+        if (hp) hipLaunchKernelGGL((swapin_kernel<PPL, true>), grid, dim3(256), 0, st, src, src_off_dev, dst_tok_dev, sel_bits_dev, dst, g, n_sel); \
+        else hipLaunchKernelGGL((swapin_kernel<PPL, false>), grid, dim3(256), 0, st, src, src_off_dev, dst_tok_dev, sel_bits_dev, dst, g, n_sel);   \
+    } while (0)
+    if (ppl == 4) KV_LAUNCH_F16(4);
+    else if (ppl == 2) KV_LAUNCH_F16(2);
+    else KV_LAUNCH_F16(1);
+#undef KV_LAUNCH_F16
     return launch_status("swapin_kernel launch");
 }
 
@@ -317,7 +347,7 @@ static int score_geom(const kv_shape_t* shape, int32_t n_queries, int32_t norm_m
                       int* nrbw) {
     if (int rc = check_shape(shape)) return rc;
     const kv_shape_t& s = *shape;
-    if (s.format != KV_FMT_F16_GROUPS) return fail(KV_ESHAPE, "scoring needs the fp16 format");
+    if (!is_f16(s)) return fail(KV_ESHAPE, "scoring needs an fp16 cache format");
     if (n_queries < 1 || n_queries > s.n_tokens || n_queries > 256)
         return fail(KV_EINVAL, "n_queries %d outside [1, min(n_tokens, 256)]", n_queries);
     if (norm_mode != KV_NORM_VISIBLE && norm_mode != KV_NORM_NONE)

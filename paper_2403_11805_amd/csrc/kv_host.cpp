@@ -31,7 +31,7 @@ int check_shape(const kv_shape_t* s) {
     if (s->n_tokens % s->chunk_tokens)
         return fail(KV_ESHAPE, "n_tokens %d is not a multiple of chunk_tokens %d", s->n_tokens,
                     s->chunk_tokens);
-    if (s->format != KV_FMT_F16_GROUPS && !is_i8(*s))
+    if (!is_f16(*s) && !is_i8(*s))
         return fail(KV_ESHAPE, "format %d unknown", s->format);
     if (s->n_q_heads % s->n_kv_heads)
         return fail(KV_ESHAPE, "n_q_heads %d is not a multiple of n_kv_heads %d", s->n_q_heads,

@@ -14,6 +14,11 @@ void clear_error();
 // KV_OK, or KV_EINVAL / KV_ESHAPE with the error text set.
 int check_shape(const kv_shape_t* s);
 
+// The fp16 group formats (parameters in fp32 or in binary16).
+inline bool is_f16(const kv_shape_t& s) {
+    return s.format == KV_FMT_F16_GROUPS || s.format == KV_FMT_F16_GROUPS_H;
+}
+
 // The int8 cache formats (channel-wise parameters in fp32 or in binary16).
 inline bool is_i8(const kv_shape_t& s) {
     return s.format == KV_FMT_I8_CHANNELS || s.format == KV_FMT_I8_CHANNELS_H;
@@ -42,8 +47,9 @@ inline uint64_t record_bytes(const kv_shape_t& s, int bits) {
                slabs_of(s) * meta * static_cast<uint64_t>(s.head_dim);
     }
     if (bits == 16) return rows * static_cast<uint64_t>(s.head_dim) * 2u;
+    const uint64_t meta = s.format == KV_FMT_F16_GROUPS_H ? 4u : 8u;      // (scale, minimum) per group
     return rows * (static_cast<uint64_t>(s.head_dim) * bits / 8u +
-                   8u * static_cast<uint64_t>(s.head_dim / s.group));
+                   meta * static_cast<uint64_t>(s.head_dim / s.group));
 }
 
 inline bool aligned(const void* p, uintptr_t a) {

@@ -164,7 +164,10 @@ __device__ __forceinline__ void group_min_max(const u4_t& raw, int lpg_log2, flo
 // lies within that distance of a half-integer.  A lane that sees |q' - rint(q')|
 // >= 0.5 - 2^BITS * 2^-20 redoes its piece with the exact division, which keeps
 // every code bit-identical to the definition.
-template <int BITS>
+// CLAMP: the scale may fall short of range / levels (a scale rounded to binary16), so the quotient can
+// pass the top level and is cut there; with an exact scale it cannot, and 8-bit codes saturate when
+// they are packed.
+template <int BITS, bool CLAMP>
 __device__ __forceinline__ void quantise_piece(const h8_t& x, float mn, float scale, float r[8]) {
     constexpr float kLevels = static_cast<float>((1 << BITS) - 1);
     constexpr float kSafe = 0.5f - static_cast<float>(1 << BITS) * 9.5367431640625e-07f;
@@ -176,6 +179,7 @@ __device__ __forceinline__ void quantise_piece(const h8_t& x, float mn, float sc
         const float q = d * inv;
         r[k] = __builtin_rintf(q);
         e[k] = __builtin_fabsf(q - r[k]);
+        if constexpr (CLAMP) r[k] = __builtin_fminf(r[k], kLevels);
     }
     const float e01 = __builtin_fmaxf(__builtin_fmaxf(e[0], e[1]), e[2]);
     const float e02 = __builtin_fmaxf(__builtin_fmaxf(e[3], e[4]), e[5]);
@@ -192,18 +196,21 @@ __device__ __forceinline__ void quantise_piece(const h8_t& x, float mn, float sc
 }
 
 // One piece -> its codes (and, from the first lane of each group, scale and mn).
-template <int BITS>
+// HP: the parameters are kept in binary16 (format KV_FMT_F16_GROUPS_H): the scale is rounded to
+// binary16 before the codes are computed, the minimum is one of the inputs and exact.
+template <int BITS, bool HP>
 __device__ __forceinline__ void compress_piece(const u4_t& raw, uint8_t* __restrict__ codes,
-                                               float* __restrict__ scale_out,
-                                               float* __restrict__ mn_out, int p, int lpg_log2,
+                                               void* __restrict__ scale_out,
+                                               void* __restrict__ mn_out, int p, int lpg_log2,
                                                int lane) {
     constexpr float kLevels = static_cast<float>((1 << BITS) - 1);
     float mn, mx;
     group_min_max(raw, lpg_log2, mn, mx);
-    const float scale = (mx - mn) / kLevels;
+    float scale = (mx - mn) / kLevels;
+    if constexpr (HP) scale = static_cast<float>(static_cast<_Float16>(scale));
     const h8_t x = __builtin_bit_cast(h8_t, raw);
     float r[8];
-    quantise_piece<BITS>(x, mn, scale, r);
+    quantise_piece<BITS, HP && BITS != 8>(x, mn, scale, r);
     if constexpr (BITS == 8) {
         uint32_t w0 = 0, w1 = 0;
         w0 = __builtin_amdgcn_cvt_pk_u8_f32(r[0], 0, w0);
@@ -233,15 +240,20 @@ __device__ __forceinline__ void compress_piece(const u4_t& raw, uint8_t* __restr
                      reinterpret_cast<uint16_t*>(codes) + p);
     }
     if ((lane & ((1 << lpg_log2) - 1)) == 0) {
-        scale_out[p >> lpg_log2] = scale;
-        mn_out[p >> lpg_log2] = mn;
+        if constexpr (HP) {
+            static_cast<_Float16*>(scale_out)[p >> lpg_log2] = static_cast<_Float16>(scale);
+            static_cast<_Float16*>(mn_out)[p >> lpg_log2] = static_cast<_Float16>(mn);
+        } else {
+            static_cast<float*>(scale_out)[p >> lpg_log2] = scale;
+            static_cast<float*>(mn_out)[p >> lpg_log2] = mn;
+        }
     }
 }
 
 // Grid (ceil(n_chunks * tpu / 4), slabs) or, record-major, (ceil(slabs * tpu / 4),
 // n_chunks); block 256 threads = 4 wavefront tasks of PPL * 64 pieces each.
 // chunk_list (may be NULL): the n_chunks chunk indices to compress instead of 0..n_chunks-1.
-template <int PPL>
+template <int PPL, bool HP>
 __global__ __launch_bounds__(64 * kWavesPerBlock) void compress_kernel(const u4_t* __restrict__ kv,
                                                        const uint8_t* __restrict__ bits,
                                                        const uint64_t* __restrict__ off,
@@ -269,21 +281,21 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void compress_kernel(const u4_
     const uint64_t code_bytes = static_cast<uint64_t>(g.pieces) * b;        // per unit
     const uint32_t groups = static_cast<uint32_t>(g.pieces) >> g.lpg_log2;  // per unit
     uint8_t* codes = base + slab * code_bytes;
-    float* scale = reinterpret_cast<float*>(base + g.slabs * code_bytes) +
-                   static_cast<uint64_t>(slab) * groups;
-    float* mn = scale + static_cast<uint64_t>(g.slabs) * groups;
+    constexpr uint64_t kParam = HP ? 2 : 4;                               // bytes per stored parameter
+    uint8_t* scale = base + g.slabs * code_bytes + static_cast<uint64_t>(slab) * groups * kParam;
+    uint8_t* mn = scale + static_cast<uint64_t>(g.slabs) * groups * kParam;
     if (b == 8) {
 #pragma unroll
         for (int u = 0; u < PPL; ++u)
-            compress_piece<8>(raw[u], codes, scale, mn, p0 + u * 64 + lane, g.lpg_log2, lane);
+            compress_piece<8, HP>(raw[u], codes, scale, mn, p0 + u * 64 + lane, g.lpg_log2, lane);
     } else if (b == 4) {
 #pragma unroll
         for (int u = 0; u < PPL; ++u)
-            compress_piece<4>(raw[u], codes, scale, mn, p0 + u * 64 + lane, g.lpg_log2, lane);
+            compress_piece<4, HP>(raw[u], codes, scale, mn, p0 + u * 64 + lane, g.lpg_log2, lane);
     } else {
 #pragma unroll
         for (int u = 0; u < PPL; ++u)
-            compress_piece<2>(raw[u], codes, scale, mn, p0 + u * 64 + lane, g.lpg_log2, lane);
+            compress_piece<2, HP>(raw[u], codes, scale, mn, p0 + u * 64 + lane, g.lpg_log2, lane);
     }
 }
 
@@ -314,10 +326,10 @@ __device__ __forceinline__ u4_t dequantise_piece(u2_t w, float sc, float mn) {
     return __builtin_bit_cast(u4_t, out);
 }
 
-template <int BITS, int PPL>
+template <int BITS, int PPL, bool HP>
 __device__ __forceinline__ void swapin_pieces(const uint8_t* __restrict__ codes,
-                                              const float* __restrict__ scale,
-                                              const float* __restrict__ mn, u4_t* __restrict__ dst,
+                                              const void* __restrict__ scale,
+                                              const void* __restrict__ mn, u4_t* __restrict__ dst,
                                               int p0, int lane, int lpg_log2) {
     u2_t w[PPL];
     float sc[PPL], m[PPL];
@@ -325,8 +337,13 @@ __device__ __forceinline__ void swapin_pieces(const uint8_t* __restrict__ codes,
     for (int u = 0; u < PPL; ++u) {
         const int p = p0 + u * 64 + lane;
         w[u] = load_codes<BITS>(codes, p);
-        sc[u] = scale[p >> lpg_log2];
-        m[u] = mn[p >> lpg_log2];
+        if constexpr (HP) {
+            sc[u] = static_cast<float>(static_cast<const _Float16*>(scale)[p >> lpg_log2]);
+            m[u] = static_cast<float>(static_cast<const _Float16*>(mn)[p >> lpg_log2]);
+        } else {
+            sc[u] = static_cast<const float*>(scale)[p >> lpg_log2];
+            m[u] = static_cast<const float*>(mn)[p >> lpg_log2];
+        }
     }
 #pragma unroll
     for (int u = 0; u < PPL; ++u)
@@ -335,7 +352,7 @@ __device__ __forceinline__ void swapin_pieces(const uint8_t* __restrict__ codes,
 }
 
 // PPL * 64 pieces of one (selected record, slab) unit of the Load primitive.
-template <int PPL>
+template <int PPL, bool HP>
 __device__ __forceinline__ void swapin_task(const uint8_t* __restrict__ base, int b, int slab,
                                             u4_t* __restrict__ dst, const QuantGeom& g, int p0,
                                             int lane) {
@@ -351,17 +368,17 @@ __device__ __forceinline__ void swapin_task(const uint8_t* __restrict__ base, in
     const uint64_t code_bytes = static_cast<uint64_t>(g.pieces) * b;
     const uint32_t groups = static_cast<uint32_t>(g.pieces) >> g.lpg_log2;
     const uint8_t* codes = base + slab * code_bytes;
-    const float* scale = reinterpret_cast<const float*>(base + g.slabs * code_bytes) +
-                         static_cast<uint64_t>(slab) * groups;
-    const float* mn = scale + static_cast<uint64_t>(g.slabs) * groups;
-    if (b == 8) swapin_pieces<8, PPL>(codes, scale, mn, dst, p0, lane, g.lpg_log2);
-    else if (b == 4) swapin_pieces<4, PPL>(codes, scale, mn, dst, p0, lane, g.lpg_log2);
-    else swapin_pieces<2, PPL>(codes, scale, mn, dst, p0, lane, g.lpg_log2);
+    constexpr uint64_t kParam = HP ? 2 : 4;                               // bytes per stored parameter
+    const uint8_t* scale = base + g.slabs * code_bytes + static_cast<uint64_t>(slab) * groups * kParam;
+    const uint8_t* mn = scale + static_cast<uint64_t>(g.slabs) * groups * kParam;
+    if (b == 8) swapin_pieces<8, PPL, HP>(codes, scale, mn, dst, p0, lane, g.lpg_log2);
+    else if (b == 4) swapin_pieces<4, PPL, HP>(codes, scale, mn, dst, p0, lane, g.lpg_log2);
+    else swapin_pieces<2, PPL, HP>(codes, scale, mn, dst, p0, lane, g.lpg_log2);
 }
 
 // Grid as for compress_kernel with the n_sel listed records in the place of
 // the chunks; gather lists in device memory.
-template <int PPL>
+template <int PPL, bool HP>
 __global__ __launch_bounds__(64 * kWavesPerBlock) void swapin_kernel(const uint8_t* __restrict__ packed,
                                                      const uint64_t* __restrict__ src_off,
                                                      const int32_t* __restrict__ dst_tok,
@@ -373,7 +390,7 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void swapin_kernel(const uint8
     if (!wave_task(g, n_sel, PPL, j, slab, p0)) return;
     u4_t* dst = kv_out + (static_cast<uint64_t>(slab) * g.n_tokens +
                           static_cast<uint64_t>(dst_tok[j])) * g.row_pieces;
-    swapin_task<PPL>(packed + src_off[j], uniform_byte(sel_bits, j), slab, dst, g, p0, lane);
+    swapin_task<PPL, HP>(packed + src_off[j], uniform_byte(sel_bits, j), slab, dst, g, p0, lane);
 }
 
 // The same Load for a record pool that stays in pinned host memory.  A wavefront of this
@@ -384,7 +401,7 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void swapin_kernel(const uint8
 // slots stay free for kernels of other streams.
 constexpr uint32_t kLinkBlocks = 128;
 
-template <int PPL>
+template <int PPL, bool HP>
 __global__ __launch_bounds__(64 * kWavesPerBlock) void swapin_link_kernel(const uint8_t* __restrict__ packed,
                                                           const uint64_t* __restrict__ src_off,
                                                           const int32_t* __restrict__ dst_tok,
@@ -398,7 +415,7 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void swapin_link_kernel(const 
         if (!wave_task_at(g, n_sel, PPL, w % gx, w / gx, j, slab, p0)) continue;
         u4_t* dst = kv_out + (static_cast<uint64_t>(slab) * g.n_tokens +
                               static_cast<uint64_t>(dst_tok[j])) * g.row_pieces;
-        swapin_task<PPL>(packed + src_off[j], uniform_byte(sel_bits, j), slab, dst, g, p0, lane);
+        swapin_task<PPL, HP>(packed + src_off[j], uniform_byte(sel_bits, j), slab, dst, g, p0, lane);
     }
 }
 
@@ -412,7 +429,7 @@ struct SwapinBatch {
     int32_t n;
 };
 
-template <int PPL>
+template <int PPL, bool HP>
 __global__ __launch_bounds__(64 * kWavesPerBlock) void swapin_batch_kernel(const uint8_t* __restrict__ staged,
                                                            SwapinBatch list,
                                                            u4_t* __restrict__ kv_out, QuantGeom g) {
@@ -421,7 +438,7 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void swapin_batch_kernel(const
     if (!wave_task(g, list.n, PPL, j, slab, p0)) return;
     u4_t* dst = kv_out + (static_cast<uint64_t>(slab) * g.n_tokens +
                           static_cast<uint64_t>(list.dst_tok[j])) * g.row_pieces;
-    swapin_task<PPL>(staged + list.src_off[j], list.bits[j], slab, dst, g, p0, lane);
+    swapin_task<PPL, HP>(staged + list.src_off[j], list.bits[j], slab, dst, g, p0, lane);
 }
 
 }  // namespace kvs

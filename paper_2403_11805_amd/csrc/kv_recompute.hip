@@ -87,7 +87,7 @@ Plan plan_workspace(const kv_shape_t& s, const kv_layer_dims_t& d, int64_t M) {
 int check_layer(const kv_shape_t* shape, const kv_layer_dims_t* dims, int32_t n_missing) {
     if (int rc = check_shape(shape)) return rc;
     if (!dims) return fail(KV_EINVAL, "dims is NULL");
-    if (shape->format != KV_FMT_F16_GROUPS) return fail(KV_ESHAPE, "recompute needs the fp16 cache format");
+    if (!is_f16(*shape)) return fail(KV_ESHAPE, "recompute needs an fp16 cache format");
     if (shape->head_dim != 64 && shape->head_dim != 128)
         return fail(KV_ESHAPE, "recompute needs head_dim 64 or 128, got %d", shape->head_dim);
     if (dims->d_model <= 0 || dims->d_model % 8 || dims->d_ff <= 0 || dims->d_ff % 8)

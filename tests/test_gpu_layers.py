@@ -28,7 +28,7 @@ def dev_gather(ks, off, bits, idx):
 def make_case(geom, fmt, seed):
     g = synth.Geometry(*geom)
     ks, os_ = both_shapes(g, fmt)
-    if fmt == 0:
+    if fmt in (0, 3):
         kv_host = synth.make_kv(g, seed, "cpu", 1, 10.0).numpy()
         bits = synth.draw_bits_uniform(g.n_chunks, seed, widths=(16, 8, 4, 2)).numpy()
     else:
@@ -55,6 +55,7 @@ def as_bits(t):
 @pytest.mark.parametrize("fmt,geom", [(0, (5, 2, 2, 128, 640, 16, 64)),     # 40 chunks, 5 layers
                                       (0, (3, 1, 1, 256, 1600, 32, 128)),   # several wavefront tasks per unit
                                       (0, (4, 3, 3, 64, 160, 16, 64)),      # head_dim 64, 3 kv heads
+                                      (3, (4, 2, 2, 128, 800, 16, 64)),
                                       (1, (4, 2, 2, 128, 800, 16, 64)),
                                       (2, (4, 2, 2, 128, 800, 16, 64))])
 def test_layer_ranges_equal_oracle(fmt, geom):
@@ -88,7 +89,7 @@ def test_layer_by_layer_is_the_whole_load():
     assert torch.equal(step.view(torch.int16), whole.view(torch.int16))
 
 
-@pytest.mark.parametrize("fmt", [0, 2])
+@pytest.mark.parametrize("fmt", [0, 2, 3])
 def test_records_read_straight_from_pinned_host_memory(fmt):
     """The same kernels with the pool left in pinned host memory: list path, layer-wise path and
     kv_load_chunks give the oracle's bytes."""
@@ -103,7 +104,7 @@ def test_records_read_straight_from_pinned_host_memory(fmt):
     lists_h = oracle.build_gather(os_, off, bits, idx)
     lists_d = dev_gather(ks, off, bits, idx)
     ref_whole = filled(ks, kv_host)[1]
-    (oracle.swapin_chunks if fmt == 0 else oracle.swapin_chunks_i8)(os_, packed, *lists_h, ref_whole)
+    (oracle.swapin_chunks if fmt in (0, 3) else oracle.swapin_chunks_i8)(os_, packed, *lists_h, ref_whole)
 
     out, _ = filled(ks, kv_host)
     kvs.kv_swapin_chunks(ks, pool, *lists_d, out)

@@ -84,20 +84,20 @@ def test_bad_list_is_refused_before_anything_is_written():
     assert bool((out.view(torch.int16) == SENTINEL).all())
 
 
-@pytest.mark.parametrize("fmt", [0, 1, 2])
+@pytest.mark.parametrize("fmt", [0, 1, 2, 3])
 def test_compress_selected_writes_only_the_listed_records(fmt):
     """kv_compress_selected (the chunks a call added, compressed when it returns, Sec. 3.4 i): the
     listed records equal the oracle's bit for bit, every other byte of the pool keeps its value."""
     g = synth.Geometry(2, 2, 2, 128, 1280, 16, 64)              # 80 chunks
     ks, os_ = both_shapes(g, fmt)
-    if fmt == 0:
+    if fmt in (0, 3):
         kv_host = synth.make_kv(g, 13, "cpu", 1, 10.0).numpy()
         bits = synth.draw_bits_uniform(g.n_chunks, 13, widths=(16, 8, 4, 2)).numpy()
     else:
         kv_host = synth.make_kv_i8(g, 13).numpy()
         bits = synth.draw_bits_uniform(g.n_chunks, 13, widths=(8, 4, 2, 1)).numpy()
     off = kvs.kv_chunk_offsets(ks, bits)
-    want = oracle.compress_chunks(os_, kv_host, bits, off) if fmt == 0 else oracle.compress_chunks_i8(os_, kv_host, bits, off)
+    want = oracle.compress_chunks(os_, kv_host, bits, off) if fmt in (0, 3) else oracle.compress_chunks_i8(os_, kv_host, bits, off)
     kv_dev = torch.from_numpy(kv_host).to(DEV)
     bits_d = torch.from_numpy(bits).to(DEV)
     off_d = torch.from_numpy(off.view(np.int64)).to(DEV)

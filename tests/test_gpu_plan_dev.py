@@ -55,7 +55,7 @@ FRACTIONS = [(1, 1, 3), (1, 2, 4), (0, 0, 1), (1, 0, 1), (0, 1, 1), (2, 3, 7)]
 @pytest.mark.parametrize("kind", ["uniform", "ties", "constant", "ascending", "signed_zero"])
 def test_plan_equals_oracle(n_chunks, kind):
     T = 16
-    for fmt in (0, 1, 2):
+    for fmt in (0, 1, 2, 3):
         ks, os_ = both_shapes((1, 1, 1, 64, n_chunks * T, T, 64), fmt)
         for k, fr in enumerate(FRACTIONS):
             d = densities(kind, n_chunks, seed=n_chunks * 31 + k)

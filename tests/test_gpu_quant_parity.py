@@ -16,8 +16,8 @@ from gpu_util import (DEV, both_shapes, chunk_view, gpu_compress, gpu_swapin, ha
 pytestmark = pytest.mark.gpu
 
 
-def check_full(geom, kv_host, bits, select=None):
-    ks, os_ = both_shapes(geom)
+def check_full(geom, kv_host, bits, select=None, fmt=0):
+    ks, os_ = both_shapes(geom, fmt)
     kv_dev = torch.from_numpy(kv_host).to(DEV)
     packed_dev, off = gpu_compress(ks, kv_dev, bits)
     want = oracle.compress_chunks(os_, kv_host, bits, off)
@@ -40,12 +40,13 @@ def check_full(geom, kv_host, bits, select=None):
     return got
 
 
-def test_tiny_workload_full():
+@pytest.mark.parametrize("fmt", [0, 3])
+def test_tiny_workload_full(fmt):
     wl = synth.WORKLOADS[0]
     kv = synth.make_kv(wl.geom, wl.seed, "cpu", wl.outlier_channels, wl.outlier_scale).numpy()
     bits = synth.draw_bits_uniform(wl.geom.n_chunks, wl.seed).numpy()
     assert wl.geom.n_chunks == 32
-    check_full(wl.geom, kv, bits)
+    check_full(wl.geom, kv, bits, fmt=fmt)
 
 
 @pytest.mark.parametrize("geom", [
@@ -75,8 +76,9 @@ def test_shapes_and_mixed_widths(geom):
         check_full(g, kv, bits, select=[0, g.n_chunks - 1])
 
 
+@pytest.mark.parametrize("fmt", [0, 3])
 @pytest.mark.parametrize("b", [8, 4, 2])
-def test_adversarial_values(b):
+def test_adversarial_values(b, fmt):
     """Exact ties (k + 0.5 on an integer grid), subnormal halves, constant and all-zero
     groups, signed zeros, the largest finite halves."""
     g = synth.Geometry(1, 2, 2, 128, 64, 16, 64)
@@ -98,17 +100,39 @@ def test_adversarial_values(b):
     x[..., 56:60, :] = np.where(rng.random((g.L, 2, g.Hkv, 4, g.D)) < 0.5, -0.0, 0.0)
     x[..., 60:64, :] = np.where(rng.random((g.L, 2, g.Hkv, 4, g.D)) < 0.5, -65504.0, 65504.0)
     kv = x.astype(np.float16)
-    check_full(g, kv, np.full(g.n_chunks, b, dtype=np.uint8))
+    check_full(g, kv, np.full(g.n_chunks, b, dtype=np.uint8), fmt=fmt)
 
 
+@pytest.mark.parametrize("fmt", [0, 3])
+@pytest.mark.parametrize("b", [8, 4, 2])
+def test_ranges_of_a_few_binary16_subnormal_steps(b, fmt):
+    """Groups whose range is a few steps of the smallest binary16 subnormal: with binary16 parameters the
+    stored scale then has one or two significant bits and may fall short of range / levels by tens of
+    per cent, so quotients run past the top level and must saturate there (never spill into the
+    neighbouring code of a packed byte)."""
+    g = synth.Geometry(1, 2, 2, 128, 64, 16, 64)
+    rng = np.random.default_rng(70 + b)
+    levels = (1 << b) - 1
+    x = np.zeros((g.L, 2, g.Hkv, g.N, g.D), dtype=np.float64)
+    for t in range(g.N):
+        top = int(round(levels * (1.05 + 0.45 * (t % 16) / 15)))      # range / levels between 1.05 and 1.5 steps ...
+        steps = 1 + t // 16                                         # ... of 1 to 4 subnormal steps
+        k = rng.integers(0, top + 1, size=(g.L, 2, g.Hkv, g.D))
+        k[..., 0::64] = 0
+        k[..., 1::64] = top
+        x[..., t, :] = k * steps * 2.0 ** -24 - (t % 3) * 2.0 ** -20
+    check_full(g, x.astype(np.float16), np.full(g.n_chunks, b, dtype=np.uint8), fmt=fmt)
+
+
+@pytest.mark.parametrize("fmt", [0, 3])
 @pytest.mark.parametrize("scale", [1.0, 1e-3, 300.0])
-def test_random_magnitudes_all_groups(scale):
+def test_random_magnitudes_all_groups(scale, fmt):
     """Many random groups per width, including ones whose quotients land within a few
     ulps of a half-integer (exercises the exact-division path)."""
     g = synth.Geometry(4, 4, 4, 128, 256, 16, 64)
     kv = (synth.make_kv(g, 5, "cpu", 1, 10.0).float() * scale).to(torch.float16).numpy()
     bits = synth.draw_bits_uniform(g.n_chunks, 5).numpy()
-    check_full(g, kv, bits)
+    check_full(g, kv, bits, fmt=fmt)
 
 
 def test_gemma_shaped_workload_full():
@@ -241,7 +265,8 @@ def test_random_valid_geometries():
         g = synth.Geometry(L, Hkv, Hkv, D, n_chunks * T, T, G)
         kv = synth.make_kv(g, 100 + done, "cpu", 1, 10.0).numpy()
         bits = rng.choice([16, 8, 4, 2], n_chunks).astype(np.uint8)
-        check_full(g, kv, bits)
+        fmt = 3 if done % 3 == 2 else 0          # every third geometry with binary16 parameters
+        check_full(g, kv, bits, fmt=fmt)
         sel = sorted(rng.choice(n_chunks, int(rng.integers(1, n_chunks + 1)), replace=False).tolist())
-        check_full(g, kv, bits, select=sel)
+        check_full(g, kv, bits, select=sel, fmt=fmt)
         done += 1

@@ -68,12 +68,40 @@ def test_int8_channel_format_sizes_offsets_and_validation():
     assert e.value.code == binding.KV_EBITS
     for bad in (good._replace(head_dim=96), good._replace(head_dim=32, chunk_tokens=32),
                 good._replace(chunk_tokens=64), good._replace(chunk_tokens=4, n_tokens=64),
-                good._replace(format=3), good._replace(format=-1)):
+                good._replace(format=4), good._replace(format=-1)):
         with pytest.raises(kvs.KvError) as e:
             kvs.kv_chunk_offsets(bad, np.full(max(bad.n_chunks, 1), 4, dtype=np.uint8))
         assert e.value.code == binding.KV_ESHAPE
     with pytest.raises(kvs.KvError):      # scoring reads fp16 keys
         kvs.kv_score_workspace_bytes(good, 8)
+
+
+def test_fp16_group_format_with_binary16_parameters_sizes_and_offsets():
+    """Format 3: format 0 with 2 x 2 bytes of parameters per group instead of 2 x 4; same widths, same
+    shape rules; sizes and offsets equal the oracle's and a hand count."""
+    for (D, T, G) in ((64, 16, 64), (128, 16, 64), (128, 32, 128), (256, 16, 64), (1024, 4, 512)):
+        ks = kvs.Shape(3, 2, 2, D, 8 * T, T, G, binding.KV_FMT_F16_GROUPS_H)
+        os_ = oracle.Shape(3, 2, 2, D, 8 * T, T, G, 3)
+        for b in (16, 8, 4, 2):
+            assert kvs.kv_record_bytes(ks, b) == oracle.record_bytes(os_, b)
+        bits = np.array([8, 4, 2, 16, 16, 2, 4, 8], dtype=np.uint8)
+        off = kvs.kv_chunk_offsets(ks, bits)
+        assert np.array_equal(off, oracle.chunk_offsets(os_, bits))
+        assert all(int(o) % 16 == 0 for o in off)
+        got = kvs.kv_build_gather(ks, off, bits, [1, 3, 6])
+        want = oracle.build_gather(os_, off, bits, [1, 3, 6])
+        assert all(np.array_equal(g, w) for g, w in zip(got, want))
+    h = kvs.Shape(32, 32, 32, 128, 4096, 16, 64, binding.KV_FMT_F16_GROUPS_H)
+    assert kvs.kv_record_bytes(h, 8) == 2048 * 16 * (128 + 8) == 4456448         # 4718592 with fp32 parameters
+    assert kvs.kv_record_bytes(h, 2) == 2048 * 16 * (32 + 8)
+    assert kvs.kv_record_bytes(h, 16) == 2048 * 16 * 256
+    with pytest.raises(kvs.KvError) as e:
+        kvs.kv_chunk_offsets(h, np.full(256, 1, dtype=np.uint8))
+    assert e.value.code == binding.KV_EBITS
+    with pytest.raises(kvs.KvError) as e:
+        kvs.kv_chunk_offsets(h._replace(group=96), np.full(256, 8, dtype=np.uint8))
+    assert e.value.code == binding.KV_ESHAPE
+    assert kvs.kv_score_workspace_bytes(h, 32) == kvs.kv_score_workspace_bytes(h._replace(format=0), 32) > 0
 
 
 def test_recompute_entry_points_validate_on_the_host():
