@@ -194,7 +194,8 @@ def run_pipeline(wl, args, dev):
     other chunks are loaded by kv_swapin_pinned on two more.  x = 0 is the plain Load.  Every layer
     has weights of its own (seeded), so that no layer finds its weights in the last-level cache."""
     g = wl.geom
-    shape = kvs.Shape(g.L, g.Hkv, g.Hq, g.D, g.N, g.T, g.G)
+    fmt = 3 if args.format == "f16h" else 0
+    shape = kvs.Shape(g.L, g.Hkv, g.Hq, g.D, g.N, g.T, g.G, fmt)
     d_model, d_ff = g.Hq * g.D, args.d_ff
     dims = kvs.LayerDims(d_model, d_ff)
     kv = synth.make_kv(g, wl.seed, dev, wl.outlier_channels, wl.outlier_scale)
@@ -304,7 +305,7 @@ def run_pipeline(wl, args, dev):
     # The same layer-by-layer order with the context stored as one pool per layer (records of a
     # one-layer shape): a layer's records are then contiguous runs, kv_swapin_pinned moves them with
     # the copy engines, and the recompute of layer l on its own stream waits for that layer's Load.
-    shape1 = kvs.Shape(1, g.Hkv, g.Hq, g.D, g.N, g.T, g.G)
+    shape1 = kvs.Shape(1, g.Hkv, g.Hq, g.D, g.N, g.T, g.G, fmt)
     off1 = kvs.kv_chunk_offsets(shape1, bits)
     total1 = int(off1[-1])
     pools = torch.empty((g.L, total1), dtype=torch.uint8).pin_memory()
@@ -366,7 +367,8 @@ def run_pipeline(wl, args, dev):
         "ms_per_step": best["delay_ms"], "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{wl.name}: [L={g.L},K/V,Hkv={g.Hkv},N={g.N},D={g.D}] fp16, chunk {g.T}, records of "
-                               f"{total} bytes in pinned host memory; Llama-2-7B-sized layers, d_ff {d_ff}",
+                               f"{total} bytes in pinned host memory{' (group parameters in binary16)' if fmt == 3 else ''}; "
+                               f"Llama-2-7B-sized layers, d_ff {d_ff}",
                    "step": "recompute of the first x chunks through all layers || streaming Load of the others"},
         "load_only_ms": base, "best": best, "gain": round(1.0 - best["delay_ms"] / base, 4), "rows": rows,
         "layer_wise_interleaved": {
