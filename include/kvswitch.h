@@ -29,6 +29,11 @@
  *    (bits, offsets, gather lists) are trusted: the caller builds them with
  *    the host helpers below, which validate them.
  *  - fp16 inputs must be finite; NaN/Inf give unspecified codes.
+ *  - Threads: the pure host functions and the device entry points keep no state
+ *    between calls (the error text is per thread) and may be called from several
+ *    threads at once, each on streams of its own.  A kv_lctru_t queue and a
+ *    kv_recompute_t handle are not synchronised: one thread at a time per object
+ *    (the service of Sec. 3 is a single process with one bookkeeping thread).
  *
  * Layouts
  *  fp16 KV cache (dev), contiguous: [n_layers][2 (K=0,V=1)][n_kv_heads][n_tokens][head_dim].
