@@ -717,8 +717,10 @@ __global__ __launch_bounds__(256, 4) void score_head_kernel(const _Float16* __re
     }
 }
 
-// One workgroup per (layer, head): global row maximum and denominator from
-// the per-run partials, then the chunk masses from the per-tile partials.
+// Grid (layer * head, parts): global row maximum and denominator from the per-run
+// partials, then the chunk masses from the per-tile partials.  `parts` workgroups
+// divide the chunks of a head among themselves so that long contexts keep enough
+// wavefronts in flight.
 __global__ __launch_bounds__(256) void score_combine_kernel(ScoreGeom g, ScoreWs ws,
                                                             float* __restrict__ chunk_mass) {
     __shared__ float sh_m[256];
@@ -770,7 +772,10 @@ __global__ __launch_bounds__(256) void score_combine_kernel(ScoreGeom g, ScoreWs
     const int grp = tid >> 5, gl = tid & 31;
     // four chunks per group and pass, all their loads issued before the arithmetic
     constexpr int kUnroll = 4;
-    for (int c0 = grp * kUnroll; c0 < n_chunks; c0 += 8 * kUnroll) {
+    // gridDim.y workgroups share a head's chunks (each derives the row statistics above for itself:
+    // they are a few KB); a chunk belongs to exactly one group of one workgroup
+    const int groups_all = 8 * static_cast<int>(gridDim.y);
+    for (int c0 = (static_cast<int>(blockIdx.y) * 8 + grp) * kUnroll; c0 < n_chunks; c0 += groups_all * kUnroll) {
         float acc[kUnroll] = {0.0f, 0.0f, 0.0f, 0.0f};
         for (int k = 0; k < sb_per_chunk; ++k) {
             for (int rr = gl; rr < g.R; rr += 32) {
