@@ -373,6 +373,9 @@ static int score_geom(const kv_shape_t* shape, int32_t n_queries, int32_t norm_m
     g.tile_par = g.rg_per_wg > 1 ? 1 : 4;
     g.run_len = std::min(g.n_tiles, g.tile_par == 1 ? 64 : 8);
     g.n_runs = (g.n_tiles + g.run_len - 1) / g.run_len;
+    if (g.n_runs > kCombineMaxRuns)        // 2M tokens with one block of query rows per kv head, 16M otherwise
+        return fail(KV_ESHAPE, "scoring handles at most %d runs of tiles per head, this shape has %d", kCombineMaxRuns,
+                    g.n_runs);
     g.norm_mode = norm_mode;
     g.scale_log2e = static_cast<float>(1.4426950408889634 / std::sqrt(static_cast<double>(s.head_dim)));
     g.inv_R = 1.0f / static_cast<float>(n_queries);
@@ -394,7 +397,7 @@ uint64_t kv_score_workspace_bytes(const kv_shape_t* shape, int32_t n_queries) {
     ScoreGeom g;
     int nrbw;
     if (score_geom(shape, n_queries, KV_NORM_VISIBLE, &g, &nrbw) != KV_OK) return 0;
-    const uint64_t bytes = (ws_floats_tile(g) + ws_floats_sub(g) + 2 * ws_floats_run(g)) * sizeof(float);
+    const uint64_t bytes = (ws_floats_tile(g) + ws_floats_sub(g) + 3 * ws_floats_run(g)) * sizeof(float);
     return (bytes + 255) & ~static_cast<uint64_t>(255);
 }
 
@@ -416,6 +419,7 @@ int32_t kv_score_chunks(const kv_shape_t* shape, const void* q, int32_t n_querie
     ws.e_sub = ws.m_tile + ws_floats_tile(g);
     ws.m_run = ws.e_sub + ws_floats_sub(g);
     ws.l_run = ws.m_run + ws_floats_run(g);
+    ws.m_fast = ws.l_run + ws_floats_run(g);
     hipStream_t st = static_cast<hipStream_t>(stream);
     const dim3 grid((g.n_runs + g.tile_par - 1) / g.tile_par,
                     (g.n_rg + g.rg_per_wg - 1) / g.rg_per_wg, g.L * g.Hkv);

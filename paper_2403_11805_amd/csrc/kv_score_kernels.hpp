@@ -50,11 +50,15 @@ struct ScoreGeom {
 //   m_tile [L*Hq][n_tiles][rows_p]   tile-local row maximum (log2 units)
 //   e_sub  [L*Hq][n_sb][rows_p]      weighted sum of 2^(s - m_tile) over the sub-block
 //   m_run, l_run [L*Hq][n_runs][rows_p]  maximum and denominator of a run of tiles
+//   m_fast [L*Hq][n_runs][rows_p]        the ONE reference of the tiles of the run that lie below the
+//                                        causal diagonal, if they were all exponentiated against it (their
+//                                        m_tile slots are then not written); NaN if every tile has its own
 struct ScoreWs {
     float* m_tile;
     float* e_sub;
     float* m_run;
     float* l_run;
+    float* m_fast;
 };
 
 // Softmax partials of one 32-token tile for one block of 32 query rows.
@@ -290,6 +294,7 @@ __global__ __launch_bounds__(256) void score_tiles_kernel(const _Float16* __rest
             const int64_t ri = (static_cast<int64_t>(lh[u]) * g.n_runs + run) * g.rows_p + row[u];
             ws.m_run[ri] = m_run[u];
             ws.l_run[ri] = l_run[u];
+            ws.m_fast[ri] = __builtin_nanf("");      // every tile of this kernel has a reference of its own
         }
     }
 }
@@ -300,11 +305,12 @@ __global__ __launch_bounds__(256) void score_tiles_kernel(const _Float16* __rest
 // store the same values to the same slots; padding rows have slots of their own
 // (rows_p per tile).  `bad` collects rows whose sum left the safe range: the
 // caller then redoes the tile through tile_epilogue.
-//   SBT = sub-blocks per tile (32 / sb_tokens); mt, es = this lane's slots of the tile.
+//   SBT = sub-blocks per tile (32 / sb_tokens); es = this lane's slots of the tile.  The reference is
+//   the same for every tile of the pass and is stored once per run by the caller (ScoreWs::m_fast).
 template <int SBT>
 __device__ __forceinline__ void fast_epilogue(const v16f_t& acc, float scale_log2e, float w,
                                               float m_ref, float& l_run, uint32_t& bad,
-                                              float* __restrict__ mt, float* __restrict__ es, int rows_p) {
+                                              float* __restrict__ es, int rows_p) {
     float l4[4];
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
@@ -330,7 +336,6 @@ __device__ __forceinline__ void fast_epilogue(const v16f_t& acc, float scale_log
     }
     l_run += lsum;
     bad |= (lsum < kRefOverflow) ? 0u : 1u;
-    mt[0] = m_ref;
 #pragma unroll
     for (int k = 0; k < SBT; ++k) es[k * rows_p] = sub[k] * w;
 }
@@ -389,8 +394,7 @@ __global__ __launch_bounds__(256, 2) void score_tiles_shared_kernel(const _Float
     v8h_t qreg[NRBW][KS];
     int row[NRBW], lh[NRBW];
     float m_run[NRBW], l_run[NRBW];
-    float* mt_base[NRBW];     // this lane's slot of tile 0 in m_tile / e_sub
-    float* es_base[NRBW];
+    float* es_base[NRBW];     // this lane's slot of tile 0 in e_sub
 #pragma unroll
     for (int u = 0; u < NRBW; ++u) {
         const int rb = rg * NRBW + u;
@@ -402,7 +406,6 @@ __global__ __launch_bounds__(256, 2) void score_tiles_shared_kernel(const _Float
         lh[u] = l * g.Hq + head;
         m_run[u] = -INFINITY;
         l_run[u] = 0.0f;
-        mt_base[u] = ws.m_tile + static_cast<int64_t>(lh[u]) * g.n_tiles * g.rows_p + r;
         es_base[u] = ws.e_sub + static_cast<int64_t>(lh[u]) * g.n_tiles * SBT * g.rows_p + r;
         const _Float16* qp = q + (static_cast<int64_t>(lh[u]) * g.R + (ok ? r : 0)) * D + half * 8;
 #pragma unroll
@@ -508,7 +511,6 @@ __global__ __launch_bounds__(256, 2) void score_tiles_shared_kernel(const _Float
 #pragma unroll
             for (int u = 0; u < NRBW; ++u)
                 fast_epilogue<SBT>(acc[cur ^ 1][u], g.scale_log2e, w_const, m_run[u], l_run[u], bad,
-                                   mt_base[u] + static_cast<int64_t>(tile - 1) * g.rows_p,
                                    es_base[u] + static_cast<int64_t>(tile - 1) * SBT * g.rows_p, g.rows_p);
             // one MFMA, then a share of the VALU work, and so on
 #pragma unroll
@@ -543,13 +545,21 @@ __global__ __launch_bounds__(256, 2) void score_tiles_shared_kernel(const _Float
             const int set = (last - tile_begin) & 1;
 #pragma unroll
             for (int u = 0; u < NRBW; ++u) {
-                float* mt = mt_base[u] + static_cast<int64_t>(last) * g.rows_p;
                 float* es = es_base[u] + static_cast<int64_t>(last) * SBT * g.rows_p;
-                if (set == 0) fast_epilogue<SBT>(acc[0][u], g.scale_log2e, w_const, m_run[u], l_run[u], bad, mt, es, g.rows_p);
-                else fast_epilogue<SBT>(acc[1][u], g.scale_log2e, w_const, m_run[u], l_run[u], bad, mt, es, g.rows_p);
+                if (set == 0) fast_epilogue<SBT>(acc[0][u], g.scale_log2e, w_const, m_run[u], l_run[u], bad, es, g.rows_p);
+                else fast_epilogue<SBT>(acc[1][u], g.scale_log2e, w_const, m_run[u], l_run[u], bad, es, g.rows_p);
             }
         }
         dirty = __syncthreads_or(static_cast<int>(bad));
+    }
+    // the reference of the fast pass, for the combine kernel (NaN: no fast pass, or it is redone below)
+    if (active) {
+        const bool fast_ok = fast_end > tile_begin && !dirty;
+#pragma unroll
+        for (int u = 0; u < NRBW; ++u)
+            if (half == 0 && row[u] >= 0)
+                ws.m_fast[(static_cast<int64_t>(lh[u]) * g.n_runs + run) * g.rows_p + row[u]] =
+                    fast_ok ? m_run[u] : __builtin_nanf("");
     }
     if (dirty) {
         // start over through the general path (which writes every slot of these tiles again)
@@ -607,7 +617,7 @@ __global__ __launch_bounds__(256, 4) void score_head_kernel(const _Float16* __re
     const int row = lrow < g.R ? lrow : -1;
     float* tmp_m = tmp + wave * 5 * 32;
     float* tmp_e = tmp_m + 32;
-    const ScoreWs no_ws = {nullptr, nullptr, nullptr, nullptr};
+    const ScoreWs no_ws = {nullptr, nullptr, nullptr, nullptr, nullptr};
 
     v8h_t qreg[KS];
     {
@@ -721,6 +731,8 @@ __global__ __launch_bounds__(256, 4) void score_head_kernel(const _Float16* __re
 // partials, then the chunk masses from the per-tile partials.  `parts` workgroups
 // divide the chunks of a head among themselves so that long contexts keep enough
 // wavefronts in flight.
+constexpr int kCombineMaxRuns = 8192;       // runs per head the combine kernel keeps a bit for (host-checked)
+
 __global__ __launch_bounds__(256) void score_combine_kernel(ScoreGeom g, ScoreWs ws,
                                                             float* __restrict__ chunk_mass) {
     __shared__ float sh_m[256];
@@ -770,13 +782,31 @@ __global__ __launch_bounds__(256) void score_combine_kernel(ScoreGeom g, ScoreWs
     const int n_sb = g.N / g.sb_tokens;
     const float* es = ws.e_sub + static_cast<int64_t>(lh) * n_sb * g.rows_p;
     const int grp = tid >> 5, gl = tid & 31;
-    // four chunks per group and pass, all their loads issued before the arithmetic
+    // tiles of a run below the causal diagonal share the run's fast reference where there is one:
+    // one bit per run (the decision is the same for every row of a head), so that the choice
+    // between the two planes is known before either is loaded
+    const float* mf = ws.m_fast + static_cast<int64_t>(lh) * g.n_runs * g.rows_p;
+    const int first_tail_tile = (g.N - g.R + 1) / 32;
+    // run_len is a power of two whenever a head has more than one run; sb_per_tile is 1, 2 or 4
+    const int run_shift = g.n_runs > 1 ? __builtin_ctz(static_cast<unsigned>(g.run_len)) : 31;
+    const int sbt_shift = __builtin_ctz(static_cast<unsigned>(sb_per_tile));
+    __shared__ uint32_t fast_bits[kCombineMaxRuns / 32];
+    for (int w = tid; w < (g.n_runs + 31) / 32; w += 256) {
+        uint32_t bitsw = 0;
+        for (int b = 0; b < 32 && w * 32 + b < g.n_runs; ++b) {
+            const float v = mf[static_cast<int64_t>(w * 32 + b) * g.rows_p];      // row 0 exists in every head
+            bitsw |= (v == v ? 1u : 0u) << b;
+        }
+        fast_bits[w] = bitsw;
+    }
+    __syncthreads();
+    // four chunks per group and pass, all their loads issued before the arithmetic (eight measured slower)
     constexpr int kUnroll = 4;
     // gridDim.y workgroups share a head's chunks (each derives the row statistics above for itself:
     // they are a few KB); a chunk belongs to exactly one group of one workgroup
     const int groups_all = 8 * static_cast<int>(gridDim.y);
     for (int c0 = (static_cast<int>(blockIdx.y) * 8 + grp) * kUnroll; c0 < n_chunks; c0 += groups_all * kUnroll) {
-        float acc[kUnroll] = {0.0f, 0.0f, 0.0f, 0.0f};
+        float acc[kUnroll] = {};
         for (int k = 0; k < sb_per_chunk; ++k) {
             for (int rr = gl; rr < g.R; rr += 32) {
                 float mi[kUnroll], e[kUnroll];
@@ -784,7 +814,12 @@ __global__ __launch_bounds__(256) void score_combine_kernel(ScoreGeom g, ScoreWs
                 for (int u = 0; u < kUnroll; ++u) {
                     const int c = min(c0 + u, n_chunks - 1);
                     const int sb = c * sb_per_chunk + k;
-                    mi[u] = mt[static_cast<int64_t>(sb / sb_per_tile) * g.rows_p + rr];
+                    const int tile = sb >> sbt_shift;
+                    const int rn = tile >> run_shift;
+                    // (uniform per group: a chunk's sub-block lies in one tile)
+                    const bool fast = tile < first_tail_tile && ((fast_bits[rn >> 5] >> (rn & 31)) & 1u);
+                    mi[u] = fast ? mf[static_cast<int64_t>(rn) * g.rows_p + rr]
+                                 : mt[static_cast<int64_t>(tile) * g.rows_p + rr];
                     e[u] = es[static_cast<int64_t>(sb) * g.rows_p + rr];
                 }
                 const float rm = row_m[rr], rf = row_f[rr];
