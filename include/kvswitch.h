@@ -221,7 +221,8 @@ uint64_t kv_score_workspace_bytes(const kv_shape_t* shape, int32_t n_queries);
  *        the last n_queries tokens (row r sits at position n_tokens-n_queries+r);
  *        1 <= n_queries <= min(n_tokens, 256).  Scoring additionally needs
  *        head_dim in {64,128,256}, chunk_tokens a power of two >= 8 and
- *        n_tokens % 32 == 0, and at most 2 097 152 tokens (else KV_ESHAPE).
+ *        n_tokens % 32 == 0, and at most 2 097 152 tokens (16 777 216 where
+ *        several blocks of 32 query rows share a kv head) (else KV_ESHAPE).
  *   kv   dev fp16 cache; only the K planes are read.  Query head h attends to
  *        kv head h / (n_q_heads / n_kv_heads).
  *   A = softmax(causal_mask(Q K^T / sqrt(head_dim))) per (layer, head), fp32.

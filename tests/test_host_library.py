@@ -347,3 +347,14 @@ def test_fit_line_and_plan_pipeline_match_oracle():
         kvs.kv_plan_pipeline((1, 0, 1, 0), [1, 1, 1], rec[::-1])
     with pytest.raises(kvs.KvError):
         kvs.kv_plan_pipeline((1, 0, 1, 0), [1, -1, 1], rec)
+
+
+def test_scoring_refuses_contexts_beyond_its_run_table():
+    """The combine kernel keeps one bit per run of tiles and head: 8192 runs, i.e. 2 097 152 tokens with
+    one block of query rows per kv head (runs of 8 tiles), 16 777 216 with several (runs of 64)."""
+    one = kvs.Shape(1, 1, 1, 64, 2097152, 1024, 64)
+    assert kvs.kv_score_workspace_bytes(one, 32) > 0
+    with pytest.raises(kvs.KvError):
+        kvs.kv_score_workspace_bytes(one._replace(n_tokens=2097152 + 1024), 32)
+    grouped = kvs.Shape(1, 1, 4, 64, 4194304, 1024, 64)
+    assert kvs.kv_score_workspace_bytes(grouped, 32) > 0
