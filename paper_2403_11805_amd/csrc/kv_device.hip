@@ -468,9 +468,12 @@ int32_t kv_score_chunks(const kv_shape_t* shape, const void* q, int32_t n_querie
 #undef KV_SCORE_SHARED
 #undef KV_SCORE_DIRECT
     if (int rc = launch_status("score_tiles_kernel launch")) return rc;
-    // 32 chunks per pass of a workgroup: up to four workgroups per head where that leaves each at least two passes
+    // 32 chunks per pass of a workgroup; a head's chunks are divided among several workgroups where the
+    // heads alone would leave the chip short of eight workgroups per CU (each then still has two passes)
     const int n_chunks_c = g.N / g.T;
-    const uint32_t combine_parts = static_cast<uint32_t>(std::max(1, std::min(4, n_chunks_c / 64)));
+    const int n_heads_c = g.L * g.Hq;
+    const uint32_t combine_parts = static_cast<uint32_t>(
+        std::max(1, std::min((2048 + n_heads_c - 1) / n_heads_c, n_chunks_c / 64)));
     hipLaunchKernelGGL(score_combine_kernel, dim3(g.L * g.Hq, combine_parts), dim3(256), 0, st, g, ws, chunk_mass);
     if (int rc = launch_status("score_combine_kernel launch")) return rc;
     const int n_chunks = g.N / g.T;

@@ -733,12 +733,12 @@ __global__ __launch_bounds__(256, 4) void score_head_kernel(const _Float16* __re
 // wavefronts in flight.
 constexpr int kCombineMaxRuns = 8192;       // runs per head the combine kernel keeps a bit for (host-checked)
 
-__global__ __launch_bounds__(256) void score_combine_kernel(ScoreGeom g, ScoreWs ws,
+__global__ __launch_bounds__(256, 8) void score_combine_kernel(ScoreGeom g, ScoreWs ws,
                                                             float* __restrict__ chunk_mass) {
     __shared__ float sh_m[256];
     __shared__ float sh_l[256];
-    __shared__ float row_m[256];
-    __shared__ float row_f[256];
+    __shared__ __align__(16) float row_m[256];
+    __shared__ __align__(16) float row_f[256];
     const int lh = blockIdx.x;
     const int tid = threadIdx.x;
     const int parts = 256 / g.rows_p;            // rows_p in {32,...,256}
@@ -747,14 +747,25 @@ __global__ __launch_bounds__(256) void score_combine_kernel(ScoreGeom g, ScoreWs
     const float* lr = ws.l_run + static_cast<int64_t>(lh) * g.n_runs * g.rows_p;
     float m = -INFINITY, lsum = 0.0f;
     if (part < parts && r < g.R) {
-        for (int t = part; t < g.n_runs; t += parts) {
-            const float mi = mr[static_cast<int64_t>(t) * g.rows_p + r];
-            const float li = lr[static_cast<int64_t>(t) * g.rows_p + r];
-            if (mi > m) {
-                lsum = lsum * __builtin_amdgcn_exp2f(m - mi) + li;   // m == -inf: lsum is 0
-                m = mi;
-            } else if (mi != -INFINITY) {
-                lsum += li * __builtin_amdgcn_exp2f(mi - m);
+        // four runs per pass, their loads issued together; a slot beyond the last run repeats it as an empty one
+        for (int t = part; t < g.n_runs; t += 4 * parts) {
+            float mi4[4], li4[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int tu = min(t + u * parts, g.n_runs - 1);
+                mi4[u] = mr[static_cast<int64_t>(tu) * g.rows_p + r];
+                li4[u] = lr[static_cast<int64_t>(tu) * g.rows_p + r];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float mi = t + u * parts < g.n_runs ? mi4[u] : -INFINITY;
+                const float li = li4[u];
+                if (mi > m) {
+                    lsum = lsum * __builtin_amdgcn_exp2f(m - mi) + li;   // m == -inf: lsum is 0
+                    m = mi;
+                } else if (mi != -INFINITY) {
+                    lsum += li * __builtin_amdgcn_exp2f(mi - m);
+                }
             }
         }
     }
@@ -774,14 +785,14 @@ __global__ __launch_bounds__(256) void score_combine_kernel(ScoreGeom g, ScoreWs
     }
     __syncthreads();
 
-    // chunk masses: 32 lanes per chunk, lane <-> row (coalesced), fixed-order sums
+    // chunk masses: 16 lanes per chunk, a lane holds four adjacent rows (16-byte loads), fixed-order sums
     const float* mt = ws.m_tile + static_cast<int64_t>(lh) * g.n_tiles * g.rows_p;
     const int n_chunks = g.N / g.T;
     const int sb_per_chunk = g.T / g.sb_tokens;
     const int sb_per_tile = 32 / g.sb_tokens;
     const int n_sb = g.N / g.sb_tokens;
     const float* es = ws.e_sub + static_cast<int64_t>(lh) * n_sb * g.rows_p;
-    const int grp = tid >> 5, gl = tid & 31;
+    const int grp = tid >> 4, gl = tid & 15;
     // tiles of a run below the causal diagonal share the run's fast reference where there is one:
     // one bit per run (the decision is the same for every row of a head), so that the choice
     // between the two planes is known before either is loaded
@@ -791,25 +802,30 @@ __global__ __launch_bounds__(256) void score_combine_kernel(ScoreGeom g, ScoreWs
     const int run_shift = g.n_runs > 1 ? __builtin_ctz(static_cast<unsigned>(g.run_len)) : 31;
     const int sbt_shift = __builtin_ctz(static_cast<unsigned>(sb_per_tile));
     __shared__ uint32_t fast_bits[kCombineMaxRuns / 32];
-    for (int w = tid; w < (g.n_runs + 31) / 32; w += 256) {
-        uint32_t bitsw = 0;
-        for (int b = 0; b < 32 && w * 32 + b < g.n_runs; ++b) {
-            const float v = mf[static_cast<int64_t>(w * 32 + b) * g.rows_p];      // row 0 exists in every head
-            bitsw |= (v == v ? 1u : 0u) << b;
+    // one run per lane, the wavefront's 64 answers collected by a ballot (loads side by side, not in turn)
+    for (int t0 = tid & ~63; t0 < g.n_runs; t0 += 256) {
+        const int t = t0 + (tid & 63);
+        const float v = mf[static_cast<int64_t>(min(t, g.n_runs - 1)) * g.rows_p];   // row 0 exists in every head
+        const uint64_t ok = __ballot(t < g.n_runs && v == v);
+        if ((tid & 63) == 0) {
+            fast_bits[t0 >> 5] = static_cast<uint32_t>(ok);
+            fast_bits[(t0 >> 5) + 1] = static_cast<uint32_t>(ok >> 32);
         }
-        fast_bits[w] = bitsw;
     }
     __syncthreads();
-    // four chunks per group and pass, all their loads issued before the arithmetic (eight measured slower)
-    constexpr int kUnroll = 4;
+    // two chunks per group and pass, all their loads issued before the arithmetic: 62 registers, eight
+    // wavefronts per SIMD (four chunks at four wavefronts per SIMD measured 10 % slower)
+    constexpr int kUnroll = 2;
     // gridDim.y workgroups share a head's chunks (each derives the row statistics above for itself:
     // they are a few KB); a chunk belongs to exactly one group of one workgroup
-    const int groups_all = 8 * static_cast<int>(gridDim.y);
-    for (int c0 = (static_cast<int>(blockIdx.y) * 8 + grp) * kUnroll; c0 < n_chunks; c0 += groups_all * kUnroll) {
+    const int groups_all = 16 * static_cast<int>(gridDim.y);
+    for (int c0 = (static_cast<int>(blockIdx.y) * 16 + grp) * kUnroll; c0 < n_chunks; c0 += groups_all * kUnroll) {
         float acc[kUnroll] = {};
         for (int k = 0; k < sb_per_chunk; ++k) {
-            for (int rr = gl; rr < g.R; rr += 32) {
-                float mi[kUnroll], e[kUnroll];
+            // rows_p is a multiple of 32 and the planes start 16-byte aligned: rr..rr+3 lie in one
+            // aligned piece, rows at or beyond R (padding) are loaded and dropped
+            for (int rr = 4 * gl; rr < g.R; rr += 64) {
+                float4 mi[kUnroll], e[kUnroll];
 #pragma unroll
                 for (int u = 0; u < kUnroll; ++u) {
                     const int c = min(c0 + u, n_chunks - 1);
@@ -818,21 +834,29 @@ __global__ __launch_bounds__(256) void score_combine_kernel(ScoreGeom g, ScoreWs
                     const int rn = tile >> run_shift;
                     // (uniform per group: a chunk's sub-block lies in one tile)
                     const bool fast = tile < first_tail_tile && ((fast_bits[rn >> 5] >> (rn & 31)) & 1u);
-                    mi[u] = fast ? mf[static_cast<int64_t>(rn) * g.rows_p + rr]
-                                 : mt[static_cast<int64_t>(tile) * g.rows_p + rr];
-                    e[u] = es[static_cast<int64_t>(sb) * g.rows_p + rr];
+                    mi[u] = *reinterpret_cast<const float4*>(fast ? mf + static_cast<int64_t>(rn) * g.rows_p + rr
+                                                                  : mt + static_cast<int64_t>(tile) * g.rows_p + rr);
+                    e[u] = *reinterpret_cast<const float4*>(es + static_cast<int64_t>(sb) * g.rows_p + rr);
                 }
-                const float rm = row_m[rr], rf = row_f[rr];
+                const float4 rm = *reinterpret_cast<const float4*>(row_m + rr);
+                const float4 rf = *reinterpret_cast<const float4*>(row_f + rr);
+                const bool l1 = rr + 1 < g.R, l2 = rr + 2 < g.R, l3 = rr + 3 < g.R;
 #pragma unroll
-                for (int u = 0; u < kUnroll; ++u)
-                    if (mi[u] != -INFINITY) acc[u] += e[u] * __builtin_amdgcn_exp2f(mi[u] - rm) * rf;
+                for (int u = 0; u < kUnroll; ++u) {
+                    // a select, not a product with 0: what padding rows hold need not be a number
+                    const float t0 = mi[u].x != -INFINITY ? e[u].x * __builtin_amdgcn_exp2f(mi[u].x - rm.x) * rf.x : 0.0f;
+                    const float t1 = (l1 && mi[u].y != -INFINITY) ? e[u].y * __builtin_amdgcn_exp2f(mi[u].y - rm.y) * rf.y : 0.0f;
+                    const float t2 = (l2 && mi[u].z != -INFINITY) ? e[u].z * __builtin_amdgcn_exp2f(mi[u].z - rm.z) * rf.z : 0.0f;
+                    const float t3 = (l3 && mi[u].w != -INFINITY) ? e[u].w * __builtin_amdgcn_exp2f(mi[u].w - rm.w) * rf.w : 0.0f;
+                    acc[u] += (t0 + t1) + (t2 + t3);
+                }
             }
         }
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             float a = acc[u];
 #pragma unroll
-            for (int o = 16; o >= 1; o >>= 1) a += __shfl_xor(a, o);
+            for (int o = 8; o >= 1; o >>= 1) a += __shfl_xor(a, o);
             if (gl == 0 && c0 + u < n_chunks) chunk_mass[static_cast<int64_t>(lh) * n_chunks + c0 + u] = a;
         }
     }
