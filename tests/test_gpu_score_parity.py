@@ -67,6 +67,7 @@ def test_peaked_and_huge_logits():
     ((1, 2, 4, 64, 4160, 16, 64), 32),     # 130 tiles: runs of 64, 64 and 2
     ((1, 1, 2, 256, 2080, 8, 64), 64),     # head_dim 256: one tile per LDS stage, 65 tiles
     ((1, 1, 3, 128, 640, 16, 64), 32),     # three row blocks per kv head: a wavefront with one block
+    ((1, 1, 2, 64, 8192, 16, 64), 70),     # 96 padded rows (not a power of two), 512 chunks over 8 combine workgroups
 ])
 def test_grouped_query_long_runs(geom, R):
     """Several heads per kv head over many tiles: the pipelined pass of the shared-K kernel."""
