@@ -451,7 +451,7 @@ int32_t kv_score_chunks(const kv_shape_t* shape, const void* q, int32_t n_querie
         if (int rc = launch_status("score_head_kernel launch")) return rc;
         const int n_chunks_h = g.N / g.T;
         const float inv_norm_h = static_cast<float>(1.0 / (static_cast<double>(g.T) * g.L * g.Hq));
-        hipLaunchKernelGGL(score_density_kernel, dim3((n_chunks_h + 63) / 64), dim3(1024), 0, st, chunk_mass, density,
+        hipLaunchKernelGGL(score_density_kernel, dim3((n_chunks_h + kDensityChunks - 1) / kDensityChunks), dim3(1024), 0, st, chunk_mass, density,
                            g.L * g.Hq, n_chunks_h, inv_norm_h);
         return launch_status("score_density_kernel launch");
     }
@@ -478,7 +478,7 @@ int32_t kv_score_chunks(const kv_shape_t* shape, const void* q, int32_t n_querie
     if (int rc = launch_status("score_combine_kernel launch")) return rc;
     const int n_chunks = g.N / g.T;
     const float inv_norm = static_cast<float>(1.0 / (static_cast<double>(g.T) * g.L * g.Hq));
-    hipLaunchKernelGGL(score_density_kernel, dim3((n_chunks + 63) / 64), dim3(1024), 0, st,
+    hipLaunchKernelGGL(score_density_kernel, dim3((n_chunks + kDensityChunks - 1) / kDensityChunks), dim3(1024), 0, st,
                        chunk_mass, density, g.L * g.Hq, n_chunks, inv_norm);
     return launch_status("score_density_kernel launch");
 }

@@ -863,31 +863,42 @@ __global__ __launch_bounds__(256, 8) void score_combine_kernel(ScoreGeom g, Scor
 }
 
 // density[i] = mean over (layer, head) of chunk_mass[.][i], per token of the chunk.
-// Block = 64 chunks x 16 partial sums over the (layer, head) axis; the 16
-// partials are added in a fixed order.
+// Block = 16 chunks x 64 partial sums over the (layer, head) axis (a few blocks of long
+// dependent load chains would be all latency); the 64 partials are added in a fixed order,
+// eight at a time.
+constexpr int kDensityChunks = 16;
 __global__ __launch_bounds__(1024) void score_density_kernel(const float* __restrict__ chunk_mass,
                                                              float* __restrict__ density,
                                                              int32_t n_lh, int32_t n_chunks,
                                                              float inv_norm) {
-    __shared__ float part[16][64];
-    const int ci = threadIdx.x & 63, p = threadIdx.x >> 6;
-    const int i = blockIdx.x * 64 + ci;
+    constexpr int kParts = 1024 / kDensityChunks;
+    __shared__ float part[kParts][kDensityChunks];
+    __shared__ float part8[8][kDensityChunks];
+    const int ci = threadIdx.x % kDensityChunks, p = threadIdx.x / kDensityChunks;
+    const int i = blockIdx.x * kDensityChunks + ci;
     float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
     if (i < n_chunks) {
         int k = p;
-        for (; k + 48 < n_lh; k += 64) {
+        for (; k + 3 * kParts < n_lh; k += 4 * kParts) {
 #pragma unroll
             for (int u = 0; u < 4; ++u)
-                acc[u] += chunk_mass[static_cast<int64_t>(k + 16 * u) * n_chunks + i];
+                acc[u] += chunk_mass[static_cast<int64_t>(k + kParts * u) * n_chunks + i];
         }
-        for (; k < n_lh; k += 16) acc[0] += chunk_mass[static_cast<int64_t>(k) * n_chunks + i];
+        for (; k < n_lh; k += kParts) acc[0] += chunk_mass[static_cast<int64_t>(k) * n_chunks + i];
     }
     part[p][ci] = (acc[0] + acc[1]) + (acc[2] + acc[3]);
+    __syncthreads();
+    if (p < 8) {
+        float t = 0.0f;
+#pragma unroll
+        for (int k = 0; k < kParts / 8; ++k) t += part[p * (kParts / 8) + k][ci];
+        part8[p][ci] = t;
+    }
     __syncthreads();
     if (p == 0 && i < n_chunks) {
         float t = 0.0f;
 #pragma unroll
-        for (int k = 0; k < 16; ++k) t += part[k][ci];
+        for (int k = 0; k < 8; ++k) t += part8[k][ci];
         density[i] = t * inv_norm;
     }
 }
