@@ -549,7 +549,10 @@ int32_t kv_plan_chunks_dev(const kv_shape_t* shape, const float* density_dev, in
     rec.w1 = i8 ? kv_record_bytes(shape, 1) : 0;
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (n <= kPlanScanThreads) {
-        hipLaunchKernelGGL(plan_small_kernel, dim3(1), dim3((n + 63) / 64 * 64), 0, st, density_dev, n, k8, k84,
+        const int width = (n + 63) / 64 * 64;
+        int parts = 1;
+        while (parts < 16 && 2 * parts * width <= kPlanScanThreads) parts *= 2;
+        hipLaunchKernelGGL(plan_small_kernel, dim3(1), dim3(parts * width), 0, st, density_dev, n, width, k8, k84,
                            shape->chunk_tokens, rec, bits_dev, off_dev, dst_tok_dev);
         return launch_status("plan_small_kernel launch");
     }

@@ -77,38 +77,46 @@ __global__ __launch_bounds__(kPlanScanThreads) void plan_offsets_kernel(
     if (tid == kPlanScanThreads - 1) off[n] = part[tid];
 }
 
-// Both steps in one workgroup for up to kPlanScanThreads chunks (one chunk per thread,
-// launched with n rounded up to whole wavefronts): a single launch between scoring and
-// compression.
+// Both steps in one workgroup for up to kPlanScanThreads chunks: a single launch between
+// scoring and compression.  `width` = n rounded up to whole wavefronts; the block has
+// parts * width threads (parts a power of two, at most 16): thread (part, i) counts the chunks
+// that come before chunk i among its share of the others, part 0 adds the counts up and goes on
+// alone (one chunk per thread).
 __global__ __launch_bounds__(kPlanScanThreads) void plan_small_kernel(
-    const float* __restrict__ density, int n, int k8, int k84, int chunk_tokens, RecordBytes rec,
+    const float* __restrict__ density, int n, int width, int k8, int k84, int chunk_tokens, RecordBytes rec,
     uint8_t* __restrict__ bits, uint64_t* __restrict__ off, int32_t* __restrict__ dst_tok) {
     __shared__ __attribute__((aligned(16))) float dens[kPlanScanThreads];
     __shared__ uint64_t part[kPlanScanThreads];
-    const int i = threadIdx.x;
-    const int width = blockDim.x;
+    __shared__ int counts[kPlanScanThreads];
+    const int parts = static_cast<int>(blockDim.x) / width;
+    const int i = static_cast<int>(threadIdx.x) % width, q = static_cast<int>(threadIdx.x) / width;
     const float di = density[i < n ? i : n - 1];
-    dens[i] = i < n ? di : -__builtin_inff();          // padding never comes before a chunk
+    if (q == 0) dens[i] = i < n ? di : -__builtin_inff();          // padding never comes before a chunk
     __syncthreads();
+    const int span = width / parts;                                 // a multiple of 4: width of 64, parts <= 16
     int rank = 0;
-    for (int j = 0; j < width; j += 4) {
+    for (int j = q * span; j < (q + 1) * span; j += 4) {
         const float4 d4 = *reinterpret_cast<const float4*>(dens + j);
         rank += (d4.x > di || (!(di > d4.x) && j + 0 < i)) ? 1 : 0;
         rank += (d4.y > di || (!(di > d4.y) && j + 1 < i)) ? 1 : 0;
         rank += (d4.z > di || (!(di > d4.z) && j + 2 < i)) ? 1 : 0;
         rank += (d4.w > di || (!(di > d4.w) && j + 3 < i)) ? 1 : 0;
     }
+    counts[threadIdx.x] = rank;
+    __syncthreads();
+    rank = 0;
+    for (int p = 0; p < parts; ++p) rank += counts[p * width + i];
     const int b = rank < k8 ? 8 : (rank < k84 ? 4 : 2);
-    const uint64_t own = i < n ? rec.of(b) : 0;
-    part[i] = own;
+    const uint64_t own = (q == 0 && i < n) ? rec.of(b) : 0;
+    if (q == 0) part[i] = own;
     __syncthreads();
     for (int d = 1; d < width; d <<= 1) {
-        const uint64_t add = i >= d ? part[i - d] : 0;
+        const uint64_t add = (q == 0 && i >= d) ? part[i - d] : 0;
         __syncthreads();
-        part[i] += add;
+        if (q == 0) part[i] += add;
         __syncthreads();
     }
-    if (i < n) {
+    if (q == 0 && i < n) {
         bits[i] = static_cast<uint8_t>(b);
         dst_tok[i] = i * chunk_tokens;
         off[i] = part[i] - own;
