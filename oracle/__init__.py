@@ -169,6 +169,32 @@ def score_chunks(shape: Shape, q, kv, norm_mode: int = NORM_VISIBLE):
     return cm, dens
 
 
+def score_chunks_valid(shape: Shape, q, kv, n_valid: int, norm_mode: int = NORM_VISIBLE):
+    """Eq. 1 for a context of n_valid tokens held in a cache padded to shape.N tokens: the valid
+    prefix is scored as the context it is (the R query rows are its last R tokens, the padding is
+    seen by no row), chunk i holds its tokens [iT, min((i+1)T, n_valid)), and the density is the
+    mean per token the chunk really has (0 for a chunk made of padding only).
+    -> (chunk_mass float64 [L][Hq][n_chunks], density float64 [n_chunks])."""
+    q, kv = _u16(q), _u16(kv)
+    R = q.shape[2]
+    assert q.shape == (shape.L, shape.Hq, R, shape.D)
+    assert kv.shape == (shape.L, 2, shape.Hkv, shape.N, shape.D)
+    assert R <= n_valid <= shape.N
+    T, n_chunks = shape.T, shape.n_chunks
+    cm = np.zeros((shape.L, shape.Hq, n_chunks), dtype=np.float64)
+    per_kv = shape.Hq // shape.Hkv
+    for l in range(shape.L):
+        for h in range(shape.Hq):
+            A = attention(q[l, h], kv[l, 0, h // per_kv, :n_valid])
+            col = column_density(A, 1, norm_mode)               # per-token mass of the valid prefix
+            for i in range(n_chunks):
+                cm[l, h, i] = col[i * T:min((i + 1) * T, n_valid)].sum()
+    count = np.clip(n_valid - np.arange(n_chunks) * T, 0, T).astype(np.float64)
+    total = cm.sum(axis=(0, 1))
+    dens = np.where(count > 0, total / (np.maximum(count, 1) * shape.L * shape.Hq), 0.0)
+    return cm, dens
+
+
 def compress_chunks(shape: Shape, kv, bits: np.ndarray, off: np.ndarray) -> np.ndarray:
     """Quantise + pack all chunks -> uint8 pool of off[-1] bytes."""
     kv = _u16(kv)

@@ -191,3 +191,47 @@ def test_large_logits_do_not_overflow():
     # rows that see column 3 put all their weight there
     for r in range(3, N):
         assert A[r, 3] == pytest.approx(1.0, abs=1e-12)
+
+
+def test_padded_context_is_the_valid_prefix_scored_alone():
+    """Scoring n_valid tokens of a padded cache: with n_valid a multiple of the chunk size it is
+    score_chunks on the truncated arrays (the padding, whatever it holds, changes nothing); with a
+    ragged tail the per-token masses are those of torch's softmax over the valid prefix, every
+    head's raw masses sum to R, and a chunk of padding only has density 0."""
+    import torch
+    from paper_2403_11805_amd import synth
+    g = synth.Geometry(2, 1, 2, 64, 96, 16, 64)
+    shape = oracle.Shape(*g)
+    kv = synth.make_kv(g, 5, "cpu", 1, 4.0).numpy().copy()
+    R = 5
+    q = (synth.make_q(g, 5, R).float() * 4).to(torch.float16).numpy()
+    kv[:, :, :, 64:] = 777.0                                      # loud padding
+    # (a) 64 valid tokens = four whole chunks
+    cm, dens = oracle.score_chunks_valid(shape, q, kv, 64, oracle.NORM_VISIBLE)
+    g64 = synth.Geometry(2, 1, 2, 64, 64, 16, 64)
+    cm64, dens64 = oracle.score_chunks(oracle.Shape(*g64), q, np.ascontiguousarray(kv[:, :, :, :64]), oracle.NORM_VISIBLE)
+    np.testing.assert_allclose(cm[:, :, :4], cm64, rtol=1e-6)
+    np.testing.assert_allclose(dens[:4], dens64, rtol=1e-6)
+    assert np.all(cm[:, :, 4:] == 0) and np.all(dens[4:] == 0)
+    # (b) 53 valid tokens: chunk 3 has 5 real tokens
+    nv = 53
+    cm, dens = oracle.score_chunks_valid(shape, q, kv, nv, oracle.NORM_NONE)
+    kvf, qf = torch.from_numpy(kv.astype(np.float32)), torch.from_numpy(q.astype(np.float32))
+    for l in range(2):
+        for h in range(2):
+            s = (qf[l, h].double() @ kvf[l, 0, 0, :nv].double().T) / 8.0
+            pos = torch.arange(nv)[None, :] > (nv - R + torch.arange(R))[:, None]
+            A = torch.softmax(s.masked_fill(pos, float("-inf")), dim=1).numpy()
+            col = A.sum(axis=0)
+            want = [col[i * 16:min((i + 1) * 16, nv)].sum() for i in range(6)]
+            np.testing.assert_allclose(cm[l, h], want, rtol=1e-9, atol=1e-15)
+            assert cm[l, h].sum() == pytest.approx(R, rel=1e-12)
+    count = np.array([16, 16, 16, 5, 0, 0])
+    np.testing.assert_allclose(dens[:4], cm.sum(axis=(0, 1))[:4] / (count[:4] * 4), rtol=1e-12)
+    assert np.all(dens[4:] == 0)
+    # (c) the whole cache valid: the plain function
+    full = synth.make_kv(g, 6, "cpu", 1, 4.0).numpy()
+    a = oracle.score_chunks_valid(shape, q, full, 96, oracle.NORM_VISIBLE)
+    b = oracle.score_chunks(shape, q, full, oracle.NORM_VISIBLE)
+    np.testing.assert_allclose(a[0], b[0], rtol=1e-6)
+    np.testing.assert_allclose(a[1], b[1], rtol=1e-6)
