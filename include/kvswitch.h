@@ -240,6 +240,21 @@ int32_t kv_score_chunks(const kv_shape_t* shape, const void* q, int32_t n_querie
                         void* workspace, uint64_t workspace_bytes,
                         float* chunk_mass, float* density, void* stream);
 
+/* The same for a context of n_valid tokens in a cache padded to n_tokens (Sec. 3.2,
+ * Eq. 1 on the valid prefix; contexts whose length is no multiple of chunk_tokens or
+ * of 32 are padded by the caller): n_queries <= n_valid <= n_tokens (else KV_EINVAL);
+ * the query rows are the last n_queries VALID tokens (row r sits at position
+ * n_valid-n_queries+r), no row sees a padding token and what the padding holds is
+ * never used (it may be anything, NaN included).  Chunk i holds its tokens
+ * [i*chunk_tokens, min((i+1)*chunk_tokens, n_valid)): its chunk_mass sums those columns
+ * and its density is divided by the number of tokens it really has (0 for a chunk of
+ * padding only).  With n_valid == n_tokens this is kv_score_chunks.  Compression and
+ * swap-in treat the padded cache like any other. */
+int32_t kv_score_chunks_valid(const kv_shape_t* shape, const void* q, int32_t n_queries,
+                              const void* kv, int32_t n_valid, int32_t norm_mode,
+                              void* workspace, uint64_t workspace_bytes,
+                              float* chunk_mass, float* density, void* stream);
+
 /* Widths, record offsets and the whole-cache gather list computed on the device
  * (Sec. 3.2, Eq. 2 with fixed thresholds; Sec. 3.1 primitive 3), for callers that
  * keep scoring, compression and swap-in on one stream with no host round trip.

@@ -343,13 +343,15 @@ int32_t kv_swapin_layers(const kv_shape_t* shape, const void* packed, const uint
 
 // --------------------------------------------------------------------- scoring
 
-static int score_geom(const kv_shape_t* shape, int32_t n_queries, int32_t norm_mode, ScoreGeom* out,
-                      int* nrbw) {
+static int score_geom(const kv_shape_t* shape, int32_t n_queries, int32_t n_valid, int32_t norm_mode,
+                      ScoreGeom* out, int* nrbw) {
     if (int rc = check_shape(shape)) return rc;
     const kv_shape_t& s = *shape;
     if (!is_f16(s)) return fail(KV_ESHAPE, "scoring needs an fp16 cache format");
     if (n_queries < 1 || n_queries > s.n_tokens || n_queries > 256)
         return fail(KV_EINVAL, "n_queries %d outside [1, min(n_tokens, 256)]", n_queries);
+    if (n_valid < n_queries || n_valid > s.n_tokens)
+        return fail(KV_EINVAL, "n_valid %d outside [n_queries, n_tokens]", n_valid);
     if (norm_mode != KV_NORM_VISIBLE && norm_mode != KV_NORM_NONE)
         return fail(KV_EINVAL, "norm_mode %d unknown", norm_mode);
     if (s.head_dim != 64 && s.head_dim != 128 && s.head_dim != 256)
@@ -359,6 +361,7 @@ static int score_geom(const kv_shape_t* shape, int32_t n_queries, int32_t norm_m
     if (s.n_tokens % 32) return fail(KV_ESHAPE, "scoring needs n_tokens %% 32 == 0, got %d", s.n_tokens);
     ScoreGeom g;
     g.L = s.n_layers; g.Hkv = s.n_kv_heads; g.Hq = s.n_q_heads; g.N = s.n_tokens; g.R = n_queries;
+    g.Nv = n_valid;
     g.T = s.chunk_tokens;
     g.sb_tokens = std::min(s.chunk_tokens, 32);
     g.n_tiles = s.n_tokens / 32;
@@ -396,7 +399,7 @@ static uint64_t ws_floats_run(const ScoreGeom& g) {
 uint64_t kv_score_workspace_bytes(const kv_shape_t* shape, int32_t n_queries) {
     ScoreGeom g;
     int nrbw;
-    if (score_geom(shape, n_queries, KV_NORM_VISIBLE, &g, &nrbw) != KV_OK) return 0;
+    if (!shape || score_geom(shape, n_queries, shape->n_tokens, KV_NORM_VISIBLE, &g, &nrbw) != KV_OK) return 0;
     const uint64_t bytes = (ws_floats_tile(g) + ws_floats_sub(g) + 3 * ws_floats_run(g)) * sizeof(float);
     return (bytes + 255) & ~static_cast<uint64_t>(255);
 }
@@ -404,9 +407,18 @@ uint64_t kv_score_workspace_bytes(const kv_shape_t* shape, int32_t n_queries) {
 int32_t kv_score_chunks(const kv_shape_t* shape, const void* q, int32_t n_queries, const void* kv,
                         int32_t norm_mode, void* workspace, uint64_t workspace_bytes,
                         float* chunk_mass, float* density, void* stream) {
+    if (!shape) return fail(KV_EINVAL, "NULL shape");
+    return kv_score_chunks_valid(shape, q, n_queries, kv, shape->n_tokens, norm_mode, workspace, workspace_bytes,
+                                 chunk_mass, density, stream);
+}
+
+int32_t kv_score_chunks_valid(const kv_shape_t* shape, const void* q, int32_t n_queries, const void* kv,
+                              int32_t n_valid, int32_t norm_mode, void* workspace, uint64_t workspace_bytes,
+                              float* chunk_mass, float* density, void* stream) {
     ScoreGeom g;
     int nrbw;
-    if (int rc = score_geom(shape, n_queries, norm_mode, &g, &nrbw)) return rc;
+    if (!shape) return fail(KV_EINVAL, "NULL shape");
+    if (int rc = score_geom(shape, n_queries, n_valid, norm_mode, &g, &nrbw)) return rc;
     if (!q || !kv || !workspace || !chunk_mass || !density) return fail(KV_EINVAL, "NULL device pointer");
     if (!aligned(q, 16) || !aligned(kv, 16) || !aligned(workspace, 256))
         return fail(KV_EINVAL, "q/kv must be 16-byte aligned, workspace 256-byte aligned");
@@ -452,7 +464,7 @@ int32_t kv_score_chunks(const kv_shape_t* shape, const void* q, int32_t n_querie
         const int n_chunks_h = g.N / g.T;
         const float inv_norm_h = static_cast<float>(1.0 / (static_cast<double>(g.T) * g.L * g.Hq));
         hipLaunchKernelGGL(score_density_kernel, dim3((n_chunks_h + kDensityChunks - 1) / kDensityChunks), dim3(1024), 0, st, chunk_mass, density,
-                           g.L * g.Hq, n_chunks_h, inv_norm_h);
+                           g.L * g.Hq, n_chunks_h, inv_norm_h, g.T, g.Nv);
         return launch_status("score_density_kernel launch");
     }
     if (g.rg_per_wg > 1) {          // several row groups per kv head: two row blocks per wavefront
@@ -479,7 +491,7 @@ int32_t kv_score_chunks(const kv_shape_t* shape, const void* q, int32_t n_querie
     const int n_chunks = g.N / g.T;
     const float inv_norm = static_cast<float>(1.0 / (static_cast<double>(g.T) * g.L * g.Hq));
     hipLaunchKernelGGL(score_density_kernel, dim3((n_chunks + kDensityChunks - 1) / kDensityChunks), dim3(1024), 0, st,
-                       chunk_mass, density, g.L * g.Hq, n_chunks, inv_norm);
+                       chunk_mass, density, g.L * g.Hq, n_chunks, inv_norm, g.T, g.Nv);
     return launch_status("score_density_kernel launch");
 }
 

@@ -30,6 +30,7 @@ typedef float v16f_t __attribute__((ext_vector_type(16)));
 
 struct ScoreGeom {
     int32_t L, Hkv, Hq, N, R;
+    int32_t Nv;           // valid tokens (<= N): the query rows are the last R of them, the rest is padding
     int32_t T;            // chunk tokens (power of two >= 8)
     int32_t sb_tokens;    // min(T, 32): tokens per stored sub-block
     int32_t n_tiles;      // N / 32
@@ -81,7 +82,7 @@ __device__ __forceinline__ void tile_epilogue(const v16f_t& acc, const ScoreGeom
                                               float& m_ref, float& l_run, float* stage_m = nullptr,
                                               float* stage_e = nullptr) {
     const int t0 = tile * 32;
-    const int first_q_pos = g.N - g.R;
+    const int first_q_pos = g.Nv - g.R;
     const bool tail = (t0 + 31 > first_q_pos);   // wave-uniform: some entry may be masked
     float m_t;
     // q4[k]: (weighted) sum over the lane's tokens 8k..8k+7 of the tile; l4[k]: unweighted
@@ -136,7 +137,9 @@ __device__ __forceinline__ void tile_epilogue(const v16f_t& acc, const ScoreGeom
             const float e = __builtin_amdgcn_exp2f(s[v] - m_use);
             l4[v / 4] += e;
             float w = 1.0f;
-            if (g.norm_mode == 0) w = 1.0f / static_cast<float>(g.N - max(tk, first_q_pos));
+            // rows that see token tk; a padding token is seen by none and its e is 0: no 0 * inf
+            const int seen = g.Nv - max(tk, first_q_pos);
+            if (g.norm_mode == 0) w = seen > 0 ? 1.0f / static_cast<float>(seen) : 0.0f;
             q4[v / 4] += e * w;
         }
         lsum = xhalf_sum((l4[0] + l4[1]) + (l4[2] + l4[3]));
@@ -386,7 +389,7 @@ __global__ __launch_bounds__(256, 2) void score_tiles_shared_kernel(const _Float
     const int l = blockIdx.z / g.Hkv, kvh = blockIdx.z % g.Hkv;
     const int qh_per_kv = g.Hq / g.Hkv;
     // tiles from here on touch the causal diagonal
-    const int first_tail_tile = (g.N - g.R + 1) / 32;
+    const int first_tail_tile = (g.Nv - g.R + 1) / 32;
     const bool two_blocks = rg * NRBW + 1 < g.n_rb;
     // the fast pass needs both row blocks in every wavefront (workgroup-uniform)
     const int fast_end = (g.n_rb % NRBW == 0) ? min(tile_end, max(first_tail_tile, tile_begin)) : tile_begin;
@@ -797,7 +800,7 @@ __global__ __launch_bounds__(256, 8) void score_combine_kernel(ScoreGeom g, Scor
     // one bit per run (the decision is the same for every row of a head), so that the choice
     // between the two planes is known before either is loaded
     const float* mf = ws.m_fast + static_cast<int64_t>(lh) * g.n_runs * g.rows_p;
-    const int first_tail_tile = (g.N - g.R + 1) / 32;
+    const int first_tail_tile = (g.Nv - g.R + 1) / 32;
     // run_len is a power of two whenever a head has more than one run; sb_per_tile is 1, 2 or 4
     const int run_shift = g.n_runs > 1 ? __builtin_ctz(static_cast<unsigned>(g.run_len)) : 31;
     const int sbt_shift = __builtin_ctz(static_cast<unsigned>(sb_per_tile));
@@ -870,7 +873,8 @@ constexpr int kDensityChunks = 16;
 __global__ __launch_bounds__(1024) void score_density_kernel(const float* __restrict__ chunk_mass,
                                                              float* __restrict__ density,
                                                              int32_t n_lh, int32_t n_chunks,
-                                                             float inv_norm) {
+                                                             float inv_norm, int32_t chunk_tokens,
+                                                             int32_t n_valid) {
     constexpr int kParts = 1024 / kDensityChunks;
     __shared__ float part[kParts][kDensityChunks];
     __shared__ float part8[8][kDensityChunks];
@@ -899,7 +903,10 @@ __global__ __launch_bounds__(1024) void score_density_kernel(const float* __rest
         float t = 0.0f;
 #pragma unroll
         for (int k = 0; k < 8; ++k) t += part8[k][ci];
-        density[i] = t * inv_norm;
+        // inv_norm = 1 / (chunk_tokens * n_lh); a chunk at the end of the valid tokens has fewer
+        const int have = min(chunk_tokens, n_valid - i * chunk_tokens);
+        density[i] = have == chunk_tokens ? t * inv_norm
+                                          : (have > 0 ? t / (static_cast<float>(have) * static_cast<float>(n_lh)) : 0.0f);
     }
 }
 

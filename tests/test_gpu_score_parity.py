@@ -230,3 +230,37 @@ def test_random_valid_shapes():
         cm, d = gpu_score(ks, q.to(DEV), kv.to(DEV), norm)
         assert_close(cm, cm_want, f"case {case} {tuple(g)} R={R}: chunk_mass")
         assert_close(d, d_want, f"case {case} {tuple(g)} R={R}: density")
+
+
+@pytest.mark.parametrize("geom,R,n_valid", [
+    ((2, 2, 2, 64, 256, 16, 64), 32, 203),      # direct kernel: ragged chunk, padding inside the last tiles
+    ((1, 2, 8, 128, 2112, 32, 128), 64, 2000),  # shared-K kernel, runs of 64 tiles, three tiles of padding
+    ((1, 1, 4, 128, 640, 16, 64), 40, 333),     # shared-K kernel, half the cache is padding
+    ((8, 32, 32, 64, 512, 16, 64), 32, 500),    # one workgroup per head (256 heads), 12 padding tokens
+    ((8, 32, 32, 128, 512, 8, 64), 20, 37),     # the same kernel, almost everything is padding
+    ((1, 2, 4, 64, 128, 16, 64), 16, 128),      # nothing is padding: the plain entry point
+])
+@pytest.mark.parametrize("norm", [oracle.NORM_VISIBLE, oracle.NORM_NONE])
+def test_padded_context(geom, R, n_valid, norm):
+    """A context shorter than its cache: the valid prefix scored as the context it is, whatever
+    the padding holds (NaN here), chunk masses over the real tokens and densities per real token."""
+    g = synth.Geometry(*geom)
+    ks, os_ = both_shapes(g)
+    kv = synth.make_kv(g, 31, "cpu", 1, 4.0)
+    q = (synth.make_q(g, 31, R).float() * 4).to(torch.float16)
+    cm_want, d_want = oracle.score_chunks_valid(os_, q.numpy(), kv.numpy(), n_valid, norm)
+    kv_dev = kv.to(DEV)
+    kv_dev[:, :, :, n_valid:] = float("nan")
+    ws = torch.empty(kvs.kv_score_workspace_bytes(ks, R), dtype=torch.uint8, device=DEV)
+    cm = torch.full((g.L, g.Hq, g.n_chunks), float("nan"), dtype=torch.float32, device=DEV)
+    d = torch.full((g.n_chunks,), float("nan"), dtype=torch.float32, device=DEV)
+    kvs.kv_score_chunks_valid(ks, q.to(DEV), kv_dev, n_valid, norm, ws, cm, d)
+    torch.cuda.synchronize()
+    cm, d = cm.cpu().numpy(), d.cpu().numpy()
+    live = np.arange(g.n_chunks) * g.T < n_valid
+    assert np.all(cm[:, :, ~live] == 0) and np.all(d[~live] == 0)
+    assert_close(cm[:, :, live], cm_want[:, :, live], "chunk_mass")
+    assert_close(d[live], d_want[live], "density")
+    if n_valid == g.N:
+        cm2, d2 = gpu_score(ks, q.to(DEV), kv_dev, norm)
+        assert np.array_equal(cm2, cm) and np.array_equal(d2, d)

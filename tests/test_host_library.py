@@ -24,7 +24,7 @@ def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "kvswitch.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     declared = set(re.findall(r"\b(kv_[a-z0-9_]+)\s*\(", header))
-    assert {"kv_score_chunks", "kv_compress_chunks", "kv_swapin_chunks", "kv_swapin_pinned",
+    assert {"kv_score_chunks", "kv_score_chunks_valid", "kv_compress_chunks", "kv_swapin_chunks", "kv_swapin_pinned",
             "kv_swapout_aot", "kv_lctru_evict", "kv_build_gather"} <= declared
     handle = ctypes.CDLL(binding.LIB_PATH)
     for name in sorted(declared):
@@ -205,6 +205,10 @@ def test_device_entry_points_validate_before_touching_the_gpu():
     assert L.kv_swapin_layers(ctypes.byref(s), None, None, None, None, 0, 0, 2, None, None) == binding.KV_OK
     assert L.kv_swapin_layers(ctypes.byref(s), None, None, None, None, 3, 0, 2, None, None) == binding.KV_EINVAL   # NULL pointers
     assert L.kv_score_chunks(ctypes.byref(s), None, 8, None, 0, None, 0, None, None, None) == binding.KV_EINVAL
+    # padded contexts: the number of valid tokens lies between the query rows and the cache size
+    for nv in (7, s.n_tokens + 1, -1):
+        assert L.kv_score_chunks_valid(ctypes.byref(s), None, 8, None, nv, 0, None, 0, None, None, None) == binding.KV_EINVAL
+        assert "n_valid" in binding.kv_last_error()
     assert L.kv_swapout_aot(None, None, 0, 0, None, None) == binding.KV_EINVAL
     bad = kvs.Shape(2, 4, 4, 64, 500, 16, 64).c()
     assert L.kv_compress_chunks(ctypes.byref(bad), None, None, None, None, None) == binding.KV_ESHAPE
