@@ -86,7 +86,6 @@ def lib() -> ctypes.CDLL:
         _lib.orc_half_to_float.argtypes = [ctypes.c_uint16]
         _lib.orc_float_to_half.restype = ctypes.c_uint16
         _lib.orc_float_to_half.argtypes = [ctypes.c_float]
-        _lib.orc_record_bytes.restype = ctypes.c_uint64
         _lib.orc_threads.restype = ctypes.c_int
     return _lib
 

@@ -97,6 +97,12 @@ uint16_t orc_float_to_half(float f)
 void orc_attention(const uint16_t* q, const uint16_t* k, int R, int N, int D, double* A)
 {
     const double inv_sqrt_d = 1.0 / sqrt((double)D);
+    /* the fp16 inputs widened once (exactly) instead of inside the dot products */
+    double* qd = (double*)malloc((size_t)R * D * sizeof(double));
+    double* kd = (double*)malloc((size_t)N * D * sizeof(double));
+    if (!qd || !kd) { free(qd); free(kd); for (size_t i = 0; i < (size_t)R * N; ++i) A[i] = NAN; return; }
+    for (size_t i = 0; i < (size_t)R * D; ++i) qd[i] = (double)orc_half_to_float(q[i]);
+    for (size_t i = 0; i < (size_t)N * D; ++i) kd[i] = (double)orc_half_to_float(k[i]);
     for (int r = 0; r < R; ++r) {
         const int last = N - R + r;            /* last visible column */
         double* row = A + (size_t)r * N;
@@ -104,8 +110,7 @@ void orc_attention(const uint16_t* q, const uint16_t* k, int R, int N, int D, do
         for (int c = 0; c <= last; ++c) {
             double s = 0.0;
             for (int d = 0; d < D; ++d)
-                s += (double)orc_half_to_float(q[(size_t)r * D + d]) *
-                     (double)orc_half_to_float(k[(size_t)c * D + d]);
+                s += qd[(size_t)r * D + d] * kd[(size_t)c * D + d];
             s *= inv_sqrt_d;
             row[c] = s;
             if (s > mx) mx = s;
@@ -118,6 +123,8 @@ void orc_attention(const uint16_t* q, const uint16_t* k, int R, int N, int D, do
         for (int c = 0; c <= last; ++c) row[c] /= denom;
         for (int c = last + 1; c < N; ++c) row[c] = 0.0;
     }
+    free(qd);
+    free(kd);
 }
 
 /*
@@ -193,21 +200,6 @@ int orc_score_chunks(const orc_shape* s, const uint16_t* q, int R, const uint16_
     }
     free(cm);
     return fail ? -1 : 0;
-}
-
-/* ----------------------------------------------------------------- record format */
-
-uint64_t orc_record_bytes(const orc_shape* s, int bits)
-{
-    const uint64_t slabs = (uint64_t)s->L * 2 * s->Hkv;
-    if (s->fmt == 1 || s->fmt == 2) {
-        const uint64_t meta = s->fmt == 1 ? 8 : 4;      /* scale + minimum per channel */
-        if (bits == 8) return slabs * s->T * s->D;
-        return slabs * ((uint64_t)s->T * s->D * bits / 8 + meta * s->D);
-    }
-    if (bits == 16) return slabs * s->T * s->D * 2;
-    /* scale + minimum per group: binary32 (fmt 0) or binary16 (fmt 3) */
-    return slabs * s->T * ((uint64_t)s->D * bits / 8 + (s->fmt == 3 ? 4ull : 8ull) * (s->D / s->G));
 }
 
 /* ----------------------------------------------------------------- compress (Sec. 3.2; Sec. 4 packing) */
