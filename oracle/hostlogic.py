@@ -63,8 +63,10 @@ def bits_optimise(density, ratio_num: int, ratio_den: int, as_printed: bool = Fa
 
     Chunks are ranked densest first (ties: lower index).  With k8 chunks at 8
     bits, k4 at 4 and k2 at 2, the average ratio (k8 + k4/2 + k2/4)/n has to be
-    the largest value that does not exceed ratio_num/ratio_den; that fixes
-    3*k8 + k4 = M = floor(n*(4*ratio - 1)) and leaves k8 free.  Every feasible k8
+    the largest reachable value that does not exceed ratio_num/ratio_den; that fixes
+    3*k8 + k4 = M = floor(n*(4*ratio - 1)) and leaves k8 free (M = 3n - 1 is the one
+    total no split of n chunks reaches - it would need k4 = 2 with one chunk left -
+    and gives way to 3n - 2).  Every feasible k8
     is evaluated: ctxInfo = sum_w weight_w * (sum of densities in bucket w), with
     weight_w = ratio_w (denser chunks should get more bits) or, as_printed,
     1/ratio_w (the formula as printed).  The first maximum (smallest k8) wins.
@@ -77,6 +79,8 @@ def bits_optimise(density, ratio_num: int, ratio_den: int, as_printed: bool = Fa
         prefix.append(prefix[-1] + d[i])
     w8, w4, w2 = (1.0, 2.0, 4.0) if as_printed else (1.0, 0.5, 0.25)
     M = n * (4 * ratio_num - ratio_den) // ratio_den
+    if n > 0 and M == 3 * n - 1:
+        M -= 1
     best = None
     for k8 in range(0, n + 1):
         k4 = M - 3 * k8

@@ -126,6 +126,30 @@ def test_optimised_thresholds_meet_the_global_ratio():
     assert oracle.bits_optimise(d, 1, 4)[1] == (0, 0, 10) and oracle.bits_optimise(d, 1, 1)[1] == (10, 0, 0)
 
 
+def test_optimised_thresholds_average_is_the_largest_reachable():
+    """Eq. 3's constraint for every ratio a small context can ask for: the chosen split has the
+    largest mean ratio that any split (k8, k4, k2) of the n chunks reaches without exceeding the
+    target, found here by trying all of them.  Ratios just below 1 ask for a bit budget no
+    split has (3*k8 + k4 = 3n - 1): counts stay non-negative and the mean stays below the target."""
+    from fractions import Fraction
+    rng = np.random.default_rng(3)
+    for n in range(1, 9):
+        d = rng.random(n).astype(np.float32)
+        for den in (4, 7, 12, 100):
+            for num in range((den + 3) // 4, den + 1):
+                target = Fraction(num, den)
+                reach = max(Fraction(4 * k8 + 2 * k4 + (n - k8 - k4), 4 * n)
+                            for k8 in range(n + 1) for k4 in range(n + 1 - k8)
+                            if Fraction(4 * k8 + 2 * k4 + (n - k8 - k4), 4 * n) <= target)
+                for printed in (False, True):
+                    bits, (k8, k4, k2) = oracle.bits_optimise(d, num, den, printed)
+                    assert min(k8, k4, k2) >= 0 and k8 + k4 + k2 == n
+                    assert [(bits == b).sum() for b in (8, 4, 2)] == [k8, k4, k2]
+                    assert Fraction(4 * k8 + 2 * k4 + k2, 4 * n) == reach, (n, num, den)
+    assert oracle.bits_optimise(np.arange(10, dtype=np.float32), 99, 100)[1] == (9, 1, 0)
+    assert oracle.bits_optimise(np.arange(3, dtype=np.float32), 11, 12)[1] == (2, 1, 0)
+
+
 def test_optimised_thresholds_against_brute_force():
     """Weights = ratio_w: no assignment of widths with the same bit budget (not only the
     rank-ordered ones) has a larger ctxInfo."""
