@@ -24,8 +24,14 @@
  *  - Device entry points only enqueue work on the caller's hipStream_t (passed
  *    as void*, NULL = the default stream) and never synchronise (the one
  *    exception, kv_recompute_tune, says so).  Host
- *    arguments are validated before anything is enqueued: an error return
- *    means nothing was launched and nothing written.  Device-side lists
+ *    arguments are validated before anything is enqueued: a validation error
+ *    (KV_EINVAL, KV_ESHAPE, KV_EBITS, KV_EINDEX, KV_ENOMEM) means nothing was
+ *    launched and nothing written.  KV_EHIP reports a failed HIP runtime call;
+ *    from an entry point that enqueues several launches or copies
+ *    (kv_swapin_stream / kv_swapin_pinned, kv_load_chunks with more than 64
+ *    records, kv_recompute_layer, kv_score_chunks) the earlier ones may already
+ *    be enqueued: the output buffers, staging and workspace are then undefined
+ *    until the streams have drained.  Device-side lists
  *    (bits, offsets, gather lists) are trusted: the caller builds them with
  *    the host helpers below, which validate them.
  *  - fp16 inputs must be finite; NaN/Inf give unspecified codes.
@@ -153,7 +159,8 @@ int32_t kv_chunk_offsets(const kv_shape_t* shape, const uint8_t* bits, uint64_t*
  * thresholds): order by (density descending, index ascending); the first
  * k8 = n*num8/den chunks get 8 bits, the next k4 = n*(num8+num4)/den - k8 get
  * 4 bits, the rest 2 bits (integer division).  density: host [n]; bits: host [n].
- * Requires den > 0, num8 >= 0, num4 >= 0, num8 + num4 <= den. */
+ * Requires den > 0, num8 >= 0, num4 >= 0, num8 + num4 <= den and finite densities
+ * (a NaN orders with nothing: KV_EINVAL). */
 int32_t kv_bits_from_scores(const float* density, int32_t n, int32_t num8,
                             int32_t num4, int32_t den, uint8_t* bits);
 
@@ -162,16 +169,17 @@ int32_t kv_bits_from_scores(const float* density, int32_t n, int32_t num8,
  * the k8 densest get 8 bits, the next k4 get 4 bits, the remaining k2 get 2 bits,
  * where (k8, k4, k2) maximises
  *     ctxInfo = w8 * S8 + w4 * S4 + w2 * S2      (S = sum of densities in the bucket)
- * subject to the average ratio (k8 + k4/2 + k2/4) / n being the largest value
- * not above ratio_num / ratio_den.  That leaves one free variable, k8:
- * 3*k8 + k4 = M = floor(n * (4*ratio_num - ratio_den) / ratio_den), k2 = n - k8 - k4,
+ * subject to the average ratio (k8 + k4/2 + k2/4) / n being the largest value some
+ * split reaches that is not above ratio_num / ratio_den.  That leaves one free variable, k8:
+ * 3*k8 + k4 = M = floor(n * (4*ratio_num - ratio_den) / ratio_den), k2 = n - k8 - k4
+ * (M = 3n - 1, which no split reaches, is replaced by 3n - 2),
  * and every feasible k8 is tried.  objective selects the weights:
  *   KV_OBJ_BITS_TO_DENSE  (w8, w4, w2) = (1, 1/2, 1/4) = ratio_w: the reading that
  *                          gives denser chunks more bits (the stated intent);
  *   KV_OBJ_AS_PRINTED     (1, 2, 4) = 1 / ratio_w: Eq. 3 exactly as printed.
  * Sums are accumulated in double in rank order; of equal maxima the smallest k8
  * wins.  density, bits: host [n]; counts (may be NULL): host [3] = k8, k4, k2.
- * Requires n >= 0, ratio_den > 0, 1/4 <= ratio_num/ratio_den <= 1. */
+ * Requires n >= 0, ratio_den > 0, 1/4 <= ratio_num/ratio_den <= 1, finite densities. */
 enum { KV_OBJ_BITS_TO_DENSE = 0, KV_OBJ_AS_PRINTED = 1 };
 int32_t kv_bits_optimise(const float* density, int32_t n, int32_t ratio_num,
                          int32_t ratio_den, int32_t objective, uint8_t* bits,

@@ -2,6 +2,7 @@
 // record sizes and offsets, rank-based bit-width assignment (Sec. 3.2, Eq. 2)
 // and the gather list of the Load primitive (Sec. 3.1).
 #include <algorithm>
+#include <cmath>
 #include <cstdarg>
 #include <cstdio>
 #include <numeric>
@@ -93,11 +94,20 @@ int32_t kv_chunk_offsets(const kv_shape_t* shape, const uint8_t* bits, uint64_t*
     return KV_OK;
 }
 
+// A NaN would make "denser than" no ordering at all (and the device planner, which counts ranks,
+// would disagree with any sort): refused.
+static int check_finite(const float* density, int32_t n) {
+    for (int32_t i = 0; i < n; ++i)
+        if (!std::isfinite(density[i])) return fail(KV_EINVAL, "density[%d] is not finite", i);
+    return KV_OK;
+}
+
 int32_t kv_bits_from_scores(const float* density, int32_t n, int32_t num8, int32_t num4,
                             int32_t den, uint8_t* bits) {
     if (!density || !bits) return fail(KV_EINVAL, "density/bits is NULL");
     if (n < 0 || den <= 0 || num8 < 0 || num4 < 0 || num8 + num4 > den)
         return fail(KV_EINVAL, "need n >= 0, den > 0, 0 <= num8, 0 <= num4, num8+num4 <= den");
+    if (int rc = check_finite(density, n)) return rc;
     std::vector<int32_t> order(static_cast<size_t>(n));
     std::iota(order.begin(), order.end(), 0);
     // densest first; equal densities keep index order
@@ -117,6 +127,7 @@ int32_t kv_bits_optimise(const float* density, int32_t n, int32_t ratio_num, int
     if (objective != KV_OBJ_BITS_TO_DENSE && objective != KV_OBJ_AS_PRINTED)
         return fail(KV_EINVAL, "objective %d unknown", objective);
     if (n > 0 && (!density || !bits)) return fail(KV_EINVAL, "density/bits is NULL");
+    if (int rc = check_finite(density, n)) return rc;
     std::vector<int32_t> order(static_cast<size_t>(n));
     std::iota(order.begin(), order.end(), 0);
     std::stable_sort(order.begin(), order.end(),
@@ -129,7 +140,10 @@ int32_t kv_bits_optimise(const float* density, int32_t n, int32_t ratio_num, int
     const double w8 = 1.0;
     const double w4 = objective == KV_OBJ_BITS_TO_DENSE ? 0.5 : 2.0;
     const double w2 = objective == KV_OBJ_BITS_TO_DENSE ? 0.25 : 4.0;
-    const int64_t M = static_cast<int64_t>(n) * (4LL * ratio_num - ratio_den) / ratio_den;
+    int64_t M = static_cast<int64_t>(n) * (4LL * ratio_num - ratio_den) / ratio_den;
+    // 3*k8 + k4 = 3n - 1 is the one total that no split of n chunks reaches (it needs k4 = 2 with
+    // a single chunk left): the largest reachable average below the target is then 3n - 2
+    if (n > 0 && M == 3LL * n - 1) --M;
     const int64_t k8_lo = std::max<int64_t>(0, (M - n + 1) / 2);   // k2 = n - M + 2*k8 >= 0
     const int64_t k8_hi = M / 3;                                   // k4 = M - 3*k8 >= 0
     int64_t best_k8 = k8_lo;

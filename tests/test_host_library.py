@@ -317,9 +317,25 @@ def test_bits_optimise_matches_oracle():
                 want_bits, want_counts = oracle.bits_optimise(d, num, den, bool(printed))
                 assert got_counts == want_counts, (n, num, den, printed)
                 assert np.array_equal(got_bits, want_bits)
+    # ratios just below 1 ask for a bit budget no split has: counts stay valid, the mean stays below
+    for n, num, den in ((10, 99, 100), (3, 11, 12), (1, 7, 8), (64, 255, 256)):
+        d = rng.random(n).astype(np.float32)
+        for printed in (0, 1):
+            got_bits, (k8, k4, k2) = kvs.kv_bits_optimise(d, num, den, printed)
+            assert min(k8, k4, k2) >= 0 and k8 + k4 + k2 == n
+            assert (k8 + k4 / 2 + k2 / 4) / n <= num / den
+            want_bits, want_counts = oracle.bits_optimise(d, num, den, bool(printed))
+            assert (k8, k4, k2) == want_counts and np.array_equal(got_bits, want_bits)
     for bad in ((1, 5), (3, 2), (0, 1), (1, 0)):
         with pytest.raises(kvs.KvError):
             kvs.kv_bits_optimise(np.ones(4, dtype=np.float32), bad[0], bad[1], 0)
+    for poison in (np.nan, np.inf, -np.inf):
+        d = np.ones(5, dtype=np.float32)
+        d[3] = poison
+        with pytest.raises(kvs.KvError):
+            kvs.kv_bits_optimise(d, 1, 2, 0)
+        with pytest.raises(kvs.KvError):
+            kvs.kv_bits_from_scores(d, 1, 1, 3)
     with pytest.raises(kvs.KvError):
         kvs.kv_bits_optimise(np.ones(4, dtype=np.float32), 1, 2, 7)
 
