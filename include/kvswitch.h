@@ -263,6 +263,23 @@ int32_t kv_score_chunks_valid(const kv_shape_t* shape, const void* q, int32_t n_
                               void* workspace, uint64_t workspace_bytes,
                               float* chunk_mass, float* density, void* stream);
 
+/* kv_score_chunks for callers that cannot allocate device memory and so have no workspace to
+ * hand over: code running under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  The partial results live in a static device array of KV_SCORE_STATIC_BYTES that
+ * every GPU the library runs on holds until the process ends; the call allocates and frees
+ * nothing (its first call on a device looks the array's address up).  Same arguments and
+ * results as kv_score_chunks without the workspace pair.  A shape whose scoring needs more
+ * scratch than the array holds is refused with KV_ENOMEM (kv_score_workspace_bytes tells; a
+ * shape that one workgroup per head scores in LDS - one block of query rows per head and at
+ * least 256 (layer, head) pairs, e.g. a 4096-token multi-head cache - needs none).  All calls
+ * on one GPU share that GPU's array: calls that overlap in time on one GPU (two streams, two
+ * threads) race and give undefined results; calls one after the other on a stream need no
+ * clearing in between. */
+#define KV_SCORE_STATIC_BYTES (32u << 20)
+int32_t kv_score_chunks_static(const kv_shape_t* shape, const void* q, int32_t n_queries,
+                               const void* kv, int32_t norm_mode,
+                               float* chunk_mass, float* density, void* stream);
+
 /* Widths, record offsets and the whole-cache gather list computed on the device
  * (Sec. 3.2, Eq. 2 with fixed thresholds; Sec. 3.1 primitive 3), for callers that
  * keep scoring, compression and swap-in on one stream with no host round trip.

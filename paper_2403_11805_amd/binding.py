@@ -79,6 +79,7 @@ _SIGNATURES = {
     "kv_score_workspace_bytes": (_u64, [_vp, _i32]),
     "kv_score_chunks": (_i32, [_vp, _vp, _i32, _vp, _i32, _vp, _u64, _vp, _vp, _vp]),
     "kv_score_chunks_valid": (_i32, [_vp, _vp, _i32, _vp, _i32, _i32, _vp, _u64, _vp, _vp, _vp]),
+    "kv_score_chunks_static": (_i32, [_vp, _vp, _i32, _vp, _i32, _vp, _vp, _vp]),
     "kv_compress_chunks": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp]),
     "kv_swapin_chunks": (_i32, [_vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp]),
     "kv_swapin_layers": (_i32, [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _vp, _vp]),
@@ -374,6 +375,26 @@ def kv_score_chunks_valid(shape: Shape, q: torch.Tensor, kv: torch.Tensor, n_val
                                        workspace.numel() * workspace.element_size(),
                                        _dev(chunk_mass, torch.float32), _dev(density, torch.float32),
                                        _stream(stream)))
+
+
+KV_SCORE_STATIC_BYTES = 32 << 20
+
+
+def kv_score_chunks_static(shape: Shape, q: torch.Tensor, kv: torch.Tensor, norm_mode: int,
+                           chunk_mass: torch.Tensor, density: torch.Tensor, stream=None) -> None:
+    s = shape.c()
+    n_queries = q.shape[2]
+    if tuple(q.shape) != (shape.n_layers, shape.n_q_heads, n_queries, shape.head_dim):
+        raise ValueError("q must be [L][Hq][R][D]")
+    if tuple(kv.shape) != shape.kv_dims:
+        raise ValueError("kv must be [L][2][Hkv][N][D]")
+    if chunk_mass.numel() != shape.n_layers * shape.n_q_heads * shape.n_chunks or \
+            density.numel() != shape.n_chunks:
+        raise ValueError("chunk_mass/density have the wrong size")
+    _check(lib().kv_score_chunks_static(ctypes.byref(s), _dev(q, torch.float16), n_queries,
+                                        _dev(kv, torch.float16), norm_mode,
+                                        _dev(chunk_mass, torch.float32), _dev(density, torch.float32),
+                                        _stream(stream)))
 
 
 def kv_compress_chunks(shape: Shape, kv: torch.Tensor, bits_dev: torch.Tensor,

@@ -5,6 +5,7 @@
 
 #include <algorithm>
 #include <cmath>
+#include <mutex>
 #include <vector>
 
 #include "kv_internal.h"
@@ -412,6 +413,18 @@ int32_t kv_score_chunks(const kv_shape_t* shape, const void* q, int32_t n_querie
                                  chunk_mass, density, stream);
 }
 
+// LDS of score_head_kernel for this geometry (one workgroup scores a whole head and keeps the
+// partials there), or 0 where that kernel does not apply: it needs one block of query rows per
+// head, at least one (layer, head) per CU and at most 40 KiB, so that four workgroups share a CU.
+static uint64_t score_head_lds_bytes(const ScoreGeom& g, int head_dim) {
+    const uint64_t head_lds = (static_cast<uint64_t>(g.N / g.sb_tokens) * 32 + 2ull * g.n_runs * 32 + 4 * 5 * 32 + 64) *
+                              sizeof(float);
+    return (g.n_rb == 1 && g.L * g.Hkv >= 256 && head_lds <= 40960 && head_dim <= 128) ? head_lds : 0;
+}
+
+static int32_t score_launch(const kv_shape_t* shape, const ScoreGeom& g, int nrbw, const void* q, const void* kv,
+                            void* workspace, float* chunk_mass, float* density, void* stream);
+
 int32_t kv_score_chunks_valid(const kv_shape_t* shape, const void* q, int32_t n_queries, const void* kv,
                               int32_t n_valid, int32_t norm_mode, void* workspace, uint64_t workspace_bytes,
                               float* chunk_mass, float* density, void* stream) {
@@ -426,6 +439,58 @@ int32_t kv_score_chunks_valid(const kv_shape_t* shape, const void* q, int32_t n_
     if (workspace_bytes < need)
         return fail(KV_ENOMEM, "workspace %llu bytes, %llu needed",
                     static_cast<unsigned long long>(workspace_bytes), static_cast<unsigned long long>(need));
+    return score_launch(shape, g, nrbw, q, kv, workspace, chunk_mass, density, stream);
+}
+
+// ---- scoring for callers that cannot allocate: the partials live in a static device array ----
+
+// Scratch of kv_score_chunks_static: one copy per GPU the library runs on, held until the process
+// ends.  In host code the name is only a handle; the device address comes from
+// hipGetSymbolAddress, once per device.
+constexpr uint64_t kStaticScratchBytes = KV_SCORE_STATIC_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static std::mutex scratch_mutex;
+static void* scratch_ptr[kMaxDevices];       // device address of `scratch` on each device, once known
+
+static int static_scratch(void** out) {
+    int dev = -1;
+    KV_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(KV_EINVAL, "device %d outside [0,%d)", dev, kMaxDevices);
+    std::lock_guard<std::mutex> hold(scratch_mutex);
+    if (!scratch_ptr[dev]) {
+        void* p = nullptr;
+        KV_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(KV_EHIP, "hipGetSymbolAddress returned a NULL address");
+        scratch_ptr[dev] = p;
+    }
+    *out = scratch_ptr[dev];
+    return KV_OK;
+}
+
+int32_t kv_score_chunks_static(const kv_shape_t* shape, const void* q, int32_t n_queries, const void* kv,
+                               int32_t norm_mode, float* chunk_mass, float* density, void* stream) {
+    ScoreGeom g;
+    int nrbw;
+    if (!shape) return fail(KV_EINVAL, "NULL shape");
+    if (int rc = score_geom(shape, n_queries, shape->n_tokens, norm_mode, &g, &nrbw)) return rc;
+    if (!q || !kv || !chunk_mass || !density) return fail(KV_EINVAL, "NULL device pointer");
+    if (!aligned(q, 16) || !aligned(kv, 16)) return fail(KV_EINVAL, "q/kv must be 16-byte aligned");
+    // a head scored by one workgroup keeps its partials in LDS and needs no scratch at all
+    const uint64_t need = score_head_lds_bytes(g, shape->head_dim) ? 0 : kv_score_workspace_bytes(shape, n_queries);
+    if (need > kStaticScratchBytes)
+        return fail(KV_ENOMEM, "scoring this shape needs %llu bytes of scratch, the static buffer holds %llu: "
+                    "use kv_score_chunks with a workspace",
+                    static_cast<unsigned long long>(need), static_cast<unsigned long long>(kStaticScratchBytes));
+    void* ws = nullptr;
+    if (int rc = static_scratch(&ws)) return rc;
+    // every slot of the partial planes is written before it is read: nothing has to start at zero
+    return score_launch(shape, g, nrbw, q, kv, ws, chunk_mass, density, stream);
+}
+
+static int32_t score_launch(const kv_shape_t* shape, const ScoreGeom& g, int nrbw, const void* q, const void* kv,
+                            void* workspace, float* chunk_mass, float* density, void* stream) {
     ScoreWs ws;
     ws.m_tile = static_cast<float*>(workspace);
     ws.e_sub = ws.m_tile + ws_floats_tile(g);
@@ -452,9 +517,8 @@ int32_t kv_score_chunks_valid(const kv_shape_t* shape, const void* q, int32_t n_
     // One block of query rows per head and at least one (layer, head) per CU: a workgroup scores a
     // whole head, keeps the partials in LDS and writes the chunk masses itself (at most 40 KiB of
     // LDS, so that four workgroups share a CU).
-    const uint64_t head_lds = (static_cast<uint64_t>(g.N / g.sb_tokens) * 32 + 2ull * g.n_runs * 32 + 4 * 5 * 32 + 64) *
-                              sizeof(float);
-    if (g.n_rb == 1 && g.L * g.Hkv >= 256 && head_lds <= 40960 && D <= 128) {
+    const uint64_t head_lds = score_head_lds_bytes(g, D);
+    if (head_lds) {
         const dim3 hgrid(static_cast<uint32_t>(g.L * g.Hkv));
         if (D == 64)
             hipLaunchKernelGGL(score_head_kernel<64>, hgrid, dim3(256), head_lds, st, qp, kp, g, chunk_mass);
