@@ -148,71 +148,6 @@ def test_gemma_shaped_workload_full():
     assert len(got) == 25952256
 
 
-def sampled_check(geom, kv_dev, bits, sample, select=None):
-    """Full-size run on the GPU; the oracle recomputes the sampled chunks one by one."""
-    ks, os_ = both_shapes(geom)
-    one = oracle.Shape(os_.L, os_.Hkv, os_.Hq, os_.D, os_.T, os_.T, os_.G)   # a one-chunk cache
-    packed_dev, off = gpu_compress(ks, kv_dev, bits)
-    idx = list(range(ks.n_chunks)) if select is None else [int(i) for i in select]
-    out_dev = torch.full(ks.kv_dims, 0x7bff, dtype=torch.int16, device=DEV).view(torch.float16)
-    gpu_swapin(ks, packed_dev, off, bits, idx, out_dev)
-    for i in sample:
-        b = np.array([bits[i]], dtype=np.uint8)
-        o1 = oracle.chunk_offsets(one, b)
-        want = oracle.compress_chunks(one, chunk_view(kv_dev, ks.chunk_tokens, i), b, o1)
-        got = packed_dev[int(off[i]):int(off[i + 1])].cpu().numpy()
-        assert np.array_equal(got, want), f"record of chunk {i} (bits {bits[i]}) differs"
-        got_out = chunk_view(out_dev, ks.chunk_tokens, i).view(np.uint16)
-        if i in idx:
-            ref = np.zeros(got_out.shape, dtype=np.uint16)
-            oracle.swapin_chunks(one, want, *oracle.build_gather(one, o1, b, [0]), ref)
-            assert half_ulp_distance(got_out, ref).max() <= 1
-            assert np.array_equal(got_out, ref)
-        else:
-            assert np.all(got_out == 0x7bff), f"unselected chunk {i} was written"
-    return packed_dev, off, out_dev
-
-
-def test_llama7b_4k_workload_sampled():
-    """Configuration 3's cache (2 GiB) with tercile widths; oracle on sampled chunks."""
-    wl = synth.WORKLOADS[2]
-    g = wl.geom
-    kv_dev = synth.make_kv(g, wl.seed, DEV, wl.outlier_channels, wl.outlier_scale)
-    scores = synth.draw_scores(g.n_chunks, wl.seed).numpy()    # widths from the score kernel are
-    bits = kvs.kv_bits_from_scores(scores, 1, 1, 3)            # covered by the scoring tests
-    assert [(bits == b).sum() for b in (8, 4, 2)] == [85, 85, 86]
-    first = {b: int(np.flatnonzero(bits == b)[0]) for b in (8, 4, 2)}
-    sample = sorted({0, g.n_chunks - 1, *first.values()})
-    _, off, out_dev = sampled_check(g, kv_dev, bits, sample)
-    assert int(off[-1]) == 759169024
-    # property at full size: every dequantised value lies within its group's [min, max]
-    x = kv_dev.view(-1, g.G).float()
-    y = out_dev.view(-1, g.G).float()
-    lo, hi = x.min(dim=1, keepdim=True).values, x.max(dim=1, keepdim=True).values
-    tol = (hi - lo) * 2 ** -10 + 1e-6
-    assert bool(((y >= lo - tol) & (y <= hi + tol)).all())
-    err = (y - x).abs().max(dim=1, keepdim=True).values
-    assert bool((err <= (hi - lo) / 3 * 0.5 + tol + hi.abs().maximum(lo.abs()) * 2 ** -10).all())
-
-
-def test_pool_workload_contexts_sampled():
-    """Configuration 4: contexts 0, 31 and 63 of the 64-context pool, each compressed with
-    its own seeded widths, then a seeded 40 % subset (51 of 128 chunks) swapped in by index."""
-    wl = synth.WORKLOADS[3]
-    g = wl.geom
-    n_sel = int(wl.select_frac * g.n_chunks)
-    assert n_sel == 51
-    for ctx in (0, 31, 63):
-        kv_dev = synth.make_kv(g, wl.seed, DEV, wl.outlier_channels, wl.outlier_scale, context=ctx)
-        bits = synth.draw_bits_uniform(g.n_chunks, wl.seed, context=ctx).numpy()
-        sel = synth.draw_subset(g.n_chunks, n_sel, wl.seed, draw=ctx).numpy()
-        unsel = sorted(set(range(g.n_chunks)) - set(sel.tolist()))
-        sample = [int(sel[0]), int(sel[-1]), int(sel[n_sel // 2]), unsel[0], unsel[-1]]
-        sampled_check(g, kv_dev, bits, sample, select=sel)
-        del kv_dev
-        torch.cuda.empty_cache()
-
-
 def test_empty_selection_and_all_passthrough():
     g = synth.Geometry(1, 2, 2, 64, 64, 16, 64)
     ks, os_ = both_shapes(g)

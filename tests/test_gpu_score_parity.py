@@ -157,45 +157,6 @@ def test_zero_queries_closed_form():
     assert_close(cm[0, 0], mass.reshape(-1, T).sum(1), "chunk_mass")
 
 
-def sampled_heads(wl_index, heads):
-    wl = synth.WORKLOADS[wl_index]
-    g = wl.geom
-    ks, os_ = both_shapes(g)
-    kv_dev = synth.make_kv(g, wl.seed, DEV, wl.outlier_channels, wl.outlier_scale)
-    q_dev = synth.make_q(g, wl.seed, wl.n_queries, DEV)
-    cm, d = gpu_score(ks, q_dev, kv_dev, oracle.NORM_VISIBLE)
-    q_host = q_dev.cpu().numpy()
-    for (l, h) in heads:
-        # the oracle reads only this layer's K plane: hand it a one-layer cache
-        kvh = h // (g.Hq // g.Hkv)
-        one = oracle.Shape(1, 1, 1, g.D, g.N, g.T, g.G)
-        k_host = kv_dev[l:l + 1, :, kvh:kvh + 1].contiguous().cpu().numpy()
-        want = oracle.score_head(one, q_host[l:l + 1, h:h + 1], k_host, 0, 0, oracle.NORM_VISIBLE)
-        assert_close(cm[l, h], want, f"chunk_mass[{l}][{h}]")
-    # density = mean over layers and heads per token, at full size
-    assert_close(d, cm.astype(np.float64).mean(axis=(0, 1)) / g.T, "density")
-    # un-normalised masses of every head sum to the number of query rows
-    cm_raw, d_raw = gpu_score(ks, q_dev, kv_dev, oracle.NORM_NONE)
-    np.testing.assert_allclose(cm_raw.astype(np.float64).sum(axis=2), wl.n_queries, rtol=2e-5)
-    assert float(d_raw.astype(np.float64).sum()) * g.T == pytest.approx(wl.n_queries, rel=2e-5)
-    return d
-
-
-def test_llama7b_4k_workload_sampled_heads():
-    """Configuration 3: R = 32, MHA, 4096 tokens; tercile widths from the GPU scores."""
-    d = sampled_heads(2, [(0, 0), (0, 31), (13, 7), (31, 31), (17, 16), (31, 0)])
-    bits = kvs.kv_bits_from_scores(d, 1, 1, 3)
-    assert [(bits == b).sum() for b in (8, 4, 2)] == [85, 85, 86]
-    assert np.array_equal(bits, oracle.bits_from_scores(d, 1, 1, 3))
-
-
-def test_llama3_32k_workload_sampled_heads():
-    """Configuration 5: R = 64, 32 query heads over 8 kv heads, 32768 tokens."""
-    d = sampled_heads(4, [(0, 0), (31, 31), (9, 14)])
-    bits = kvs.kv_bits_from_scores(d, 1, 1, 3)
-    assert [(bits == b).sum() for b in (8, 4, 2)] == [341, 341, 342]
-
-
 def test_determinism():
     g = synth.Geometry(2, 2, 4, 128, 512, 16, 64)
     ks, _ = both_shapes(g)

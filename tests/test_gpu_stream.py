@@ -80,34 +80,6 @@ def test_streaming_argument_checks():
     assert not bool(out.any()), "a refused call must not write"
 
 
-def test_llama3_32k_workload_streamed_from_pinned_host():
-    """Configuration 5: 4 GiB GQA cache, chunk 32, group 128; widths by terciles of seeded
-    scores; records swapped out ahead of time to pinned host memory, then streamed back."""
-    wl = synth.WORKLOADS[4]
-    g = wl.geom
-    ks, os_ = both_shapes(g)
-    kv_dev = synth.make_kv(g, wl.seed, DEV, wl.outlier_channels, wl.outlier_scale)
-    bits = kvs.kv_bits_from_scores(synth.draw_scores(g.n_chunks, wl.seed).numpy(), 1, 1, 3)
-    assert [(bits == b).sum() for b in (8, 4, 2)] == [341, 341, 342]
-    packed_dev, off = gpu_compress(ks, kv_dev, bits)
-    assert int(off[-1]) == 341 * 2228224 + 341 * 1179648 + 342 * 655360
-    idx = list(range(g.n_chunks))
-    out, pinned = roundtrip_through_host(ks, packed_dev, off, bits, idx, 4 * (64 << 20), 4)
-    ref_dev = torch.empty(ks.kv_dims, dtype=torch.float16, device=DEV)
-    gpu_swapin(ks, packed_dev, off, bits, idx, ref_dev)
-    assert torch.equal(out.view(torch.int16), ref_dev.view(torch.int16))
-    one = oracle.Shape(os_.L, os_.Hkv, os_.Hq, os_.D, os_.T, os_.T, os_.G)
-    for i in (0, 511, g.n_chunks - 1):
-        b = np.array([bits[i]], dtype=np.uint8)
-        o1 = oracle.chunk_offsets(one, b)
-        want = oracle.compress_chunks(one, chunk_view(kv_dev, g.T, i), b, o1)
-        assert np.array_equal(pinned[int(off[i]):int(off[i + 1])].numpy(), want)
-        ref = np.zeros((g.L, 2, g.Hkv, g.T, g.D), dtype=np.uint16)
-        oracle.swapin_chunks(one, want, *oracle.build_gather(one, o1, b, [0]), ref)
-        got = chunk_view(out, g.T, i).view(np.uint16)
-        assert half_ulp_distance(got, ref).max() <= 1 and np.array_equal(got, ref)
-
-
 def test_records_survive_a_file_round_trip(tmp_path):
     """The swapped-out records are the persistent form of a context (Sec. 2.2: contexts outlive the
     app; Sec. 4: chunks are written to storage): a record pool written to a file together with its
