@@ -301,6 +301,23 @@ int32_t kv_plan_chunks_dev(const kv_shape_t* shape, const float* density_dev,
                            uint8_t* bits_dev, uint64_t* off_dev, int32_t* dst_tok_dev,
                            void* stream);
 
+/* The same with the thresholds chosen from a global ratio (Sec. 3.2, Eq. 2 and Eq. 3): the
+ * results equal, bit for bit, those of kv_bits_optimise(density, n_chunks, ratio_num, ratio_den,
+ * objective) followed by kv_chunk_offsets and by kv_build_gather over all chunks.  Chunks are
+ * ranked by counting; the densities are added up in rank order, in double, by one thread (the
+ * host function's order, so that equal maxima of ctxInfo break the same way) and every feasible
+ * k8 is tried in parallel.
+ *   density_dev / bits_dev / off_dev / dst_tok_dev as for kv_plan_chunks_dev (off_dev and
+ *   dst_tok_dev also serve as scratch between the two kernels of the call);
+ *   counts_dev  dev i32 [3] = (k8, k4, k2), may be NULL.
+ * fp16 formats only (Eq. 3 is stated for the levels {8/8, 4/8, 2/8}); ratio and objective as
+ * for kv_bits_optimise (else KV_EINVAL); n_chunks <= 8192 (else KV_ESHAPE: plan on the host).
+ * The packed pool must hold the worst case, n_chunks records of 8 bits. */
+int32_t kv_plan_optimise_dev(const kv_shape_t* shape, const float* density_dev,
+                             int32_t ratio_num, int32_t ratio_den, int32_t objective,
+                             uint8_t* bits_dev, uint64_t* off_dev, int32_t* dst_tok_dev,
+                             int32_t* counts_dev, void* stream);
+
 /* Quantise and bit-pack every chunk at its bit-width (Sec. 3.2 "Compressing
  * chunks"; Sec. 4 bit-shift packing).
  *   kv dev fp16 cache (read only); bits_dev dev u8 [n_chunks];

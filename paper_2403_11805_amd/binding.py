@@ -86,6 +86,7 @@ _SIGNATURES = {
     "kv_compress_selected": (_i32, [_vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp]),
     "kv_load_chunks": (_i32, [_vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp]),
     "kv_plan_chunks_dev": (_i32, [_vp, _vp, _i32, _i32, _i32, _vp, _vp, _vp, _vp]),
+    "kv_plan_optimise_dev": (_i32, [_vp, _vp, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp]),
     "kv_swapin_pinned": (_i32, [_vp, _vp, _vp, _vp, _vp, _i32, _vp, _u64, _i32, _vp, _vp, _vp]),
     "kv_swapout_aot": (_i32, [_vp, _vp, _u64, _u64, _vp, _vp]),
     "kv_recompute_create": (_vp, []),
@@ -434,6 +435,22 @@ def kv_plan_chunks_dev(shape: Shape, density_dev: torch.Tensor, num8: int, num4:
     _check(lib().kv_plan_chunks_dev(ctypes.byref(s), _dev(density_dev, torch.float32), num8, num4, den,
                                     _dev(bits_dev, torch.uint8), _dev(off_dev, torch.int64),
                                     _dev(dst_tok_dev, torch.int32), _stream(stream)))
+
+
+def kv_plan_optimise_dev(shape: Shape, density_dev: torch.Tensor, ratio_num: int, ratio_den: int, objective: int,
+                         bits_dev: torch.Tensor, off_dev: torch.Tensor, dst_tok_dev: torch.Tensor,
+                         counts_dev: torch.Tensor = None, stream=None) -> None:
+    s = shape.c()
+    n = shape.n_chunks
+    if density_dev.numel() != n or bits_dev.numel() != n or dst_tok_dev.numel() != n or off_dev.numel() != n + 1:
+        raise ValueError("need density/bits/dst_tok of n_chunks entries and off of n_chunks + 1")
+    if counts_dev is not None and counts_dev.numel() != 3:
+        raise ValueError("counts_dev must have 3 entries")
+    _check(lib().kv_plan_optimise_dev(ctypes.byref(s), _dev(density_dev, torch.float32), ratio_num, ratio_den,
+                                      objective, _dev(bits_dev, torch.uint8), _dev(off_dev, torch.int64),
+                                      _dev(dst_tok_dev, torch.int32),
+                                      None if counts_dev is None else _dev(counts_dev, torch.int32),
+                                      _stream(stream)))
 
 
 def kv_swapin_chunks(shape: Shape, packed: torch.Tensor, src_off_dev: torch.Tensor,

@@ -640,6 +640,48 @@ int32_t kv_plan_chunks_dev(const kv_shape_t* shape, const float* density_dev, in
     return launch_status("plan_offsets_kernel launch");
 }
 
+int32_t kv_plan_optimise_dev(const kv_shape_t* shape, const float* density_dev, int32_t ratio_num,
+                             int32_t ratio_den, int32_t objective, uint8_t* bits_dev, uint64_t* off_dev,
+                             int32_t* dst_tok_dev, int32_t* counts_dev, void* stream) {
+    if (int rc = check_shape(shape)) return rc;
+    if (is_i8(*shape)) return fail(KV_ESHAPE, "Eq. 3 is stated for the levels {8/8, 4/8, 2/8}: fp16 formats only");
+    if (!density_dev || !bits_dev || !off_dev || !dst_tok_dev) return fail(KV_EINVAL, "NULL device pointer");
+    if (!aligned(density_dev, 4) || !aligned(off_dev, 8) || !aligned(dst_tok_dev, 4) ||
+        (counts_dev && !aligned(counts_dev, 4)))
+        return fail(KV_EINVAL, "density_dev/dst_tok_dev/counts_dev must be 4-byte aligned, off_dev 8-byte aligned");
+    if (ratio_den <= 0 || ratio_num <= 0) return fail(KV_EINVAL, "need a positive ratio");
+    if (static_cast<int64_t>(ratio_num) * 4 < ratio_den || ratio_num > ratio_den)
+        return fail(KV_EINVAL, "ratio %d/%d outside [1/4, 1]", ratio_num, ratio_den);
+    if (objective != KV_OBJ_BITS_TO_DENSE && objective != KV_OBJ_AS_PRINTED)
+        return fail(KV_EINVAL, "objective %d unknown", objective);
+    const int32_t n = shape->n_tokens / shape->chunk_tokens;
+    if (n > kPlanOptMaxChunks)
+        return fail(KV_ESHAPE, "device optimiser handles at most %d chunks, not %d", kPlanOptMaxChunks, n);
+    // the one free variable of Eq. 3 and its feasible range, as in kv_bits_optimise
+    int64_t M = static_cast<int64_t>(n) * (4LL * ratio_num - ratio_den) / ratio_den;
+    if (M == 3LL * n - 1) --M;
+    const int64_t k8_lo = std::max<int64_t>(0, (M - n + 1) / 2);
+    const int64_t k8_hi = M / 3;
+    RecordBytes rec;
+    rec.w16 = kv_record_bytes(shape, 16);
+    rec.w8 = kv_record_bytes(shape, 8);
+    rec.w4 = kv_record_bytes(shape, 4);
+    rec.w2 = kv_record_bytes(shape, 2);
+    rec.w1 = 0;
+    const double w4 = objective == KV_OBJ_BITS_TO_DENSE ? 0.5 : 2.0;
+    const double w2 = objective == KV_OBJ_BITS_TO_DENSE ? 0.25 : 4.0;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // ranks into dst_tok_dev, densities in rank order (as doubles) into off_dev: the two outputs serve as
+    // the scratch between the kernels
+    hipLaunchKernelGGL(plan_rank_kernel, dim3((n + kPlanRankThreads - 1) / kPlanRankThreads), dim3(kPlanRankThreads),
+                       0, st, density_dev, n, dst_tok_dev, reinterpret_cast<double*>(off_dev));
+    if (int rc = launch_status("plan_rank_kernel launch")) return rc;
+    hipLaunchKernelGGL(plan_optimise_kernel, dim3(1), dim3(kPlanScanThreads), 0, st, n, M, static_cast<int>(k8_lo),
+                       static_cast<int>(k8_hi), w4, w2, shape->chunk_tokens, rec, off_dev, dst_tok_dev, bits_dev,
+                       counts_dev);
+    return launch_status("plan_optimise_kernel launch");
+}
+
 // --------------------------------------------------------------------- streaming Load / AoT swap-out
 
 int32_t kv_swapin_pinned(const kv_shape_t* shape, const void* packed_pinned, const uint64_t* src_off,

@@ -124,4 +124,147 @@ __global__ __launch_bounds__(kPlanScanThreads) void plan_small_kernel(
     }
 }
 
+// ------------------------------------------------------------------ thresholds from a global ratio (Eq. 2-3)
+
+constexpr int kPlanOptMaxChunks = 8192;      // sorted densities of one context held in LDS as doubles
+
+// Rank of every chunk as in plan_bits_kernel, written out with the densities in rank order:
+// rank_out[i] = rank of chunk i, sorted_out[rank] = density of chunk i as a double.  Ranks are a
+// permutation, so every slot of sorted_out is written exactly once.
+__global__ __launch_bounds__(kPlanRankThreads) void plan_rank_kernel(
+    const float* __restrict__ density, int n, int32_t* __restrict__ rank_out, double* __restrict__ sorted_out) {
+    __shared__ float tile[kPlanRankThreads];
+    const int i = blockIdx.x * kPlanRankThreads + threadIdx.x;
+    const float di = density[i < n ? i : n - 1];
+    int rank = 0;
+    for (int base = 0; base < n; base += kPlanRankThreads) {
+        const int j0 = base + threadIdx.x;
+        __syncthreads();
+        tile[threadIdx.x] = density[j0 < n ? j0 : n - 1];
+        __syncthreads();
+        const int lim = n - base < kPlanRankThreads ? n - base : kPlanRankThreads;
+        for (int jj = 0; jj < lim; ++jj) {
+            const float dj = tile[jj];
+            const bool before = dj > di || (!(di > dj) && base + jj < i);
+            rank += before ? 1 : 0;
+        }
+    }
+    if (i < n) {
+        rank_out[i] = rank;
+        sorted_out[rank] = static_cast<double>(di);
+    }
+}
+
+// Eq. 3 over the ranked densities, then widths, offsets and the gather list; one workgroup of
+// kPlanScanThreads threads, n <= kPlanOptMaxChunks.
+//   sorted_off : in: the n densities in rank order as doubles (plan_rank_kernel); out: the n + 1
+//                record offsets (the same buffer: every density is in LDS before an offset is written)
+//   rank_dst   : in: rank of chunk i; out: dst_tok[i] = i * chunk_tokens
+// The sums are those of the host function, bit for bit: prefix[k] = the k densest added one by one in
+// rank order in double (one thread: a chain of n additions), and for every feasible k8 in
+// [k8_lo, k8_hi] ctxInfo = w8*S8 + w4*S4 + w2*S2 with S4 = prefix[k8+k4] - prefix[k8], S2 = prefix[n] -
+// prefix[k8+k4], k4 = M - 3*k8; the largest value wins, the smallest k8 among equal ones.
+__global__ __launch_bounds__(kPlanScanThreads) void plan_optimise_kernel(
+    int n, int64_t M, int k8_lo, int k8_hi, double w4, double w2, int chunk_tokens, RecordBytes rec,
+    uint64_t* __restrict__ sorted_off, int32_t* __restrict__ rank_dst, uint8_t* __restrict__ bits,
+    int32_t* __restrict__ counts) {
+    __shared__ double prefix[kPlanOptMaxChunks + 1];
+    __shared__ double best_v[kPlanScanThreads / 64];
+    __shared__ int best_k[kPlanScanThreads / 64];
+    __shared__ uint64_t part[kPlanScanThreads];
+    __shared__ int chosen_k8;
+    const int tid = threadIdx.x;
+    const double* sorted = reinterpret_cast<const double*>(sorted_off);
+    for (int k = tid; k < n; k += kPlanScanThreads) prefix[k + 1] = sorted[k];
+    __syncthreads();
+    if (tid == 0) {
+        double acc = 0.0;
+        prefix[0] = 0.0;
+        for (int k = 1; k <= n; ++k) {
+            acc += prefix[k];
+            prefix[k] = acc;
+        }
+    }
+    __syncthreads();
+    // every feasible k8, strided over the threads; a thread keeps the first of its equal maxima
+    double bv = 0.0;
+    int bk = -1;
+    for (int k8 = k8_lo + tid; k8 <= k8_hi; k8 += kPlanScanThreads) {
+        const int k4 = static_cast<int>(M - 3 * static_cast<int64_t>(k8));
+        const double s8 = prefix[k8];
+        const double s4 = prefix[k8 + k4] - prefix[k8];
+        const double s2 = prefix[n] - prefix[k8 + k4];
+        const double info = 1.0 * s8 + w4 * s4 + w2 * s2;
+        if (bk < 0 || info > bv) {
+            bv = info;
+            bk = k8;
+        }
+    }
+    // (value, smallest k8) maximum over the wavefront, then over the workgroup
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) {
+        const double ov = __shfl_xor(bv, o);
+        const int ok = __shfl_xor(bk, o);
+        const bool take = ok >= 0 && (bk < 0 || ov > bv || (ov == bv && ok < bk));
+        if (take) {
+            bv = ov;
+            bk = ok;
+        }
+    }
+    if ((tid & 63) == 0) {
+        best_v[tid >> 6] = bv;
+        best_k[tid >> 6] = bk;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        double v = best_v[0];
+        int k = best_k[0];
+        for (int w = 1; w < kPlanScanThreads / 64; ++w) {
+            const double ov = best_v[w];
+            const int ok = best_k[w];
+            if (ok >= 0 && (k < 0 || ov > v || (ov == v && ok < k))) {
+                v = ov;
+                k = ok;
+            }
+        }
+        chosen_k8 = k;
+        if (counts) {
+            const int k4 = static_cast<int>(M - 3 * static_cast<int64_t>(k));
+            counts[0] = k;
+            counts[1] = k4;
+            counts[2] = n - k - k4;
+        }
+    }
+    __syncthreads();
+    const int k8 = chosen_k8;
+    const int k84 = k8 + static_cast<int>(M - 3 * static_cast<int64_t>(k8));
+    // widths from the ranks, offsets by a scan of the record sizes (each thread owns a run of chunks)
+    const int per = (n + kPlanScanThreads - 1) / kPlanScanThreads;
+    const int begin = tid * per < n ? tid * per : n;
+    const int end = begin + per < n ? begin + per : n;
+    uint64_t sum = 0;
+    for (int i = begin; i < end; ++i) {
+        const int r = rank_dst[i];
+        const int b = r < k8 ? 8 : (r < k84 ? 4 : 2);
+        bits[i] = static_cast<uint8_t>(b);
+        rank_dst[i] = i * chunk_tokens;
+        sum += rec.of(b);
+    }
+    part[tid] = sum;
+    __syncthreads();
+    for (int d = 1; d < kPlanScanThreads; d <<= 1) {
+        const uint64_t add = tid >= d ? part[tid - d] : 0;
+        __syncthreads();
+        part[tid] += add;
+        __syncthreads();
+    }
+    uint64_t at = part[tid] - sum;
+    for (int i = begin; i < end; ++i) {
+        sorted_off[i] = at;
+        const int b = bits[i];                   // this thread's own store above
+        at += rec.of(b);
+    }
+    if (tid == kPlanScanThreads - 1) sorted_off[n] = part[tid];
+}
+
 }  // namespace kvs
