@@ -23,6 +23,7 @@ from .hostlogic import (  # noqa: F401  (re-exported)
     chunk_offsets,
     fit_line,
     pipeline_delay,
+    pipeline_split,
     plan_pipeline,
     record_bytes,
 )

@@ -140,6 +140,26 @@ def plan_pipeline(model, missing, record_bytes):
     return best
 
 
+def pipeline_split(missing_idx, bits, recompute):
+    """The chunks a plan of Eq. 4 sends to each stage.  `missing_idx` (strictly ascending) are
+    the chunks to recover, bits[i] the width of chunk i, recompute = (r8, r4, r2) the number of
+    8-, 4- and 2-bit chunks to recompute.  The paper leaves open WHICH chunks of a width are
+    recomputed; the reading here: the earliest ones (lowest index), so that a recomputed
+    token depends on as few loaded chunks as possible.  Returns (recompute_idx, load_idx),
+    both ascending: together they are missing_idx."""
+    want = {8: recompute[0], 4: recompute[1], 2: recompute[2]}
+    re_idx, io_idx = [], []
+    for i in missing_idx:
+        b = int(bits[int(i)])
+        if want.get(b, 0) > 0:
+            want[b] -= 1
+            re_idx.append(int(i))
+        else:
+            io_idx.append(int(i))
+    assert all(v == 0 for v in want.values()), "more chunks of a width to recompute than are missing"
+    return np.array(re_idx, dtype=np.int32), np.array(io_idx, dtype=np.int32)
+
+
 def build_gather(shape, off, bits, chunk_idx):
     """Gather list for loading the chunks `chunk_idx` (strictly ascending):
     where each record starts, which token it lands on, and its bit-width."""

@@ -244,3 +244,33 @@ def test_plan_pipeline_closed_forms():
     assert r[0] == 2 and r[2] == 0 and 0 < r[1] < 50      # 8-bit chunks first, then 4-bit
     # a fixed recompute cost larger than the whole IO: do not start recomputing
     assert oracle.plan_pipeline((1e-6, 1.0, 1e-6, 0.0), [5, 5, 5], rec)[0] == (0, 0, 0)
+
+
+def test_pipeline_split_hand_example_and_properties():
+    """Which chunks a plan recomputes: the earliest of each width.  A hand-made example, then random
+    cases checked through what defines the result: the two lists partition the missing chunks, each
+    is ascending, the recomputed ones hold exactly the planned number per width, and no loaded chunk
+    of a width precedes a recomputed chunk of the same width."""
+    bits = np.array([8, 4, 2, 8, 4, 2, 8, 4, 2, 8], dtype=np.uint8)
+    re, io = oracle.pipeline_split([0, 1, 3, 4, 5, 6, 8, 9], bits, (2, 1, 1))
+    assert re.tolist() == [0, 1, 3, 5] and io.tolist() == [4, 6, 8, 9]
+    re, io = oracle.pipeline_split([2, 5, 7], bits, (0, 0, 0))
+    assert re.tolist() == [] and io.tolist() == [2, 5, 7]
+    re, io = oracle.pipeline_split([2, 5, 7], bits, (0, 1, 2))
+    assert re.tolist() == [2, 5, 7] and io.tolist() == []
+    rng = np.random.default_rng(4)
+    for _ in range(50):
+        n = int(rng.integers(1, 40))
+        bits = rng.choice([8, 4, 2], n).astype(np.uint8)
+        missing = np.flatnonzero(rng.random(n) < 0.6)
+        have = [int((bits[missing] == b).sum()) for b in (8, 4, 2)]
+        plan = tuple(int(rng.integers(0, h + 1)) for h in have)
+        re, io = oracle.pipeline_split(missing, bits, plan)
+        assert sorted(re.tolist() + io.tolist()) == missing.tolist()
+        assert re.tolist() == sorted(re.tolist()) and io.tolist() == sorted(io.tolist())
+        for b, want in zip((8, 4, 2), plan):
+            mine = [i for i in re if bits[i] == b]
+            assert len(mine) == want
+            assert all(j > max(mine) for j in io if bits[j] == b) if mine else True
+    with pytest.raises(AssertionError):
+        oracle.pipeline_split([0, 1], np.array([8, 8], dtype=np.uint8), (3, 0, 0))
