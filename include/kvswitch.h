@@ -18,7 +18,8 @@
  *    "host" pointers ordinary host memory, "pinned" host memory obtained from
  *    hipHostMalloc (or torch pin_memory).  The library keeps no pointer after a
  *    call returns and allocates no device memory (kv_swapin_pinned and
- *    kv_swapout_aot create and destroy a few HIP events per call; a
+ *    kv_swapout_aot create and destroy a few HIP events per call, a
+ *    kv_loader_t handle owns its events until it is destroyed; a
  *    kv_recompute_t handle owns the GEMM library's handle, with that library's
  *    own device workspace, until it is destroyed).
  *  - Device entry points only enqueue work on the caller's hipStream_t (passed
@@ -37,7 +38,7 @@
  *  - fp16 inputs must be finite; NaN/Inf give unspecified codes.
  *  - Threads: the pure host functions and the device entry points keep no state
  *    between calls (the error text is per thread) and may be called from several
- *    threads at once, each on streams of its own.  A kv_lctru_t queue and a
+ *    threads at once, each on streams of its own.  A kv_lctru_t queue, a kv_loader_t and a
  *    kv_recompute_t handle are not synchronised: one thread at a time per object
  *    (the service of Sec. 3 is a single process with one bookkeeping thread).
  *
@@ -210,6 +211,20 @@ int32_t kv_fit_line(const double* x, const double* t, int32_t n, double* slope, 
  * slopes and intercepts. */
 int32_t kv_plan_pipeline(const kv_pipeline_model_t* model, const int32_t* missing,
                          const uint64_t* record_bytes, int32_t* recompute, double* delay);
+
+/* The chunks a plan of Eq. 4 sends to each stage (Sec. 3.3 ii): of the n_missing chunks
+ * missing_idx (strictly ascending, else KV_EINDEX) with widths bits[i] (host [n_chunks]), the
+ * recompute[w] EARLIEST chunks of width 8, 4, 2 (w = 0, 1, 2) go to the recompute stage, all
+ * others - pass-through and 1-bit chunks included - to the Load.  (The paper leaves open which
+ * chunks of a width are recomputed; the earliest depend on the fewest loaded chunks.)
+ * recompute_idx, load_idx: host, room for n_missing entries each, filled in ascending order;
+ * load_idx is what kv_build_gather / kv_load_chunks take, recompute_idx what
+ * kv_recompute_layer takes.  KV_EINVAL if the plan recomputes more chunks of a width than are
+ * missing. */
+int32_t kv_pipeline_split(const kv_shape_t* shape, const uint8_t* bits, const int32_t* missing_idx,
+                          int32_t n_missing, const int32_t* recompute,
+                          int32_t* recompute_idx, int32_t* n_recompute,
+                          int32_t* load_idx, int32_t* n_load);
 
 /* Load primitive, list building (Sec. 3.1, primitive 3): for n_sel strictly
  * ascending chunk indices produce src_off[j] = off[idx_j], dst_tok[j] =
@@ -387,6 +402,11 @@ int32_t kv_load_chunks(const kv_shape_t* shape, const void* packed, const uint64
  * the recompute stage.  The listed records are copied host->device in batches
  * on copy_stream into n_buffers staging slots while earlier batches are
  * dequantised on compute_stream.
+ *   ld  a loader handle: it owns the HIP events that order copies and kernels (created
+ *   once, by kv_loader_create, on the device that is current then) and remembers which
+ *   staging slots a kernel of an earlier call may still be reading, so that calls one
+ *   after the other through one loader may share their staging memory and streams.
+ *   One thread at a time per loader.
  *   packed_pinned pinned host pool; src_off/dst_tok/sel_bits HOST lists [n_sel]
  *   as produced by kv_build_gather (ascending chunks, hence ascending offsets);
  *   staging_dev dev scratch of staging_bytes, 256-byte aligned, split into
@@ -395,13 +415,23 @@ int32_t kv_load_chunks(const kv_shape_t* shape, const void* packed, const uint64
  *   kv_out dev fp16 cache.  copy_stream and compute_stream must differ and
  *   must not be the NULL stream.  Returns after enqueuing everything;
  *   completion = both streams idle (the last kernel is on compute_stream).
- *   The staging slots belong to the call until its last kernel has finished: a
- *   further call on the same streams needs staging memory of its own, or
- *   copy_stream must first wait for compute_stream (an event).
  *   A context kept as one pool per layer (records of a shape with n_layers = 1,
  *   kv_out pointing at the layer's slice of the cache) is loaded layer by layer
  *   with one such call per layer: the order of the swapping-recompute pipeline
  *   (Sec. 3.3), with the copies on the DMA engines. */
+typedef struct kv_loader kv_loader_t;
+kv_loader_t* kv_loader_create(void);               /* NULL on failure (kv_last_error has the text) */
+void         kv_loader_destroy(kv_loader_t* ld);   /* after the streams it was used on have drained */
+int32_t kv_swapin_stream(kv_loader_t* ld, const kv_shape_t* shape, const void* packed_pinned,
+                         const uint64_t* src_off, const int32_t* dst_tok,
+                         const uint8_t* sel_bits, int32_t n_sel,
+                         void* staging_dev, uint64_t staging_bytes, int32_t n_buffers,
+                         void* kv_out, void* copy_stream, void* compute_stream);
+
+/* kv_swapin_stream for a single Load, without a loader: the events are created for the call
+ * and destroyed when it returns (the enqueued work keeps what it needs).  The staging slots
+ * belong to the call until its last kernel has finished: a further call on the same streams
+ * needs staging memory of its own, or copy_stream must first wait for compute_stream. */
 int32_t kv_swapin_pinned(const kv_shape_t* shape, const void* packed_pinned,
                          const uint64_t* src_off, const int32_t* dst_tok,
                          const uint8_t* sel_bits, int32_t n_sel,

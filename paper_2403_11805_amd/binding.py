@@ -75,6 +75,7 @@ _SIGNATURES = {
     "kv_bits_optimise": (_i32, [_vp, _i32, _i32, _i32, _i32, _vp, _vp]),
     "kv_fit_line": (_i32, [_vp, _vp, _i32, _vp, _vp]),
     "kv_plan_pipeline": (_i32, [_vp, _vp, _vp, _vp, _vp]),
+    "kv_pipeline_split": (_i32, [_vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp]),
     "kv_build_gather": (_i32, [_vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp]),
     "kv_score_workspace_bytes": (_u64, [_vp, _i32]),
     "kv_score_chunks": (_i32, [_vp, _vp, _i32, _vp, _i32, _vp, _u64, _vp, _vp, _vp]),
@@ -88,6 +89,9 @@ _SIGNATURES = {
     "kv_plan_chunks_dev": (_i32, [_vp, _vp, _i32, _i32, _i32, _vp, _vp, _vp, _vp]),
     "kv_plan_optimise_dev": (_i32, [_vp, _vp, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp]),
     "kv_swapin_pinned": (_i32, [_vp, _vp, _vp, _vp, _vp, _i32, _vp, _u64, _i32, _vp, _vp, _vp]),
+    "kv_loader_create": (_vp, []),
+    "kv_loader_destroy": (None, [_vp]),
+    "kv_swapin_stream": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _u64, _i32, _vp, _vp, _vp]),
     "kv_swapout_aot": (_i32, [_vp, _vp, _u64, _u64, _vp, _vp]),
     "kv_recompute_create": (_vp, []),
     "kv_recompute_destroy": (None, [_vp]),
@@ -316,6 +320,23 @@ def kv_plan_pipeline(model, missing, record_bytes):
     return tuple(int(v) for v in out), d.value
 
 
+def kv_pipeline_split(shape: Shape, bits, missing_idx, recompute):
+    """-> (recompute_idx, load_idx), both int32 ascending."""
+    s = shape.c()
+    bits, missing_idx = _np(bits, np.uint8), _np(missing_idx, np.int32)
+    if len(bits) != shape.n_chunks:
+        raise ValueError("bits must have n_chunks entries")
+    plan = _np(recompute, np.int32)
+    if len(plan) != 3:
+        raise ValueError("recompute must have 3 entries")
+    n = len(missing_idx)
+    re_idx, io_idx = np.empty(max(n, 1), dtype=np.int32), np.empty(max(n, 1), dtype=np.int32)
+    n_re, n_io = ctypes.c_int32(0), ctypes.c_int32(0)
+    _check(lib().kv_pipeline_split(ctypes.byref(s), _hp(bits), _hp(missing_idx), n, _hp(plan), _hp(re_idx),
+                                   ctypes.byref(n_re), _hp(io_idx), ctypes.byref(n_io)))
+    return re_idx[:n_re.value].copy(), io_idx[:n_io.value].copy()
+
+
 def kv_build_gather(shape: Shape, off, bits, chunk_idx):
     s = shape.c()
     off, bits, idx = _np(off, np.uint64), _np(bits, np.uint8), _np(chunk_idx, np.int32)
@@ -517,6 +538,45 @@ def kv_swapin_pinned(shape: Shape, packed_pinned: torch.Tensor, src_off, dst_tok
                                   staging_dev.numel() * staging_dev.element_size(), n_buffers,
                                   _dev(kv_out, shape.cache_dtype), _stream(copy_stream),
                                   _stream(compute_stream)))
+
+
+class Loader:
+    """Owner of a kv_loader_t handle (kv_loader_create / kv_loader_destroy); swapin_stream is
+    kv_swapin_stream."""
+
+    def __init__(self):
+        self._h = lib().kv_loader_create()
+        if not self._h:
+            raise KvError(KV_EHIP, kv_last_error())
+
+    def close(self):
+        if self._h:
+            lib().kv_loader_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def swapin_stream(self, shape: Shape, packed_pinned: torch.Tensor, src_off, dst_tok, sel_bits,
+                      staging_dev: torch.Tensor, n_buffers: int, kv_out: torch.Tensor,
+                      copy_stream, compute_stream) -> None:
+        s = shape.c()
+        if packed_pinned.is_cuda or not packed_pinned.is_pinned():
+            raise TypeError("packed_pinned must be a pinned host tensor")
+        src_off, dst_tok, sel_bits = _np(src_off, np.uint64), _np(dst_tok, np.int32), _np(sel_bits, np.uint8)
+        n_sel = len(src_off)
+        if len(dst_tok) != n_sel or len(sel_bits) != n_sel:
+            raise ValueError("gather lists differ in length")
+        if kv_out.numel() != int(np.prod(shape.kv_dims)):
+            raise ValueError("kv_out must hold [L][2][Hkv][N][D]")
+        _check(lib().kv_swapin_stream(self._h, ctypes.byref(s), packed_pinned.data_ptr(), _hp(src_off),
+                                      _hp(dst_tok), _hp(sel_bits), n_sel, _dev(staging_dev),
+                                      staging_dev.numel() * staging_dev.element_size(), n_buffers,
+                                      _dev(kv_out, shape.cache_dtype), _stream(copy_stream),
+                                      _stream(compute_stream)))
 
 
 def kv_swapout_aot(packed_dev: torch.Tensor, packed_pinned: torch.Tensor, begin: int, end: int,

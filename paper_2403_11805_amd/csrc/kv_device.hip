@@ -6,6 +6,7 @@
 #include <algorithm>
 #include <cmath>
 #include <mutex>
+#include <new>
 #include <vector>
 
 #include "kv_internal.h"
@@ -684,10 +685,64 @@ int32_t kv_plan_optimise_dev(const kv_shape_t* shape, const float* density_dev, 
 
 // --------------------------------------------------------------------- streaming Load / AoT swap-out
 
-int32_t kv_swapin_pinned(const kv_shape_t* shape, const void* packed_pinned, const uint64_t* src_off,
-                         const int32_t* dst_tok, const uint8_t* sel_bits, int32_t n_sel,
+// Events of a streaming Load: copied[b] is recorded on the copy stream behind the copies into staging
+// slot b, consumed[b] on the compute stream behind the kernel that read the slot.
+struct kv_loader {
+    hipEvent_t copied[8];
+    hipEvent_t consumed[8];
+    bool slot_used[8];       // consumed[b] has been recorded: the slot may still be read by that kernel
+    int n_events;
+};
+
+static void loader_release(kv_loader* ld) {
+    for (int i = 0; i < ld->n_events; ++i) {
+        (void)hipEventDestroy(ld->copied[i]);
+        (void)hipEventDestroy(ld->consumed[i]);
+    }
+    ld->n_events = 0;
+}
+
+static int loader_init(kv_loader* ld, int n) {
+    ld->n_events = 0;
+    for (int i = 0; i < 8; ++i) ld->slot_used[i] = false;
+    for (; ld->n_events < n; ++ld->n_events) {
+        hipError_t e = hipEventCreateWithFlags(&ld->copied[ld->n_events], hipEventDisableTiming);
+        if (e == hipSuccess) {
+            e = hipEventCreateWithFlags(&ld->consumed[ld->n_events], hipEventDisableTiming);
+            if (e != hipSuccess) (void)hipEventDestroy(ld->copied[ld->n_events]);
+        }
+        if (e != hipSuccess) {
+            loader_release(ld);
+            return hip_fail(e, "hipEventCreateWithFlags");
+        }
+    }
+    return KV_OK;
+}
+
+kv_loader_t* kv_loader_create(void) {
+    kv_loader* ld = new (std::nothrow) kv_loader;
+    if (!ld) {
+        fail(KV_ENOMEM, "out of host memory");
+        return nullptr;
+    }
+    if (loader_init(ld, 8) != KV_OK) {
+        delete ld;
+        return nullptr;
+    }
+    return ld;
+}
+
+void kv_loader_destroy(kv_loader_t* ld) {
+    if (!ld) return;
+    loader_release(ld);
+    delete ld;
+}
+
+int32_t kv_swapin_stream(kv_loader_t* ld, const kv_shape_t* shape, const void* packed_pinned,
+                         const uint64_t* src_off, const int32_t* dst_tok, const uint8_t* sel_bits, int32_t n_sel,
                          void* staging_dev, uint64_t staging_bytes, int32_t n_buffers, void* kv_out,
                          void* copy_stream, void* compute_stream) {
+    if (!ld) return fail(KV_EINVAL, "NULL loader");
     if (int rc = check_shape(shape)) return rc;
     const int32_t n_chunks = shape->n_tokens / shape->chunk_tokens;
     if (n_sel < 0 || n_sel > n_chunks) return fail(KV_EINVAL, "n_sel %d outside [0,%d]", n_sel, n_chunks);
@@ -722,41 +777,19 @@ int32_t kv_swapin_pinned(const kv_shape_t* shape, const void* packed_pinned, con
     if (g.slabs > 65535) return fail(KV_ESHAPE, "more than 65535 slabs exceed the launch grid");
     hipStream_t cs = static_cast<hipStream_t>(copy_stream);
     hipStream_t ks = static_cast<hipStream_t>(compute_stream);
-    hipEvent_t copied[8], consumed[8];
-    int n_ev = 0;
-    auto destroy_events = [&]() {
-        for (int i = 0; i < n_ev; ++i) {
-            (void)hipEventDestroy(copied[i]);
-            (void)hipEventDestroy(consumed[i]);
-        }
-    };
-    for (; n_ev < n_buffers; ++n_ev) {
-        hipError_t e = hipEventCreateWithFlags(&copied[n_ev], hipEventDisableTiming);
-        if (e == hipSuccess) {
-            e = hipEventCreateWithFlags(&consumed[n_ev], hipEventDisableTiming);
-            if (e != hipSuccess) (void)hipEventDestroy(copied[n_ev]);
-        }
-        if (e != hipSuccess) {
-            destroy_events();
-            return hip_fail(e, "hipEventCreateWithFlags");
-        }
-    }
-
     const uint8_t* host = static_cast<const uint8_t*>(packed_pinned);
     uint8_t* staging = static_cast<uint8_t*>(staging_dev);
-    int rc = KV_OK;
     int32_t j = 0;
-    for (int batch = 0; j < n_sel && rc == KV_OK; ++batch) {
+    for (int batch = 0; j < n_sel; ++batch) {
         const int b = batch % n_buffers;
         uint8_t* slot_dev = staging + static_cast<uint64_t>(b) * slot;
         // records of one batch: as many consecutive list entries as fit the slot
         SwapinBatch list;
         list.n = 0;
         uint64_t used = 0;
-        if (batch >= n_buffers) {   // slot is free once the kernel that read it has finished
-            hipError_t e = hipStreamWaitEvent(cs, consumed[b], 0);
-            if (e != hipSuccess) { rc = hip_fail(e, "hipStreamWaitEvent"); break; }
-        }
+        // the slot is free once the kernel that last read it has finished (an earlier batch of this
+        // call, or of an earlier call through this loader)
+        if (ld->slot_used[b]) KV_HIP(hipStreamWaitEvent(cs, ld->consumed[b], 0));
         while (j < n_sel && list.n < kBatchMax) {
             const uint64_t bytes = record_bytes(*shape, sel_bits[j]);
             if (used + bytes > slot) break;
@@ -769,9 +802,7 @@ int32_t kv_swapin_pinned(const kv_shape_t* shape, const void* packed_pinned, con
                 run += bj;
                 ++j2;
             }
-            hipError_t e = hipMemcpyAsync(slot_dev + used, host + src_off[j], run,
-                                          hipMemcpyHostToDevice, cs);
-            if (e != hipSuccess) { rc = hip_fail(e, "hipMemcpyAsync H2D"); break; }
+            KV_HIP(hipMemcpyAsync(slot_dev + used, host + src_off[j], run, hipMemcpyHostToDevice, cs));
             uint64_t o = used;
             for (int32_t k = j; k < j2; ++k) {
                 list.src_off[list.n] = o;
@@ -783,16 +814,29 @@ int32_t kv_swapin_pinned(const kv_shape_t* shape, const void* packed_pinned, con
             used += run;
             j = j2;
         }
-        if (rc != KV_OK) break;
-        hipError_t e = hipEventRecord(copied[b], cs);
-        if (e == hipSuccess) e = hipStreamWaitEvent(ks, copied[b], 0);
-        if (e != hipSuccess) { rc = hip_fail(e, "event record/wait"); break; }
-        rc = launch_swapin_batch(*shape, g, ppl, slot_dev, list, static_cast<u4_t*>(kv_out), ks);
-        if (rc != KV_OK) break;
-        e = hipEventRecord(consumed[b], ks);
-        if (e != hipSuccess) { rc = hip_fail(e, "hipEventRecord"); break; }
+        KV_HIP(hipEventRecord(ld->copied[b], cs));
+        KV_HIP(hipStreamWaitEvent(ks, ld->copied[b], 0));
+        if (int rc = launch_swapin_batch(*shape, g, ppl, slot_dev, list, static_cast<u4_t*>(kv_out), ks)) return rc;
+        KV_HIP(hipEventRecord(ld->consumed[b], ks));
+        ld->slot_used[b] = true;
     }
-    destroy_events();
+    return KV_OK;
+}
+
+int32_t kv_swapin_pinned(const kv_shape_t* shape, const void* packed_pinned, const uint64_t* src_off,
+                         const int32_t* dst_tok, const uint8_t* sel_bits, int32_t n_sel,
+                         void* staging_dev, uint64_t staging_bytes, int32_t n_buffers, void* kv_out,
+                         void* copy_stream, void* compute_stream) {
+    if (n_buffers < 2 || n_buffers > 8) return fail(KV_EINVAL, "n_buffers %d outside [2,8]", n_buffers);
+    if (n_sel == 0) {
+        if (int rc = check_shape(shape)) return rc;
+        return KV_OK;
+    }
+    kv_loader once;
+    if (int rc = loader_init(&once, n_buffers)) return rc;
+    const int32_t rc = kv_swapin_stream(&once, shape, packed_pinned, src_off, dst_tok, sel_bits, n_sel, staging_dev,
+                                        staging_bytes, n_buffers, kv_out, copy_stream, compute_stream);
+    loader_release(&once);
     return rc;
 }
 

@@ -231,6 +231,46 @@ int32_t kv_plan_pipeline(const kv_pipeline_model_t* model, const int32_t* missin
     return KV_OK;
 }
 
+int32_t kv_pipeline_split(const kv_shape_t* shape, const uint8_t* bits, const int32_t* missing_idx,
+                          int32_t n_missing, const int32_t* recompute, int32_t* recompute_idx,
+                          int32_t* n_recompute, int32_t* load_idx, int32_t* n_load) {
+    if (int rc = check_shape(shape)) return rc;
+    if (n_missing < 0) return fail(KV_EINVAL, "n_missing %d < 0", n_missing);
+    if (!recompute || !n_recompute || !n_load) return fail(KV_EINVAL, "NULL pointer");
+    if (n_missing > 0 && (!bits || !missing_idx || !recompute_idx || !load_idx)) return fail(KV_EINVAL, "NULL list pointer");
+    if (recompute[0] < 0 || recompute[1] < 0 || recompute[2] < 0) return fail(KV_EINVAL, "negative chunk count");
+    const int32_t n = shape->n_tokens / shape->chunk_tokens;
+    int64_t have[3] = {0, 0, 0};
+    for (int32_t j = 0; j < n_missing; ++j) {
+        const int32_t i = missing_idx[j];
+        if (i < 0 || i >= n) return fail(KV_EINDEX, "missing_idx[%d] = %d outside [0,%d)", j, i, n);
+        if (j && i <= missing_idx[j - 1]) return fail(KV_EINDEX, "missing_idx not strictly ascending at position %d", j);
+        if (!valid_bits(*shape, bits[i])) return fail(KV_EBITS, "bits[%d] = %d not in %s", i, bits[i], bits_set(*shape));
+        if (bits[i] == 8) ++have[0];
+        else if (bits[i] == 4) ++have[1];
+        else if (bits[i] == 2) ++have[2];
+    }
+    for (int w = 0; w < 3; ++w)
+        if (recompute[w] > have[w])
+            return fail(KV_EINVAL, "plan recomputes %d chunks of %d bits, %lld are missing", recompute[w], 8 >> w,
+                        static_cast<long long>(have[w]));
+    int32_t left[3] = {recompute[0], recompute[1], recompute[2]};
+    int32_t n_re = 0, n_io = 0;
+    for (int32_t j = 0; j < n_missing; ++j) {
+        const int32_t i = missing_idx[j];
+        const int w = bits[i] == 8 ? 0 : (bits[i] == 4 ? 1 : (bits[i] == 2 ? 2 : -1));
+        if (w >= 0 && left[w] > 0) {
+            --left[w];
+            recompute_idx[n_re++] = i;
+        } else {
+            load_idx[n_io++] = i;
+        }
+    }
+    *n_recompute = n_re;
+    *n_load = n_io;
+    return KV_OK;
+}
+
 int32_t kv_build_gather(const kv_shape_t* shape, const uint64_t* off, const uint8_t* bits,
                         const int32_t* chunk_idx, int32_t n_sel, uint64_t* src_off,
                         int32_t* dst_tok, uint8_t* sel_bits) {

@@ -111,3 +111,36 @@ def test_records_survive_a_file_round_trip(tmp_path):
     want = oracle.compress_chunks(os_, kv.numpy(), bits, off)
     oracle.swapin_chunks(os_, want, *oracle.build_gather(os_, off, bits, idx), ref)
     assert np.array_equal(out.cpu().numpy().view(np.uint16), ref)
+
+
+def test_loader_handle_serves_loads_one_after_the_other():
+    """kv_swapin_stream through one loader: two Loads enqueued back to back on the same streams and the
+    SAME staging slots with no synchronisation in between (the loader's events keep the second call's
+    copies behind the first call's kernels), twice over; both caches equal the oracle."""
+    g = synth.Geometry(2, 2, 2, 128, 512, 16, 64)
+    ks, os_ = both_shapes(g)
+    copy_s, comp_s = torch.cuda.Stream(), torch.cuda.Stream()
+    staging = torch.empty(3 * kvs.kv_record_bytes(ks, 16), dtype=torch.uint8, device=DEV)
+    loader = kvs.Loader()
+    jobs = []
+    for seed in (81, 82):
+        kv = synth.make_kv(g, seed, "cpu", 1, 10.0)
+        bits = synth.draw_bits_uniform(g.n_chunks, seed, widths=(16, 8, 4, 2)).numpy()
+        off = oracle.chunk_offsets(os_, bits)
+        want = oracle.compress_chunks(os_, kv.numpy(), bits, off)
+        idx = synth.draw_subset(g.n_chunks, 20, seed).numpy().tolist()
+        ref = np.full(kv.shape, 0x7bff, dtype=np.uint16)
+        oracle.swapin_chunks(os_, want, *oracle.build_gather(os_, off, bits, idx), ref)
+        out = torch.full(ks.kv_dims, 0x7bff, dtype=torch.int16, device=DEV).view(torch.float16)
+        jobs.append((torch.from_numpy(want).pin_memory(), kvs.kv_build_gather(ks, off, bits, idx), out, ref))
+    torch.cuda.synchronize()
+    for rep in range(2):
+        for pinned, (src, dst, sb), out, ref in jobs:
+            loader.swapin_stream(ks, pinned, src, dst, sb, staging, 3, out, copy_s, comp_s)
+        comp_s.synchronize()
+        copy_s.synchronize()
+        for pinned, lists, out, ref in jobs:
+            assert np.array_equal(out.cpu().numpy().view(np.uint16), ref)
+            out.view(torch.int16).fill_(0x7bff)
+        torch.cuda.synchronize()
+    loader.close()

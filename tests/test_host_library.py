@@ -378,3 +378,31 @@ def test_scoring_refuses_contexts_beyond_its_run_table():
         kvs.kv_score_workspace_bytes(one._replace(n_tokens=2097152 + 1024), 32)
     grouped = kvs.Shape(1, 1, 4, 64, 4194304, 1024, 64)
     assert kvs.kv_score_workspace_bytes(grouped, 32) > 0
+
+
+def test_pipeline_split_matches_oracle():
+    rng = np.random.default_rng(31)
+    for fmt in (0, 3):
+        for _ in range(40):
+            n = int(rng.integers(1, 60))
+            ks = kvs.Shape(1, 1, 1, 64, n * 16, 16, 64, fmt)
+            bits = rng.choice([16, 8, 4, 2], n, p=[0.1, 0.3, 0.3, 0.3]).astype(np.uint8)
+            missing = np.flatnonzero(rng.random(n) < 0.7).astype(np.int32)
+            have = [int((bits[missing] == b).sum()) for b in (8, 4, 2)]
+            plan = [int(rng.integers(0, h + 1)) for h in have]
+            re, io = kvs.kv_pipeline_split(ks, bits, missing, plan)
+            want_re, want_io = oracle.pipeline_split(missing, bits, plan)
+            assert np.array_equal(re, want_re) and np.array_equal(io, want_io)
+    ks = kvs.Shape(1, 1, 1, 64, 64, 16, 64)
+    bits = np.array([8, 8, 4, 2], dtype=np.uint8)
+    for missing, plan in (([0, 1], [3, 0, 0]), ([0, 1], [0, 1, 0]), ([0, 1], [-1, 0, 0])):
+        with pytest.raises(kvs.KvError) as e:
+            kvs.kv_pipeline_split(ks, bits, missing, plan)
+        assert e.value.code == kvs.KV_EINVAL
+    for missing in ([1, 0], [0, 0], [4], [-1]):
+        with pytest.raises(kvs.KvError) as e:
+            kvs.kv_pipeline_split(ks, bits, missing, [0, 0, 0])
+        assert e.value.code == kvs.KV_EINDEX
+    with pytest.raises(kvs.KvError) as e:
+        kvs.kv_pipeline_split(ks, np.array([8, 3, 4, 2], dtype=np.uint8), [1], [0, 0, 0])
+    assert e.value.code == kvs.KV_EBITS
