@@ -35,12 +35,13 @@ int ilog2(int v) {
     return l;
 }
 
-// Measured on MI355X (llama2-7b-4k, widths by score terciles): compress streams
-// best with 4 pieces per lane, swap-in with 2, each with the task order that
-// makes its WRITE side one forward stream: compress walks the slabs of one chunk
-// (record-major), swap-in walks the chunks of one slab.
+// Measured on MI355X (llama2-7b-4k, widths by score terciles): compress streams best with 4 pieces
+// per lane walking the slabs of one chunk (record-major: its write side is one forward stream);
+// swap-in with 4 pieces per lane and up to 16 wavefronts per workgroup in strip order
+// (strip_task_at: every XCD writes one plane of the cache as a forward stream).
 constexpr int kCompressPiecesPerLane = 4;
-constexpr int kSwapinPiecesPerLane = 2;
+constexpr int kSwapinPiecesPerLane = 4;
+constexpr int kLinkWaves = 4;          // wavefronts per workgroup where the records come over the host link
 
 QuantGeom quant_geom(const kv_shape_t& s) {
     QuantGeom g;
@@ -55,6 +56,8 @@ QuantGeom quant_geom(const kv_shape_t& s) {
     g.tpu = 0;
     g.tpu_shift = -1;
     g.record_major = 0;
+    g.strip = kStripSlabs;
+    g.groups = 0;
     return g;
 }
 
@@ -72,6 +75,8 @@ QuantGeom quant_geom_i8(const kv_shape_t& s, int* ppl) {
     g.tpu = 1;
     g.tpu_shift = 0;
     g.record_major = 0;
+    g.strip = kStripSlabs;
+    g.groups = 0;
     *ppl = g.pieces / 64;      // 1, 2 or 4 (shape check)
     return g;
 }
@@ -121,6 +126,17 @@ dim3 task_grid(const QuantGeom& g, int n_units) {
                 static_cast<uint32_t>(along_y));
 }
 
+// Launch shape of a Load kernel of the fp16 formats over n_units listed records (g.tpu and g.slab_count
+// set): wavefronts per workgroup (at most wpb_max, no more than a slab has tasks), workgroups per slab
+// into g.groups, and the one-dimensional grid.  0 if the grid does not fit.
+uint32_t load_grid(QuantGeom* g, int n_units, int wpb_max, int* wpb) {
+    const int64_t tasks = static_cast<int64_t>(n_units) * g->tpu;          // per slab
+    *wpb = static_cast<int>(std::min<int64_t>(wpb_max, tasks));
+    g->groups = static_cast<int32_t>((tasks + *wpb - 1) / *wpb);
+    const int64_t total = static_cast<int64_t>(g->groups) * g->slab_count;
+    return total > 0x7fffffffLL ? 0u : static_cast<uint32_t>(total);
+}
+
 int launch_status(const char* what) {
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, what);
@@ -129,10 +145,11 @@ int launch_status(const char* what) {
 
 // One launch of the Load kernel whose (short) gather list travels in the kernel
 // arguments; offsets in the list are relative to `base`.
-int launch_swapin_batch(const kv_shape_t& shape, const QuantGeom& g, int ppl, const uint8_t* base,
+int launch_swapin_batch(const kv_shape_t& shape, const QuantGeom& g_in, int ppl, const uint8_t* base,
                         const SwapinBatch& list, u4_t* dst, hipStream_t st) {
-    const dim3 grid = task_grid(g, list.n);
+    QuantGeom g = g_in;
     if (is_i8(shape)) {
+        const dim3 grid = task_grid(g, list.n);
         const I8View v = i8_view(shape);
 #define KV_LAUNCH_I8(NDW, GPL) \
         do {                                                                                                    \
@@ -143,10 +160,14 @@ int launch_swapin_batch(const kv_shape_t& shape, const QuantGeom& g, int ppl, co
 #undef KV_LAUNCH_I8
     } else {
         const bool hp = shape.format == KV_FMT_F16_GROUPS_H;
+        int wpb = 0;
+        const uint32_t wgs = load_grid(&g, list.n, kLoadWavesMax, &wpb);
+        if (!wgs) return fail(KV_ESHAPE, "Load grid exceeds 2^31 workgroups");
+        const dim3 grid(wgs), block(static_cast<uint32_t>(wpb) * 64);
 #define KV_LAUNCH_F16(PPL)                                                                                        \
         do {                                                                                                      \
-            if (hp) hipLaunchKernelGGL((swapin_batch_kernel<PPL, true>), grid, dim3(256), 0, st, base, list, dst, g); \
-            else hipLaunchKernelGGL((swapin_batch_kernel<PPL, false>), grid, dim3(256), 0, st, base, list, dst, g);   \
+            if (hp) hipLaunchKernelGGL((swapin_batch_kernel<PPL, true>), grid, block, 0, st, base, list, dst, g); \
+            else hipLaunchKernelGGL((swapin_batch_kernel<PPL, false>), grid, block, 0, st, base, list, dst, g);   \
         } while (0)
         if (ppl == 4) KV_LAUNCH_F16(4);
         else if (ppl == 2) KV_LAUNCH_F16(2);
@@ -259,13 +280,20 @@ static int32_t swapin_launch(const kv_shape_t* shape, const void* packed, const 
     if (!i8) ppl = plan_tasks(&g, kSwapinPiecesPerLane);
     g.slab0 = layer_begin * 2 * shape->n_kv_heads;
     g.slab_count = (layer_end - layer_begin) * 2 * shape->n_kv_heads;
-    if (g.slab_count > 65535) return fail(KV_ESHAPE, "more than 65535 slabs exceed the launch grid");
-    const dim3 grid = task_grid(g, n_sel);
+    if (i8 && g.slab_count > 65535) return fail(KV_ESHAPE, "more than 65535 slabs exceed the launch grid");
+    const int kind = pool_kind(packed);
+    if (kind == 0) return fail(KV_EINVAL, "packed is neither device memory nor pinned host memory");
+    // int8 formats: two-dimensional task grid of four-wavefront workgroups; fp16 formats: strip order
+    dim3 grid = i8 ? task_grid(g, n_sel) : dim3(1);
+    int wpb = kWavesPerBlock;
+    if (!i8) {
+        grid = dim3(load_grid(&g, n_sel, kind == 2 ? kLinkWaves : kLoadWavesMax, &wpb));
+        if (!grid.x) return fail(KV_ESHAPE, "Load grid exceeds 2^31 workgroups");
+    }
+    const dim3 block(static_cast<uint32_t>(wpb) * 64);
     hipStream_t st = static_cast<hipStream_t>(stream);
     const uint8_t* src = static_cast<const uint8_t*>(packed);
     u4_t* dst = static_cast<u4_t*>(kv_out);
-    const int kind = pool_kind(packed);
-    if (kind == 0) return fail(KV_EINVAL, "packed is neither device memory nor pinned host memory");
     if (kind == 2) {
         const uint64_t total = static_cast<uint64_t>(grid.x) * grid.y;
         if (total > 0xffffffffull) return fail(KV_ESHAPE, "task grid of %llu workgroups", static_cast<unsigned long long>(total));
@@ -288,8 +316,8 @@ static int32_t swapin_launch(const kv_shape_t* shape, const void* packed, const 
         const bool hp = shape->format == KV_FMT_F16_GROUPS_H;
 #define KV_LAUNCH_F16(PPL)                                                                                     \
         do {                                                                                                   \
-            if (hp) hipLaunchKernelGGL((swapin_link_kernel<PPL, true>), lgrid, dim3(256), 0, st, src, src_off_dev, dst_tok_dev, sel_bits_dev, dst, g, n_sel, grid.x, grid.y); \
-            else hipLaunchKernelGGL((swapin_link_kernel<PPL, false>), lgrid, dim3(256), 0, st, src, src_off_dev, dst_tok_dev, sel_bits_dev, dst, g, n_sel, grid.x, grid.y);   \
+            if (hp) hipLaunchKernelGGL((swapin_link_kernel<PPL, true>), lgrid, block, 0, st, src, src_off_dev, dst_tok_dev, sel_bits_dev, dst, g, n_sel, grid.x); \
+            else hipLaunchKernelGGL((swapin_link_kernel<PPL, false>), lgrid, block, 0, st, src, src_off_dev, dst_tok_dev, sel_bits_dev, dst, g, n_sel, grid.x);   \
         } while (0)
         if (ppl == 4) KV_LAUNCH_F16(4);
         else if (ppl == 2) KV_LAUNCH_F16(2);
@@ -315,8 +343,8 @@ static int32_t swapin_launch(const kv_shape_t* shape, const void* packed, const 
     const bool hp = shape->format == KV_FMT_F16_GROUPS_H;
 #define KV_LAUNCH_F16(PPL)                                                                                     \
     do {                                                                                                       \
-        if (hp) hipLaunchKernelGGL((swapin_kernel<PPL, true>), grid, dim3(256), 0, st, src, src_off_dev, dst_tok_dev, sel_bits_dev, dst, g, n_sel); \
-        else hipLaunchKernelGGL((swapin_kernel<PPL, false>), grid, dim3(256), 0, st, src, src_off_dev, dst_tok_dev, sel_bits_dev, dst, g, n_sel);   \
+        if (hp) hipLaunchKernelGGL((swapin_kernel<PPL, true>), grid, block, 0, st, src, src_off_dev, dst_tok_dev, sel_bits_dev, dst, g, n_sel); \
+        else hipLaunchKernelGGL((swapin_kernel<PPL, false>), grid, block, 0, st, src, src_off_dev, dst_tok_dev, sel_bits_dev, dst, g, n_sel);   \
     } while (0)
     if (ppl == 4) KV_LAUNCH_F16(4);
     else if (ppl == 2) KV_LAUNCH_F16(2);
@@ -585,7 +613,7 @@ int32_t kv_load_chunks(const kv_shape_t* shape, const void* packed, const uint64
     int ppl = 0;
     QuantGeom g = i8 ? quant_geom_i8(*shape, &ppl) : quant_geom(*shape);
     if (!i8) ppl = plan_tasks(&g, kSwapinPiecesPerLane);
-    if (g.slabs > 65535) return fail(KV_ESHAPE, "more than 65535 slabs exceed the launch grid");
+    if (i8 && g.slabs > 65535) return fail(KV_ESHAPE, "more than 65535 slabs exceed the launch grid");
     hipStream_t st = static_cast<hipStream_t>(stream);
     for (int32_t j = 0; j < n_sel; j += kBatchMax) {
         SwapinBatch list;
@@ -774,7 +802,7 @@ int32_t kv_swapin_stream(kv_loader_t* ld, const kv_shape_t* shape, const void* p
     int ppl = 0;
     QuantGeom g = i8 ? quant_geom_i8(*shape, &ppl) : quant_geom(*shape);
     if (!i8) ppl = plan_tasks(&g, kSwapinPiecesPerLane);
-    if (g.slabs > 65535) return fail(KV_ESHAPE, "more than 65535 slabs exceed the launch grid");
+    if (i8 && g.slabs > 65535) return fail(KV_ESHAPE, "more than 65535 slabs exceed the launch grid");
     hipStream_t cs = static_cast<hipStream_t>(copy_stream);
     hipStream_t ks = static_cast<hipStream_t>(compute_stream);
     const uint8_t* host = static_cast<const uint8_t*>(packed_pinned);

@@ -38,6 +38,8 @@ struct QuantGeom {
     int32_t tpu_shift;     // log2(tpu) if tpu is a power of two, else -1
     int32_t record_major;  // task order: 0 = walk the chunks of one slab (cache side is one
                            // stream), 1 = walk the slabs of one chunk (record side is one stream)
+    int32_t strip;         // Load kernels (fp16 formats): slabs written side by side, one per XCD (kStripSlabs)
+    int32_t groups;        // Load kernels: workgroups per slab = ceil(listed chunks * tpu / waves per workgroup)
 };
 
 constexpr int kWavesPerBlock = 4;
@@ -74,6 +76,41 @@ __device__ __forceinline__ bool wave_task_at(const QuantGeom& g, int n_chunks, i
     chunk = unit;
     slab = g.slab0 + static_cast<int>(by);
     return unit < n_chunks;
+}
+
+// Task order of the Load kernels of the fp16 formats.  The launch is one-dimensional; a workgroup of
+// `wpb` wavefronts takes wpb consecutive tasks of ONE slab (consecutive chunks of the list: their
+// tokens are adjacent in the cache where the chunks are), and consecutive workgroup ids walk a strip
+// of kStripSlabs slabs before they move on along the token axis.  Workgroup ids are dealt to the
+// eight XCDs in turn, so with a strip of eight every XCD writes ONE plane of the cache as a forward
+// stream through its own L2, and the eight planes of a strip are neighbours in memory.  Measured on
+// MI355X (4096-token multi-head cache, stores only): 7.4 TB/s, against 6.0 TB/s when consecutive
+// workgroups write consecutive 8 KiB blocks of one plane (each XCD then sees every eighth block) -
+// and the whole kernel 0.485 against 0.517 ms.
+constexpr int kStripSlabs = 8;
+constexpr int kLoadWavesMax = 16;     // wavefronts per workgroup of the Load kernels at most
+
+__device__ __forceinline__ bool strip_task_at(const QuantGeom& g, int n_units, int ppl, uint32_t id, int wpb,
+                                              int& unit, int& slab, int& piece0) {
+    const int wave = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6));
+    const uint32_t per_strip = static_cast<uint32_t>(g.groups) * static_cast<uint32_t>(g.strip);
+    const uint32_t s = id / per_strip;                      // strip (the last one may be narrower)
+    const uint32_t local = id - s * per_strip;
+    const int first = static_cast<int>(s) * g.strip;
+    const int width = min(g.strip, g.slab_count - first);
+    const uint32_t grp = local / static_cast<uint32_t>(width);
+    slab = g.slab0 + first + static_cast<int>(local - grp * static_cast<uint32_t>(width));
+    const int t = static_cast<int>(grp) * wpb + wave;       // task inside the slab
+    int sub;
+    if (g.tpu_shift >= 0) {
+        unit = t >> g.tpu_shift;
+        sub = t & (g.tpu - 1);
+    } else {
+        unit = t / g.tpu;
+        sub = t - unit * g.tpu;
+    }
+    piece0 = sub * 64 * ppl;
+    return unit < n_units;
 }
 
 __device__ __forceinline__ bool wave_task(const QuantGeom& g, int n_chunks, int ppl, int& chunk,
@@ -376,10 +413,10 @@ __device__ __forceinline__ void swapin_task(const uint8_t* __restrict__ base, in
     else swapin_pieces<2, PPL, HP>(codes, scale, mn, dst, p0, lane, g.lpg_log2);
 }
 
-// Grid as for compress_kernel with the n_sel listed records in the place of
-// the chunks; gather lists in device memory.
+// One-dimensional grid of g.groups * g.slab_count workgroups of up to kLoadWavesMax wavefronts in
+// strip order (strip_task_at); gather lists in device memory.
 template <int PPL, bool HP>
-__global__ __launch_bounds__(64 * kWavesPerBlock) void swapin_kernel(const uint8_t* __restrict__ packed,
+__global__ __launch_bounds__(64 * kLoadWavesMax) void swapin_kernel(const uint8_t* __restrict__ packed,
                                                      const uint64_t* __restrict__ src_off,
                                                      const int32_t* __restrict__ dst_tok,
                                                      const uint8_t* __restrict__ sel_bits,
@@ -387,7 +424,7 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void swapin_kernel(const uint8
                                                      int32_t n_sel) {
     const int lane = threadIdx.x & 63;
     int j, slab, p0;
-    if (!wave_task(g, n_sel, PPL, j, slab, p0)) return;
+    if (!strip_task_at(g, n_sel, PPL, blockIdx.x, static_cast<int>(blockDim.x >> 6), j, slab, p0)) return;
     u4_t* dst = kv_out + (static_cast<uint64_t>(slab) * g.n_tokens +
                           static_cast<uint64_t>(dst_tok[j])) * g.row_pieces;
     swapin_task<PPL, HP>(packed + src_off[j], uniform_byte(sel_bits, j), slab, dst, g, p0, lane);
@@ -402,17 +439,16 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void swapin_kernel(const uint8
 constexpr uint32_t kLinkBlocks = 128;
 
 template <int PPL, bool HP>
-__global__ __launch_bounds__(64 * kWavesPerBlock) void swapin_link_kernel(const uint8_t* __restrict__ packed,
+__global__ __launch_bounds__(64 * kLoadWavesMax) void swapin_link_kernel(const uint8_t* __restrict__ packed,
                                                           const uint64_t* __restrict__ src_off,
                                                           const int32_t* __restrict__ dst_tok,
                                                           const uint8_t* __restrict__ sel_bits,
                                                           u4_t* __restrict__ kv_out, QuantGeom g,
-                                                          int32_t n_sel, uint32_t gx, uint32_t gy) {
+                                                          int32_t n_sel, uint32_t total) {
     const int lane = threadIdx.x & 63;
-    const uint32_t total = gx * gy;
     for (uint32_t w = blockIdx.x; w < total; w += gridDim.x) {
         int j, slab, p0;
-        if (!wave_task_at(g, n_sel, PPL, w % gx, w / gx, j, slab, p0)) continue;
+        if (!strip_task_at(g, n_sel, PPL, w, static_cast<int>(blockDim.x >> 6), j, slab, p0)) continue;
         u4_t* dst = kv_out + (static_cast<uint64_t>(slab) * g.n_tokens +
                               static_cast<uint64_t>(dst_tok[j])) * g.row_pieces;
         swapin_task<PPL, HP>(packed + src_off[j], uniform_byte(sel_bits, j), slab, dst, g, p0, lane);
@@ -430,12 +466,12 @@ struct SwapinBatch {
 };
 
 template <int PPL, bool HP>
-__global__ __launch_bounds__(64 * kWavesPerBlock) void swapin_batch_kernel(const uint8_t* __restrict__ staged,
+__global__ __launch_bounds__(64 * kLoadWavesMax) void swapin_batch_kernel(const uint8_t* __restrict__ staged,
                                                            SwapinBatch list,
                                                            u4_t* __restrict__ kv_out, QuantGeom g) {
     const int lane = threadIdx.x & 63;
     int j, slab, p0;
-    if (!wave_task(g, list.n, PPL, j, slab, p0)) return;
+    if (!strip_task_at(g, list.n, PPL, blockIdx.x, static_cast<int>(blockDim.x >> 6), j, slab, p0)) return;
     u4_t* dst = kv_out + (static_cast<uint64_t>(slab) * g.n_tokens +
                           static_cast<uint64_t>(list.dst_tok[j])) * g.row_pieces;
     swapin_task<PPL, HP>(staged + list.src_off[j], list.bits[j], slab, dst, g, p0, lane);
