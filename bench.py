@@ -372,7 +372,7 @@ def run_pipeline(wl, args, dev):
         "metric": "context Load from pinned host memory with the swapping-recompute pipeline (Sec. 3.3), ms",
         "value": best["delay_ms"], "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": best["delay_ms"], "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "dtype": "f16", "data": "synthetic",
         "config": {"workload": f"{wl.name}: [L={g.L},K/V,Hkv={g.Hkv},N={g.N},D={g.D}] fp16, chunk {g.T}, records of "
                                f"{total} bytes in pinned host memory{' (group parameters in binary16)' if fmt == 3 else ''}; "
                                f"Llama-2-7B-sized layers, d_ff {d_ff}",
@@ -416,40 +416,97 @@ def graph_ms_per_step(path, args):
     return (time.perf_counter() - t0) / args.steps * 1e3
 
 
-def cpu_baseline(path, budget_s=20.0):
-    """The CPU oracle, as it stands, on a bounded sample of the same workload."""
+def cpu_baseline(path):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload: once on all the threads
+    it takes (the reported value) and once on a single thread (the per-core rate, which does not
+    depend on how many cores a box has).  Where the workload scores chunks the oracle scores the whole
+    cache; its densities also tell how many chunks would get another width than under the GPU's."""
     import oracle
     g = path.g
+    n_all = oracle.threads()
     one = oracle.Shape(g.L, g.Hkv, g.Hq, g.D, g.T, g.T, g.G)
-    n_sample = 3
-    sample = [0, g.n_chunks // 2, g.n_chunks - 1][:n_sample]
-    t_cs = 0.0
-    for i in sample:
-        x = path.kv[:, :, :, i * g.T:(i + 1) * g.T, :].contiguous().cpu().numpy()
-        b = np.array([path.bits[i]], dtype=np.uint8)
-        off = oracle.chunk_offsets(one, b)
-        t0 = time.perf_counter()
-        packed = oracle.compress_chunks(one, x, b, off)
-        out = np.empty(x.shape, dtype=np.float16)
-        oracle.swapin_chunks(one, packed, *oracle.build_gather(one, off, b, [0]), out)
-        t_cs += time.perf_counter() - t0
-    full_s = t_cs / len(sample) * g.n_chunks
-    desc = f"compress+swap-in of {len(sample)} of {g.n_chunks} chunks"
+
+    def quant_seconds(sample):
+        t = 0.0
+        for i in sample:
+            x = path.kv[:, :, :, i * g.T:(i + 1) * g.T, :].contiguous().cpu().numpy()
+            b = np.array([path.bits[i]], dtype=np.uint8)
+            off = oracle.chunk_offsets(one, b)
+            t0 = time.perf_counter()
+            packed = oracle.compress_chunks(one, x, b, off)
+            out = np.empty(x.shape, dtype=np.float16)
+            oracle.swapin_chunks(one, packed, *oracle.build_gather(one, off, b, [0]), out)
+            t += time.perf_counter() - t0
+        return t / len(sample) * g.n_chunks
+
+    first = {b: int(np.flatnonzero(path.bits == b)[0]) for b in (8, 4, 2) if (path.bits == b).any()}
+    sample = sorted(set(first.values()) | {0, g.n_chunks // 2, g.n_chunks - 1})
+    full_s = quant_seconds(sample)
+    desc = f"compress+swap-in of {len(sample)} of {g.n_chunks} chunks, scaled to all"
+    extra = {}
     if path.R:
-        # a one-layer slice with as many kv heads as the oracle has threads (it runs heads in parallel)
-        per_kv = g.Hq // g.Hkv
-        n_kv = max(1, min(g.Hkv, oracle.threads() // per_kv))
-        n_q = n_kv * per_kv
-        hs = oracle.Shape(1, n_kv, n_q, g.D, g.N, g.T, g.G)
-        q_host = path.q[0:1, 0:n_q].contiguous().cpu().numpy()
-        k_host = path.kv[0:1, :, 0:n_kv].contiguous().cpu().numpy()
+        q_host = path.q.cpu().numpy()
+        kv_host = path.kv.cpu().numpy()
+        os_ = oracle.Shape(g.L, g.Hkv, g.Hq, g.D, g.N, g.T, g.G)
         t0 = time.perf_counter()
-        oracle.score_chunks(hs, q_host, k_host, oracle.NORM_VISIBLE)
-        t_sc = time.perf_counter() - t0
-        full_s += t_sc * (g.L * g.Hq) / n_q
-        desc += f"; scoring of {n_q} of {g.L * g.Hq} (layer, head) pairs"
-    return {"value": round(g.elements * 2 / full_s / 1e9, 4), "unit": "GB/s", "cores": oracle.threads(),
-            "kind": "oracle", "sample": desc + "; scaled to the whole cache"}
+        _, d_orc = oracle.score_chunks(os_, q_host, kv_host, oracle.NORM_VISIBLE)
+        full_s += time.perf_counter() - t0
+        desc += f"; scoring of all {g.L * g.Hq} (layer, head) pairs"
+        num8, num4, den = FRACTIONS[path.wl.bits_rule]
+        moved = int((oracle.bits_from_scores(d_orc, num8, num4, den) != path.bits).sum())
+        extra["chunks_in_another_bucket_under_oracle_scores"] = moved
+    # one thread: one chunk, one (layer, head) pair
+    oracle.set_threads(1)
+    try:
+        one_s = quant_seconds(sample[:1])
+        if path.R:
+            hs = oracle.Shape(1, 1, 1, g.D, g.N, g.T, g.G)
+            q1 = path.q[0:1, 0:1].contiguous().cpu().numpy()
+            k1 = path.kv[0:1, :, 0:1].contiguous().cpu().numpy()
+            t0 = time.perf_counter()
+            oracle.score_chunks(hs, q1, k1, oracle.NORM_VISIBLE)
+            one_s += (time.perf_counter() - t0) * g.L * g.Hq
+    finally:
+        oracle.set_threads(n_all)
+    return {"value": round(g.elements * 2 / full_s / 1e9, 4), "unit": "GB/s", "cores": n_all,
+            "kind": "oracle", "sample": desc,
+            "per_core_value": round(g.elements * 2 / one_s / 1e9, 5),
+            "per_core_sample": "one thread: one chunk" + (" and one (layer, head) pair" if path.R else "") + ", scaled to all",
+            **extra}
+
+
+def clock_state():
+    """GPU clocks and power state as the driver reports them just before the timed region (sysfs of
+    the first amdgpu card; None where the box does not expose it).  Read once, outside the timing."""
+    import glob
+    out = {}
+    for card in sorted(glob.glob("/sys/class/drm/card*/device")):
+        if not os.path.exists(os.path.join(card, "pp_dpm_sclk")):
+            continue
+        for key, name in (("sclk", "pp_dpm_sclk"), ("mclk", "pp_dpm_mclk"), ("fclk", "pp_dpm_fclk")):
+            try:
+                lines = open(os.path.join(card, name)).read().split("\n")
+                active = [l for l in lines if l.strip().endswith("*")]
+                if active:
+                    out[f"{key}_mhz"] = int("".join(ch for ch in active[0].split(":")[1] if ch.isdigit()))
+            except (OSError, ValueError, IndexError):
+                pass
+        try:
+            out["performance_level"] = open(os.path.join(card, "power_dpm_force_performance_level")).read().strip()
+        except OSError:
+            pass
+        try:
+            hw = glob.glob(os.path.join(card, "hwmon", "hwmon*", "power1_average"))
+            if hw:
+                out["power_w"] = round(int(open(hw[0]).read()) / 1e6, 1)
+        except (OSError, ValueError):
+            pass
+        break
+    try:
+        out["max_sclk_mhz"] = torch.cuda.get_device_properties(0).clock_rate // 1000
+    except Exception:
+        pass
+    return out or None
 
 
 def read_traffic(workload, kernel):
@@ -567,7 +624,7 @@ def run_pool(wl, args, dev):
         "value": round(sel_fp16 / float(np.mean(wall_ms)) / 1e6, 2), "unit": "GB/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(float(np.mean(wall_ms)), 4), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "vs_baseline": None, "dtype": "f16", "data": "synthetic",
         "config": {"workload": f"{wl.name}: {n_ctx} contexts of [L={g.L},K/V,Hkv={g.Hkv},N={g.N},D={g.D}] fp16, "
                                f"chunk {g.T}, mixed 8/4/2 bits; a step swaps in {n_sel} of {g.n_chunks} chunks",
                    "pool_bytes": int(sum(int(o[-1]) for o in ctx_off)), "selected_fp16_bytes": sel_fp16,
@@ -659,7 +716,7 @@ def run_stream(wl, args, dev):
         "value": round(cache_bytes / mean["stream"] / 1e6, 2), "unit": "GB/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(mean["stream"], 4), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "vs_baseline": None, "dtype": "f16", "data": "synthetic",
         "config": {"workload": f"{wl.name}: [L={g.L},K/V,Hkv={g.Hkv},N={g.N},D={g.D}] fp16, chunk {g.T}, "
                                f"group {g.G}, R={path.R}; records in pinned host memory"
                                + (", record parameters in binary16" if shape.format == 3 else ""),
@@ -763,7 +820,7 @@ def run_i8(wl, args, dev):
         "metric": "KV GB/s (fp16-equiv) compress + swap-in, % of HBM peak; ms per 4K-ctx switch",
         "value": round(cache_bytes / ms_per_step / 1e6, 2), "unit": "GB/s (int8 cache bytes)",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "i8", "data": "synthetic",
         "config": {"workload": f"{wl.name}, int8 channel-wise format ({'binary16' if half else 'fp32'} parameters): [L={g.L},K/V,Hkv={g.Hkv},N={g.N},D={g.D}] int8, "
                                f"chunk {g.T}, widths 8/4/2 by terciles of seeded scores",
                    "cache_bytes": cache_bytes, "packed_bytes": int(off[-1]), "step": "compress + swap-in"},
@@ -939,6 +996,7 @@ def main():
     # step to read the densities); the per-kernel events are read after the timed region
     path.reserve_event_sets(args.steps)
     torch.cuda.synchronize()
+    clocks = clock_state()          # right behind the warm-up steps, before the timed region
     first = path.step_no
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -960,11 +1018,13 @@ def main():
     kernels = {}
     plan_ms = sums.pop("plan", None)
     for k, v in sums.items():
-        ms = float(np.mean(v))
+        ms, med = float(np.mean(v)), float(np.median(v))
         gbps = alg[k] / ms / 1e6
-        kernels[k] = {"ms": round(ms, 4), "ms_median": round(float(np.median(v)), 4),
+        kernels[k] = {"ms": round(ms, 4), "ms_median": round(med, 4),
                       "ms_min": round(float(np.min(v)), 4), "algorithmic_bytes": alg[k], "hbm_gbps": round(gbps, 1),
                       "hbm_frac": round(gbps / HBM_PEAK_GBPS, 4),
+                      "hbm_gbps_median": round(alg[k] / med / 1e6, 1),
+                      "hbm_frac_median": round(alg[k] / med / 1e6 / HBM_PEAK_GBPS, 4),
                       "fp16_equiv_gbps": round(cache_bytes / ms / 1e6, 1)}
     if path.R:
         flops = 2.0 * path.R * g.N * g.D * g.L * g.Hq
@@ -975,8 +1035,11 @@ def main():
     names = {"compress": "compress_kernel", "swapin": "swapin_kernel",
              "score": "score_head_kernel" if one_block else "score_tiles_kernel"}
     dom = max(kernels, key=lambda k: kernels[k]["ms"])
+    # achieved / frac: algorithmic bytes over the MEAN launch duration (what a kernel trace's average must
+    # agree with); the median of the same launches is given beside it
     roofline = {"kernel": names[dom], "bound": "hbm", "achieved": kernels[dom]["hbm_gbps"],
                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": kernels[dom]["hbm_frac"],
+                "achieved_median": kernels[dom]["hbm_gbps_median"], "frac_median": kernels[dom]["hbm_frac_median"],
                 "traffic": read_traffic(wl.name, names[dom])}
 
     out = {
@@ -986,7 +1049,9 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "dtype": "f16", "dtype_note": "fp16 cache and MFMA operands; softmax, accumulation and the quantiser's "
+                                      "arithmetic in f32",
+        "data": "synthetic",
         "config": {"workload": f"{wl.name}: [L={g.L},K/V,Hkv={g.Hkv},N={g.N},D={g.D}] fp16, "
                                f"chunk {g.T}, group {g.G}, R={path.R}, widths {wl.bits_rule}"
                                + (", record parameters in binary16" if path.shape.format == 3 else ""),
@@ -1002,6 +1067,7 @@ def main():
     }
     if plan_ms is not None:
         out["plan_ms"] = round(float(np.mean(plan_ms)), 4)
+    out["clocks_before_timed_region"] = clocks
     if args.graph and path.device_plan:
         out["hip_graph"] = {"ms_per_step": round(graph_ms_per_step(path, args), 4),
                             "note": "the same step captured once per buffer set and replayed; no events inside"}

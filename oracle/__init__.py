@@ -95,6 +95,11 @@ def threads() -> int:
     return int(lib().orc_threads())
 
 
+def set_threads(n: int) -> None:
+    """Threads the C loops use from now on (the benchmark times the oracle on one core as well)."""
+    lib().orc_set_threads(ctypes.c_int(int(n)))
+
+
 def _p(a: np.ndarray):
     return a.ctypes.data_as(ctypes.c_void_p)
 

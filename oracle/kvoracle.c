@@ -32,6 +32,16 @@ typedef struct {
                       2: as 1 with the parameters stored (and used) in binary16 */
 } orc_shape;
 
+/* Number of threads the parallel loops below may use from now on (timing the checker on one core). */
+void orc_set_threads(int n)
+{
+#ifdef _OPENMP
+    if (n > 0) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
 int orc_threads(void)
 {
 #ifdef _OPENMP
