@@ -28,7 +28,6 @@ def build_library(verbose: bool = False) -> str:
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
            "-Wall", "-Wno-unused-command-line-argument",
            "-I", INCLUDE, "-I", CSRC]
-    cmd += os.environ.get("KVS_EXTRA_FLAGS", "").split()
     cmd += [os.path.join(CSRC, s) for s in SOURCES]
     tmp = LIB_PATH + ".tmp"
     cmd += ["-ldl", "-o", tmp]

@@ -70,18 +70,11 @@ __device__ __forceinline__ float refined_rcp(float s) {
 // scale per range 0..255, level count and parameter precision), and the GPU tests compare the
 // codes of every such pair with the oracle's true division: one correction reproduces all of
 // them, none does not.
-#ifndef KVS_I8_DIV_STEPS
-#define KVS_I8_DIV_STEPS 1
-#endif
 // d / s rounded as the division does on this domain (rinv = refined_rcp(s)).
 __device__ __forceinline__ float div_exact(float d, float s, float rinv) {
-    float q = d * rinv;
-#pragma unroll
-    for (int i = 0; i < KVS_I8_DIV_STEPS; ++i) {
-        const float e = __builtin_fmaf(-s, q, d);
-        q = __builtin_fmaf(e, rinv, q);
-    }
-    return q;
+    const float q = d * rinv;
+    const float e = __builtin_fmaf(-s, q, d);
+    return __builtin_fmaf(e, rinv, q);
 }
 
 template <int BYTES>
@@ -89,15 +82,15 @@ __device__ __forceinline__ void copy_out(const uint8_t* __restrict__ img, uint8_
     if constexpr (BYTES >= 16) {
 #pragma unroll
         for (int u = 0; u < BYTES / 16; ++u)
-            stream_store<KVS_NT_CODE_STORE>(reinterpret_cast<const u4_t*>(img)[u * 64 + lane],
+            stream_store<true>(reinterpret_cast<const u4_t*>(img)[u * 64 + lane],
                                             reinterpret_cast<u4_t*>(dst) + u * 64 + lane);
     } else if constexpr (BYTES == 8) {
-        stream_store<KVS_NT_CODE_STORE>(reinterpret_cast<const u2_t*>(img)[lane], reinterpret_cast<u2_t*>(dst) + lane);
+        stream_store<true>(reinterpret_cast<const u2_t*>(img)[lane], reinterpret_cast<u2_t*>(dst) + lane);
     } else if constexpr (BYTES == 4) {
-        stream_store<KVS_NT_CODE_STORE>(reinterpret_cast<const uint32_t*>(img)[lane],
+        stream_store<true>(reinterpret_cast<const uint32_t*>(img)[lane],
                                         reinterpret_cast<uint32_t*>(dst) + lane);
     } else {
-        stream_store<KVS_NT_CODE_STORE>(reinterpret_cast<const uint16_t*>(img)[lane],
+        stream_store<true>(reinterpret_cast<const uint16_t*>(img)[lane],
                                         reinterpret_cast<uint16_t*>(dst) + lane);
     }
 }
@@ -247,13 +240,13 @@ __global__ __launch_bounds__(256) void compress_i8_kernel(const u4_t* __restrict
                             static_cast<uint64_t>(chunk) * g.chunk_tokens) * g.row_pieces;
     u4_t raw[PPL];
 #pragma unroll
-    for (int u = 0; u < PPL; ++u) raw[u] = stream_load<KVS_NT_CACHE_LOAD>(src + u * 64 + lane);
+    for (int u = 0; u < PPL; ++u) raw[u] = stream_load<true>(src + u * 64 + lane);
     const int b = uniform_byte(bits, chunk);
     uint8_t* base = packed + off[chunk];
     if (b == 8) {
 #pragma unroll
         for (int u = 0; u < PPL; ++u)
-            stream_store<KVS_NT_CODE_STORE>(raw[u], reinterpret_cast<u4_t*>(base) +
+            stream_store<true>(raw[u], reinterpret_cast<u4_t*>(base) +
                                             static_cast<uint64_t>(slab) * g.pieces + u * 64 + lane);
         return;
     }
@@ -291,15 +284,15 @@ __device__ __forceinline__ void copy_in(const uint8_t* __restrict__ src, uint8_t
 #pragma unroll
         for (int u = 0; u < BYTES / 16; ++u)
             reinterpret_cast<u4_t*>(img)[u * 64 + lane] =
-                stream_load<KVS_NT_CODE_LOAD>(reinterpret_cast<const u4_t*>(src) + u * 64 + lane);
+                stream_load<true>(reinterpret_cast<const u4_t*>(src) + u * 64 + lane);
     } else if constexpr (BYTES == 8) {
-        reinterpret_cast<u2_t*>(img)[lane] = stream_load<KVS_NT_CODE_LOAD>(reinterpret_cast<const u2_t*>(src) + lane);
+        reinterpret_cast<u2_t*>(img)[lane] = stream_load<true>(reinterpret_cast<const u2_t*>(src) + lane);
     } else if constexpr (BYTES == 4) {
         reinterpret_cast<uint32_t*>(img)[lane] =
-            stream_load<KVS_NT_CODE_LOAD>(reinterpret_cast<const uint32_t*>(src) + lane);
+            stream_load<true>(reinterpret_cast<const uint32_t*>(src) + lane);
     } else {
         reinterpret_cast<uint16_t*>(img)[lane] =
-            stream_load<KVS_NT_CODE_LOAD>(reinterpret_cast<const uint16_t*>(src) + lane);
+            stream_load<true>(reinterpret_cast<const uint16_t*>(src) + lane);
     }
 }
 
@@ -371,7 +364,7 @@ __device__ __forceinline__ void swapin_i8_unit(const uint8_t* __restrict__ codes
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 #pragma unroll
     for (int u = 0; u < PPL; ++u)
-        stream_store<KVS_NT_CACHE_STORE>(reinterpret_cast<const u4_t*>(raw_img)[u * 64 + lane], dst + u * 64 + lane);
+        stream_store<true>(reinterpret_cast<const u4_t*>(raw_img)[u * 64 + lane], dst + u * 64 + lane);
 }
 
 template <int NDW, int GPL, bool HM>
@@ -383,9 +376,9 @@ __device__ __forceinline__ void swapin_i8_task(const uint8_t* __restrict__ base,
         const u4_t* src = reinterpret_cast<const u4_t*>(base) + static_cast<uint64_t>(slab) * g.pieces;
         u4_t raw[PPL];
 #pragma unroll
-        for (int u = 0; u < PPL; ++u) raw[u] = stream_load<KVS_NT_CODE_LOAD>(src + u * 64 + lane);
+        for (int u = 0; u < PPL; ++u) raw[u] = stream_load<true>(src + u * 64 + lane);
 #pragma unroll
-        for (int u = 0; u < PPL; ++u) stream_store<KVS_NT_CACHE_STORE>(raw[u], dst + u * 64 + lane);
+        for (int u = 0; u < PPL; ++u) stream_store<true>(raw[u], dst + u * 64 + lane);
         return;
     }
     const uint64_t code_bytes = static_cast<uint64_t>(g.pieces) * 2 * b;
