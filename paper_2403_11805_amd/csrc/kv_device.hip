@@ -154,12 +154,15 @@ int launch_swapin_batch(const kv_shape_t& shape, const QuantGeom& g_in, int ppl,
                         const SwapinBatch& list, u4_t* dst, hipStream_t st) {
     QuantGeom g = g_in;
     if (is_i8(shape)) {
-        const dim3 grid = task_grid(g, list.n);
+        int wpb = 0;
+        const uint32_t wgs = load_grid(&g, list.n, kWavesPerBlock, &wpb);
+        if (!wgs) return fail(KV_ESHAPE, "Load grid exceeds 2^31 workgroups");
+        const dim3 grid(wgs), block(static_cast<uint32_t>(wpb) * 64);
         const I8View v = i8_view(shape);
 #define KV_LAUNCH_I8(NDW, GPL) \
         do {                                                                                                    \
-            if (v.half_meta) hipLaunchKernelGGL((swapin_i8_batch_kernel<NDW, GPL, true>), grid, dim3(256), 0, st, base, list, dst, g, v); \
-            else hipLaunchKernelGGL((swapin_i8_batch_kernel<NDW, GPL, false>), grid, dim3(256), 0, st, base, list, dst, g, v);            \
+            if (v.half_meta) hipLaunchKernelGGL((swapin_i8_batch_kernel<NDW, GPL, true>), grid, block, 0, st, base, list, dst, g, v); \
+            else hipLaunchKernelGGL((swapin_i8_batch_kernel<NDW, GPL, false>), grid, block, 0, st, base, list, dst, g, v);            \
         } while (0)
         KV_I8_DISPATCH(ppl, shape.head_dim, KV_LAUNCH_I8);
 #undef KV_LAUNCH_I8
@@ -285,34 +288,28 @@ static int32_t swapin_launch(const kv_shape_t* shape, const void* packed, const 
     if (!i8) ppl = plan_tasks(&g, kSwapinPiecesPerLane);
     g.slab0 = layer_begin * 2 * shape->n_kv_heads;
     g.slab_count = (layer_end - layer_begin) * 2 * shape->n_kv_heads;
-    if (i8 && g.slab_count > 65535) return fail(KV_ESHAPE, "more than 65535 slabs exceed the launch grid");
     const int kind = pool_kind(packed);
     if (kind == 0) return fail(KV_EINVAL, "packed is neither device memory nor pinned host memory");
-    // int8 formats: two-dimensional task grid of four-wavefront workgroups; fp16 formats: strip order
-    dim3 grid = i8 ? task_grid(g, n_sel) : dim3(1);
-    int wpb = kWavesPerBlock;
-    if (!i8) {
-        grid = dim3(load_grid(&g, n_sel, kind == 2 ? kLinkWaves : kLoadWavesMax, &wpb));
-        if (!grid.x) return fail(KV_ESHAPE, "Load grid exceeds 2^31 workgroups");
-    }
+    // strip order; the int8 kernels keep a slab in LDS per wavefront and stay at four wavefronts per workgroup
+    int wpb = 0;
+    const dim3 grid(load_grid(&g, n_sel, i8 ? kWavesPerBlock : (kind == 2 ? kLinkWaves : kLoadWavesMax), &wpb));
+    if (!grid.x) return fail(KV_ESHAPE, "Load grid exceeds 2^31 workgroups");
     const dim3 block(static_cast<uint32_t>(wpb) * 64);
     hipStream_t st = static_cast<hipStream_t>(stream);
     const uint8_t* src = static_cast<const uint8_t*>(packed);
     u4_t* dst = static_cast<u4_t*>(kv_out);
     if (kind == 2) {
-        const uint64_t total = static_cast<uint64_t>(grid.x) * grid.y;
-        if (total > 0xffffffffull) return fail(KV_ESHAPE, "task grid of %llu workgroups", static_cast<unsigned long long>(total));
-        const dim3 lgrid(static_cast<uint32_t>(std::min<uint64_t>(total, kLinkBlocks)));
+        const dim3 lgrid(std::min<uint32_t>(grid.x, kLinkBlocks));
         if (i8) {
             const I8View v = i8_view(*shape);
 #define KV_LAUNCH_I8(NDW, GPL)                                                                            \
             do {                                                                                          \
                 if (v.half_meta)                                                                          \
-                    hipLaunchKernelGGL((swapin_i8_link_kernel<NDW, GPL, true>), lgrid, dim3(256), 0, st, src,    \
-                                       src_off_dev, dst_tok_dev, sel_bits_dev, dst, g, v, n_sel, grid.x, grid.y); \
+                    hipLaunchKernelGGL((swapin_i8_link_kernel<NDW, GPL, true>), lgrid, block, 0, st, src,        \
+                                       src_off_dev, dst_tok_dev, sel_bits_dev, dst, g, v, n_sel, grid.x);         \
                 else                                                                                      \
-                    hipLaunchKernelGGL((swapin_i8_link_kernel<NDW, GPL, false>), lgrid, dim3(256), 0, st, src,   \
-                                       src_off_dev, dst_tok_dev, sel_bits_dev, dst, g, v, n_sel, grid.x, grid.y); \
+                    hipLaunchKernelGGL((swapin_i8_link_kernel<NDW, GPL, false>), lgrid, block, 0, st, src,       \
+                                       src_off_dev, dst_tok_dev, sel_bits_dev, dst, g, v, n_sel, grid.x);         \
             } while (0)
             KV_I8_DISPATCH(ppl, shape->head_dim, KV_LAUNCH_I8);
 #undef KV_LAUNCH_I8
@@ -335,10 +332,10 @@ static int32_t swapin_launch(const kv_shape_t* shape, const void* packed, const 
 #define KV_LAUNCH_I8(NDW, GPL)                                                                            \
         do {                                                                                              \
             if (v.half_meta)                                                                              \
-                hipLaunchKernelGGL((swapin_i8_kernel<NDW, GPL, true>), grid, dim3(256), 0, st, src, src_off_dev, \
+                hipLaunchKernelGGL((swapin_i8_kernel<NDW, GPL, true>), grid, block, 0, st, src, src_off_dev,     \
                                    dst_tok_dev, sel_bits_dev, dst, g, v, n_sel);                          \
             else                                                                                          \
-                hipLaunchKernelGGL((swapin_i8_kernel<NDW, GPL, false>), grid, dim3(256), 0, st, src, src_off_dev, \
+                hipLaunchKernelGGL((swapin_i8_kernel<NDW, GPL, false>), grid, block, 0, st, src, src_off_dev,    \
                                    dst_tok_dev, sel_bits_dev, dst, g, v, n_sel);                          \
         } while (0)
         KV_I8_DISPATCH(ppl, shape->head_dim, KV_LAUNCH_I8);
@@ -618,7 +615,6 @@ int32_t kv_load_chunks(const kv_shape_t* shape, const void* packed, const uint64
     int ppl = 0;
     QuantGeom g = i8 ? quant_geom_i8(*shape, &ppl) : quant_geom(*shape);
     if (!i8) ppl = plan_tasks(&g, kSwapinPiecesPerLane);
-    if (i8 && g.slabs > 65535) return fail(KV_ESHAPE, "more than 65535 slabs exceed the launch grid");
     hipStream_t st = static_cast<hipStream_t>(stream);
     for (int32_t j = 0; j < n_sel; j += kBatchMax) {
         SwapinBatch list;
@@ -807,7 +803,6 @@ int32_t kv_swapin_stream(kv_loader_t* ld, const kv_shape_t* shape, const void* p
     int ppl = 0;
     QuantGeom g = i8 ? quant_geom_i8(*shape, &ppl) : quant_geom(*shape);
     if (!i8) ppl = plan_tasks(&g, kSwapinPiecesPerLane);
-    if (i8 && g.slabs > 65535) return fail(KV_ESHAPE, "more than 65535 slabs exceed the launch grid");
     hipStream_t cs = static_cast<hipStream_t>(copy_stream);
     hipStream_t ks = static_cast<hipStream_t>(compute_stream);
     const uint8_t* host = static_cast<const uint8_t*>(packed_pinned);

@@ -393,7 +393,8 @@ __device__ __forceinline__ void swapin_i8_task(const uint8_t* __restrict__ base,
     else swapin_i8_unit<1, NDW, GPL, HM>(codes, scale, mn, code_img, raw_img, dst, v, lane);
 }
 
-// LDS per wavefront as in compress_i8_kernel: the unit (NDW * 256 bytes) and its codes.
+// LDS per wavefront as in compress_i8_kernel: the unit (NDW * 256 bytes) and its codes.  Launched like the
+// fp16 Load kernels (one-dimensional grid in strip order) with at most kWavesPerBlock wavefronts per workgroup.
 template <int NDW, int GPL, bool HM>
 __global__ __launch_bounds__(256) void swapin_i8_kernel(const uint8_t* __restrict__ packed,
                                                         const uint64_t* __restrict__ src_off,
@@ -405,7 +406,7 @@ __global__ __launch_bounds__(256) void swapin_i8_kernel(const uint8_t* __restric
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6));
     int j, slab, p0;
-    if (!wave_task(g, n_sel, NDW / 4, j, slab, p0)) return;
+    if (!strip_task_at(g, n_sel, NDW / 4, blockIdx.x, static_cast<int>(blockDim.x >> 6), j, slab, p0)) return;
     u4_t* dst = kv_out + (static_cast<uint64_t>(slab) * g.n_tokens +
                           static_cast<uint64_t>(dst_tok[j])) * g.row_pieces;
     swapin_i8_task<NDW, GPL, HM>(packed + src_off[j], uniform_byte(sel_bits, j), slab, dst, g, v, lds[wave], lane);
@@ -419,14 +420,13 @@ __global__ __launch_bounds__(256) void swapin_i8_link_kernel(const uint8_t* __re
                                                              const int32_t* __restrict__ dst_tok,
                                                              const uint8_t* __restrict__ sel_bits,
                                                              u4_t* __restrict__ kv_out, QuantGeom g, I8View v,
-                                                             int32_t n_sel, uint32_t gx, uint32_t gy) {
+                                                             int32_t n_sel, uint32_t total) {
     __shared__ __align__(16) uint8_t lds[kWavesPerBlock][NDW * 256 + NDW * 128];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6));
-    const uint32_t total = gx * gy;
     for (uint32_t w = blockIdx.x; w < total; w += gridDim.x) {
         int j, slab, p0;
-        if (!wave_task_at(g, n_sel, NDW / 4, w % gx, w / gx, j, slab, p0)) continue;
+        if (!strip_task_at(g, n_sel, NDW / 4, w, static_cast<int>(blockDim.x >> 6), j, slab, p0)) continue;
         u4_t* dst = kv_out + (static_cast<uint64_t>(slab) * g.n_tokens +
                               static_cast<uint64_t>(dst_tok[j])) * g.row_pieces;
         swapin_i8_task<NDW, GPL, HM>(packed + src_off[j], uniform_byte(sel_bits, j), slab, dst, g, v, lds[wave], lane);
@@ -441,7 +441,7 @@ __global__ __launch_bounds__(256) void swapin_i8_batch_kernel(const uint8_t* __r
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6));
     int j, slab, p0;
-    if (!wave_task(g, list.n, NDW / 4, j, slab, p0)) return;
+    if (!strip_task_at(g, list.n, NDW / 4, blockIdx.x, static_cast<int>(blockDim.x >> 6), j, slab, p0)) return;
     u4_t* dst = kv_out + (static_cast<uint64_t>(slab) * g.n_tokens +
                           static_cast<uint64_t>(list.dst_tok[j])) * g.row_pieces;
     swapin_i8_task<NDW, GPL, HM>(staged + list.src_off[j], list.bits[j], slab, dst, g, v, lds[wave], lane);
