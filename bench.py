@@ -841,6 +841,8 @@ def run_recompute(wl, args, dev):
     dims = kvs.LayerDims(d_model, d_ff)
     w = synth.make_layer_weights(d_model, g.Hq, g.Hkv, g.D, d_ff, wl.seed, dev)
     kv = synth.make_kv(synth.Geometry(1, g.Hkv, g.Hq, g.D, g.N, g.T, g.G), wl.seed, dev)
+    if args.own_gemm:
+        os.environ["KVSWITCH_OWN_GEMM"] = "1"        # read when the handle is created
     rc = kvs.Recompute()
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     points = []
@@ -867,7 +869,9 @@ def run_recompute(wl, args, dev):
         t = float(np.mean(ms))
         points.append({"chunks": x, "tokens": M, "ms": round(t, 4), "ms_min": round(float(np.min(ms)), 4),
                        "gemm_gflop": round(gemm_flop / 1e9, 1), "attention_gflop": round(attn_flop / 1e9, 1),
-                       "tflops": round((gemm_flop + attn_flop) / t / 1e9, 1), "gemm_shapes_retuned": improved})
+                       "tflops": round((gemm_flop + attn_flop) / t / 1e9, 1),
+                       "projections": "gemm_f16_kernel" if M <= 256 or args.own_gemm else "rocBLAS",
+                       "gemm_shapes_retuned": improved})
         del ws, x_in, x_out
     rc.close()
     slope, icpt = kvs.kv_fit_line([float(p["chunks"]) for p in points], [p["ms"] * 1e-3 for p in points])
@@ -907,7 +911,7 @@ def run_recompute(wl, args, dev):
         "plan": {"missing_8_4_2": missing, "record_bytes_8_4_2": rec, "layers": g.L,
                  "recompute_8_4_2": list(recompute), "planned_delay_ms": round(delay * 1e3, 3),
                  "io_only_delay_ms": round(io_only * 1e3, 3)},
-        "roofline": {"kernel": "kv_recompute_layer (rocBLAS GEMMs + recompute_attention_kernel)", "bound": "mfma",
+        "roofline": {"kernel": "kv_recompute_layer (" + big["projections"] + " projections + recompute_attention_kernel)", "bound": "mfma",
                      "achieved": big["tflops"], "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(big["tflops"] / MFMA_F16_PEAK_TFLOPS, 4), "traffic": None},
     }
@@ -938,6 +942,8 @@ def main():
     ap.add_argument("--pipeline", action="store_true",
                     help="instead of the benchmark: a context Load from pinned host memory with the first x chunks "
                          "recomputed meanwhile (Sec. 3.3 pipeline), measured for several x")
+    ap.add_argument("--own-gemm", action="store_true",
+                    help="--recompute: every projection on the library's own GEMM kernel (default: rocBLAS above 256 rows)")
     ap.add_argument("--no-tune", action="store_true",
                     help="--recompute: keep the GEMM library's own choice of kernels (default: kv_recompute_tune first)")
     ap.add_argument("--graph", action="store_true",

@@ -484,9 +484,13 @@ typedef struct {
     const void* w_down;   /* [d_ff][d_model]                  */
 } kv_layer_weights_t;
 
-/* Handle of the recompute path: owns the dense-GEMM library handle (rocBLAS, loaded on
- * creation; its own device workspace lives until kv_recompute_destroy).  NULL on failure
- * (kv_last_error has the text).  One handle serves one stream at a time. */
+/* Handle of the recompute path.  The projections of up to 256 recomputed tokens (what a plan
+ * of Eq. 4 recomputes beside a Load) run on the library's own MFMA GEMM; larger ones are handed
+ * to rocBLAS, which is loaded on creation if it is installed (the handle then owns that
+ * library's handle, whose device workspace lives until kv_recompute_destroy).  Without
+ * rocBLAS, or with KVSWITCH_OWN_GEMM=1 in the environment at creation, every size runs on the
+ * library's own kernel (about half the GEMM library's rate at thousands of rows).  NULL on
+ * failure (kv_last_error has the text).  One handle serves one stream at a time. */
 typedef struct kv_recompute kv_recompute_t;
 kv_recompute_t* kv_recompute_create(void);
 void            kv_recompute_destroy(kv_recompute_t* rc);
@@ -504,8 +508,9 @@ uint64_t kv_recompute_workspace_bytes(const kv_shape_t* shape, const kv_layer_di
  * kv_recompute_layer calls with the same n_missing if it beats the standard choice by more than
  * 5 %.  Unlike every other device call this one SYNCHRONISES `stream`, takes of the order of a
  * second, and overwrites the workspace.  n_improved (may be NULL) receives the number of shapes
- * that got another kernel; 0 and KV_OK if the library cannot list its kernels.  Results are the
- * same up to the summation order inside a GEMM. */
+ * that got another kernel; 0 and KV_OK if the library cannot list its kernels, and where the
+ * projections do not go to the GEMM library at all (up to 256 tokens, or no rocBLAS): nothing is
+ * then timed.  Results are the same up to the summation order inside a GEMM. */
 int32_t kv_recompute_tune(kv_recompute_t* rc, const kv_shape_t* shape, const kv_layer_dims_t* dims,
                           const kv_layer_weights_t* weights, int32_t n_missing, void* workspace,
                           uint64_t workspace_bytes, void* stream, int32_t* n_improved);

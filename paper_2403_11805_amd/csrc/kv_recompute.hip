@@ -1,8 +1,11 @@
 // libkvswitch: recompute of interleaved chunks through one Llama-style block
 // (Sec. 3.3, "Making interleaved chunks recomputable").  Host side: argument
-// checks, the workspace plan, the dense projections as rocBLAS GEMMs (loaded at
-// run time, so the rest of the library does not depend on it) and the launches
-// of the kernels in kv_recompute_kernels.hpp.
+// checks, the workspace plan, the dense projections and the launches of the
+// kernels in kv_recompute_kernels.hpp.  The projections of up to kHandGemmRows
+// recomputed tokens - what a plan of Eq. 4 recomputes beside a Load - run on the
+// library's own MFMA GEMM (kv_gemm_kernels.hpp); larger ones go to rocBLAS, which
+// is loaded at run time if it is there (the rest of the library does not depend
+// on it, and without it every size runs on the library's own kernel).
 
 #include <dlfcn.h>
 #include <hip/hip_runtime.h>
@@ -10,9 +13,11 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdint>
+#include <cstdlib>
 #include <new>
 #include <vector>
 
+#include "kv_gemm_kernels.hpp"
 #include "kv_internal.h"
 #include "kv_recompute_kernels.hpp"
 
@@ -42,9 +47,41 @@ typedef int (*rb_get_solutions_fn)(rb_handle, int, int, int, int, int, const voi
 uint64_t align256(uint64_t v) { return (v + 255) & ~static_cast<uint64_t>(255); }
 
 struct Plan {
-    uint64_t xn, q32, k32, v32, q16, attn, x1, gate, up, part_o, part_ml, total;
+    uint64_t xn, q32, k32, v32, q16, attn, x1, gate, up, part_o, part_ml, gemm_part, total;
     int splits;          // workgroups that share the key range of one attention row block (1: no split)
 };
+
+// Measured on MI355X against rocBLAS (Llama-2-7B projections, us for q|k|v|o, gate|up, down):
+//   128 rows   own 21 / 34 / 33    library's standard kernels 22 / 38 / 88   (its best after tuning: 22 / 33 / 38)
+//   256 rows   own 27 / 48 / 45    library 27 / 39 / 124
+//   816 rows   own 53 / 121 / 121  library 41 / 72 / 183
+//   4096 rows  own 190 / 504 / 485 (720-760 TFLOP/s)   library 114 / 298 / 266 (1.2-1.4 PFLOP/s)
+constexpr int64_t kHandGemmRows = 256;
+
+// Launch shape of the library's own GEMM: row blocks per tile, K range per split, number of splits.
+struct HandGemm {
+    int mb, k_slice, splits;
+    uint32_t tiles_n, tiles_m;
+};
+
+HandGemm hand_gemm_plan(int64_t M, int64_t N, int64_t K) {
+    HandGemm h;
+    h.mb = M <= 32 ? 1 : (M <= 64 ? 2 : 4);
+    h.tiles_n = static_cast<uint32_t>((N + 127) / 128);
+    h.tiles_m = static_cast<uint32_t>((M + h.mb * 32 - 1) / (h.mb * 32));
+    // K is divided until some 512 workgroups exist (two per CU), at least 256 of K per split
+    const int64_t tiles = static_cast<int64_t>(h.tiles_n) * h.tiles_m;
+    int64_t want = (512 + tiles - 1) / tiles;
+    want = std::min<int64_t>(want, std::min<int64_t>(kGemmMaxSplits, std::max<int64_t>(1, K / 256)));
+    h.k_slice = static_cast<int>(((K + want - 1) / want + kGemmKStep - 1) / kGemmKStep * kGemmKStep);
+    h.splits = static_cast<int>((K + h.k_slice - 1) / h.k_slice);
+    return h;
+}
+
+uint64_t hand_gemm_part_bytes(int64_t M, int64_t N, int64_t K) {
+    const HandGemm h = hand_gemm_plan(M, N, K);
+    return h.splits > 1 ? static_cast<uint64_t>(h.splits) * M * N * 4u : 0u;
+}
 
 // With few recomputed rows the attention kernel has too few workgroups to fill 256 CUs: the key
 // range is then divided among up to 16 workgroups (one workgroup per CU in total: measured, more
@@ -80,6 +117,14 @@ Plan plan_workspace(const kv_shape_t& s, const kv_layer_dims_t& d, int64_t M) {
     if (p.splits > 1) o += align256(static_cast<uint64_t>(p.splits) * M * dq * 4u);
     p.part_ml = o;
     if (p.splits > 1) o += align256(static_cast<uint64_t>(p.splits) * M * s.n_q_heads * 8u);
+    // partial tiles of the largest split projection (q | k | v, o, gate | up, down)
+    p.gemm_part = o;
+    uint64_t part = hand_gemm_part_bytes(M, static_cast<int64_t>(dq), d.d_model);
+    part = std::max(part, hand_gemm_part_bytes(M, static_cast<int64_t>(dkv), d.d_model));
+    part = std::max(part, hand_gemm_part_bytes(M, d.d_model, static_cast<int64_t>(dq)));
+    part = std::max(part, hand_gemm_part_bytes(M, d.d_ff, d.d_model));
+    part = std::max(part, hand_gemm_part_bytes(M, d.d_model, d.d_ff));
+    o += align256(part);
     p.total = o;
     return p;
 }
@@ -136,8 +181,37 @@ int gemm_status(kv_recompute* rc, const GemmShape& g, const void* A, const void*
                        solution < 0 ? 0 : solution, 0);
 }
 
-int gemm(kv_recompute* rc, int64_t M, int64_t N, int64_t K, const void* A, const void* B,
-         const void* Cin, void* Cout, bool out_f32, const char* what) {
+// The library's own GEMM (kv_gemm_kernels.hpp); `part` holds hand_gemm_part_bytes(M, N, K).
+int hand_gemm(hipStream_t st, int64_t M, int64_t N, int64_t K, const void* A, const void* B, const void* Cin,
+              void* Cout, bool out_f32, float* part, const char* what) {
+    if (N % 8 || K % 8 || N < 8 || K < 8 || M < 1) return fail(KV_ESHAPE, "GEMM (%s) needs N and K multiples of 8", what);
+    const HandGemm h = hand_gemm_plan(M, N, K);
+    GemmArgs g;
+    g.A = static_cast<const _Float16*>(A);
+    g.B = static_cast<const _Float16*>(B);
+    g.Cin = static_cast<const _Float16*>(Cin);
+    g.C = Cout;
+    g.part = part;
+    g.M = static_cast<int32_t>(M);
+    g.N = static_cast<int32_t>(N);
+    g.K = static_cast<int32_t>(K);
+    g.k_slice = h.k_slice;
+    g.splits = h.splits;
+    g.out_f32 = out_f32 ? 1 : 0;
+    const dim3 grid(h.tiles_n, static_cast<uint32_t>(h.splits), h.tiles_m);
+    if (h.mb == 1) hipLaunchKernelGGL(gemm_f16_kernel<1>, grid, dim3(256), 0, st, g);
+    else if (h.mb == 2) hipLaunchKernelGGL(gemm_f16_kernel<2>, grid, dim3(256), 0, st, g);
+    else hipLaunchKernelGGL(gemm_f16_kernel<4>, grid, dim3(256), 0, st, g);
+    if (h.splits > 1)
+        hipLaunchKernelGGL(gemm_reduce_kernel, dim3(static_cast<uint32_t>((M * N / 4 + 255) / 256)), dim3(256), 0, st, g);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(KV_EHIP, "gemm_f16_kernel launch (%s): %s", what, hipGetErrorString(e));
+    return KV_OK;
+}
+
+int gemm(kv_recompute* rc, hipStream_t stream, float* part, int64_t M, int64_t N, int64_t K, const void* A,
+         const void* B, const void* Cin, void* Cout, bool out_f32, const char* what) {
+    if (M <= kHandGemmRows || !rc->gemm_ex) return hand_gemm(stream, M, N, K, A, B, Cin, Cout, out_f32, part, what);
     const GemmShape g = {M, N, K, out_f32, Cin != nullptr};
     int solution = -1;
     for (const auto& t : rc->tuned)
@@ -258,13 +332,13 @@ kv_recompute_t* kv_recompute_create(void) {
         fail(KV_ENOMEM, "out of host memory");
         return nullptr;
     }
+    // KVSWITCH_OWN_GEMM=1 in the environment keeps the GEMM library out: every projection then runs
+    // on the library's own kernel, as it does where rocBLAS is not installed
+    const char* own = getenv("KVSWITCH_OWN_GEMM");
+    if (own && own[0] == '1') return rc;
     rc->lib = dlopen("librocblas.so.5", RTLD_NOW | RTLD_LOCAL);
     if (!rc->lib) rc->lib = dlopen("librocblas.so", RTLD_NOW | RTLD_LOCAL);
-    if (!rc->lib) {
-        fail(KV_EHIP, "rocBLAS not found: %s", dlerror());
-        delete rc;
-        return nullptr;
-    }
+    if (!rc->lib) return rc;
     rb_create_fn create = reinterpret_cast<rb_create_fn>(dlsym(rc->lib, "rocblas_create_handle"));
     rc->destroy = reinterpret_cast<rb_destroy_fn>(dlsym(rc->lib, "rocblas_destroy_handle"));
     rc->set_stream = reinterpret_cast<rb_set_stream_fn>(dlsym(rc->lib, "rocblas_set_stream"));
@@ -288,7 +362,7 @@ kv_recompute_t* kv_recompute_create(void) {
 
 void kv_recompute_destroy(kv_recompute_t* rc) {
     if (!rc) return;
-    if (rc->handle) rc->destroy(rc->handle);
+    if (rc->handle && rc->destroy) rc->destroy(rc->handle);
     // the library stays loaded: other users in the process may share it
     delete rc;
 }
@@ -313,7 +387,8 @@ int32_t kv_recompute_tune(kv_recompute_t* rc, const kv_shape_t* shape, const kv_
     if (workspace_bytes < p.total)
         return fail(KV_ENOMEM, "workspace %llu bytes, %llu needed", static_cast<unsigned long long>(workspace_bytes),
                     static_cast<unsigned long long>(p.total));
-    if (!rc->get_solutions) return KV_OK;                     // this GEMM library cannot list its kernels
+    // projections of few rows run on the library's own kernel; nothing to choose there, nor without a GEMM library
+    if (M <= kHandGemmRows || !rc->gemm_ex || !rc->get_solutions) return KV_OK;
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (rc->set_stream(rc->handle, st) != 0) return fail(KV_EHIP, "rocblas_set_stream failed");
     // operands of ordinary magnitude and varied bits in every buffer a GEMM reads
@@ -376,9 +451,11 @@ int32_t kv_recompute_layer(kv_recompute_t* rc, const kv_shape_t* shape, const kv
         return fail(KV_ENOMEM, "workspace %llu bytes, %llu needed", static_cast<unsigned long long>(workspace_bytes),
                     static_cast<unsigned long long>(p.total));
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (rc->set_stream(rc->handle, st) != 0) return fail(KV_EHIP, "rocblas_set_stream failed");
+    if (rc->gemm_ex && M > kHandGemmRows && rc->set_stream(rc->handle, st) != 0)
+        return fail(KV_EHIP, "rocblas_set_stream failed");
 
     uint8_t* base = static_cast<uint8_t*>(workspace);
+    float* gpart = reinterpret_cast<float*>(base + p.gemm_part);
     _Float16* xn = reinterpret_cast<_Float16*>(base + p.xn);
     float* q32 = reinterpret_cast<float*>(base + p.q32);
     float* k32 = reinterpret_cast<float*>(base + p.k32);
@@ -398,9 +475,9 @@ int32_t kv_recompute_layer(kv_recompute_t* rc, const kv_shape_t* shape, const kv
     // 1. norm, q/k/v projections (binary32 results, rounded once after the rotation)
     hipLaunchKernelGGL(rmsnorm_kernel, rows, dim3(256), 0, st, xin, static_cast<const _Float16*>(w->w_norm1), xn,
                        static_cast<int32_t>(M), dims->d_model, dims->rms_eps);
-    if (int e = gemm(rc, M, dq, dims->d_model, xn, w->wq, nullptr, q32, true, "q")) return e;
-    if (int e = gemm(rc, M, dkv, dims->d_model, xn, w->wk, nullptr, k32, true, "k")) return e;
-    if (int e = gemm(rc, M, dkv, dims->d_model, xn, w->wv, nullptr, v32, true, "v")) return e;
+    if (int e = gemm(rc, st, gpart, M, dq, dims->d_model, xn, w->wq, nullptr, q32, true, "q")) return e;
+    if (int e = gemm(rc, st, gpart, M, dkv, dims->d_model, xn, w->wk, nullptr, k32, true, "k")) return e;
+    if (int e = gemm(rc, st, gpart, M, dkv, dims->d_model, xn, w->wv, nullptr, v32, true, "v")) return e;
     // 2. global position encoding; the recomputed K/V go to their places in the cache
     RopeTable tab;
     for (int i = 0; i < D / 2; ++i) tab.theta[i] = std::pow(static_cast<double>(dims->rope_base), -2.0 * i / D);
@@ -445,15 +522,15 @@ int32_t kv_recompute_layer(kv_recompute_t* rc, const kv_shape_t* shape, const kv
                                k_plane, v_plane, chunk_idx_dev, attn, g, nullptr, nullptr, 0);
     }
     // 4. output projection + residual, feed-forward + residual
-    if (int e = gemm(rc, M, dims->d_model, dq, attn, w->wo, xin, x1, false, "o")) return e;
+    if (int e = gemm(rc, st, gpart, M, dims->d_model, dq, attn, w->wo, xin, x1, false, "o")) return e;
     hipLaunchKernelGGL(rmsnorm_kernel, rows, dim3(256), 0, st, x1, static_cast<const _Float16*>(w->w_norm2), xn,
                        static_cast<int32_t>(M), dims->d_model, dims->rms_eps);
-    if (int e = gemm(rc, M, dims->d_ff, dims->d_model, xn, w->w_gate, nullptr, gate, false, "gate")) return e;
-    if (int e = gemm(rc, M, dims->d_ff, dims->d_model, xn, w->w_up, nullptr, up, false, "up")) return e;
+    if (int e = gemm(rc, st, gpart, M, dims->d_ff, dims->d_model, xn, w->w_gate, nullptr, gate, false, "gate")) return e;
+    if (int e = gemm(rc, st, gpart, M, dims->d_ff, dims->d_model, xn, w->w_up, nullptr, up, false, "up")) return e;
     const int64_t n8 = M * dims->d_ff / 8;
     hipLaunchKernelGGL(silu_mul_kernel, dim3(static_cast<uint32_t>((n8 + 255) / 256)), dim3(256), 0, st, gate, up,
                        gate, n8);
-    if (int e = gemm(rc, M, dims->d_model, dims->d_ff, gate, w->w_down, x1, x_out, false, "down")) return e;
+    if (int e = gemm(rc, st, gpart, M, dims->d_model, dims->d_ff, gate, w->w_down, x1, x_out, false, "down")) return e;
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(KV_EHIP, "recompute launch: %s", hipGetErrorString(e));
     return KV_OK;

@@ -93,6 +93,8 @@ def run_case(L, Hkv, Hq, D, N, T, d_model, d_ff, layer, missing, seed, tune=Fals
     (1, 2, 2, 128, 384, 16, 256, 256, 0, [0, 1, 2, 5, 7, 8, 13, 20, 23]),   # five row blocks per head
     (1, 1, 2, 64, 128, 32, 128, 256, 0, [3]),                    # only the last chunk
     (1, 1, 1, 128, 96, 16, 128, 128, 0, [0, 1, 2, 3, 4, 5]),     # everything: the plain forward pass
+    (1, 1, 2, 64, 128, 8, 200, 328, 0, [1, 5, 6]),               # widths that fill no GEMM tile or k-step: M = 24
+    (1, 2, 4, 64, 512, 16, 264, 1096, 0, [0, 2, 3, 7, 8, 9, 12, 15, 16, 20, 21, 22, 30]),  # M = 208: two row tiles, a ragged one
 ])
 def test_small_layers_full(case):
     run_case(*case, seed=41)
@@ -111,6 +113,14 @@ def test_tuned_gemm_kernels_keep_parity():
     run_case(2, 2, 4, 64, 256, 16, 256, 512, 1, [2, 4, 5, 11], seed=41, tune=True)
     run_case(1, 8, 8, 128, 2048, 16, 1024, 2816, 0,
              sorted(np.random.default_rng(7).choice(128, size=51, replace=False).tolist()), seed=43, tune=True)
+
+
+def test_own_gemm_kernel_at_every_size(monkeypatch):
+    """Without the GEMM library (switched off through the environment) the projections of the
+    816-row case run on the library's own kernel as well: same bars."""
+    monkeypatch.setenv("KVSWITCH_OWN_GEMM", "1")
+    run_case(1, 8, 8, 128, 2048, 16, 1024, 2816, 0,
+             sorted(np.random.default_rng(7).choice(128, size=51, replace=False).tolist()), seed=43)
 
 
 def test_long_cache_positions_near_32768():

@@ -116,7 +116,10 @@ def test_recompute_entry_points_validate_on_the_host():
         return (up(M * 4096 * 2) + 3 * up(M * dq * 4) + 2 * up(M * dq * 2) + up(M * 4096 * 2) + 2 * up(M * 11008 * 2))
     # 128 rows give 32 attention workgroups: the key range is shared by 8 workgroups each, whose
     # partial outputs (binary32) and (maximum, denominator) pairs are part of the workspace
-    want = plain(M) + 8 * M * dq * 4 + 8 * M * 32 * 8
+    # and the projections of so few rows divide K among several workgroups per tile; the widest set of
+    # binary32 partial tiles is gate | up's: 86 column tiles want 6 shares of K, 704 of K each (a
+    # multiple of 32) makes 6 shares of [128][11008]
+    want = plain(M) + 8 * M * dq * 4 + 8 * M * 32 * 8 + 6 * M * 11008 * 4
     assert kvs.kv_recompute_workspace_bytes(shape, dims, 8) == want
     assert kvs.kv_recompute_workspace_bytes(shape, dims, 256) == plain(4096)       # enough workgroups: no split
     for bad_shape, bad_dims, n in ((shape._replace(head_dim=256, group=64), dims, 8),
