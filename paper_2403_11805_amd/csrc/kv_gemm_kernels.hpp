@@ -8,8 +8,14 @@
 // columns, MB accumulator blocks of 32x32) and walks a slice of K in steps of 32: global loads run
 // three steps ahead in registers, LDS holds two steps.  With few rows (the usual case: some tens of
 // chunks are recomputed beside a Load) the tiles alone do not fill 256 CUs: K is then divided among
-// up to 16 workgroups per tile whose binary32 partial tiles a second kernel adds in a fixed order
-// (and adds Cin and rounds).  All extents are guarded: M any, N and K multiples of 8.
+// up to 16 workgroups per tile, each of which writes a binary32 partial tile.  The kernel that reads
+// the product next adds the partial tiles in split order as it loads them (rotary encoding, the
+// second norm, the gate activation: kv_recompute_kernels.hpp); gemm_reduce_kernel does it where no
+// such kernel follows.  (Measured: a workgroup that counts itself in on a tile counter and, as the
+// last to arrive, adds the tiles itself needs device-scope fences around the counter; with some 500
+// workgroups per launch these more than double the time of a layer.)  Up to three weight matrices
+// that share A (q | k | v, gate | up) go through one launch, which needs fewer splits and fewer
+// launches.  All extents are guarded: M any, N and K multiples of 8.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -26,20 +32,24 @@ typedef unsigned int gu4_t __attribute__((ext_vector_type(4)));
 constexpr int kGemmKStep = 32;
 constexpr int kGemmXPitch = 32 + 8;          // halves per LDS row of the activation tile (pitch 80 B)
 constexpr int kGemmMaxSplits = 16;
+constexpr int kGemmMaxMats = 3;
 
 struct GemmArgs {
-    const _Float16* A;      // [M][K]
-    const _Float16* B;      // [K][N]
-    const _Float16* Cin;    // [M][N] fp16 or NULL (added before the result is rounded)
-    void* C;                // [M][N] fp16 or binary32
-    float* part;            // [splits][M][N] binary32 partial tiles (splits > 1)
-    int32_t M, N, K;
-    int32_t k_slice;        // K range of one split: a multiple of kGemmKStep
+    const _Float16* A;                  // [M][K]
+    const _Float16* B[kGemmMaxMats];    // [K][N[j]]
+    void* C[kGemmMaxMats];              // [M][N[j]] fp16 or binary32
+    const _Float16* Cin;                // [M][N[0]] fp16 or NULL (added before the result is rounded; one matrix only)
+    float* part;                        // matrix j: part + part_at[j], [splits][M][N[j]] binary32 (splits > 1)
+    uint64_t part_at[kGemmMaxMats];
+    int32_t N[kGemmMaxMats];
+    int32_t tile_end[kGemmMaxMats];     // column tiles of matrices 0..j together; unused entries: the total
+    int32_t M, K;
+    int32_t k_slice;                    // K range of one split: a multiple of kGemmKStep
     int32_t splits;
     int32_t out_f32;
 };
 
-// Grid (ceil(N / 128), splits, ceil(M / (MB * 32))), 256 threads; MB in {1, 2, 4}.  (Measured on MI355X: taller
+// Grid (column tiles of all matrices, splits, ceil(M / (MB * 32))), 256 threads; MB in {1, 2, 4}.  (Measured on MI355X: taller
 // tiles - eight row blocks per wavefront, or 256 x 128 tiles with the wavefronts two by two - are slower at
 // every size, 600 against 720-760 TFLOP/s at 4096 rows; the GEMM library reaches 1.2-1.4 PFLOP/s there, which
 // is why the host side hands problems of more than 256 rows to it.)
@@ -56,8 +66,12 @@ __global__ __launch_bounds__(256) void gemm_f16_kernel(GemmArgs g) {
     __shared__ __attribute__((aligned(16))) _Float16 xt[2][kRows * kGemmXPitch];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int n0 = blockIdx.x * kCols;
+    const int tile = blockIdx.x;
+    const int mat = (tile >= g.tile_end[0]) + (tile >= g.tile_end[1]);
+    const int n0 = (tile - (mat ? g.tile_end[mat - 1] : 0)) * kCols;
     const int m0 = blockIdx.z * kRows;
+    const int N = g.N[mat];
+    const _Float16* __restrict__ Bm = g.B[mat];
     const int wm = wave / WN, wn = wave % WN;
     const int kb = blockIdx.y * g.k_slice;
     const int ke = min(g.K, kb + g.k_slice);
@@ -75,8 +89,8 @@ __global__ __launch_bounds__(256) void gemm_f16_kernel(GemmArgs g) {
         for (int p = 0; p < WPER; ++p) {
             const int id = tid + 256 * p;            // k row id / WROW, 8 columns at (id % WROW) * 8
             const int kr = min(kk + id / WROW, g.K - 1);
-            const int nc = min(n0 + (id % WROW) * 8, g.N - 8);
-            wreg[set][p] = *reinterpret_cast<const gu4_t*>(g.B + static_cast<size_t>(kr) * g.N + nc);
+            const int nc = min(n0 + (id % WROW) * 8, N - 8);
+            wreg[set][p] = *reinterpret_cast<const gu4_t*>(Bm + static_cast<size_t>(kr) * N + nc);
         }
 #pragma unroll
         for (int p = 0; p < XPER; ++p) {
@@ -91,7 +105,7 @@ __global__ __launch_bounds__(256) void gemm_f16_kernel(GemmArgs g) {
 #pragma unroll
         for (int p = 0; p < WPER; ++p) {
             const int id = tid + 256 * p;
-            const bool in = kk + id / WROW < ke && n0 + (id % WROW) * 8 < g.N;
+            const bool in = kk + id / WROW < ke && n0 + (id % WROW) * 8 < N;
             *reinterpret_cast<gu4_t*>(&wt[buf][(id / WROW) * kGemmWPitch + (id % WROW) * 8]) = in ? wreg[set][p] : zero;
         }
 #pragma unroll
@@ -159,41 +173,46 @@ __global__ __launch_bounds__(256) void gemm_f16_kernel(GemmArgs g) {
         one(step + 5, 2, 1);
     }
     // acc[c][mb][v]: row m0 + (wm*MB + mb)*32 + 8*(v/4) + 4*(lane/32) + v%4, column n0 + c*WN*32 + wn*32 + lane%32
+    if (g.splits == 1) {
 #pragma unroll
-    for (int c = 0; c < NB; ++c) {
-        const int n = n0 + c * (32 * WN) + wn * 32 + (lane & 31);
-        if (n >= g.N) continue;
-        if (g.splits > 1) {
-            float* dst = g.part + static_cast<size_t>(blockIdx.y) * g.M * g.N;
+        for (int c = 0; c < NB; ++c) {
+            const int n = n0 + c * (32 * WN) + wn * 32 + (lane & 31);
+            if (n >= N) continue;
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int m = m0 + (wm * MB + mb) * 32 + 8 * (v / 4) + 4 * (lane >> 5) + (v % 4);
-                    if (m < g.M) dst[static_cast<size_t>(m) * g.N + n] = acc[c][mb][v];
+                    if (m < g.M) {
+                        const size_t at = static_cast<size_t>(m) * N + n;
+                        float r = acc[c][mb][v];
+                        if (g.Cin) r += static_cast<float>(g.Cin[at]);
+                        if (g.out_f32) static_cast<float*>(g.C[mat])[at] = r;
+                        else static_cast<_Float16*>(g.C[mat])[at] = static_cast<_Float16>(r);
+                    }
                 }
-            continue;
         }
+        return;
+    }
+    float* dst = g.part + g.part_at[mat] + blockIdx.y * (static_cast<size_t>(g.M) * N);
+#pragma unroll
+    for (int c = 0; c < NB; ++c) {
+        const int n = n0 + c * (32 * WN) + wn * 32 + (lane & 31);
+        if (n >= N) continue;
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int m = m0 + (wm * MB + mb) * 32 + 8 * (v / 4) + 4 * (lane >> 5) + (v % 4);
-                if (m < g.M) {
-                    const size_t at = static_cast<size_t>(m) * g.N + n;
-                    float r = acc[c][mb][v];
-                    if (g.Cin) r += static_cast<float>(g.Cin[at]);
-                    if (g.out_f32) static_cast<float*>(g.C)[at] = r;
-                    else static_cast<_Float16*>(g.C)[at] = static_cast<_Float16>(r);
-                }
+                if (m < g.M) dst[static_cast<size_t>(m) * N + n] = acc[c][mb][v];
             }
     }
 }
 
-// Sum of the partial tiles in split order, + Cin, rounded once; four adjacent columns per thread (N % 4 == 0).
+// C[0] = sum of matrix 0's partial tiles in split order + Cin, rounded once; four adjacent columns per thread.
 __global__ __launch_bounds__(256) void gemm_reduce_kernel(GemmArgs g) {
     typedef float f4_t __attribute__((ext_vector_type(4)));
-    const size_t n4 = static_cast<size_t>(g.M) * g.N / 4;
+    const size_t n4 = static_cast<size_t>(g.M) * g.N[0] / 4;
     const size_t i = static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x;
     if (i >= n4) return;
     const f4_t* part = reinterpret_cast<const f4_t*>(g.part);
@@ -204,11 +223,11 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(GemmArgs g) {
         a += f4_t{static_cast<float>(c[0]), static_cast<float>(c[1]), static_cast<float>(c[2]), static_cast<float>(c[3])};
     }
     if (g.out_f32) {
-        reinterpret_cast<f4_t*>(g.C)[i] = a;
+        reinterpret_cast<f4_t*>(g.C[0])[i] = a;
     } else {
         const gv4h_t h = {static_cast<_Float16>(a[0]), static_cast<_Float16>(a[1]), static_cast<_Float16>(a[2]),
                           static_cast<_Float16>(a[3])};
-        reinterpret_cast<gv4h_t*>(g.C)[i] = h;
+        reinterpret_cast<gv4h_t*>(g.C[0])[i] = h;
     }
 }
 

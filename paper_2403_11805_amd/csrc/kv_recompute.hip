@@ -58,16 +58,30 @@ struct Plan {
 //   4096 rows  own 190 / 504 / 485 (720-760 TFLOP/s)   library 114 / 298 / 266 (1.2-1.4 PFLOP/s)
 constexpr int64_t kHandGemmRows = 256;
 
+// Up to three weight matrices [K][N[j]] applied to the same activations in one launch.
+struct GemmGroup {
+    int n;
+    int64_t N[kGemmMaxMats];
+    const void* B[kGemmMaxMats];
+    void* C[kGemmMaxMats];
+};
+
 // Launch shape of the library's own GEMM: row blocks per tile, K range per split, number of splits.
 struct HandGemm {
     int mb, k_slice, splits;
     uint32_t tiles_n, tiles_m;
+    uint64_t part_bytes;
 };
 
-HandGemm hand_gemm_plan(int64_t M, int64_t N, int64_t K) {
+HandGemm hand_gemm_plan(int64_t M, const int64_t* N, int n_mats, int64_t K) {
     HandGemm h;
     h.mb = M <= 32 ? 1 : (M <= 64 ? 2 : 4);
-    h.tiles_n = static_cast<uint32_t>((N + 127) / 128);
+    h.tiles_n = 0;
+    int64_t n_sum = 0;
+    for (int j = 0; j < n_mats; ++j) {
+        h.tiles_n += static_cast<uint32_t>((N[j] + 127) / 128);
+        n_sum += N[j];
+    }
     h.tiles_m = static_cast<uint32_t>((M + h.mb * 32 - 1) / (h.mb * 32));
     // K is divided until some 512 workgroups exist (two per CU), at least 256 of K per split
     const int64_t tiles = static_cast<int64_t>(h.tiles_n) * h.tiles_m;
@@ -75,12 +89,8 @@ HandGemm hand_gemm_plan(int64_t M, int64_t N, int64_t K) {
     want = std::min<int64_t>(want, std::min<int64_t>(kGemmMaxSplits, std::max<int64_t>(1, K / 256)));
     h.k_slice = static_cast<int>(((K + want - 1) / want + kGemmKStep - 1) / kGemmKStep * kGemmKStep);
     h.splits = static_cast<int>((K + h.k_slice - 1) / h.k_slice);
+    h.part_bytes = h.splits > 1 ? static_cast<uint64_t>(h.splits) * M * n_sum * 4u : 0u;
     return h;
-}
-
-uint64_t hand_gemm_part_bytes(int64_t M, int64_t N, int64_t K) {
-    const HandGemm h = hand_gemm_plan(M, N, K);
-    return h.splits > 1 ? static_cast<uint64_t>(h.splits) * M * N * 4u : 0u;
 }
 
 // With few recomputed rows the attention kernel has too few workgroups to fill 256 CUs: the key
@@ -117,13 +127,14 @@ Plan plan_workspace(const kv_shape_t& s, const kv_layer_dims_t& d, int64_t M) {
     if (p.splits > 1) o += align256(static_cast<uint64_t>(p.splits) * M * dq * 4u);
     p.part_ml = o;
     if (p.splits > 1) o += align256(static_cast<uint64_t>(p.splits) * M * s.n_q_heads * 8u);
-    // partial tiles of the largest split projection (q | k | v, o, gate | up, down)
+    // the library's own GEMM: partial tiles of the largest of its four launches
+    const int64_t n_qkv[3] = {static_cast<int64_t>(dq), static_cast<int64_t>(dkv), static_cast<int64_t>(dkv)};
+    const int64_t n_o[1] = {d.d_model}, n_ff[2] = {d.d_ff, d.d_ff};
+    const HandGemm hg[4] = {hand_gemm_plan(M, n_qkv, 3, d.d_model), hand_gemm_plan(M, n_o, 1, static_cast<int64_t>(dq)),
+                            hand_gemm_plan(M, n_ff, 2, d.d_model), hand_gemm_plan(M, n_o, 1, d.d_ff)};
+    uint64_t part = 0;
+    for (const HandGemm& h : hg) part = std::max(part, h.part_bytes);
     p.gemm_part = o;
-    uint64_t part = hand_gemm_part_bytes(M, static_cast<int64_t>(dq), d.d_model);
-    part = std::max(part, hand_gemm_part_bytes(M, static_cast<int64_t>(dkv), d.d_model));
-    part = std::max(part, hand_gemm_part_bytes(M, d.d_model, static_cast<int64_t>(dq)));
-    part = std::max(part, hand_gemm_part_bytes(M, d.d_ff, d.d_model));
-    part = std::max(part, hand_gemm_part_bytes(M, d.d_model, d.d_ff));
     o += align256(part);
     p.total = o;
     return p;
@@ -181,19 +192,38 @@ int gemm_status(kv_recompute* rc, const GemmShape& g, const void* A, const void*
                        solution < 0 ? 0 : solution, 0);
 }
 
-// The library's own GEMM (kv_gemm_kernels.hpp); `part` holds hand_gemm_part_bytes(M, N, K).
-int hand_gemm(hipStream_t st, int64_t M, int64_t N, int64_t K, const void* A, const void* B, const void* Cin,
-              void* Cout, bool out_f32, float* part, const char* what) {
-    if (N % 8 || K % 8 || N < 8 || K < 8 || M < 1) return fail(KV_ESHAPE, "GEMM (%s) needs N and K multiples of 8", what);
-    const HandGemm h = hand_gemm_plan(M, N, K);
+// The library's own GEMM (kv_gemm_kernels.hpp) over a group of weight matrices; `part` holds what hand_gemm_plan
+// asks for.  With `splits_left` a product that was divided along K stays in `part` as *splits_left > 1 partial
+// products per matrix ([splits][M][N[j]], matrix after matrix) for the caller's next kernel to add; otherwise
+// (one matrix only) it is added here.
+int hand_gemm(hipStream_t st, int64_t M, int64_t K, const void* A, const GemmGroup& grp, const void* Cin,
+              bool out_f32, float* part, int* splits_left, const char* what) {
+    if (splits_left) *splits_left = 1;
+    if (!splits_left && grp.n != 1) return fail(KV_EINVAL, "GEMM (%s): a group is added by its reader", what);
+    if (K % 8 || K < 8 || M < 1 || grp.n < 1 || grp.n > kGemmMaxMats || (Cin && grp.n != 1))
+        return fail(KV_ESHAPE, "GEMM (%s): unsupported shape", what);
+    for (int j = 0; j < grp.n; ++j)
+        if (grp.N[j] % 8 || grp.N[j] < 8) return fail(KV_ESHAPE, "GEMM (%s) needs N a multiple of 8", what);
+    const HandGemm h = hand_gemm_plan(M, grp.N, grp.n, K);
     GemmArgs g;
     g.A = static_cast<const _Float16*>(A);
-    g.B = static_cast<const _Float16*>(B);
     g.Cin = static_cast<const _Float16*>(Cin);
-    g.C = Cout;
     g.part = part;
+    int32_t tiles = 0;
+    uint64_t at = 0;
+    for (int j = 0; j < kGemmMaxMats; ++j) {
+        const int k = std::min(j, grp.n - 1);                 // unused entries repeat the last matrix and get no tile
+        g.B[j] = static_cast<const _Float16*>(grp.B[k]);
+        g.C[j] = grp.C[k];
+        g.N[j] = static_cast<int32_t>(grp.N[k]);
+        g.part_at[j] = at;
+        if (j < grp.n) {
+            tiles += static_cast<int32_t>((grp.N[j] + 127) / 128);
+            at += static_cast<uint64_t>(h.splits) * M * grp.N[j];
+        }
+        g.tile_end[j] = tiles;
+    }
     g.M = static_cast<int32_t>(M);
-    g.N = static_cast<int32_t>(N);
     g.K = static_cast<int32_t>(K);
     g.k_slice = h.k_slice;
     g.splits = h.splits;
@@ -202,22 +232,30 @@ int hand_gemm(hipStream_t st, int64_t M, int64_t N, int64_t K, const void* A, co
     if (h.mb == 1) hipLaunchKernelGGL(gemm_f16_kernel<1>, grid, dim3(256), 0, st, g);
     else if (h.mb == 2) hipLaunchKernelGGL(gemm_f16_kernel<2>, grid, dim3(256), 0, st, g);
     else hipLaunchKernelGGL(gemm_f16_kernel<4>, grid, dim3(256), 0, st, g);
-    if (h.splits > 1)
-        hipLaunchKernelGGL(gemm_reduce_kernel, dim3(static_cast<uint32_t>((M * N / 4 + 255) / 256)), dim3(256), 0, st, g);
+    if (h.splits > 1) {
+        if (splits_left) *splits_left = h.splits;
+        else hipLaunchKernelGGL(gemm_reduce_kernel, dim3(static_cast<uint32_t>((M * grp.N[0] / 4 + 255) / 256)),
+                                dim3(256), 0, st, g);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(KV_EHIP, "gemm_f16_kernel launch (%s): %s", what, hipGetErrorString(e));
     return KV_OK;
 }
 
-int gemm(kv_recompute* rc, hipStream_t stream, float* part, int64_t M, int64_t N, int64_t K, const void* A,
-         const void* B, const void* Cin, void* Cout, bool out_f32, const char* what) {
-    if (M <= kHandGemmRows || !rc->gemm_ex) return hand_gemm(stream, M, N, K, A, B, Cin, Cout, out_f32, part, what);
-    const GemmShape g = {M, N, K, out_f32, Cin != nullptr};
-    int solution = -1;
-    for (const auto& t : rc->tuned)
-        if (t.first == g) solution = t.second;
-    const int st = gemm_status(rc, g, A, B, Cin, Cout, solution);
-    if (st != 0) return fail(KV_EHIP, "rocblas_gemm_ex (%s) failed with status %d", what, st);
+// The projections of a group: one launch of the library's own kernel, or one GEMM of the library per matrix.
+int gemm(kv_recompute* rc, hipStream_t stream, float* part, int* splits_left, int64_t M, int64_t K, const void* A,
+         const GemmGroup& grp, const void* Cin, bool out_f32, const char* what) {
+    if (M <= kHandGemmRows || !rc->gemm_ex)
+        return hand_gemm(stream, M, K, A, grp, Cin, out_f32, part, splits_left, what);
+    if (splits_left) *splits_left = 1;
+    for (int j = 0; j < grp.n; ++j) {
+        const GemmShape g = {M, grp.N[j], K, out_f32, Cin != nullptr};
+        int solution = -1;
+        for (const auto& t : rc->tuned)
+            if (t.first == g) solution = t.second;
+        const int st = gemm_status(rc, g, A, grp.B[j], Cin, grp.C[j], solution);
+        if (st != 0) return fail(KV_EHIP, "rocblas_gemm_ex (%s, matrix %d) failed with status %d", what, j, st);
+    }
     return KV_OK;
 }
 
@@ -473,16 +511,21 @@ int32_t kv_recompute_layer(kv_recompute_t* rc, const kv_shape_t* shape, const kv
     const dim3 rows(static_cast<uint32_t>((M + 3) / 4));
 
     // 1. norm, q/k/v projections (binary32 results, rounded once after the rotation)
+    // (a product whose K range was divided stays in `gpart` as partial products, which the next kernel adds)
+    const float* no_part = nullptr;
     hipLaunchKernelGGL(rmsnorm_kernel, rows, dim3(256), 0, st, xin, static_cast<const _Float16*>(w->w_norm1), xn,
                        static_cast<int32_t>(M), dims->d_model, dims->rms_eps);
-    if (int e = gemm(rc, st, gpart, M, dq, dims->d_model, xn, w->wq, nullptr, q32, true, "q")) return e;
-    if (int e = gemm(rc, st, gpart, M, dkv, dims->d_model, xn, w->wk, nullptr, k32, true, "k")) return e;
-    if (int e = gemm(rc, st, gpart, M, dkv, dims->d_model, xn, w->wv, nullptr, v32, true, "v")) return e;
+    int sp = 1;
+    const GemmGroup qkv = {3, {dq, dkv, dkv}, {w->wq, w->wk, w->wv}, {q32, k32, v32}};
+    if (int e = gemm(rc, st, gpart, &sp, M, dims->d_model, xn, qkv, nullptr, true, "q | k | v")) return e;
+    const float* q_src = sp > 1 ? gpart : q32;
+    const float* k_src = sp > 1 ? gpart + sp * M * dq : k32;
+    const float* v_src = sp > 1 ? gpart + sp * M * (dq + dkv) : v32;
     // 2. global position encoding; the recomputed K/V go to their places in the cache
     RopeTable tab;
     for (int i = 0; i < D / 2; ++i) tab.theta[i] = std::pow(static_cast<double>(dims->rope_base), -2.0 * i / D);
-    hipLaunchKernelGGL(rope_scatter_kernel, dim3(static_cast<uint32_t>(M)), dim3(256), 0, st, q32, k32, v32,
-                       chunk_idx_dev, q16, k_plane, v_plane, tab, s.chunk_tokens, s.n_tokens, Hq, Hkv, D);
+    hipLaunchKernelGGL(rope_scatter_kernel, dim3(static_cast<uint32_t>(M)), dim3(256), 0, st, q_src, k_src, v_src,
+                       chunk_idx_dev, q16, k_plane, v_plane, tab, s.chunk_tokens, s.n_tokens, Hq, Hkv, D, sp);
     // 3. causal attention over the recovered K/V
     AttnGeom g;
     g.M = static_cast<int32_t>(M);
@@ -522,15 +565,22 @@ int32_t kv_recompute_layer(kv_recompute_t* rc, const kv_shape_t* shape, const kv
                                k_plane, v_plane, chunk_idx_dev, attn, g, nullptr, nullptr, 0);
     }
     // 4. output projection + residual, feed-forward + residual
-    if (int e = gemm(rc, st, gpart, M, dims->d_model, dq, attn, w->wo, xin, x1, false, "o")) return e;
-    hipLaunchKernelGGL(rmsnorm_kernel, rows, dim3(256), 0, st, x1, static_cast<const _Float16*>(w->w_norm2), xn,
-                       static_cast<int32_t>(M), dims->d_model, dims->rms_eps);
-    if (int e = gemm(rc, st, gpart, M, dims->d_ff, dims->d_model, xn, w->w_gate, nullptr, gate, false, "gate")) return e;
-    if (int e = gemm(rc, st, gpart, M, dims->d_ff, dims->d_model, xn, w->w_up, nullptr, up, false, "up")) return e;
+    const GemmGroup og = {1, {dims->d_model}, {w->wo}, {x1}};
+    if (int e = gemm(rc, st, gpart, &sp, M, dq, attn, og, xin, false, "o")) return e;
+    if (sp > 1)
+        hipLaunchKernelGGL(rmsnorm_sum_kernel, dim3(static_cast<uint32_t>(M)), dim3(256), 0, st, gpart, sp, xin, x1,
+                           static_cast<const _Float16*>(w->w_norm2), xn, static_cast<int32_t>(M), dims->d_model,
+                           dims->rms_eps);
+    else
+        hipLaunchKernelGGL(rmsnorm_kernel, rows, dim3(256), 0, st, x1, static_cast<const _Float16*>(w->w_norm2), xn,
+                           static_cast<int32_t>(M), dims->d_model, dims->rms_eps);
+    const GemmGroup ff = {2, {dims->d_ff, dims->d_ff}, {w->w_gate, w->w_up}, {gate, up}};
+    if (int e = gemm(rc, st, gpart, &sp, M, dims->d_model, xn, ff, nullptr, false, "gate | up")) return e;
     const int64_t n8 = M * dims->d_ff / 8;
     hipLaunchKernelGGL(silu_mul_kernel, dim3(static_cast<uint32_t>((n8 + 255) / 256)), dim3(256), 0, st, gate, up,
-                       gate, n8);
-    if (int e = gemm(rc, st, gpart, M, dims->d_model, dims->d_ff, gate, w->w_down, x1, x_out, false, "down")) return e;
+                       gate, n8, sp > 1 ? gpart : no_part, sp > 1 ? gpart + sp * M * dims->d_ff : no_part, sp);
+    const GemmGroup down = {1, {dims->d_model}, {w->w_down}, {x_out}};
+    if (int e = gemm(rc, st, gpart, nullptr, M, dims->d_ff, gate, down, x1, false, "down")) return e;
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(KV_EHIP, "recompute launch: %s", hipGetErrorString(e));
     return KV_OK;

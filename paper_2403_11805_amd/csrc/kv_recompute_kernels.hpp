@@ -58,6 +58,62 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const _Float16* __restrict
     }
 }
 
+// The same norm over a row that a projection left as `splits` binary32 partial products
+// [splits][M][d_model]:  x[m][:] = fp16(part[0][m][:] + part[1][m][:] + ... + resid[m][:])  (split order,
+// rounded once) is stored - it is the next residual - and normed.  One workgroup per row: with few rows
+// the partial products are most of what a layer reads here, and a wavefront per row would leave the
+// memory system idle.
+__global__ __launch_bounds__(256) void rmsnorm_sum_kernel(const float* __restrict__ part, int32_t splits,
+                                                          const _Float16* __restrict__ resid,
+                                                          _Float16* __restrict__ x,
+                                                          const _Float16* __restrict__ w,
+                                                          _Float16* __restrict__ xn, int32_t M,
+                                                          int32_t d_model, float eps) {
+    __shared__ float wave_ss[4];
+    const int m = blockIdx.x;
+    const int pieces = d_model / 8;
+    const int64_t plane4 = static_cast<int64_t>(M) * d_model / 4;
+    const rv4f_t* src = reinterpret_cast<const rv4f_t*>(part) + static_cast<int64_t>(m) * d_model / 4;
+    const rv8h_t* res = reinterpret_cast<const rv8h_t*>(resid + static_cast<int64_t>(m) * d_model);
+    rv8h_t* row = reinterpret_cast<rv8h_t*>(x + static_cast<int64_t>(m) * d_model);
+    float ss = 0.0f;
+    for (int p = threadIdx.x; p < pieces; p += 256) {
+        rv4f_t lo = src[2 * p], hi = src[2 * p + 1];
+#pragma unroll 4
+        for (int sp = 1; sp < splits; ++sp) {
+            lo += src[sp * plane4 + 2 * p];
+            hi += src[sp * plane4 + 2 * p + 1];
+        }
+        const rv8h_t r = res[p];
+        rv8h_t v;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            v[k] = static_cast<_Float16>(lo[k] + static_cast<float>(r[k]));
+            v[k + 4] = static_cast<_Float16>(hi[k] + static_cast<float>(r[k + 4]));
+        }
+        row[p] = v;                                  // read again below by this same thread
+#pragma unroll
+        for (int k = 0; k < 8; ++k) ss += static_cast<float>(v[k]) * static_cast<float>(v[k]);
+    }
+#pragma unroll
+    for (int o = 16; o >= 1; o >>= 1) ss += __shfl_xor(ss, o);
+    ss = xhalf_sum(ss);
+    if ((threadIdx.x & 63) == 0) wave_ss[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    ss = (wave_ss[0] + wave_ss[1]) + (wave_ss[2] + wave_ss[3]);
+    const float r = 1.0f / sqrtf(ss / static_cast<float>(d_model) + eps);
+    const rv8h_t* wp = reinterpret_cast<const rv8h_t*>(w);
+    rv8h_t* out = reinterpret_cast<rv8h_t*>(xn + static_cast<int64_t>(m) * d_model);
+    for (int p = threadIdx.x; p < pieces; p += 256) {
+        const rv8h_t v = row[p], g = wp[p];
+        rv8h_t o;
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            o[k] = static_cast<_Float16>(static_cast<float>(v[k]) * r * static_cast<float>(g[k]));
+        out[p] = o;
+    }
+}
+
 // Rotary angles: theta[i] = base^(-2i/D) in double, computed on the host.
 struct RopeTable {
     double theta[128];      // head_dim / 2 <= 128
@@ -67,7 +123,9 @@ struct RopeTable {
 //   q16[m][h][:]            = rope(q32[m][h][:], p)                       (fp16)
 //   K plane [g][p][:]       = rope(k32[m][g][:], p)   V plane [g][p][:] = v32[m][g][:]   (fp16 cache)
 // The pair (i, i + D/2) is rotated by p * theta[i]; sine and cosine are taken in
-// double (positions reach tens of thousands of radians).
+// double (positions reach tens of thousands of radians).  q32, k32 and v32 may be `splits` partial
+// products each ([splits][M][heads * D], M = the grid size), which are added in split order as they
+// are read.
 __global__ __launch_bounds__(256) void rope_scatter_kernel(const float* __restrict__ q32,
                                                            const float* __restrict__ k32,
                                                            const float* __restrict__ v32,
@@ -76,11 +134,23 @@ __global__ __launch_bounds__(256) void rope_scatter_kernel(const float* __restri
                                                            _Float16* __restrict__ k_plane,
                                                            _Float16* __restrict__ v_plane,
                                                            RopeTable tab, int32_t T, int32_t N,
-                                                           int32_t Hq, int32_t Hkv, int32_t D) {
-    __shared__ float cs[2][128];
+                                                           int32_t Hq, int32_t Hkv, int32_t D, int32_t splits) {
+    __shared__ __attribute__((aligned(16))) float cs[2][128];
+    const int64_t plane_q = static_cast<int64_t>(gridDim.x) * Hq * D, plane_kv = static_cast<int64_t>(gridDim.x) * Hkv * D;
+    // four adjacent elements, the partial products added in split order
+    auto sum4 = [&](const float* at, int64_t plane) {
+        rv4f_t a = *reinterpret_cast<const rv4f_t*>(at);
+#pragma unroll 4
+        for (int sp = 1; sp < splits; ++sp) a += *reinterpret_cast<const rv4f_t*>(at + sp * plane);
+        return a;
+    };
+    auto to_half4 = [](rv4f_t a) {
+        return rv4h_t{static_cast<_Float16>(a[0]), static_cast<_Float16>(a[1]), static_cast<_Float16>(a[2]),
+                      static_cast<_Float16>(a[3])};
+    };
     const int m = blockIdx.x;
     const int p = global_position(chunk_idx, T, m);
-    const int half = D / 2;
+    const int half = D / 2, half4 = D / 8;
     for (int i = threadIdx.x; i < half; i += blockDim.x) {
         double s, c;
         sincos(static_cast<double>(p) * tab.theta[i], &s, &c);
@@ -90,36 +160,58 @@ __global__ __launch_bounds__(256) void rope_scatter_kernel(const float* __restri
     __syncthreads();
     const float* qrow = q32 + static_cast<int64_t>(m) * Hq * D;
     _Float16* qout = q16 + static_cast<int64_t>(m) * Hq * D;
-    for (int e = threadIdx.x; e < Hq * half; e += blockDim.x) {
-        const int h = e / half, i = e % half;
-        const float a = qrow[h * D + i], b = qrow[h * D + i + half];
-        const float c = cs[0][i], s = cs[1][i];
-        qout[h * D + i] = static_cast<_Float16>(a * c - b * s);
-        qout[h * D + i + half] = static_cast<_Float16>(b * c + a * s);
+    for (int e = threadIdx.x; e < Hq * half4; e += blockDim.x) {
+        const int h = e / half4, i = (e % half4) * 4;
+        const rv4f_t a = sum4(qrow + h * D + i, plane_q), b = sum4(qrow + h * D + i + half, plane_q);
+        const rv4f_t c = *reinterpret_cast<const rv4f_t*>(&cs[0][i]), s = *reinterpret_cast<const rv4f_t*>(&cs[1][i]);
+        *reinterpret_cast<rv4h_t*>(qout + h * D + i) = to_half4(a * c - b * s);
+        *reinterpret_cast<rv4h_t*>(qout + h * D + i + half) = to_half4(b * c + a * s);
     }
     const float* krow = k32 + static_cast<int64_t>(m) * Hkv * D;
     const float* vrow = v32 + static_cast<int64_t>(m) * Hkv * D;
-    for (int e = threadIdx.x; e < Hkv * half; e += blockDim.x) {
-        const int g = e / half, i = e % half;
-        const float a = krow[g * D + i], b = krow[g * D + i + half];
-        const float c = cs[0][i], s = cs[1][i];
+    for (int e = threadIdx.x; e < Hkv * half4; e += blockDim.x) {
+        const int g = e / half4, i = (e % half4) * 4;
+        const rv4f_t a = sum4(krow + g * D + i, plane_kv), b = sum4(krow + g * D + i + half, plane_kv);
+        const rv4f_t c = *reinterpret_cast<const rv4f_t*>(&cs[0][i]), s = *reinterpret_cast<const rv4f_t*>(&cs[1][i]);
         _Float16* dst = k_plane + (static_cast<int64_t>(g) * N + p) * D;
-        dst[i] = static_cast<_Float16>(a * c - b * s);
-        dst[i + half] = static_cast<_Float16>(b * c + a * s);
+        *reinterpret_cast<rv4h_t*>(dst + i) = to_half4(a * c - b * s);
+        *reinterpret_cast<rv4h_t*>(dst + i + half) = to_half4(b * c + a * s);
     }
-    for (int e = threadIdx.x; e < Hkv * D; e += blockDim.x) {
-        const int g = e / D, d = e % D;
-        v_plane[(static_cast<int64_t>(g) * N + p) * D + d] = static_cast<_Float16>(vrow[e]);
+    for (int e = threadIdx.x; e < Hkv * D / 4; e += blockDim.x) {
+        const int g = e / (D / 4), d = (e % (D / 4)) * 4;
+        *reinterpret_cast<rv4h_t*>(v_plane + (static_cast<int64_t>(g) * N + p) * D + d) = to_half4(sum4(vrow + e * 4, plane_kv));
     }
 }
 
 // act = silu(gate) * up, elementwise, 8 elements per thread (n % 8 == 0).
 // (act may be gate: each thread reads its elements before it writes them)
+// With `part_gate` the two operands are first made from projections left as `splits` binary32 partial
+// products of n8 * 8 elements each: gate = fp16(sum in split order), up likewise.
 __global__ __launch_bounds__(256) void silu_mul_kernel(const _Float16* gate, const _Float16* up,
-                                                       _Float16* act, int64_t n8) {
+                                                       _Float16* act, int64_t n8,
+                                                       const float* __restrict__ part_gate,
+                                                       const float* __restrict__ part_up, int32_t splits) {
     const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
     if (i >= n8) return;
-    const rv8h_t g = reinterpret_cast<const rv8h_t*>(gate)[i], u = reinterpret_cast<const rv8h_t*>(up)[i];
+    rv8h_t g, u;
+    if (part_gate) {
+        const rv4f_t* pg = reinterpret_cast<const rv4f_t*>(part_gate);
+        const rv4f_t* pu = reinterpret_cast<const rv4f_t*>(part_up);
+        rv4f_t g0 = pg[2 * i], g1 = pg[2 * i + 1], u0 = pu[2 * i], u1 = pu[2 * i + 1];
+        for (int sp = 1; sp < splits; ++sp) {
+            const int64_t at = (sp * n8 + i) * 2;
+            g0 += pg[at]; g1 += pg[at + 1];
+            u0 += pu[at]; u1 += pu[at + 1];
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            g[k] = static_cast<_Float16>(g0[k]); g[k + 4] = static_cast<_Float16>(g1[k]);
+            u[k] = static_cast<_Float16>(u0[k]); u[k + 4] = static_cast<_Float16>(u1[k]);
+        }
+    } else {
+        g = reinterpret_cast<const rv8h_t*>(gate)[i];
+        u = reinterpret_cast<const rv8h_t*>(up)[i];
+    }
     rv8h_t o;
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
