@@ -870,7 +870,7 @@ def run_recompute(wl, args, dev):
         points.append({"chunks": x, "tokens": M, "ms": round(t, 4), "ms_min": round(float(np.min(ms)), 4),
                        "gemm_gflop": round(gemm_flop / 1e9, 1), "attention_gflop": round(attn_flop / 1e9, 1),
                        "tflops": round((gemm_flop + attn_flop) / t / 1e9, 1),
-                       "projections": "gemm_f16_kernel" if M <= 256 or args.own_gemm else "rocBLAS",
+                       "projections": "gemm_f16_kernel" if M <= kvs.KV_RECOMPUTE_OWN_GEMM_ROWS or args.own_gemm else "rocBLAS",
                        "gemm_shapes_retuned": improved})
         del ws, x_in, x_out
     rc.close()
@@ -943,7 +943,7 @@ def main():
                     help="instead of the benchmark: a context Load from pinned host memory with the first x chunks "
                          "recomputed meanwhile (Sec. 3.3 pipeline), measured for several x")
     ap.add_argument("--own-gemm", action="store_true",
-                    help="--recompute: every projection on the library's own GEMM kernel (default: rocBLAS above 256 rows)")
+                    help="--recompute: every projection on the library's own GEMM kernel (default: rocBLAS above 512 rows)")
     ap.add_argument("--no-tune", action="store_true",
                     help="--recompute: keep the GEMM library's own choice of kernels (default: kv_recompute_tune first)")
     ap.add_argument("--graph", action="store_true",

@@ -484,13 +484,16 @@ typedef struct {
     const void* w_down;   /* [d_ff][d_model]                  */
 } kv_layer_weights_t;
 
-/* Handle of the recompute path.  The projections of up to 256 recomputed tokens (what a plan
- * of Eq. 4 recomputes beside a Load) run on the library's own MFMA GEMM; larger ones are handed
+/* Handle of the recompute path.  The projections of up to KV_RECOMPUTE_OWN_GEMM_ROWS recomputed
+ * tokens (what a plan of Eq. 4 recomputes beside a Load) run on the library's own MFMA GEMM,
+ * which is the faster one there (0.27 against 0.34 ms per Llama-2-7B layer at 128 tokens, 0.32
+ * against 0.35 at 256, 0.47 against 0.49 at 512, rocBLAS with its best kernels); larger ones are handed
  * to rocBLAS, which is loaded on creation if it is installed (the handle then owns that
  * library's handle, whose device workspace lives until kv_recompute_destroy).  Without
  * rocBLAS, or with KVSWITCH_OWN_GEMM=1 in the environment at creation, every size runs on the
  * library's own kernel (about half the GEMM library's rate at thousands of rows).  NULL on
  * failure (kv_last_error has the text).  One handle serves one stream at a time. */
+#define KV_RECOMPUTE_OWN_GEMM_ROWS 512
 typedef struct kv_recompute kv_recompute_t;
 kv_recompute_t* kv_recompute_create(void);
 void            kv_recompute_destroy(kv_recompute_t* rc);
@@ -509,7 +512,7 @@ uint64_t kv_recompute_workspace_bytes(const kv_shape_t* shape, const kv_layer_di
  * 5 %.  Unlike every other device call this one SYNCHRONISES `stream`, takes of the order of a
  * second, and overwrites the workspace.  n_improved (may be NULL) receives the number of shapes
  * that got another kernel; 0 and KV_OK if the library cannot list its kernels, and where the
- * projections do not go to the GEMM library at all (up to 256 tokens, or no rocBLAS): nothing is
+ * projections do not go to the GEMM library at all (few tokens, see above, or no rocBLAS): nothing is
  * then timed.  Results are the same up to the summation order inside a GEMM. */
 int32_t kv_recompute_tune(kv_recompute_t* rc, const kv_shape_t* shape, const kv_layer_dims_t* dims,
                           const kv_layer_weights_t* weights, int32_t n_missing, void* workspace,

@@ -400,6 +400,7 @@ def kv_score_chunks_valid(shape: Shape, q: torch.Tensor, kv: torch.Tensor, n_val
 
 
 KV_SCORE_STATIC_BYTES = 32 << 20
+KV_RECOMPUTE_OWN_GEMM_ROWS = 512
 
 
 def kv_score_chunks_static(shape: Shape, q: torch.Tensor, kv: torch.Tensor, norm_mode: int,

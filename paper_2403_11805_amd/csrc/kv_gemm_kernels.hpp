@@ -30,7 +30,8 @@ typedef float gv16f_t __attribute__((ext_vector_type(16)));
 typedef unsigned int gu4_t __attribute__((ext_vector_type(4)));
 
 constexpr int kGemmKStep = 32;
-constexpr int kGemmXPitch = 32 + 8;          // halves per LDS row of the activation tile (pitch 80 B)
+constexpr int kGemmXPitch = kGemmKStep + 8;  // halves per LDS row of the activation tile
+constexpr int kGemmXRow = kGemmKStep / 8;    // 16-byte pieces per row of the activation tile
 constexpr int kGemmMaxSplits = 16;
 constexpr int kGemmMaxMats = 3;
 
@@ -76,7 +77,7 @@ __global__ __launch_bounds__(256) void gemm_f16_kernel(GemmArgs g) {
     const int kb = blockIdx.y * g.k_slice;
     const int ke = min(g.K, kb + g.k_slice);
     const int n_steps = (ke - kb + kGemmKStep - 1) / kGemmKStep;
-    constexpr int XPIECES = kRows * 4;               // 16-byte pieces of an activation tile (4 per row)
+    constexpr int XPIECES = kRows * kGemmXRow;       // 16-byte pieces of an activation tile
     constexpr int XPER = (XPIECES + 255) / 256;
     constexpr int PF = 3;                            // global loads in flight: this many k-steps ahead
     gu4_t wreg[PF][WPER], xreg[PF][XPER];
@@ -95,8 +96,8 @@ __global__ __launch_bounds__(256) void gemm_f16_kernel(GemmArgs g) {
 #pragma unroll
         for (int p = 0; p < XPER; ++p) {
             const int id = tid + 256 * p;
-            const int row = min(m0 + min(id / 4, kRows - 1), g.M - 1);
-            const int kc = min(kk + (id % 4) * 8, g.K - 8);
+            const int row = min(m0 + min(id / kGemmXRow, kRows - 1), g.M - 1);
+            const int kc = min(kk + (id % kGemmXRow) * 8, g.K - 8);
             xreg[set][p] = *reinterpret_cast<const gu4_t*>(g.A + static_cast<size_t>(row) * g.K + kc);
         }
     };
@@ -112,8 +113,9 @@ __global__ __launch_bounds__(256) void gemm_f16_kernel(GemmArgs g) {
         for (int p = 0; p < XPER; ++p) {
             const int id = tid + 256 * p;
             if (id < XPIECES) {
-                const bool in = kk + (id % 4) * 8 < ke;      // rows beyond M repeat row M - 1 and are never stored
-                *reinterpret_cast<gu4_t*>(&xt[buf][(id / 4) * kGemmXPitch + (id % 4) * 8]) = in ? xreg[set][p] : zero;
+                const bool in = kk + (id % kGemmXRow) * 8 < ke;      // rows beyond M repeat row M - 1 and are never stored
+                *reinterpret_cast<gu4_t*>(&xt[buf][(id / kGemmXRow) * kGemmXPitch + (id % kGemmXRow) * 8]) =
+                    in ? xreg[set][p] : zero;
             }
         }
     };

@@ -51,12 +51,14 @@ struct Plan {
     int splits;          // workgroups that share the key range of one attention row block (1: no split)
 };
 
-// Measured on MI355X against rocBLAS (Llama-2-7B projections, us for q|k|v|o, gate|up, down):
-//   128 rows   own 21 / 34 / 33    library's standard kernels 22 / 38 / 88   (its best after tuning: 22 / 33 / 38)
-//   256 rows   own 27 / 48 / 45    library 27 / 39 / 124
-//   816 rows   own 53 / 121 / 121  library 41 / 72 / 183
-//   4096 rows  own 190 / 504 / 485 (720-760 TFLOP/s)   library 114 / 298 / 266 (1.2-1.4 PFLOP/s)
-constexpr int64_t kHandGemmRows = 256;
+// Measured on MI355X (Llama-2-7B layer; the seven projections in us, the library's after kv_recompute_tune,
+// and the whole layer in ms):
+//   128 rows   own 164   library 266   layer 0.27 against 0.34
+//   256 rows   own 211   library 253   layer 0.32 against 0.35
+//   512 rows   own 349   library 363   layer 0.47 against 0.49
+//   1024 rows  own 640   library 474   layer 0.79 against 0.67
+//   4096 rows  own 2200 (750 TFLOP/s)   library 1420 (1.2-1.4 PFLOP/s)
+constexpr int64_t kHandGemmRows = KV_RECOMPUTE_OWN_GEMM_ROWS;
 
 // Up to three weight matrices [K][N[j]] applied to the same activations in one launch.
 struct GemmGroup {
