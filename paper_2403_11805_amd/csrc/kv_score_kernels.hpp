@@ -633,15 +633,27 @@ __global__ __launch_bounds__(256, 4) void score_head_kernel(const _Float16* __re
         }
     }
     const _Float16* kbase = kv + (static_cast<int64_t>(l) * 2 * g.Hkv + kvh) * g.N * D;
-    // K tiles are double-buffered in registers across the tiles and runs of this wavefront
+    // K tiles are double-buffered in registers across the tiles and runs of this wavefront.  A wavefront
+    // walks a contiguous quarter of the plane: four streams a quarter plane apart
+    const int runs_per_wave = (g.n_runs + 3) / 4;
+    const int run_first = wave * runs_per_wave, run_last = min(run_first + runs_per_wave, g.n_runs);
+    // ... each plane starting at another of its runs, so that the streams of different planes are not all at
+    // the same offset of their planes at the same time
+    const int n_mine = run_last - run_first;
+    const int rot = n_mine > 0 ? static_cast<int>(blockIdx.x % static_cast<uint32_t>(n_mine)) : 0;
+    auto nth_run = [&](int i) __attribute__((always_inline)) {
+        const int k = i + rot;
+        return run_first + (k >= n_mine ? k - n_mine : k);
+    };
     v8h_t knext[KS];
     {
-        const int t_first = min(wave * g.run_len, g.n_tiles - 1);
+        const int t_first = min(nth_run(0) * g.run_len, g.n_tiles - 1);
         const _Float16* kp = kbase + static_cast<int64_t>(t_first * 32 + lrow) * D + half * 8;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) knext[ks] = *reinterpret_cast<const v8h_t*>(kp + ks * 16);
     }
-    for (int run = wave; run < g.n_runs; run += 4) {
+    for (int ri = 0; ri < n_mine; ++ri) {
+        const int run = nth_run(ri);
         const int tile_begin = run * g.run_len;
         const int tile_end = min(tile_begin + g.run_len, g.n_tiles);
         float m_ref = -INFINITY, l_run = 0.0f;
@@ -651,7 +663,7 @@ __global__ __launch_bounds__(256, 4) void score_head_kernel(const _Float16* __re
             for (int ks = 0; ks < KS; ++ks) kreg[ks] = knext[ks];
             {   // the next tile of the run, or the first tile of this wavefront's next run
                 int nt = tile + 1;
-                if (nt >= tile_end) nt = min((run + 4) * g.run_len, g.n_tiles - 1);
+                if (nt >= tile_end) nt = min(nth_run(ri + 1 < n_mine ? ri + 1 : ri) * g.run_len, g.n_tiles - 1);
                 const _Float16* kp = kbase + static_cast<int64_t>(nt * 32 + lrow) * D + half * 8;
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) knext[ks] = *reinterpret_cast<const v8h_t*>(kp + ks * 16);
