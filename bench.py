@@ -43,9 +43,10 @@ def find_workload(name):
 class Path:
     """Device buffers and the per-step call sequence for one context."""
 
-    def __init__(self, wl, dev, host_plan=False, fmt=0):
+    def __init__(self, wl, dev, host_plan=False, fmt=0, ratio=None):
         g = wl.geom
         self.wl, self.g, self.dev = wl, g, dev
+        self.ratio = ratio                  # (num, den): thresholds from a global ratio (Eq. 2-3) instead of fixed fractions
         self.shape = kvs.Shape(g.L, g.Hkv, g.Hq, g.D, g.N, g.T, g.G, fmt)
         self.kv = synth.make_kv(g, wl.seed, dev, wl.outlier_channels, wl.outlier_scale)
         # caches below ~640 MB would be served from the 256 MB Infinity Cache when reused every
@@ -120,6 +121,16 @@ class Path:
         return (cut("bits", torch.uint8), cut("off", torch.int64), cut("src", torch.int64),
                 cut("dst", torch.int32), cut("sb", torch.uint8))
 
+    def _plan_dev(self):
+        """Widths, offsets and gather list on the device: the workload's fixed fractions (Eq. 2 with fixed
+        thresholds) or, with --ratio, the thresholds of Eq. 2-3 for that global ratio."""
+        if self.ratio:
+            kvs.kv_plan_optimise_dev(self.shape, self.density, self.ratio[0], self.ratio[1], kvs.KV_OBJ_BITS_TO_DENSE,
+                                     self.bits_d, self.off_d, self.dst_d)
+        else:
+            kvs.kv_plan_chunks_dev(self.shape, self.density, *FRACTIONS[self.wl.bits_rule], self.bits_d, self.off_d,
+                                   self.dst_d)
+
     def step(self, record_events=True):
         s = self.shape
         k = self.step_no % self.n_sets
@@ -130,8 +141,7 @@ class Path:
             n = self.g.n_chunks
             kvs.kv_score_chunks(s, self.q, self.kv, kvs.KV_NORM_VISIBLE, self.ws, self.chunk_mass,
                                 self.density)
-            kvs.kv_plan_chunks_dev(s, self.density, *FRACTIONS[self.wl.bits_rule], self.bits_d, self.off_d,
-                                   self.dst_d)
+            self._plan_dev()
             kvs.kv_compress_chunks(s, self.kv, self.bits_d, self.off_d, self.packed)
             kvs.kv_swapin_chunks(s, self.packed, self.off_d[:n], self.dst_d, self.bits_d, self.kv_out)
             return
@@ -148,8 +158,7 @@ class Path:
                                 self.density)
             self.ev["score"][1].record()
             self.ev["plan"][0].record()
-            kvs.kv_plan_chunks_dev(s, self.density, *FRACTIONS[self.wl.bits_rule], self.bits_d, self.off_d,
-                                   self.dst_d)
+            self._plan_dev()
             self.ev["plan"][1].record()
             self.ev["compress"][0].record()
             kvs.kv_compress_chunks(s, self.kv, self.bits_d, self.off_d, self.packed)
@@ -962,6 +971,9 @@ def main():
     ap.add_argument("--pipeline", action="store_true",
                     help="instead of the benchmark: a context Load from pinned host memory with the first x chunks "
                          "recomputed meanwhile (Sec. 3.3 pipeline), measured for several x")
+    ap.add_argument("--ratio", default=None, metavar="NUM/DEN",
+                    help="device-planned step: widths by the thresholds of Eq. 2-3 for this global compression ratio "
+                         "(kv_plan_optimise_dev) instead of the workload's fixed fractions")
     ap.add_argument("--own-gemm", action="store_true",
                     help="--recompute: every projection on the library's own GEMM kernel (default: rocBLAS above 512 rows)")
     ap.add_argument("--no-tune", action="store_true",
@@ -1001,7 +1013,11 @@ def main():
     if wl.name == "llama3-8b-32k" and not args.calibrate_copy:
         print(json.dumps(run_stream(wl, args, dev)))
         return
-    path = Path(wl, dev, host_plan=args.host_plan, fmt=(3 if args.format == "f16h" else 0))
+    ratio = None
+    if args.ratio:
+        num, den = (int(v) for v in args.ratio.split("/"))
+        ratio = (num, den)
+    path = Path(wl, dev, host_plan=args.host_plan, fmt=(3 if args.format == "f16h" else 0), ratio=ratio)
     g = wl.geom
 
     if args.calibrate_copy:
@@ -1099,7 +1115,8 @@ def main():
                                       "arithmetic in f32",
         "data": "synthetic",
         "config": {"workload": f"{wl.name}: [L={g.L},K/V,Hkv={g.Hkv},N={g.N},D={g.D}] fp16, "
-                               f"chunk {g.T}, group {g.G}, R={path.R}, widths {wl.bits_rule}"
+                               f"chunk {g.T}, group {g.G}, R={path.R}, widths "
+                               + (f"by Eq. 2-3 for ratio {args.ratio}" if path.ratio and path.device_plan else wl.bits_rule)
                                + (", record parameters in binary16" if path.shape.format == 3 else ""),
                    "cache_bytes": cache_bytes, "packed_bytes": path.packed_bytes,
                    "step": ("score + widths/offsets/gather list (device) + compress + swap-in, one stream, no "
