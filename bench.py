@@ -227,6 +227,7 @@ def run_pipeline(wl, args, dev):
     del packed
     weights = [synth.make_layer_weights(d_model, g.Hq, g.Hkv, g.D, d_ff, wl.seed, dev, layer=l) for l in range(g.L)]
     copy_s, comp_s, re_s = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    loader = kvs.Loader()              # owns the events of the staging slots for every streaming Load below
     staging = torch.empty(args.stream_buffers * (args.stream_slot_mib << 20), dtype=torch.uint8, device=dev)
     out = torch.zeros_like(kv)
     rc = kvs.Recompute()
@@ -246,7 +247,7 @@ def run_pipeline(wl, args, dev):
         for it in range(args.warmup + args.steps):
             torch.cuda.synchronize()
             t0 = time.perf_counter()
-            kvs.kv_swapin_pinned(shape, pinned, src, dst, sb, staging, args.stream_buffers, out, copy_s, comp_s)
+            loader.swapin_stream(shape, pinned, src, dst, sb, staging, args.stream_buffers, out, copy_s, comp_s)
             if x:
                 with torch.cuda.stream(re_s):
                     for l in range(g.L):
@@ -332,7 +333,7 @@ def run_pipeline(wl, args, dev):
         pools[l].copy_(tmp)
     torch.cuda.synchronize()
     del tmp
-    stage2 = [torch.empty(4 * (8 << 20), dtype=torch.uint8, device=dev) for _ in range(2)]
+    stage2 = torch.empty(8 * (8 << 20), dtype=torch.uint8, device=dev)
     rows_lm = []
     for x in [x for x in xs if x <= len(heavy)]:
         pick = np.unique(heavy[np.linspace(0, len(heavy) - 1, x).astype(np.int64)]).astype(np.int32) if x else \
@@ -350,9 +351,8 @@ def run_pipeline(wl, args, dev):
             torch.cuda.synchronize()
             t0 = time.perf_counter()
             for l in range(g.L):
-                if l >= 2:
-                    copy_s.wait_event(layer_done[l - 2])      # the staging area of two layers ago is free
-                kvs.kv_swapin_pinned(shape1, pools[l], src1, dst1, sb1, stage2[l & 1], 4, out[l:l + 1], copy_s, comp_s)
+                # one handle, one staging area: a call waits by itself for the slots its predecessor still uses
+                loader.swapin_stream(shape1, pools[l], src1, dst1, sb1, stage2, 8, out[l:l + 1], copy_s, comp_s)
                 layer_done[l].record(comp_s)
                 if x:
                     re_s.wait_event(layer_done[l])
@@ -373,6 +373,7 @@ def run_pipeline(wl, args, dev):
         assert torch.equal(out[:, :, :, tok].view(torch.int16), ref[:, :, :, tok].view(torch.int16))
         assert bool(torch.isfinite(out[:, :, :, ~tok].float()).all())
     rc.close()
+    loader.close()
     best = min(rows, key=lambda r: r["delay_ms"])
     base = rows[0]["delay_ms"]
     best_il = min(rows_il, key=lambda r: r["delay_ms"])
@@ -394,7 +395,7 @@ def run_pipeline(wl, args, dev):
             "gain": round(1.0 - best_il["delay_ms"] / rows_il[0]["delay_ms"], 4), "rows": rows_il},
         "layer_wise_layer_major_pools": {
             "step": "the same interleaved chunks and layer-by-layer order with the context stored as one pool per "
-                    "layer: kv_swapin_pinned per layer (copy engines), recompute of layer l waits for that layer",
+                    "layer: kv_swapin_stream per layer (copy engines, one loader handle), recompute of layer l waits for that layer",
             "load_only_ms": rows_lm[0]["delay_ms"], "best": best_lm,
             "gain": round(1.0 - best_lm["delay_ms"] / rows_lm[0]["delay_ms"], 4), "rows": rows_lm},
     }
@@ -682,6 +683,7 @@ def run_stream(wl, args, dev):
     path = Path(wl, dev, host_plan=True, fmt=(3 if args.format == "f16h" else 0))     # the host owns the pinned pool: it needs the offsets
     shape = path.shape
     copy_s, comp_s = torch.cuda.Stream(), torch.cuda.Stream()
+    loader = kvs.Loader()
     path.step()                                  # score + compress (+ resident swap-in)
     torch.cuda.synchronize()
     off = kvs.kv_chunk_offsets(shape, path.bits)
@@ -701,7 +703,7 @@ def run_stream(wl, args, dev):
                                torch.cuda.current_stream(), copy_s)
         copy_s.synchronize()
         t1 = time.perf_counter()
-        kvs.kv_swapin_pinned(shape, pinned, src, dst, sb, staging, args.stream_buffers, path.kv_out,
+        loader.swapin_stream(shape, pinned, src, dst, sb, staging, args.stream_buffers, path.kv_out,
                              copy_s, comp_s)
         comp_s.synchronize(); copy_s.synchronize()
         t2 = time.perf_counter()

@@ -405,7 +405,9 @@ int32_t kv_load_chunks(const kv_shape_t* shape, const void* packed, const uint64
  *   ld  a loader handle: it owns the HIP events that order copies and kernels (created
  *   once, by kv_loader_create, on the device that is current then) and remembers which
  *   staging slots a kernel of an earlier call may still be reading, so that calls one
- *   after the other through one loader may share their staging memory and streams.
+ *   after the other through one loader may share their staging memory and streams
+ *   (they walk the slots round robin; a call with another staging_dev, staging_bytes or
+ *   n_buffers than its predecessor first waits, on copy_stream, for all of that call's kernels).
  *   One thread at a time per loader.
  *   packed_pinned pinned host pool; src_off/dst_tok/sel_bits HOST lists [n_sel]
  *   as produced by kv_build_gather (ascending chunks, hence ascending offsets);

@@ -721,6 +721,15 @@ struct kv_loader {
     hipEvent_t consumed[8];
     bool slot_used[8];       // consumed[b] has been recorded: the slot may still be read by that kernel
     int n_events;
+    // the staging layout of the last call and the slot its successor starts with (calls one after the
+    // other walk the slots round robin instead of all queueing for slot 0)
+    const void* staging;
+    uint64_t staging_bytes;
+    int n_buffers, next;
+    // consumed[b] was the seq[b]-th event recorded, all of them on `compute`: an event of that stream
+    // having fired, every one recorded before it has fired too
+    uint64_t seq[8], recorded;
+    const void* compute;
 };
 
 static void loader_release(kv_loader* ld) {
@@ -734,6 +743,13 @@ static void loader_release(kv_loader* ld) {
 static int loader_init(kv_loader* ld, int n) {
     ld->n_events = 0;
     for (int i = 0; i < 8; ++i) ld->slot_used[i] = false;
+    ld->staging = nullptr;
+    ld->staging_bytes = 0;
+    ld->n_buffers = 0;
+    ld->next = 0;
+    ld->recorded = 0;
+    ld->compute = nullptr;
+    for (int i = 0; i < 8; ++i) ld->seq[i] = 0;
     for (; ld->n_events < n; ++ld->n_events) {
         hipError_t e = hipEventCreateWithFlags(&ld->copied[ld->n_events], hipEventDisableTiming);
         if (e == hipSuccess) {
@@ -807,9 +823,53 @@ int32_t kv_swapin_stream(kv_loader_t* ld, const kv_shape_t* shape, const void* p
     hipStream_t ks = static_cast<hipStream_t>(compute_stream);
     const uint8_t* host = static_cast<const uint8_t*>(packed_pinned);
     uint8_t* staging = static_cast<uint8_t*>(staging_dev);
+    if (ld->staging != staging_dev || ld->staging_bytes != staging_bytes || ld->n_buffers != n_buffers ||
+        ld->compute != compute_stream) {
+        // another staging layout than the last call's (its slots do not correspond to the old ones) or another
+        // compute stream (its events say nothing about the old one's): the copies of this call wait for
+        // every kernel that may still read a slot
+        for (int b = 0; b < 8; ++b)
+            if (ld->slot_used[b]) {
+                KV_HIP(hipStreamWaitEvent(cs, ld->consumed[b], 0));
+                ld->slot_used[b] = false;
+            }
+        ld->staging = staging_dev;
+        ld->staging_bytes = staging_bytes;
+        ld->n_buffers = n_buffers;
+        ld->next = 0;
+        ld->compute = compute_stream;
+    }
+    // Every wait on the copy stream costs the copy engine a pause between two copies (measured: 128 copies of
+    // 5.6 MB with a wait before each take 3.5 ms longer than without).  The first n_buffers batches of this
+    // call reuse slots of earlier calls in the order these were used: ONE wait, for the newest of those that
+    // lie ahead, serves them all; later batches reuse slots of this call and wait one by one.
+    uint64_t waited = 0;
+    {
+        // batches of this call: consecutive records while they fit a slot, at most kBatchMax each (as below)
+        int n_batches = 0;
+        for (int32_t k = 0; k < n_sel && n_batches < n_buffers; ++n_batches) {
+            uint64_t used = 0;
+            int n = 0;
+            while (k < n_sel && n < kBatchMax && used + record_bytes(*shape, sel_bits[k]) <= slot) {
+                used += record_bytes(*shape, sel_bits[k]);
+                ++n;
+                ++k;
+            }
+        }
+        int newest = -1;
+        for (int k = 0; k < n_batches; ++k) {
+            const int b = (ld->next + k) % n_buffers;
+            if (ld->slot_used[b] && (newest < 0 || ld->seq[b] > ld->seq[newest])) newest = b;
+        }
+        if (newest >= 0) {
+            KV_HIP(hipStreamWaitEvent(cs, ld->consumed[newest], 0));
+            waited = ld->seq[newest];
+        }
+    }
     int32_t j = 0;
-    for (int batch = 0; j < n_sel; ++batch) {
-        const int b = batch % n_buffers;
+    while (j < n_sel) {
+        const int b = ld->next;
+        ld->next = (ld->next + 1) % n_buffers;
         uint8_t* slot_dev = staging + static_cast<uint64_t>(b) * slot;
         // records of one batch: as many consecutive list entries as fit the slot
         SwapinBatch list;
@@ -817,7 +877,10 @@ int32_t kv_swapin_stream(kv_loader_t* ld, const kv_shape_t* shape, const void* p
         uint64_t used = 0;
         // the slot is free once the kernel that last read it has finished (an earlier batch of this
         // call, or of an earlier call through this loader)
-        if (ld->slot_used[b]) KV_HIP(hipStreamWaitEvent(cs, ld->consumed[b], 0));
+        if (ld->slot_used[b] && ld->seq[b] > waited) {
+            KV_HIP(hipStreamWaitEvent(cs, ld->consumed[b], 0));
+            waited = ld->seq[b];
+        }
         while (j < n_sel && list.n < kBatchMax) {
             const uint64_t bytes = record_bytes(*shape, sel_bits[j]);
             if (used + bytes > slot) break;
@@ -847,6 +910,7 @@ int32_t kv_swapin_stream(kv_loader_t* ld, const kv_shape_t* shape, const void* p
         if (int rc = launch_swapin_batch(*shape, g, ppl, slot_dev, list, static_cast<u4_t*>(kv_out), ks)) return rc;
         KV_HIP(hipEventRecord(ld->consumed[b], ks));
         ld->slot_used[b] = true;
+        ld->seq[b] = ++ld->recorded;
     }
     return KV_OK;
 }

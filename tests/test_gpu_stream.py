@@ -143,4 +143,16 @@ def test_loader_handle_serves_loads_one_after_the_other():
             assert np.array_equal(out.cpu().numpy().view(np.uint16), ref)
             out.view(torch.int16).fill_(0x7bff)
         torch.cuda.synchronize()
+    # the same loader with another staging layout right behind a call with the first one (two slots in the
+    # upper part of the same memory, which overlap the old slots 1 and 2): the second call must wait for
+    # every kernel of the first
+    pinned, (src, dst, sb), out, ref = jobs[0]
+    pinned2, (src2, dst2, sb2), out2, ref2 = jobs[1]
+    rec = kvs.kv_record_bytes(ks, 16)
+    loader.swapin_stream(ks, pinned, src, dst, sb, staging, 3, out, copy_s, comp_s)
+    loader.swapin_stream(ks, pinned2, src2, dst2, sb2, staging[rec // 2 // 256 * 256:], 2, out2, copy_s, comp_s)
+    comp_s.synchronize()
+    copy_s.synchronize()
+    assert np.array_equal(out.cpu().numpy().view(np.uint16), ref)
+    assert np.array_equal(out2.cpu().numpy().view(np.uint16), ref2)
     loader.close()
