@@ -131,11 +131,14 @@ dim3 task_grid(const QuantGeom& g, int n_units) {
 // into g.groups, and the one-dimensional grid.  0 if the grid does not fit.
 // Measured: workgroups of 16 wavefronts are best where the launch writes gigabytes (llama2-7b-4k: 0.485
 // against 0.495 ms with 4); below about a gigabyte ramp and tail weigh more and 8 do better (51 of 128
-// chunks of a 2048-token cache: 0.122 against 0.131 ms; gemma2b-4k: 0.022 against 0.024 ms).
+// chunks of a 2048-token cache: 0.122 against 0.131 ms; gemma2b-4k: 0.022 against 0.024 ms); where a unit
+// has fewer than 256 pieces, so that a wavefront moves 1 or 2 KiB instead of 4, 4 do better (chunks of 4
+// and 8 tokens at head_dim 128: 0.69 and 0.51 ms against 0.80 and 0.55 ms with 16).
 uint32_t load_grid(QuantGeom* g, int n_units, int wpb_max, int* wpb) {
     const int64_t tasks = static_cast<int64_t>(n_units) * g->tpu;          // per slab
     const int64_t out_bytes = static_cast<int64_t>(n_units) * g->pieces * 16 * g->slab_count;
     if (out_bytes < (1LL << 30)) wpb_max = std::min(wpb_max, 8);
+    if (g->pieces < 256) wpb_max = std::min(wpb_max, 4);
     *wpb = static_cast<int>(std::min<int64_t>(wpb_max, tasks));
     g->groups = static_cast<int32_t>((tasks + *wpb - 1) / *wpb);
     const int64_t total = static_cast<int64_t>(g->groups) * g->slab_count;
