@@ -129,15 +129,26 @@ dim3 task_grid(const QuantGeom& g, int n_units) {
 // Launch shape of a Load kernel of the fp16 formats over n_units listed records (g.tpu and g.slab_count
 // set): wavefronts per workgroup (at most wpb_max, no more than a slab has tasks), workgroups per slab
 // into g.groups, and the one-dimensional grid.  0 if the grid does not fit.
-// Measured: workgroups of 16 wavefronts are best where the launch writes gigabytes (llama2-7b-4k: 0.485
-// against 0.495 ms with 4); below about a gigabyte ramp and tail weigh more and 8 do better (51 of 128
-// chunks of a 2048-token cache: 0.122 against 0.131 ms; gemma2b-4k: 0.022 against 0.024 ms); where a unit
-// has fewer than 256 pieces, so that a wavefront moves 1 or 2 KiB instead of 4, 4 do better (chunks of 4
-// and 8 tokens at head_dim 128: 0.69 and 0.51 ms against 0.80 and 0.55 ms with 16).
-uint32_t load_grid(QuantGeom* g, int n_units, int wpb_max, int* wpb) {
+// A Load runs fastest with 24 wavefronts on a CU, not the 32 that fit: its stores are 2.7 times its reads,
+// and a store stream is served best with few bytes in flight per CU (stores alone: 7.5 TB/s with 32 KB in
+// flight per CU, 5.9 TB/s with 128 KB), while the record reads want many.  Measured over the 2 GiB cache:
+// 20 wavefronts per CU 0.521 ms, 24: 0.473, 28: 0.482, 32: 0.487-0.494 (workgroups of 16, 8 or 4 wavefronts
+// alike); the pool's switch (0.58 GB) 0.1069 against 0.1091 ms, gemma2b-4k (0.1 GB) 0.0210 against 0.0212.
+// The cap is set by asking for LDS that the kernel does not use (*idle_lds bytes per workgroup of 4
+// wavefronts: six such workgroups fit the 160 KB of a CU).  Launches under 32 MiB (a Fault) keep
+// workgroups of up to 8 wavefronts and no cap; where a unit has fewer than 256 pieces, so that a wavefront
+// moves 1 or 2 KiB instead of 4, workgroups of 4 without a cap do best (chunks of 4 and 8 tokens at
+// head_dim 128: 0.69 and 0.51 ms against 0.80 and 0.55 ms with 16).
+constexpr uint32_t kIdleLdsBytes = 26 * 1024;
+uint32_t load_grid(QuantGeom* g, int n_units, int wpb_max, int* wpb, uint32_t* idle_lds) {
     const int64_t tasks = static_cast<int64_t>(n_units) * g->tpu;          // per slab
     const int64_t out_bytes = static_cast<int64_t>(n_units) * g->pieces * 16 * g->slab_count;
-    if (out_bytes < (1LL << 30)) wpb_max = std::min(wpb_max, 8);
+    *idle_lds = 0;
+    if (out_bytes < (32LL << 20)) wpb_max = std::min(wpb_max, 8);
+    else if (wpb_max == kLoadWavesMax && g->pieces >= 256) {
+        wpb_max = 4;
+        *idle_lds = kIdleLdsBytes;
+    }
     if (g->pieces < 256) wpb_max = std::min(wpb_max, 4);
     *wpb = static_cast<int>(std::min<int64_t>(wpb_max, tasks));
     g->groups = static_cast<int32_t>((tasks + *wpb - 1) / *wpb);
@@ -158,7 +169,8 @@ int launch_swapin_batch(const kv_shape_t& shape, const QuantGeom& g_in, int ppl,
     QuantGeom g = g_in;
     if (is_i8(shape)) {
         int wpb = 0;
-        const uint32_t wgs = load_grid(&g, list.n, kWavesPerBlock, &wpb);
+        uint32_t idle_lds = 0;
+        const uint32_t wgs = load_grid(&g, list.n, kWavesPerBlock, &wpb, &idle_lds);
         if (!wgs) return fail(KV_ESHAPE, "Load grid exceeds 2^31 workgroups");
         const dim3 grid(wgs), block(static_cast<uint32_t>(wpb) * 64);
         const I8View v = i8_view(shape);
@@ -172,13 +184,14 @@ int launch_swapin_batch(const kv_shape_t& shape, const QuantGeom& g_in, int ppl,
     } else {
         const bool hp = shape.format == KV_FMT_F16_GROUPS_H;
         int wpb = 0;
-        const uint32_t wgs = load_grid(&g, list.n, kLoadWavesMax, &wpb);
+        uint32_t idle_lds = 0;
+        const uint32_t wgs = load_grid(&g, list.n, kLoadWavesMax, &wpb, &idle_lds);
         if (!wgs) return fail(KV_ESHAPE, "Load grid exceeds 2^31 workgroups");
         const dim3 grid(wgs), block(static_cast<uint32_t>(wpb) * 64);
 #define KV_LAUNCH_F16(PPL)                                                                                        \
         do {                                                                                                      \
-            if (hp) hipLaunchKernelGGL((swapin_batch_kernel<PPL, true>), grid, block, 0, st, base, list, dst, g); \
-            else hipLaunchKernelGGL((swapin_batch_kernel<PPL, false>), grid, block, 0, st, base, list, dst, g);   \
+            if (hp) hipLaunchKernelGGL((swapin_batch_kernel<PPL, true>), grid, block, idle_lds, st, base, list, dst, g); \
+            else hipLaunchKernelGGL((swapin_batch_kernel<PPL, false>), grid, block, idle_lds, st, base, list, dst, g);   \
         } while (0)
         if (ppl == 4) KV_LAUNCH_F16(4);
         else if (ppl == 2) KV_LAUNCH_F16(2);
@@ -295,7 +308,8 @@ static int32_t swapin_launch(const kv_shape_t* shape, const void* packed, const 
     if (kind == 0) return fail(KV_EINVAL, "packed is neither device memory nor pinned host memory");
     // strip order; the int8 kernels keep a slab in LDS per wavefront and stay at four wavefronts per workgroup
     int wpb = 0;
-    const dim3 grid(load_grid(&g, n_sel, i8 ? kWavesPerBlock : (kind == 2 ? kLinkWaves : kLoadWavesMax), &wpb));
+    uint32_t idle_lds = 0;
+    const dim3 grid(load_grid(&g, n_sel, i8 ? kWavesPerBlock : (kind == 2 ? kLinkWaves : kLoadWavesMax), &wpb, &idle_lds));
     if (!grid.x) return fail(KV_ESHAPE, "Load grid exceeds 2^31 workgroups");
     const dim3 block(static_cast<uint32_t>(wpb) * 64);
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -348,8 +362,8 @@ static int32_t swapin_launch(const kv_shape_t* shape, const void* packed, const 
     const bool hp = shape->format == KV_FMT_F16_GROUPS_H;
 #define KV_LAUNCH_F16(PPL)                                                                                     \
     do {                                                                                                       \
-        if (hp) hipLaunchKernelGGL((swapin_kernel<PPL, true>), grid, block, 0, st, src, src_off_dev, dst_tok_dev, sel_bits_dev, dst, g, n_sel); \
-        else hipLaunchKernelGGL((swapin_kernel<PPL, false>), grid, block, 0, st, src, src_off_dev, dst_tok_dev, sel_bits_dev, dst, g, n_sel);   \
+        if (hp) hipLaunchKernelGGL((swapin_kernel<PPL, true>), grid, block, idle_lds, st, src, src_off_dev, dst_tok_dev, sel_bits_dev, dst, g, n_sel); \
+        else hipLaunchKernelGGL((swapin_kernel<PPL, false>), grid, block, idle_lds, st, src, src_off_dev, dst_tok_dev, sel_bits_dev, dst, g, n_sel);   \
     } while (0)
     if (ppl == 4) KV_LAUNCH_F16(4);
     else if (ppl == 2) KV_LAUNCH_F16(2);

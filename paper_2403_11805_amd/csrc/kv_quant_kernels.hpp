@@ -88,7 +88,7 @@ __device__ __forceinline__ bool wave_task_at(const QuantGeom& g, int n_chunks, i
 // workgroups write consecutive 8 KiB blocks of one plane (each XCD then sees every eighth block) -
 // and the whole kernel 0.485 against 0.517 ms.
 constexpr int kStripSlabs = 8;
-constexpr int kLoadWavesMax = 16;     // wavefronts per workgroup of the Load kernels at most
+constexpr int kLoadWavesMax = 8;      // wavefronts per workgroup of the Load kernels at most
 
 __device__ __forceinline__ bool strip_task_at(const QuantGeom& g, int n_units, int ppl, uint32_t id, int wpb,
                                               int& unit, int& slab, int& piece0) {
