@@ -148,6 +148,22 @@ def test_gemma_shaped_workload_full():
     assert len(got) == 25952256
 
 
+@pytest.mark.parametrize("geom,select_every", [
+    ((3, 3, 3, 128, 8192, 16, 64), 1),    # 36 MiB, 18 planes: two strips of eight and a ragged one
+    ((5, 1, 1, 64, 32768, 8, 64), 1),     # 40 MiB, 10 planes of small units (64 pieces): wavefronts of 1 KiB
+    ((3, 3, 3, 128, 16384, 16, 64), 3),   # a third of the chunks of a 72 MiB cache: a launch just under 32 MiB
+])
+def test_launch_shapes_of_the_load_kernels(geom, select_every):
+    """Caches around the size at which the Load kernels change their launch shape (workgroups of 4
+    wavefronts with six to a CU from 32 MiB written, up to 8 wavefronts below, 4 for small units), with
+    plane counts that are no multiple of the eight planes a strip holds: records and swapped-in cache
+    bit-exact."""
+    g = synth.Geometry(*geom)
+    kv = synth.make_kv(g, 91, "cpu", 1, 10.0).numpy()
+    bits = synth.draw_bits_uniform(g.n_chunks, 91, widths=(16, 8, 4, 2)).numpy()
+    check_full(g, kv, bits, select=list(range(0, g.n_chunks, select_every)))
+
+
 def test_empty_selection_and_all_passthrough():
     g = synth.Geometry(1, 2, 2, 64, 64, 16, 64)
     ks, os_ = both_shapes(g)
