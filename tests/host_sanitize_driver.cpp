@@ -4,6 +4,7 @@
 #include <cstdint>
 #include <cstdio>
 #include <cstdlib>
+#include <cmath>
 #include <vector>
 
 #include "kvswitch.h"
@@ -86,6 +87,40 @@ int main() {
     EXPECT(re[0] >= 0 && re[0] <= 85 && re[1] >= 0 && re[2] >= 0);
     const uint64_t rec_bad[3] = {10, 20, 30};
     EXPECT(kv_plan_pipeline(&m, missing, rec_bad, re, &delay) == KV_EINVAL);
+    // the split of a plan: counts per width add up, lists ascending, a plan that asks for too much is refused
+    {
+        EXPECT(kv_bits_from_scores(dens.data(), n, 1, 1, 3, bits.data()) == KV_OK);
+        std::vector<int32_t> miss;
+        for (int i = 1; i < n; i += 2) miss.push_back(i);
+        int32_t have[3] = {0, 0, 0};
+        for (int32_t i : miss) ++have[bits[i] == 8 ? 0 : bits[i] == 4 ? 1 : 2];
+        const int32_t want[3] = {have[0] / 2, have[1], 0};
+        std::vector<int32_t> ri(miss.size()), li(miss.size());
+        int32_t nr = -1, nl = -1;
+        EXPECT(kv_pipeline_split(&s, bits.data(), miss.data(), static_cast<int32_t>(miss.size()), want, ri.data(), &nr,
+                                 li.data(), &nl) == KV_OK);
+        EXPECT(nr == want[0] + want[1] && nr + nl == static_cast<int32_t>(miss.size()));
+        for (int32_t k = 1; k < nr; ++k) EXPECT(ri[k] > ri[k - 1]);
+        for (int32_t k = 1; k < nl; ++k) EXPECT(li[k] > li[k - 1]);
+        const int32_t too_many[3] = {have[0] + 1, 0, 0};
+        EXPECT(kv_pipeline_split(&s, bits.data(), miss.data(), static_cast<int32_t>(miss.size()), too_many, ri.data(), &nr,
+                                 li.data(), &nl) == KV_EINVAL);
+        miss[1] = miss[0];
+        EXPECT(kv_pipeline_split(&s, bits.data(), miss.data(), static_cast<int32_t>(miss.size()), want, ri.data(), &nr,
+                                 li.data(), &nl) == KV_EINDEX);
+        EXPECT(kv_pipeline_split(&s, bits.data(), miss.data(), 0, too_many, ri.data(), &nr, li.data(), &nl) == KV_EINVAL ||
+               (nr == 0 && nl == 0));
+    }
+    // densities that are not finite are refused before any sort sees them
+    {
+        std::vector<float> d2(dens);
+        d2[3] = std::nanf("");
+        EXPECT(kv_bits_from_scores(d2.data(), n, 1, 1, 3, bits.data()) == KV_EINVAL);
+        EXPECT(kv_bits_optimise(d2.data(), n, 1, 2, KV_OBJ_BITS_TO_DENSE, bits.data(), counts) == KV_EINVAL);
+        EXPECT(kv_bits_from_scores(dens.data(), n, 1, 1, 3, bits.data()) == KV_OK);
+        EXPECT(kv_bits_optimise(dens.data(), n, 99, 100, KV_OBJ_BITS_TO_DENSE, bits.data(), counts) == KV_OK);
+        EXPECT(counts[0] >= 0 && counts[1] >= 0 && counts[2] >= 0 && counts[0] + counts[1] + counts[2] == n);
+    }
 
     // LCTRU: a long random sequence; sizes stay consistent, locked contexts are never evicted
     kv_lctru_t* q = kv_lctru_create();
