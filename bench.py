@@ -1033,14 +1033,23 @@ def main():
         print(json.dumps({"calibrate_copy": args.calibrate_copy, "bytes_read": g.elements * 2,
                           "bytes_written": g.elements * 2}))
         return
+    # Untimed: the shader clock of an idle GPU needs some tens of milliseconds of load to come up, and the
+    # compress kernel, whose VALU work is close to its memory time, is some 25 % slower until it has (its
+    # time over the steps of a cold start: 0.57, 0.55, 0.55, ... 0.43 ms from the twentieth step on).  So
+    # steps are run for 100 ms before the W warm-up steps, which are enqueued back to back like the timed ones.
+    n_ramp, t_ramp = 0, time.perf_counter()
+    while (time.perf_counter() - t_ramp) < 0.1:
+        for _ in range(8):
+            path.step()
+        torch.cuda.synchronize()
+        n_ramp += 8
+    path.reserve_event_sets(args.steps)
     for _ in range(args.warmup):
         path.step()
-        torch.cuda.synchronize()
+    clocks = clock_state()          # read while the warm-up steps are running: the clock under this load
     # the K timed steps are enqueued back to back (the host-plan route synchronises inside each
     # step to read the densities); the per-kernel events are read after the timed region
-    path.reserve_event_sets(args.steps)
     torch.cuda.synchronize()
-    clocks = clock_state()          # right behind the warm-up steps, before the timed region
     first = path.step_no
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -1133,6 +1142,7 @@ def main():
     if plan_ms is not None:
         out["plan_ms"] = round(float(np.mean(plan_ms)), 4)
     out["clocks_before_timed_region"] = clocks
+    out["untimed_ramp_steps"] = n_ramp
     if args.graph and path.device_plan:
         out["hip_graph"] = {"ms_per_step": round(graph_ms_per_step(path, args), 4),
                             "note": "the same step captured once per buffer set and replayed; no events inside"}

@@ -183,25 +183,31 @@ __device__ __forceinline__ void group_min_max(const u4_t& raw, int lpg_log2, flo
 
 // Quantise the 8 elements of one piece to BITS-bit codes (exact small floats
 // in r[]).  The contract is code = rint((x - mn) / scale) with a true binary32
-// division.  The fast path multiplies by an approximate reciprocal (1 ulp); its
-// result q' differs from the correctly rounded quotient by less than
-// 4.1 * 2^-24 * q, so rint(q') can only differ from the defined code when q'
-// lies within that distance of a half-integer.  A lane that sees |q' - rint(q')|
-// >= 0.5 - 2^BITS * 2^-20 redoes its piece with the exact division, which keeps
-// every code bit-identical to the definition.
+// division.  The fast path takes q' = fma(x, inv, c) with inv = rcp(scale) (1 ulp)
+// and c = -mn * inv rounded once; the fp16 element enters the FMA as it is
+// (v_fma_mix_f32), so an element costs one instruction where conversion,
+// subtraction and product cost three.  With q the exact quotient,
+//   |q' - q| <= q * (2^-23 + 2^-24) + |c| * 2^-24 * (1 + 2^-22)
+// (the reciprocal's ulp, the rounding of the sum, the rounding of c), so rint(q')
+// can only differ from the defined code when q' lies within that distance of a
+// half-integer.  A lane that sees |q' - rint(q')| >= 0.5 - (2^BITS * 2^-22 +
+// |c| * 2^-23) redoes its piece with the exact division, which keeps every code
+// bit-identical to the definition (a group far from zero against its range, e.g.
+// values 1000..1001, has a large |c| and takes the exact path more often).
 // CLAMP: the scale may fall short of range / levels (a scale rounded to binary16), so the quotient can
 // pass the top level and is cut there; with an exact scale it cannot, and 8-bit codes saturate when
 // they are packed.
 template <int BITS, bool CLAMP>
 __device__ __forceinline__ void quantise_piece(const h8_t& x, float mn, float scale, float r[8]) {
     constexpr float kLevels = static_cast<float>((1 << BITS) - 1);
-    constexpr float kSafe = 0.5f - static_cast<float>(1 << BITS) * 9.5367431640625e-07f;
     const float inv = (scale != 0.0f) ? __builtin_amdgcn_rcpf(scale) : 0.0f;
+    const float c = -mn * inv;
+    const float safe = 0.5f - __builtin_fmaf(__builtin_fabsf(c), 1.1920928955078125e-07f,
+                                             static_cast<float>(1 << BITS) * 2.384185791015625e-07f);
     float e[8];
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
-        const float d = static_cast<float>(x[k]) - mn;
-        const float q = d * inv;
+        const float q = __builtin_fmaf(static_cast<float>(x[k]), inv, c);
         r[k] = __builtin_rintf(q);
         e[k] = __builtin_fabsf(q - r[k]);
         if constexpr (CLAMP) r[k] = __builtin_fminf(r[k], kLevels);
@@ -209,13 +215,13 @@ __device__ __forceinline__ void quantise_piece(const h8_t& x, float mn, float sc
     const float e01 = __builtin_fmaxf(__builtin_fmaxf(e[0], e[1]), e[2]);
     const float e02 = __builtin_fmaxf(__builtin_fmaxf(e[3], e[4]), e[5]);
     const float emax = __builtin_fmaxf(__builtin_fmaxf(e01, e02), __builtin_fmaxf(e[6], e[7]));
-    if (emax >= kSafe) {
+    if (!(emax < safe)) {
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
             const float d = static_cast<float>(x[k]) - mn;
-            float c = __builtin_rintf(d / scale);
-            c = __builtin_fminf(__builtin_fmaxf(c, 0.0f), kLevels);
-            r[k] = c;
+            float c2 = __builtin_rintf(d / scale);
+            c2 = __builtin_fminf(__builtin_fmaxf(c2, 0.0f), kLevels);
+            r[k] = c2;
         }
     }
 }
