@@ -125,6 +125,29 @@ def test_ranges_of_a_few_binary16_subnormal_steps(b, fmt):
 
 
 @pytest.mark.parametrize("fmt", [0, 3])
+@pytest.mark.parametrize("b", [8, 4, 2])
+def test_groups_far_from_zero(b, fmt):
+    """Groups whose minimum is thousands of steps away from zero (a range of 1 to 600 units in the last
+    place at magnitudes from 1 to 32768, both signs): the quotient (x - min) / scale is then a small
+    difference of large terms, the case in which a quantiser that folds the minimum into one
+    multiply-add has the least margin, and every value sits on a grid on which exact ties are common."""
+    g = synth.Geometry(1, 2, 2, 128, 64, 16, 64)
+    rng = np.random.default_rng(170 + b)
+    x = np.zeros((g.L, 2, g.Hkv, g.N, g.D), dtype=np.float64)
+    for t in range(g.N):
+        e = t % 16                                                   # binade 2^e .. 2^(e+1)
+        base = (1.0 + rng.integers(0, 1024) / 1024.0) * 2.0 ** e
+        ulp = 2.0 ** (e - 10)
+        width = int(rng.integers(1, 601))
+        j = rng.integers(0, width + 1, size=(g.L, 2, g.Hkv, g.D))
+        j[..., 0::64] = 0
+        j[..., 1::64] = width
+        row = base + j * ulp
+        x[..., t, :] = np.minimum(row, 65504.0) * (-1.0 if t % 2 else 1.0)
+    check_full(g, x.astype(np.float16), np.full(g.n_chunks, b, dtype=np.uint8), fmt=fmt)
+
+
+@pytest.mark.parametrize("fmt", [0, 3])
 @pytest.mark.parametrize("scale", [1.0, 1e-3, 300.0])
 def test_random_magnitudes_all_groups(scale, fmt):
     """Many random groups per width, including ones whose quotients land within a few
