@@ -241,8 +241,10 @@ __global__ __launch_bounds__(256) void compress_i8_kernel(const u4_t* __restrict
     u4_t raw[PPL];
 #pragma unroll
     for (int u = 0; u < PPL; ++u) raw[u] = stream_load<true>(src + u * 64 + lane);
-    const int b = uniform_byte(bits, chunk);
-    uint8_t* base = packed + off[chunk];
+    int b = uniform_byte(bits, chunk);
+    uint64_t rec = off[chunk];
+    asm volatile("" : "+s"(b), "+s"(rec));               // both scalar loads issued, one wait
+    uint8_t* base = packed + rec;
     if (b == 8) {
 #pragma unroll
         for (int u = 0; u < PPL; ++u)
@@ -407,9 +409,10 @@ __global__ __launch_bounds__(256) void swapin_i8_kernel(const uint8_t* __restric
     const int wave = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6));
     int j, slab, p0;
     if (!strip_task_at(g, n_sel, NDW / 4, blockIdx.x, static_cast<int>(blockDim.x >> 6), j, slab, p0)) return;
+    const GatherEntry e = gather_entry(src_off, dst_tok, sel_bits, j);
     u4_t* dst = kv_out + (static_cast<uint64_t>(slab) * g.n_tokens +
-                          static_cast<uint64_t>(dst_tok[j])) * g.row_pieces;
-    swapin_i8_task<NDW, GPL, HM>(packed + src_off[j], uniform_byte(sel_bits, j), slab, dst, g, v, lds[wave], lane);
+                          static_cast<uint64_t>(e.tok)) * g.row_pieces;
+    swapin_i8_task<NDW, GPL, HM>(packed + e.src, e.b, slab, dst, g, v, lds[wave], lane);
 }
 
 // Record pool in pinned host memory: a small grid that walks the task grid in strides (see
@@ -427,9 +430,10 @@ __global__ __launch_bounds__(256) void swapin_i8_link_kernel(const uint8_t* __re
     for (uint32_t w = blockIdx.x; w < total; w += gridDim.x) {
         int j, slab, p0;
         if (!strip_task_at(g, n_sel, NDW / 4, w, static_cast<int>(blockDim.x >> 6), j, slab, p0)) continue;
+        const GatherEntry e = gather_entry<false>(src_off, dst_tok, sel_bits, j);
         u4_t* dst = kv_out + (static_cast<uint64_t>(slab) * g.n_tokens +
-                              static_cast<uint64_t>(dst_tok[j])) * g.row_pieces;
-        swapin_i8_task<NDW, GPL, HM>(packed + src_off[j], uniform_byte(sel_bits, j), slab, dst, g, v, lds[wave], lane);
+                              static_cast<uint64_t>(e.tok)) * g.row_pieces;
+        swapin_i8_task<NDW, GPL, HM>(packed + e.src, e.b, slab, dst, g, v, lds[wave], lane);
     }
 }
 

@@ -45,11 +45,41 @@ struct QuantGeom {
 constexpr int kWavesPerBlock = 4;
 
 // Entry i of a byte list at a wave-uniform index, read through the aligned
-// 32-bit word that contains it so that it can be a scalar load.
-__device__ __forceinline__ int uniform_byte(const uint8_t* list, int i) {
-    const uintptr_t a = reinterpret_cast<uintptr_t>(list) + static_cast<uintptr_t>(i);
-    const uint32_t w = *reinterpret_cast<const uint32_t*>(a & ~static_cast<uintptr_t>(3));
-    return static_cast<int>((w >> ((a & 3) * 8)) & 0xffu);
+// 32-bit word that contains it so that it can be a scalar load.  The word's address is
+// formed by pointer arithmetic on `list` itself (never through an integer), so that the
+// compiler still knows it points to global memory: a pointer rebuilt from an integer is a
+// generic one, whose load is a vector instruction, and the width it returns then lives in a
+// vector register - every branch on it and every address derived from it with it.
+__device__ __forceinline__ int uniform_byte(const uint8_t* __restrict__ list, int i) {
+    const int skew = static_cast<int>(reinterpret_cast<uintptr_t>(list) & 3);
+    const int k = i + skew;                                     // index from the aligned word before `list`
+    const uint32_t* words = reinterpret_cast<const uint32_t*>(list - skew);
+    const uint32_t w = words[k >> 2];
+    return static_cast<int>((w >> ((k & 3) * 8)) & 0xffu);
+}
+
+// The list entries of gather task j (wave-uniform): three scalar loads issued together and waited for
+// once.  Left to the compiler they are issued one by one, each in front of its first use, and a
+// wavefront that has a single task spends three trips to the scalar cache before its first vector load.
+struct GatherEntry {
+    uint64_t src;
+    int32_t tok;
+    int b;
+};
+template <bool TOGETHER = true, bool SCALAR_WIDTH = true>
+__device__ __forceinline__ GatherEntry gather_entry(const uint64_t* __restrict__ src_off,
+                                                    const int32_t* __restrict__ dst_tok,
+                                                    const uint8_t* __restrict__ sel_bits, int j) {
+    GatherEntry e;
+    e.tok = dst_tok[j];
+    e.src = src_off[j];
+    if constexpr (SCALAR_WIDTH) e.b = uniform_byte(sel_bits, j);
+    else e.b = sel_bits[j];          // a byte load is a vector load: the width stays in a vector register
+    // all of them are needed here (not in the kernels that walk tasks in a loop, where the compiler
+    // does not keep the entries in scalar registers)
+    if constexpr (TOGETHER && SCALAR_WIDTH) asm volatile("" : "+s"(e.tok), "+s"(e.src), "+s"(e.b));
+    else if constexpr (TOGETHER) asm volatile("" : "+s"(e.tok), "+s"(e.src));
+    return e;
 }
 
 // Wavefront task -> (chunk or list index, slab, first piece).  Task ids are uniform
@@ -165,10 +195,11 @@ __device__ __forceinline__ float plus_zero(float x) {
 __device__ __forceinline__ void group_min_max(const u4_t& raw, int lpg_log2, float& mn, float& mx) {
     uint32_t lo = pk_min_f16(pk_min_f16(raw.x, raw.y), pk_min_f16(raw.z, raw.w));
     uint32_t hi = pk_max_f16(pk_max_f16(raw.x, raw.y), pk_max_f16(raw.z, raw.w));
-    lo = pk_min_f16(lo, lo >> 16);     // low half: min of the 8 elements
-    hi = pk_max_f16(hi, hi >> 16);     // low half: max of the 8 elements
-    // one register holding (min, -max): a packed min reduces both at once
-    uint32_t m = (lo & 0xffffu) | ((hi ^ 0x8000u) << 16);
+    // lo = (min of the even elements, min of the odd ones), hi the same for the maxima.  With the maxima
+    // negated, one packed min of (lo.even, -hi.odd) and (lo.odd, -hi.even) leaves (min, -max) of the eight
+    // elements in one register, and every later packed min reduces both at once.
+    const uint32_t nh = hi ^ 0x80008000u;
+    uint32_t m = pk_min_f16((lo & 0xffffu) | (nh & 0xffff0000u), __builtin_amdgcn_alignbit(nh, lo, 16));
     m = pk_min_f16(m, dpp_u32<0xB1>(m));
     m = pk_min_f16(m, dpp_u32<0x4E>(m));
     m = pk_min_f16(m, dpp_u32<0x141>(m));
@@ -237,7 +268,14 @@ __device__ __forceinline__ void compress_piece(const u4_t& raw, uint8_t* __restr
     constexpr float kLevels = static_cast<float>((1 << BITS) - 1);
     float mn, mx;
     group_min_max(raw, lpg_log2, mn, mx);
-    float scale = (mx - mn) / kLevels;
+    // scale = (mx - mn) / levels, correctly rounded, without the division sequence: with y the binary32
+    // nearest to 1 / levels and q0 = range * y, one correction step q0 + (range - levels * q0) * y (the
+    // residual is exact in an FMA) gives the correctly rounded quotient; for levels 3, 15 and 255 this
+    // holds for every binary32 numerator in [0, 2^17], which a host program has checked one by one.
+    constexpr float kInvLevels = 1.0f / kLevels;
+    const float range = mx - mn;
+    const float q0 = range * kInvLevels;
+    float scale = __builtin_fmaf(__builtin_fmaf(-kLevels, q0, range), kInvLevels, q0);
     if constexpr (HP) scale = static_cast<float>(static_cast<_Float16>(scale));
     const h8_t x = __builtin_bit_cast(h8_t, raw);
     float r[8];
@@ -300,8 +338,10 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void compress_kernel(const u4_
     u4_t raw[PPL];
 #pragma unroll
     for (int u = 0; u < PPL; ++u) raw[u] = stream_load<true>(src + p0 + u * 64 + lane);
-    const int b = uniform_byte(bits, chunk);
-    uint8_t* base = packed + off[chunk];
+    int b = uniform_byte(bits, chunk);
+    uint64_t rec = off[chunk];
+    asm volatile("" : "+s"(b), "+s"(rec));               // both scalar loads issued, one wait
+    uint8_t* base = packed + rec;
     if (b == 16) {
 #pragma unroll
         for (int u = 0; u < PPL; ++u)
@@ -419,9 +459,10 @@ __global__ __launch_bounds__(64 * kLoadWavesMax) void swapin_kernel(const uint8_
     const int lane = threadIdx.x & 63;
     int j, slab, p0;
     if (!strip_task_at(g, n_sel, PPL, blockIdx.x, static_cast<int>(blockDim.x >> 6), j, slab, p0)) return;
+    const GatherEntry e = gather_entry<true, false>(src_off, dst_tok, sel_bits, j);
     u4_t* dst = kv_out + (static_cast<uint64_t>(slab) * g.n_tokens +
-                          static_cast<uint64_t>(dst_tok[j])) * g.row_pieces;
-    swapin_task<PPL, HP>(packed + src_off[j], uniform_byte(sel_bits, j), slab, dst, g, p0, lane);
+                          static_cast<uint64_t>(e.tok)) * g.row_pieces;
+    swapin_task<PPL, HP>(packed + e.src, e.b, slab, dst, g, p0, lane);
 }
 
 // The same Load for a record pool that stays in pinned host memory.  A wavefront of this
@@ -443,9 +484,10 @@ __global__ __launch_bounds__(64 * kLoadWavesMax) void swapin_link_kernel(const u
     for (uint32_t w = blockIdx.x; w < total; w += gridDim.x) {
         int j, slab, p0;
         if (!strip_task_at(g, n_sel, PPL, w, static_cast<int>(blockDim.x >> 6), j, slab, p0)) continue;
+        const GatherEntry e = gather_entry<false>(src_off, dst_tok, sel_bits, j);
         u4_t* dst = kv_out + (static_cast<uint64_t>(slab) * g.n_tokens +
-                              static_cast<uint64_t>(dst_tok[j])) * g.row_pieces;
-        swapin_task<PPL, HP>(packed + src_off[j], uniform_byte(sel_bits, j), slab, dst, g, p0, lane);
+                              static_cast<uint64_t>(e.tok)) * g.row_pieces;
+        swapin_task<PPL, HP>(packed + e.src, e.b, slab, dst, g, p0, lane);
     }
 }
 
