@@ -126,6 +126,27 @@ def test_ranges_of_a_few_binary16_subnormal_steps(b, fmt):
 
 @pytest.mark.parametrize("fmt", [0, 3])
 @pytest.mark.parametrize("b", [8, 4, 2])
+def test_scale_for_every_binary16_range(b, fmt):
+    """The stored scale is (max - min) / levels as a correctly rounded binary32 division.  One group per
+    positive finite binary16 value h with range h (minimum 0), and one with range h + h' (minimum -h', h'
+    another binary16 value, so that the numerator is a sum that binary32 may have to round): 63 486
+    numerators per width, compared bit for bit with the oracle's division like every other record byte."""
+    g = synth.Geometry(1, 2, 2, 128, 8192, 16, 64)
+    rng = np.random.default_rng(300 + b)
+    halves = np.arange(1, 0x7c00, dtype=np.uint16).view(np.float16).astype(np.float64)   # every positive finite value
+    n_groups = 2 * g.Hkv * g.N * (g.D // g.G)
+    assert n_groups >= 2 * len(halves)
+    top = np.resize(halves, n_groups)
+    low = np.where(np.arange(n_groups) < len(halves), 0.0, -halves[(np.arange(n_groups) * 7919) % len(halves)])
+    x = low[:, None] + rng.random((n_groups, g.G)) * (top - low)[:, None]
+    x[:, 0] = low
+    x[:, 1] = top
+    kv = x.reshape(g.L, 2, g.Hkv, g.N, g.D).astype(np.float16)
+    check_full(g, kv, np.full(g.n_chunks, b, dtype=np.uint8), fmt=fmt)
+
+
+@pytest.mark.parametrize("fmt", [0, 3])
+@pytest.mark.parametrize("b", [8, 4, 2])
 def test_groups_far_from_zero(b, fmt):
     """Groups whose minimum is thousands of steps away from zero (a range of 1 to 600 units in the last
     place at magnitudes from 1 to 32768, both signs): the quotient (x - min) / scale is then a small
