@@ -488,8 +488,8 @@ typedef struct {
 
 /* Handle of the recompute path.  The projections of up to KV_RECOMPUTE_OWN_GEMM_ROWS recomputed
  * tokens (what a plan of Eq. 4 recomputes beside a Load) run on the library's own MFMA GEMM,
- * which is the faster one there (0.27 against 0.34 ms per Llama-2-7B layer at 128 tokens, 0.32
- * against 0.35 at 256, 0.47 against 0.49 at 512, rocBLAS with its best kernels); larger ones are handed
+ * which is the faster one there (0.26 against 0.34 ms per Llama-2-7B layer at 128 tokens, 0.33
+ * against 0.35 at 256, 0.46 against 0.49 at 512, rocBLAS with its best kernels); larger ones are handed
  * to rocBLAS, which is loaded on creation if it is installed (the handle then owns that
  * library's handle, whose device workspace lives until kv_recompute_destroy).  Without
  * rocBLAS, or with KVSWITCH_OWN_GEMM=1 in the environment at creation, every size runs on the
