@@ -85,9 +85,12 @@ HandGemm hand_gemm_plan(int64_t M, const int64_t* N, int n_mats, int64_t K) {
         n_sum += N[j];
     }
     h.tiles_m = static_cast<uint32_t>((M + h.mb * 32 - 1) / (h.mb * 32));
-    // K is divided until some 512 workgroups exist (two per CU), at least 256 of K per split
+    // K is divided until some 512 workgroups exist (two per CU), at least 256 of K per split.  Up to 128
+    // rows 256 workgroups are as fast (measured: the four launches of a layer take 164-168 us with 256,
+    // 384, 512 and 768 workgroups) and leave half the partial products for the next kernel to add.
     const int64_t tiles = static_cast<int64_t>(h.tiles_n) * h.tiles_m;
-    int64_t want = (512 + tiles - 1) / tiles;
+    const int64_t groups = M <= 128 ? 256 : 512;
+    int64_t want = (groups + tiles - 1) / tiles;
     want = std::min<int64_t>(want, std::min<int64_t>(kGemmMaxSplits, std::max<int64_t>(1, K / 256)));
     h.k_slice = static_cast<int>(((K + want - 1) / want + kGemmKStep - 1) / kGemmKStep * kGemmKStep);
     h.splits = static_cast<int>((K + h.k_slice - 1) / h.k_slice);

@@ -116,10 +116,11 @@ def test_recompute_entry_points_validate_on_the_host():
         return (up(M * 4096 * 2) + 3 * up(M * dq * 4) + 2 * up(M * dq * 2) + up(M * 4096 * 2) + 2 * up(M * 11008 * 2))
     # 128 rows give 32 attention workgroups: the key range is shared by 8 workgroups each, whose
     # partial outputs (binary32) and (maximum, denominator) pairs are part of the workspace
-    # and the projections of so few rows divide K among several workgroups per tile; the widest set of
-    # binary32 partial tiles is that of q | k | v in one launch: 96 column tiles want 6 shares of K,
-    # 704 of K each (a multiple of 32) makes 6 shares of [128][3 * 4096]
-    want = plain(M) + 8 * M * dq * 4 + 8 * M * 32 * 8 + 6 * M * 3 * 4096 * 4
+    # and the projections of so few rows divide K among several workgroups per tile (some 256 workgroups per
+    # launch up to 128 rows); the widest set of binary32 partial tiles is that of gate | up in one launch:
+    # 172 column tiles want 2 shares of K, [128][2 * 11008] each (q | k | v: 3 shares of [128][3 * 4096];
+    # o and down: 8 shares of [128][4096])
+    want = plain(M) + 8 * M * dq * 4 + 8 * M * 32 * 8 + 2 * M * 2 * 11008 * 4
     assert kvs.kv_recompute_workspace_bytes(shape, dims, 8) == want
     assert kvs.kv_recompute_workspace_bytes(shape, dims, 256) == plain(4096)       # enough workgroups: no split
     for bad_shape, bad_dims, n in ((shape._replace(head_dim=256, group=64), dims, 8),
