@@ -529,7 +529,7 @@ int32_t kv_recompute_layer(kv_recompute_t* rc, const kv_shape_t* shape, const kv
     // 2. global position encoding; the recomputed K/V go to their places in the cache
     RopeTable tab;
     for (int i = 0; i < D / 2; ++i) tab.theta[i] = std::pow(static_cast<double>(dims->rope_base), -2.0 * i / D);
-    hipLaunchKernelGGL(rope_scatter_kernel, dim3(static_cast<uint32_t>(M)), dim3(256), 0, st, q_src, k_src, v_src,
+    hipLaunchKernelGGL(rope_scatter_kernel, dim3(static_cast<uint32_t>(M), 4), dim3(256), 0, st, q_src, k_src, v_src,
                        chunk_idx_dev, q16, k_plane, v_plane, tab, s.chunk_tokens, s.n_tokens, Hq, Hkv, D, sp);
     // 3. causal attention over the recovered K/V
     AttnGeom g;

@@ -119,7 +119,9 @@ struct RopeTable {
     double theta[128];      // head_dim / 2 <= 128
 };
 
-// One workgroup per recomputed token m at global position p:
+// Four workgroups per recomputed token m at global position p (grid (M, 4): q, k and the two halves of v;
+// with some hundred tokens a workgroup per token leaves half the CUs idle and walks its row in eight
+// dependent trips to memory):
 //   q16[m][h][:]            = rope(q32[m][h][:], p)                       (fp16)
 //   K plane [g][p][:]       = rope(k32[m][g][:], p)   V plane [g][p][:] = v32[m][g][:]   (fp16 cache)
 // The pair (i, i + D/2) is rotated by p * theta[i]; sine and cosine are taken in
@@ -149,8 +151,18 @@ __global__ __launch_bounds__(256) void rope_scatter_kernel(const float* __restri
                       static_cast<_Float16>(a[3])};
     };
     const int m = blockIdx.x;
+    const int part = blockIdx.y;            // 0: q, 1: k, 2 and 3: the halves of v (uniform per workgroup)
     const int p = global_position(chunk_idx, T, m);
     const int half = D / 2, half4 = D / 8;
+    if (part >= 2) {
+        const float* vrow = v32 + static_cast<int64_t>(m) * Hkv * D;
+        const int n4 = Hkv * D / 4, mid = n4 / 2;
+        for (int e = (part == 2 ? 0 : mid) + threadIdx.x; e < (part == 2 ? mid : n4); e += blockDim.x) {
+            const int g = e / (D / 4), d = (e % (D / 4)) * 4;
+            *reinterpret_cast<rv4h_t*>(v_plane + (static_cast<int64_t>(g) * N + p) * D + d) = to_half4(sum4(vrow + e * 4, plane_kv));
+        }
+        return;
+    }
     for (int i = threadIdx.x; i < half; i += blockDim.x) {
         double s, c;
         sincos(static_cast<double>(p) * tab.theta[i], &s, &c);
@@ -158,17 +170,19 @@ __global__ __launch_bounds__(256) void rope_scatter_kernel(const float* __restri
         cs[1][i] = static_cast<float>(s);
     }
     __syncthreads();
-    const float* qrow = q32 + static_cast<int64_t>(m) * Hq * D;
-    _Float16* qout = q16 + static_cast<int64_t>(m) * Hq * D;
-    for (int e = threadIdx.x; e < Hq * half4; e += blockDim.x) {
-        const int h = e / half4, i = (e % half4) * 4;
-        const rv4f_t a = sum4(qrow + h * D + i, plane_q), b = sum4(qrow + h * D + i + half, plane_q);
-        const rv4f_t c = *reinterpret_cast<const rv4f_t*>(&cs[0][i]), s = *reinterpret_cast<const rv4f_t*>(&cs[1][i]);
-        *reinterpret_cast<rv4h_t*>(qout + h * D + i) = to_half4(a * c - b * s);
-        *reinterpret_cast<rv4h_t*>(qout + h * D + i + half) = to_half4(b * c + a * s);
+    if (part == 0) {
+        const float* qrow = q32 + static_cast<int64_t>(m) * Hq * D;
+        _Float16* qout = q16 + static_cast<int64_t>(m) * Hq * D;
+        for (int e = threadIdx.x; e < Hq * half4; e += blockDim.x) {
+            const int h = e / half4, i = (e % half4) * 4;
+            const rv4f_t a = sum4(qrow + h * D + i, plane_q), b = sum4(qrow + h * D + i + half, plane_q);
+            const rv4f_t c = *reinterpret_cast<const rv4f_t*>(&cs[0][i]), s = *reinterpret_cast<const rv4f_t*>(&cs[1][i]);
+            *reinterpret_cast<rv4h_t*>(qout + h * D + i) = to_half4(a * c - b * s);
+            *reinterpret_cast<rv4h_t*>(qout + h * D + i + half) = to_half4(b * c + a * s);
+        }
+        return;
     }
     const float* krow = k32 + static_cast<int64_t>(m) * Hkv * D;
-    const float* vrow = v32 + static_cast<int64_t>(m) * Hkv * D;
     for (int e = threadIdx.x; e < Hkv * half4; e += blockDim.x) {
         const int g = e / half4, i = (e % half4) * 4;
         const rv4f_t a = sum4(krow + g * D + i, plane_kv), b = sum4(krow + g * D + i + half, plane_kv);
@@ -176,10 +190,6 @@ __global__ __launch_bounds__(256) void rope_scatter_kernel(const float* __restri
         _Float16* dst = k_plane + (static_cast<int64_t>(g) * N + p) * D;
         *reinterpret_cast<rv4h_t*>(dst + i) = to_half4(a * c - b * s);
         *reinterpret_cast<rv4h_t*>(dst + i + half) = to_half4(b * c + a * s);
-    }
-    for (int e = threadIdx.x; e < Hkv * D / 4; e += blockDim.x) {
-        const int g = e / (D / 4), d = (e % (D / 4)) * 4;
-        *reinterpret_cast<rv4h_t*>(v_plane + (static_cast<int64_t>(g) * N + p) * D + d) = to_half4(sum4(vrow + e * 4, plane_kv));
     }
 }
 
